@@ -1,0 +1,176 @@
+/*
+ * libpvq — group-wise Pyramid Vector Quantization of weight matrices on AMD MI355X (gfx950).
+ *
+ * The method is that of "Pyramid Vector Quantization for LLMs" (arXiv 2410.16926).  A weight
+ * matrix W [rows x cols], cols = G*D, is cut into groups of D consecutive weights of a row.
+ * Each group is stored as
+ *   - the index of its direction on the integer pyramid P(D,K) = { p in Z^D : sum |p_d| = K }
+ *     (Sec. 2.4), an integer in [0, N(D,K)) produced by the pyramid enumeration of App. B.2, and
+ *   - its amplitude ||w||_2 (Sec. 2.3), either as a float32 or as a scale_bits-bit code against
+ *     quantiles of the Beta(D/2, D(G-1)/2) distribution of the normalised squared amplitudes
+ *     (Sec. 3.3 Step 5, Sec. 3.4), plus one float32 normaliser per row.
+ *
+ * Conventions for every call
+ *   - Plain C ABI; no exceptions cross it.  Every function returns PVQ_OK (0) or a negative
+ *     pvq_status; pvq_strerror() names it.  On error nothing has been launched.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     memory.  The library never allocates, frees or keeps caller-visible device memory.  A context
+ *     owns small read-only device tables of its own.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  encode / decode /
+ *     decode_gemv enqueue kernels on it and return without synchronising.  Outputs are overwritten
+ *     in full; inputs are never modified.  Concurrent calls on different streams are safe.
+ *   - Matrices are row-major; `ld*` arguments are the distance between rows in ELEMENTS.
+ *
+ * Packed layout (fixed; it is the storage format of the codes)
+ *   - Index plane: for every row a little-endian bit stream over 32-bit words.  The index of group g
+ *     occupies bits [g*b, (g+1)*b) of its row's stream, least significant bit first, b = index_bits =
+ *     bit_length(N(D,K)-1).  Every row starts on a word boundary: row stride =
+ *     ceil(G*b/32) words.  Unused high bits of a row's last word are written as zero.
+ *   - Scale plane, scale_bits == 0: float32 [rows][G], the amplitudes.
+ *     Scale plane, scale_bits in {1,2,4,8}: bit stream per row exactly like the index plane with
+ *     b = scale_bits.
+ *   - Row normaliser: float32 [rows], the row's sum of squared weights (only used with codes).
+ */
+#ifndef PVQ_H
+#define PVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pvq_ctx pvq_ctx;
+
+typedef enum {
+    PVQ_OK = 0,
+    PVQ_E_INVALID_ARG = -1, /* null pointer, negative size, ld < cols, bad enum value ...          */
+    PVQ_E_UNSUPPORTED = -2, /* D not in {8,16,32}; K out of range; index wider than 128 bits;
+                               cols not a multiple of D; scale_bits not in {0,1,2,4,8}; batch > 16 */
+    PVQ_E_ALIGNMENT = -3,   /* a device pointer or ld breaks the alignment stated at the call      */
+    PVQ_E_HIP = -4,         /* a HIP runtime call failed; see pvq_last_hip_error()                 */
+    PVQ_E_NOMEM = -5        /* host allocation failed                                              */
+} pvq_status;
+
+typedef enum { PVQ_F32 = 0, PVQ_F16 = 1, PVQ_BF16 = 2 } pvq_dtype;
+
+/* Text for a status code (static storage). */
+const char *pvq_strerror(int status);
+
+/* The hipError_t value of the last failing HIP call made by this thread through the library
+ * (0 if none). */
+int pvq_last_hip_error(void);
+
+/* ---- host-only helpers (exact integer arithmetic, no GPU needed) ------------------------- */
+
+/*
+ * N(D,K), the number of points of P(D,K) (Sec. 2.4: N(D,0)=1, N(0,K>=1)=0,
+ * N(D,K) = N(D-1,K) + N(D,K-1) + N(D-1,K-1)), as 8 little-endian 32-bit words in count_words
+ * (host, may be NULL), and the width of an index, bit_length(N-1), in index_bits (host, may be NULL).
+ * 1 <= D <= 256, 0 <= K <= 1024; PVQ_E_UNSUPPORTED if N does not fit 256 bits.
+ */
+int pvq_count(int D, int K, uint32_t *count_words, int *index_bits);
+
+/*
+ * Sec. 3.3 Step 2: the largest K >= 1 whose index fits in bit_budget bits (1..255).
+ * PVQ_E_UNSUPPORTED if not even K = 1 fits.
+ */
+int pvq_max_k(int D, int bit_budget, int *K);
+
+/*
+ * Quantile tables of the amplitude quantiser (Sec. 3.4) for Beta(D/2, D(G-1)/2), D even, G >= 2:
+ *   edges[j-1]  = PPF(j / 2^b),        j = 1 .. 2^b - 1   (quantize(u) = floor(CDF(u) 2^b)
+ *                                                           = number of edges <= u)
+ *   centers[q]  = PPF((q + 0.5) / 2^b), q = 0 .. 2^b - 1   (dequantize)
+ * Both host float64 arrays written by the call.  scale_bits in {1,2,4,8}.
+ */
+int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, double *centers);
+
+/* ---- context ------------------------------------------------------------------------------- */
+
+/*
+ * Builds the size tables for (D,K) on the host, uploads them (and the amplitude tables) to the
+ * current HIP device, and returns an immutable context usable from any thread and stream of that
+ * device.  D in {8,16,32}; 1 <= K <= 127; index_bits <= 128.
+ * scale_bits == 0: amplitudes are float32, edges/centers are ignored (may be NULL).
+ * scale_bits in {1,2,4,8}: edges (2^b - 1 ascending values) and centers (2^b values), host float64,
+ *   e.g. from pvq_beta_tables.  Encoding compares float32(u) with float32(edges[j]); decoding
+ *   uses float32(sqrt(centers[q])).
+ * This call synchronises (it copies tables); the others do not.
+ */
+int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const double *edges,
+                   const double *centers);
+int pvq_ctx_destroy(pvq_ctx *ctx);
+
+/* Any of the out pointers may be NULL. */
+int pvq_ctx_info(const pvq_ctx *ctx, int *D, int *K, int *index_bits, int *scale_bits);
+
+/*
+ * Sizes in bytes of the three planes for a rows x cols matrix (host out pointers, may be NULL):
+ * index plane rows*ceil(G*index_bits/32)*4; scale plane rows*G*4 (scale_bits == 0) or
+ * rows*ceil(G*scale_bits/32)*4; row normaliser rows*4.
+ */
+int pvq_packed_sizes(const pvq_ctx *ctx, int64_t rows, int64_t cols, size_t *index_bytes,
+                     size_t *scale_bytes, size_t *rownorm_bytes);
+
+/* ---- the hot path --------------------------------------------------------------------------- */
+
+/*
+ * Encode a matrix: Sec. 2.5 "Quantizing the direction" (project each group onto the l1 ball of
+ * radius K, round, repair the pulse count by +-1 on the coordinates of largest deviation), App. B.2
+ * (enumerate the point to its index), Sec. 2.3 (amplitude = l2 norm) and, with scale_bits > 0,
+ * Sec. 3.3 Step 5 (amplitude code = floor(CDF(||w_g||^2 / ||w_row||^2) 2^b)).
+ *
+ *   W           device, [rows][ldw] of `dtype` (PVQ_F32 or PVQ_BF16), 16-byte aligned, ldw >= cols and
+ *               ldw*sizeof(element) a multiple of 16.
+ *   index_out   device, index plane (see layout), 4-byte aligned.
+ *   scale_out   device, scale plane, 4-byte aligned.
+ *   rownorm_out device, float32 [rows]; required and written when scale_bits > 0, ignored (may be
+ *               NULL) otherwise.
+ *   pulses_out  device, int8 [rows][cols], 16-byte aligned, or NULL: the integer points themselves,
+ *               for checking.
+ *
+ * Arithmetic is float32 in a fixed order (pairwise sums of |w| and w*w over adjacent elements,
+ * one correctly rounded division K/||w||_1, products, round-to-nearest-even; ties in the repair go
+ * to the lowest coordinate), so results do not depend on the launch shape.  A group of zeros (or so
+ * small that K/||w||_1 overflows) gets the point (0,...,0,+K), index 0.  Non-finite weights give
+ * unspecified codes (never an out-of-bounds access).
+ */
+int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64_t cols,
+               int64_t ldw, uint32_t *index_out, void *scale_out, float *rownorm_out,
+               int8_t *pulses_out, void *stream);
+
+/*
+ * Decode a matrix: App. B.3 (index -> point p), Sec. 2.4 (direction p/||p||_2 on the unit sphere),
+ * times the amplitude (the stored float32, or sqrt(centers[q] * rownorm[row]) per Sec. 3.4).
+ *
+ *   index, scale, rownorm   device, the planes written by pvq_encode (rownorm may be NULL when
+ *                           scale_bits == 0).
+ *   W_out       device, [rows][ldw] of out_dtype (PVQ_F32, PVQ_F16 or PVQ_BF16), 16-byte aligned,
+ *               ldw >= cols and ldw*sizeof(element) a multiple of 16.  Float32 arithmetic, one
+ *               round-to-nearest-even conversion to the output type.
+ * A stored index >= N(D,K) (corrupt data) decodes to unspecified values without any out-of-bounds
+ * access.
+ */
+int pvq_decode(const pvq_ctx *ctx, const uint32_t *index, const void *scale, const float *rownorm,
+               int64_t rows, int64_t cols, void *W_out, int out_dtype, int64_t ldw, void *stream);
+
+/*
+ * Decode fused into a matrix-vector product, without materialising the weights:
+ *   y[b][r] = sum_c W_hat[r][c] * x[b][c],   W_hat as produced by pvq_decode in float32.
+ * Not in the paper; it is the inference-side use of the decoder (Sec. 2.3: the rotated, quantised
+ * weights multiply the activations directly).
+ *
+ *   x   device, bf16 [batch][ldx], 16-byte aligned, ldx >= cols, ldx a multiple of 8; 1 <= batch <= 16.
+ *   y   device, float32 [batch][ldy], ldy >= rows.  Float32 accumulation in a fixed order
+ *       (deterministic for a given shape).
+ */
+int pvq_decode_gemv(const pvq_ctx *ctx, const uint32_t *index, const void *scale,
+                    const float *rownorm, int64_t rows, int64_t cols, const void *x, int batch,
+                    int64_t ldx, float *y, int64_t ldy, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PVQ_H */

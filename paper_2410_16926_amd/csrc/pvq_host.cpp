@@ -1,0 +1,421 @@
+// Host side of libpvq: status codes, exact size tables, the choice of K, Beta quantile tables,
+// the context, and argument validation in front of the kernel launchers.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "pvq_internal.h"
+
+// ------------------------------------------------------------------------------------------
+// status
+// ------------------------------------------------------------------------------------------
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return PVQ_E_HIP;
+}
+
+extern "C" const char *pvq_strerror(int status)
+{
+    switch (status) {
+    case PVQ_OK: return "ok";
+    case PVQ_E_INVALID_ARG: return "invalid argument";
+    case PVQ_E_UNSUPPORTED: return "unsupported configuration";
+    case PVQ_E_ALIGNMENT: return "pointer or leading dimension not aligned as required";
+    case PVQ_E_HIP: return "HIP runtime error (see pvq_last_hip_error)";
+    case PVQ_E_NOMEM: return "out of host memory";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int pvq_last_hip_error(void) { return g_last_hip_error; }
+
+// ------------------------------------------------------------------------------------------
+// 256-bit unsigned integers (four 64-bit limbs) for the size tables
+// ------------------------------------------------------------------------------------------
+
+namespace {
+
+struct U256 {
+    uint64_t limb[4] = {0, 0, 0, 0};
+
+    static U256 of(uint64_t v)
+    {
+        U256 r;
+        r.limb[0] = v;
+        return r;
+    }
+    // returns true when the sum left 256 bits
+    bool add(const U256 &o)
+    {
+        unsigned __int128 carry = 0;
+        for (int i = 0; i < 4; i++) {
+            unsigned __int128 s = (unsigned __int128)limb[i] + o.limb[i] + carry;
+            limb[i] = (uint64_t)s;
+            carry = s >> 64;
+        }
+        return carry != 0;
+    }
+    void decrement()  // value > 0
+    {
+        for (int i = 0; i < 4; i++)
+            if (limb[i]-- != 0) break;
+    }
+    int bit_length() const
+    {
+        for (int i = 3; i >= 0; i--)
+            if (limb[i]) return 64 * i + 64 - __builtin_clzll(limb[i]);
+        return 0;
+    }
+    uint32_t word(int i) const { return (uint32_t)(limb[i >> 1] >> (32 * (i & 1))); }
+};
+
+// Pyramid sizes N(d,k) for d <= D, k <= K (Sec. 2.4).  Rolling rows would do for a single count,
+// but the kernels need every row, so the whole table is kept.
+struct SizeTable {
+    int D, K;
+    int first_bad_k;      // smallest k with an entry that left 256 bits (K+1 if none); columns
+                          // below it are exact, because N(d,k) only depends on columns <= k
+    bool overflow;
+    std::vector<U256> n;  // (D+1) x (K+1)
+
+    SizeTable(int D_, int K_) : D(D_), K(K_), first_bad_k(K_ + 1), n((size_t)(D_ + 1) * (K_ + 1))
+    {
+        for (int k = 0; k <= K; k++) at(0, k) = U256::of(k == 0 ? 1 : 0);
+        for (int d = 1; d <= D; d++) {
+            at(d, 0) = U256::of(1);
+            for (int k = 1; k <= K; k++) {
+                U256 v = at(d - 1, k);
+                bool bad = v.add(at(d, k - 1));
+                bad |= v.add(at(d - 1, k - 1));
+                if (bad && k < first_bad_k) first_bad_k = k;
+                at(d, k) = v;
+            }
+        }
+        overflow = first_bad_k <= K;
+    }
+    U256 &at(int d, int k) { return n[(size_t)d * (K + 1) + k]; }
+    const U256 &at(int d, int k) const { return n[(size_t)d * (K + 1) + k]; }
+    int index_bits() const
+    {
+        U256 top = at(D, K);
+        top.decrement();
+        return top.bit_length();
+    }
+};
+
+}  // namespace
+
+extern "C" int pvq_count(int D, int K, uint32_t *count_words, int *index_bits)
+{
+    if (D < 1 || D > 256 || K < 0 || K > 1024) return PVQ_E_INVALID_ARG;
+    SizeTable t(D, K);
+    if (t.overflow) return PVQ_E_UNSUPPORTED;
+    if (count_words)
+        for (int i = 0; i < 8; i++) count_words[i] = t.at(D, K).word(i);
+    if (index_bits) *index_bits = t.index_bits();
+    return PVQ_OK;
+}
+
+extern "C" int pvq_max_k(int D, int bit_budget, int *K)
+{
+    if (D < 1 || D > 256 || bit_budget < 1 || bit_budget > 255 || !K) return PVQ_E_INVALID_ARG;
+    // One table with a generous K bound; N(D,k) grows with k, so the first k that does not fit
+    // (or that left the 256-bit integers) ends the search.
+    int kmax = 1024;
+    SizeTable t(D, kmax);
+    int best = 0;
+    for (int k = 1; k <= kmax && k < t.first_bad_k; k++) {
+        U256 top = t.at(D, k);
+        top.decrement();
+        if (top.bit_length() > bit_budget) break;
+        best = k;
+    }
+    if (best < 1) return PVQ_E_UNSUPPORTED;
+    *K = best;
+    return PVQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Beta(a, b) quantiles for integer a (D even): Sec. 3.4
+// ------------------------------------------------------------------------------------------
+
+namespace {
+
+// For integer a the upper tail of Beta(a, b) is a short sum of positive terms,
+//   P[X > x] = (1-x)^b * sum_{j < a} C(b+j-1, j) x^j,
+// evaluated in long double.  The lower tail is 1 minus it; the probabilities asked for are
+// multiples of 2^-9 at the finest, so the subtraction costs nothing that matters at 64 mantissa bits.
+long double beta_upper_tail(long double x, int a, long double b)
+{
+    if (x <= 0) return 1.0L;
+    if (x >= 1) return 0.0L;
+    long double lead = expl(b * log1pl(-x));
+    long double term = 1.0L;  // C(b+j-1, j) x^j at j = 0
+    long double sum = 0.0L;
+    for (int j = 0; j < a; j++) {
+        sum += term;
+        term *= (b + j) * x / (long double)(j + 1);
+    }
+    return lead * sum;
+}
+
+// PPF(p) by bisection: the upper tail decreases in x.
+double beta_ppf(long double p, int a, long double b)
+{
+    long double lo = 0.0L, hi = 1.0L;
+    long double target = 1.0L - p;
+    for (int it = 0; it < 400; it++) {
+        long double mid = 0.5L * (lo + hi);
+        if (mid == lo || mid == hi) break;
+        if (beta_upper_tail(mid, a, b) > target) lo = mid; else hi = mid;
+    }
+    return (double)(0.5L * (lo + hi));
+}
+
+bool scale_bits_ok(int sb) { return sb == 0 || sb == 1 || sb == 2 || sb == 4 || sb == 8; }
+
+}  // namespace
+
+extern "C" int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, double *centers)
+{
+    if (!edges || !centers || D < 2 || G < 2) return PVQ_E_INVALID_ARG;
+    if ((D & 1) || !scale_bits_ok(scale_bits) || scale_bits == 0) return PVQ_E_UNSUPPORTED;
+    int a = D / 2;
+    long double b = (long double)D * (long double)(G - 1) / 2.0L;
+    int n = 1 << scale_bits;
+    for (int j = 1; j < n; j++) edges[j - 1] = beta_ppf((long double)j / n, a, b);
+    for (int q = 0; q < n; q++) centers[q] = beta_ppf(((long double)q + 0.5L) / n, a, b);
+    return PVQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// context
+// ------------------------------------------------------------------------------------------
+
+extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const double *edges,
+                              const double *centers)
+{
+    if (!out) return PVQ_E_INVALID_ARG;
+    *out = nullptr;
+    if (D != 8 && D != 16 && D != 32) return PVQ_E_UNSUPPORTED;
+    if (K < 1 || K > 127) return PVQ_E_UNSUPPORTED;
+    if (!scale_bits_ok(scale_bits)) return PVQ_E_UNSUPPORTED;
+    if (scale_bits > 0 && (!edges || !centers)) return PVQ_E_INVALID_ARG;
+
+    SizeTable t(D, K);
+    if (t.overflow) return PVQ_E_UNSUPPORTED;
+    int bits = t.index_bits();
+    if (bits < 1 || bits > 128) return PVQ_E_UNSUPPORTED;
+    int words = bits <= 32 ? 1 : (bits <= 64 ? 2 : 4);
+
+    int n = scale_bits ? (1 << scale_bits) : 0;
+    std::vector<float> e32, sc32;
+    if (scale_bits) {
+        for (int j = 0; j + 1 < n; j++) {
+            if (!(edges[j] >= 0.0) || (j > 0 && !(edges[j] >= edges[j - 1]))) return PVQ_E_INVALID_ARG;
+            e32.push_back((float)edges[j]);
+        }
+        for (int q = 0; q < n; q++) {
+            if (!(centers[q] >= 0.0)) return PVQ_E_INVALID_ARG;
+            sc32.push_back((float)std::sqrt(centers[q]));
+        }
+    }
+
+    // tab_n[dp][k] = N(dp,k); tab_u[dp][k+1] = N(dp,0) + ... + N(dp,k), tab_u[dp][0] = 0.
+    // Every entry is below N(D,K) (the pyramid of one more dimension contains all of them), so it
+    // fits `words` words.
+    std::vector<uint32_t> hn((size_t)D * (K + 1) * words), hu((size_t)D * (K + 2) * words);
+    for (int dp = 0; dp < D; dp++) {
+        U256 run;  // running sum
+        for (int w = 0; w < words; w++) hu[((size_t)dp * (K + 2)) * words + w] = 0;
+        for (int k = 0; k <= K; k++) {
+            const U256 &v = t.at(dp, k);
+            run.add(v);
+            for (int w = 0; w < words; w++) {
+                hn[((size_t)dp * (K + 1) + k) * words + w] = v.word(w);
+                hu[((size_t)dp * (K + 2) + k + 1) * words + w] = run.word(w);
+            }
+        }
+    }
+
+    pvq_ctx *c = new (std::nothrow) pvq_ctx();
+    if (!c) return PVQ_E_NOMEM;
+    c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
+    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr;
+    c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
+
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->tab_n, c->tab_n_bytes);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->tab_u, c->tab_u_bytes);
+    if (e == hipSuccess) e = hipMemcpy(c->tab_n, hn.data(), c->tab_n_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->tab_u, hu.data(), c->tab_u_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess && scale_bits) {
+        // the edge table is padded to 2^b entries with +inf so that kernels may read a full table
+        e32.push_back(INFINITY);
+        e = hipMalloc((void **)&c->edges, sizeof(float) * n);
+        if (e == hipSuccess) e = hipMalloc((void **)&c->sqrtc, sizeof(float) * n);
+        if (e == hipSuccess) e = hipMemcpy(c->edges, e32.data(), sizeof(float) * n, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->sqrtc, sc32.data(), sizeof(float) * n, hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+        pvq_ctx_destroy(c);
+        return hip_fail(e);
+    }
+    *out = c;
+    return PVQ_OK;
+}
+
+extern "C" int pvq_ctx_destroy(pvq_ctx *c)
+{
+    if (!c) return PVQ_OK;
+    hipError_t first = hipSuccess;
+    void *ptrs[4] = {c->tab_n, c->tab_u, c->edges, c->sqrtc};
+    for (void *p : ptrs) {
+        if (!p) continue;
+        hipError_t e = hipFree(p);
+        if (first == hipSuccess) first = e;
+    }
+    delete c;
+    return first == hipSuccess ? PVQ_OK : hip_fail(first);
+}
+
+extern "C" int pvq_ctx_info(const pvq_ctx *c, int *D, int *K, int *index_bits, int *scale_bits)
+{
+    if (!c) return PVQ_E_INVALID_ARG;
+    if (D) *D = c->D;
+    if (K) *K = c->K;
+    if (index_bits) *index_bits = c->index_bits;
+    if (scale_bits) *scale_bits = c->scale_bits;
+    return PVQ_OK;
+}
+
+static int64_t stream_words(int64_t groups, int bits) { return (groups * bits + 31) / 32; }
+
+static int check_shape(const pvq_ctx *c, int64_t rows, int64_t cols)
+{
+    if (!c || rows < 0 || cols < 0) return PVQ_E_INVALID_ARG;
+    if (cols % c->D) return PVQ_E_UNSUPPORTED;
+    // 32-bit bit offsets inside a row and 31-bit element counts per launch dimension
+    if (cols > (int64_t)1 << 24 || rows > (int64_t)1 << 30) return PVQ_E_UNSUPPORTED;
+    return PVQ_OK;
+}
+
+extern "C" int pvq_packed_sizes(const pvq_ctx *c, int64_t rows, int64_t cols, size_t *index_bytes,
+                                size_t *scale_bytes, size_t *rownorm_bytes)
+{
+    int rc = check_shape(c, rows, cols);
+    if (rc) return rc;
+    int64_t G = cols / c->D;
+    if (index_bytes) *index_bytes = (size_t)(rows * stream_words(G, c->index_bits) * 4);
+    if (scale_bytes)
+        *scale_bytes = (size_t)(c->scale_bits ? rows * stream_words(G, c->scale_bits) * 4 : rows * G * 4);
+    if (rownorm_bytes) *rownorm_bytes = (size_t)(rows * 4);
+    return PVQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// the hot path: validation, then launch
+// ------------------------------------------------------------------------------------------
+
+static bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+static int check_device(const pvq_ctx *c)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    return dev == c->device ? PVQ_OK : PVQ_E_INVALID_ARG;
+}
+
+extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t rows, int64_t cols,
+                          int64_t ldw, uint32_t *index_out, void *scale_out, float *rownorm_out,
+                          int8_t *pulses_out, void *stream)
+{
+    int rc = check_shape(c, rows, cols);
+    if (rc) return rc;
+    if (dtype != PVQ_F32 && dtype != PVQ_BF16) return PVQ_E_INVALID_ARG;
+    if (rows == 0 || cols == 0) return PVQ_OK;
+    if (!W || !index_out || !scale_out || ldw < cols) return PVQ_E_INVALID_ARG;
+    if (c->scale_bits > 0 && !rownorm_out) return PVQ_E_INVALID_ARG;
+    size_t esz = dtype == PVQ_F32 ? 4 : 2;
+    if (!aligned(W, 16) || (ldw * esz) % 16 || !aligned(index_out, 4) || !aligned(scale_out, 4) ||
+        (rownorm_out && !aligned(rownorm_out, 4)))
+        return PVQ_E_ALIGNMENT;
+    if ((rc = check_device(c))) return rc;
+
+    pvq_encode_args a;
+    a.W = W; a.rows = rows; a.cols = cols; a.ldw = ldw; a.groups = cols / c->D;
+    a.index_out = index_out; a.scale_out = scale_out; a.rownorm_out = rownorm_out;
+    a.pulses_out = pulses_out;
+    a.index_row_words = stream_words(a.groups, c->index_bits);
+    a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
+    hipError_t e = pvq_launch_encode(c, a, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
+static int fill_decode_args(const pvq_ctx *c, pvq_decode_args &a, const uint32_t *index,
+                            const void *scale, const float *rownorm, int64_t rows, int64_t cols)
+{
+    if (!index || !scale) return PVQ_E_INVALID_ARG;
+    if (c->scale_bits > 0 && !rownorm) return PVQ_E_INVALID_ARG;
+    if (!aligned(index, 4) || !aligned(scale, 4) || (rownorm && !aligned(rownorm, 4))) return PVQ_E_ALIGNMENT;
+    memset(&a, 0, sizeof a);
+    a.index = index; a.scale = scale; a.rownorm = rownorm;
+    a.rows = rows; a.cols = cols; a.groups = cols / c->D;
+    a.index_row_words = stream_words(a.groups, c->index_bits);
+    a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
+    return PVQ_OK;
+}
+
+extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *scale,
+                          const float *rownorm, int64_t rows, int64_t cols, void *W_out,
+                          int out_dtype, int64_t ldw, void *stream)
+{
+    int rc = check_shape(c, rows, cols);
+    if (rc) return rc;
+    if (out_dtype != PVQ_F32 && out_dtype != PVQ_F16 && out_dtype != PVQ_BF16) return PVQ_E_INVALID_ARG;
+    if (rows == 0 || cols == 0) return PVQ_OK;
+    if (!W_out || ldw < cols) return PVQ_E_INVALID_ARG;
+    size_t esz = out_dtype == PVQ_F32 ? 4 : 2;
+    if (!aligned(W_out, 16) || (ldw * esz) % 16) return PVQ_E_ALIGNMENT;
+    pvq_decode_args a;
+    if ((rc = fill_decode_args(c, a, index, scale, rownorm, rows, cols))) return rc;
+    if ((rc = check_device(c))) return rc;
+    a.W_out = W_out; a.ldw = ldw;
+    hipError_t e = pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
+extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const void *scale,
+                               const float *rownorm, int64_t rows, int64_t cols, const void *x,
+                               int batch, int64_t ldx, float *y, int64_t ldy, void *stream)
+{
+    int rc = check_shape(c, rows, cols);
+    if (rc) return rc;
+    if (batch < 0) return PVQ_E_INVALID_ARG;
+    if (batch > 16) return PVQ_E_UNSUPPORTED;
+    if (rows == 0 || batch == 0) return PVQ_OK;
+    if (!y || ldy < rows) return PVQ_E_INVALID_ARG;
+    if (!aligned(y, 4)) return PVQ_E_ALIGNMENT;
+    pvq_decode_args a;
+    if (cols == 0) {
+        // an empty sum: y = 0
+        hipError_t e = hipSuccess;
+        for (int b = 0; b < batch && e == hipSuccess; b++)
+            e = hipMemsetAsync(y + (int64_t)b * ldy, 0, sizeof(float) * rows, (hipStream_t)stream);
+        return e == hipSuccess ? PVQ_OK : hip_fail(e);
+    }
+    if (!x || ldx < cols) return PVQ_E_INVALID_ARG;
+    if (!aligned(x, 16) || ldx % 8) return PVQ_E_ALIGNMENT;
+    if ((rc = fill_decode_args(c, a, index, scale, rownorm, rows, cols))) return rc;
+    if ((rc = check_device(c))) return rc;
+    a.x = x; a.batch = batch; a.ldx = ldx; a.y = y; a.ldy = ldy;
+    hipError_t e = pvq_launch_decode_gemv(c, a, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}

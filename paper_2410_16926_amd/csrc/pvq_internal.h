@@ -1,0 +1,55 @@
+// Internal interface between the host side of libpvq (argument checks, size tables, context) and
+// its kernels.  Not installed; the public contract is include/pvq.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pvq.h"
+
+struct pvq_ctx {
+    int D, K;
+    int index_bits;
+    int words;       // 32-bit words of one table entry / one index in registers: 1, 2 or 4
+    int scale_bits;  // 0 = float32 amplitudes
+    int device;
+    // Device tables.  Entries are `words` little-endian 32-bit words.
+    //   tab_n[dp][k]  = N(dp, k),                      dp = 0..D-1, k = 0..K        (App. B.3 walks it)
+    //   tab_u[dp][k+1] = sum_{i=0..k} N(dp, i), tab_u[dp][0] = 0,  k = -1..K         (cumulative form of
+    //                    App. C.2's V table, shifted so that the empty sum is an entry)
+    uint32_t *tab_n;
+    uint32_t *tab_u;
+    float *edges;   // 2^scale_bits - 1 float32 edges (or nullptr)
+    float *sqrtc;   // 2^scale_bits float32 sqrt(centers) (or nullptr)
+    size_t tab_n_bytes, tab_u_bytes;
+};
+
+struct pvq_encode_args {
+    const void *W;
+    int64_t rows, cols, ldw, groups;
+    uint32_t *index_out;
+    void *scale_out;
+    float *rownorm_out;
+    int8_t *pulses_out;
+    int64_t index_row_words, scale_row_words;
+};
+
+struct pvq_decode_args {
+    const uint32_t *index;
+    const void *scale;
+    const float *rownorm;
+    int64_t rows, cols, groups;
+    int64_t index_row_words, scale_row_words;
+    void *W_out;
+    int64_t ldw;
+    const void *x;  // gemv only
+    int batch;
+    int64_t ldx;
+    float *y;
+    int64_t ldy;
+};
+
+// Each returns a hipError_t from the launch (hipSuccess if enqueued).
+hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
+hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
+hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);

@@ -1,0 +1,182 @@
+"""GPU parity: the library (through its C ABI) against the CPU oracle on the same seeded inputs.
+Integer results (pulse vectors, packed indices, amplitude codes) and the encoder's float32 values
+must be identical; decoded weights within 1e-6 relative (float32) / 1 ulp (16-bit outputs); the
+fused product within 1e-3 relative."""
+import numpy as np
+import pytest
+
+import paper_2410_16926_amd as pvq
+import synth_inputs as si
+from oracle import pvq_oracle as oracle
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def run_case(W32, D, K, scale_bits, src_bits=None, batches=(1, 4), out_dtypes=("f32", "f16", "bf16"), seed=1):
+    rows, cols = W32.shape
+    G = cols // D
+    ctx, oe, oc = gu.make_ctx(D, K, scale_bits, G)
+    Wd = gu.to_dev_bf16(src_bits) if src_bits is not None else gu.to_dev_f32(W32)
+    packed = pvq.pvq_encode(ctx, Wd, want_pulses=True)
+    torch.cuda.synchronize()
+    enc = oracle.encode(W32, D, K, scale_bits, oe, nthreads=8)
+    gu.assert_encode_equal(packed, enc)
+
+    ref, _, _ = oracle.decode(enc, oc, nthreads=8)
+    if "f32" in out_dtypes:
+        got = pvq.pvq_decode(ctx, packed, torch.float32).cpu().numpy()
+        gu.assert_decode_close(got, ref)
+    if "f16" in out_dtypes:
+        got = pvq.pvq_decode(ctx, packed, torch.float16).cpu().numpy()
+        assert gu.ulp_f16(oracle.to_f16(ref).view(np.uint16), got.view(np.uint16)) <= 1
+    if "bf16" in out_dtypes:
+        got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
+        assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
+    for B in batches:
+        xf, xb = si.activations(B, cols, seed=seed + B)
+        y = pvq.pvq_decode_gemv(ctx, packed, gu.to_dev_bf16(xb)).cpu().numpy()
+        want = xf.astype(np.float64) @ ref.T
+        gu.assert_gemv_close(y, want)
+    ctx.close()
+    return packed, enc
+
+
+def test_config0_512x512_fp32_amplitudes():
+    # 512x512 float32, N(0, 0.02^2), rotated; D=8, 24-bit indices (K=16), float32 amplitudes
+    W = si.gaussian_weights(512, 512, 0.02, seed=si.BASE_SEED + 0)
+    K = pvq.pvq_max_k(8, 24)
+    assert K == 16
+    run_case(W, 8, K, 0, batches=(1, 3, 16))
+
+
+@pytest.mark.parametrize("bits", [8, 2, 4, 1])
+def test_amplitude_codes_bf16_source(bits):
+    # the Llama-3-8B up-projection family (bf16 source, N(0, 0.015^2), 4096 inputs), a row slice
+    wf, wb = si.gaussian_weights(192, 4096, 0.015, seed=si.BASE_SEED + 1, bf16=True)
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(1, 4))
+
+
+@pytest.mark.parametrize("D,budget", [(16, 52), (32, 104), (16, 64), (8, 40), (16, 30), (32, 32)])
+def test_wide_indices(D, budget):
+    # multi-word indices: 52-bit (2 words) and 104-bit (4 words), plus widths that do not fill
+    # their words and single-word indices at D=16/32
+    K = pvq.pvq_max_k(D, budget)
+    wf, wb = si.gaussian_weights(96, 2048, 0.015, seed=si.BASE_SEED + 2 + D, bf16=True)
+    run_case(wf, D, K, 0, src_bits=wb, batches=(1, 2))
+
+
+@pytest.mark.parametrize("D,budget,bits", [(16, 52, 4), (32, 104, 8)])
+def test_wide_indices_with_codes(D, budget, bits):
+    K = pvq.pvq_max_k(D, budget)
+    W = si.gaussian_weights(64, 1024, 0.02, seed=si.BASE_SEED + 20 + D)
+    run_case(W, D, K, bits, batches=(1,))
+
+
+@pytest.mark.parametrize("rows,cols,D", [(1, 8, 8), (3, 8 * 37, 8), (5, 8 * 257, 8), (7, 16 * 33, 16),
+                                         (2, 32 * 9, 32), (257, 8 * 3, 8), (4, 8 * 3584, 8)])
+def test_ragged_shapes(rows, cols, D):
+    # partial tiles, a single group, odd group counts (odd leftovers in the row sum), long rows
+    K = pvq.pvq_max_k(D, 3 * D)
+    W = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + rows + cols, rotate=False)
+    run_case(W, D, K, 0, batches=(1,), out_dtypes=("f32",))
+    if cols // D >= 2:
+        run_case(W, D, K, 2, batches=(1,), out_dtypes=("f32",))
+
+
+@pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])
+def test_adversarial_groups(D, K):
+    # rounding ties, repair ties, zeros, one-hot, wide dynamic range; 64k groups
+    n = 1 << 16
+    W = si.adversarial_groups(n, D, seed=77 + D + K).reshape(n * D // 2048, 2048)
+    run_case(W, D, K, 0, batches=(1,), out_dtypes=("f32",))
+
+
+def test_leading_dimensions_and_views():
+    D, K = 8, 16
+    rows, cols, ld = 33, 512, 640
+    wf, wb = si.gaussian_weights(rows, ld, 0.02, seed=si.BASE_SEED + 50, bf16=True)
+    ctx = pvq.pvq_ctx_create(D, K)
+    big = gu.to_dev_bf16(wb)
+    view = big[:, :cols]
+    packed = pvq.pvq_encode(ctx, view, want_pulses=True)
+    enc = oracle.encode(np.ascontiguousarray(wf[:, :cols]), D, K)
+    gu.assert_encode_equal(packed, enc)
+    out_big = torch.full((rows, ld), 7.0, dtype=torch.float32, device="cuda")
+    pvq.pvq_decode(ctx, packed, out=out_big[:, :cols])
+    ref, _, _ = oracle.decode(enc)
+    gu.assert_decode_close(out_big[:, :cols].cpu().numpy(), ref)
+    assert torch.all(out_big[:, cols:] == 7.0)          # nothing written past cols
+    xf, xb = si.activations(2, ld, seed=5)
+    xv = gu.to_dev_bf16(xb)[:, :cols]
+    y_big = torch.full((2, rows + 5), -3.0, dtype=torch.float32, device="cuda")
+    pvq.pvq_decode_gemv(ctx, packed, xv, out=y_big[:, :rows])
+    gu.assert_gemv_close(y_big[:, :rows].cpu().numpy(), xf[:, :cols].astype(np.float64) @ ref.T)
+    assert torch.all(y_big[:, rows:] == -3.0)
+    ctx.close()
+
+
+def test_empty_inputs_and_argument_errors():
+    ctx = pvq.pvq_ctx_create(8, 16)
+    L = pvq.lib()
+    h = ctx.handle
+    # rows == 0 / cols == 0: nothing to do, success, no pointer is touched
+    assert L.pvq_encode(h, None, 0, 0, 512, 512, None, None, None, None, None) == 0
+    assert L.pvq_decode(h, None, None, None, 0, 512, None, 0, 512, None) == 0
+    assert L.pvq_decode_gemv(h, None, None, None, 0, 512, None, 1, 512, None, 0, None) == 0
+    y = torch.full((2, 16), 5.0, device="cuda")
+    assert L.pvq_decode_gemv(h, None, None, None, 16, 0, None, 2, 0, y.data_ptr(), 16, None) == 0
+    torch.cuda.synchronize()
+    assert torch.all(y == 0)                            # empty sum
+    W = torch.zeros((4, 512), dtype=torch.float32, device="cuda")
+    p = pvq.alloc_packed(ctx, 4, 512, W.device)
+    args = [h, W.data_ptr(), 0, 4, 512, 512, p.index.data_ptr(), p.scale.data_ptr(), None, None, None]
+    bad = list(args); bad[4] = 516                      # cols not a multiple of D
+    assert L.pvq_encode(*bad) == -2
+    bad = list(args); bad[5] = 256                      # ld < cols
+    assert L.pvq_encode(*bad) == -1
+    bad = list(args); bad[1] = W.data_ptr() + 4         # misaligned
+    assert L.pvq_encode(*bad) == -3
+    bad = list(args); bad[2] = 1                        # float16 source is not supported
+    assert L.pvq_encode(*bad) == -1
+    bad = list(args); bad[6] = None
+    assert L.pvq_encode(*bad) == -1
+    x = torch.zeros((17, 512), dtype=torch.bfloat16, device="cuda")
+    yy = torch.zeros((17, 4), device="cuda")
+    assert L.pvq_decode_gemv(h, p.index.data_ptr(), p.scale.data_ptr(), None, 4, 512, x.data_ptr(), 17,
+                             512, yy.data_ptr(), 4, None) == -2
+    for D, K in [(7, 5), (8, 0), (8, 128), (32, 100)]:
+        with pytest.raises(pvq.PvqError):
+            pvq.pvq_ctx_create(D, K)
+    with pytest.raises(pvq.PvqError):
+        pvq.pvq_ctx_create(8, 16, 3, np.zeros(7), np.zeros(8))
+    ctx.close()
+
+
+def test_zero_matrix_and_nonfinite_inputs_are_safe():
+    D, K = 8, 16
+    ctx = pvq.pvq_ctx_create(D, K)
+    W = torch.zeros((8, 256), dtype=torch.float32, device="cuda")
+    packed = pvq.pvq_encode(ctx, W, want_pulses=True)
+    assert torch.all(packed.index == 0) and torch.all(packed.scale == 0)
+    assert torch.all(pvq.pvq_decode(ctx, packed, torch.float32) == 0)
+    W[0, 3] = float("nan"); W[1, 9] = float("inf"); W[2, :] = float("-inf"); W[3, 0] = 3e38; W[3, 1] = 3e38
+    packed = pvq.pvq_encode(ctx, W, want_pulses=True)
+    torch.cuda.synchronize()
+    p = packed.pulses.cpu().numpy().astype(np.int64).reshape(8, 32, 8)
+    assert np.all(np.abs(p).sum(axis=2) == K)           # every stored point is on the pyramid
+    idx = np.array(oracle.unpack_fields(gu.words(packed.index), 32, 24))
+    assert idx.max() < pvq.pvq_count(D, K)[0]
+    ctx.close()
+
+
+def test_corrupt_indices_do_not_fault():
+    D, K = 8, 16
+    ctx = pvq.pvq_ctx_create(D, K)
+    idx = torch.full((16, 96), -1, dtype=torch.int32, device="cuda")     # every field = 2^24-1 >= N
+    p = pvq.Packed(16, 1024, idx, torch.ones((16, 128), device="cuda"), torch.ones(16, device="cuda"))
+    out = pvq.pvq_decode(ctx, p, torch.float32)
+    torch.cuda.synchronize()
+    assert out.shape == (16, 1024)
+    ctx.close()

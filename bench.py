@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the PVQ hot path on one MI355X.
+
+A step is one pass of the whole path over the Llama-3-70B gate-projection shape (28672 x 8192,
+bf16 source, D = 8, K = 16 -> 24-bit indices, 2-bit amplitude codes = 3.25 bits per weight):
+    pvq_encode  ->  pvq_decode (to bf16)  ->  pvq_decode_gemv at batch 1, 4 and 16.
+Inputs are resident in HBM before the timed region.  Steps rotate over several sets of packed
+planes so that the fused product reads its codes from HBM rather than from the last-level cache.
+
+Prints ONE JSON line.  `value` is the fused decode+GEMV's algorithmic bandwidth at batch 1
+(bytes the method must move per launch / the kernel's mean duration, HIP events on the launch
+stream); the other kernels' rates are extra keys of the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+ROWS, COLS = 28672, 8192        # Llama-3-70B gate projection (out x in)
+D, INDEX_BUDGET, SCALE_BITS = 8, 24, 2
+BATCHES = (1, 4, 16)
+
+
+def algorithmic_bytes(rows, cols, index_bits, scale_bits, batch):
+    """What one launch has to move (per weight: (index_bits + scale_bits)/8/D bytes of codes)."""
+    G = cols // D
+    codes = rows * ((G * index_bits + 31) // 32 + (G * scale_bits + 31) // 32) * 4
+    gemv = codes + rows * 4 + batch * cols * 2 + batch * rows * 4
+    decode = codes + rows * 4 + rows * cols * 2
+    encode = rows * cols * 2 + codes + rows * 4
+    return {"gemv": gemv, "decode": decode, "encode": encode}
+
+
+def cpu_baseline(wf_rows, xf, K, threads):
+    """The CPU oracle, as it stands, on a row sample of the same workload: encode, then
+    decode + product at batch 1.  Returns rates in the units of the GPU figures."""
+    import numpy as np
+
+    from oracle import pvq_oracle as oracle
+    rows, cols = wf_rows.shape
+    G = cols // D
+    edges, centers = oracle.beta_tables(D, G, SCALE_BITS)
+    t0 = time.perf_counter()
+    enc = oracle.encode(wf_rows, D, K, SCALE_BITS, edges, want_pulses=False, nthreads=threads)
+    t1 = time.perf_counter()
+    oracle.decode(enc, centers, x=xf.astype(np.float64), want_weights=False, nthreads=threads)
+    t2 = time.perf_counter()
+    ab = algorithmic_bytes(rows, cols, enc.index_bits, SCALE_BITS, 1)
+    return {
+        "value": ab["gemv"] / (t2 - t1) / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {rows} of {ROWS} rows of the same matrix ({rows * cols / 1e6:.1f} M weights), "
+                  f"decode + product at batch 1; encode timed beside it",
+        "decode_gemv_gweights_per_s": rows * cols / (t2 - t1) / 1e9,
+        "encode_gweights_per_s": rows * cols / (t1 - t0) / 1e9,
+        "seconds": round(t2 - t0, 2),
+    }
+
+
+def read_traffic():
+    """HBM bytes per launch of the batch-1 fused kernel from the committed counter summary
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs), or None if there is none."""
+    path = os.path.join(ROOT, "profiles", "gemv_b1_gate_70b_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's sample (0 = auto)")
+    ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (rows would shard across "
+                 "GPUs without any exchange, see DESIGN.md)")
+
+    import numpy as np
+    import torch
+
+    import paper_2410_16926_amd as pvq
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    K = pvq.pvq_max_k(D, INDEX_BUDGET)
+    G = COLS // D
+    edges, centers = pvq.pvq_beta_tables(D, G, SCALE_BITS)
+    ctx = pvq.pvq_ctx_create(D, K, SCALE_BITS, edges, centers)
+
+    # synthetic weights: Gaussian, block Hadamard rotation along the input dim, bf16
+    t_gen = time.perf_counter()
+    W = si.gaussian_weights_device(ROWS, COLS, 0.015, si.BASE_SEED + 4, dev)
+    xs = {}
+    xf1 = None
+    for B in BATCHES:
+        xf, xb = si.activations(B, COLS, seed=si.BASE_SEED + 4 + B)
+        xs[B] = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
+        if B == 1:
+            xf1 = xf
+    t_gen = time.perf_counter() - t_gen
+
+    sets = [pvq.alloc_packed(ctx, ROWS, COLS, dev) for _ in range(max(1, args.sets))]
+    Wout = torch.empty((ROWS, COLS), dtype=torch.bfloat16, device=dev)
+    ys = {B: torch.empty((B, ROWS), dtype=torch.float32, device=dev) for B in BATCHES}
+
+    names = ["encode", "decode"] + [f"gemv_b{B}" for B in BATCHES]
+
+    def step(i, events=None):
+        p = sets[i % len(sets)]
+        ev = events
+        if ev: ev[0].record()
+        pvq.pvq_encode(ctx, W, out=p)
+        if ev: ev[1].record()
+        pvq.pvq_decode(ctx, p, out=Wout)
+        if ev: ev[2].record()
+        for j, B in enumerate(BATCHES):
+            pvq.pvq_decode_gemv(ctx, p, xs[B], out=ys[B])
+            if ev: ev[3 + j].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    all_events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+                  for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, all_events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = {n: 0.0 for n in names}
+    for ev in all_events:
+        for j, n in enumerate(names):
+            ms[n] += ev[j].elapsed_time(ev[j + 1])
+    for n in names:
+        ms[n] /= args.steps
+
+    weights = ROWS * COLS
+    ab = {B: algorithmic_bytes(ROWS, COLS, ctx.index_bits, SCALE_BITS, B) for B in BATCHES}
+    gbps = lambda nbytes, t_ms: nbytes / (t_ms * 1e-3) / 1e9
+    gemv1 = gbps(ab[1]["gemv"], ms["gemv_b1"])
+
+    result = {
+        "metric": "pvq_decode_gemv_hbm_GBps",
+        "value": round(gemv1, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {
+            "workload": "llama3-70b gate_proj 28672x8192 bf16, D=8 K=16 (24-bit index) + 2-bit Beta "
+                        "amplitude code = 3.25 bpw; step = encode + decode(bf16) + decode_gemv batch 1/4/16",
+            "rows": ROWS, "cols": COLS, "D": D, "K": K, "index_bits": ctx.index_bits,
+            "scale_bits": SCALE_BITS, "packed_sets": len(sets),
+        },
+        "kernel_ms": {n: round(v, 4) for n, v in ms.items()},
+        "pct_of_hbm_peak": round(100 * gemv1 / HBM_PEAK_GBPS, 2),
+        "encode_gweights_per_s": round(weights / (ms["encode"] * 1e-3) / 1e9, 2),
+        "decode_gweights_per_s": round(weights / (ms["decode"] * 1e-3) / 1e9, 2),
+        "decode_GBps": round(gbps(ab[1]["decode"], ms["decode"]), 1),
+        "gemv_gweights_per_s": {f"b{B}": round(weights / (ms[f"gemv_b{B}"] * 1e-3) / 1e9, 2) for B in BATCHES},
+        "gemv_GBps": {f"b{B}": round(gbps(ab[B]["gemv"], ms[f"gemv_b{B}"]), 1) for B in BATCHES},
+        "roofline": {
+            "kernel": "pvq_decode_gemv batch 1",
+            "bound": "hbm",
+            "achieved": round(gemv1, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(gemv1 / HBM_PEAK_GBPS, 4),
+            "traffic": read_traffic(),
+            "algorithmic_bytes_per_launch": ab[1]["gemv"],
+        },
+        "input_generation_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        threads = min(os.cpu_count() or 1, 16)
+        rows = args.cpu_rows or 256 * threads
+        rows = min(rows, ROWS)
+        sample = W[:rows].to(torch.float32).cpu().numpy()      # the bf16 values, widened exactly
+        result["cpu_baseline"] = cpu_baseline(np.ascontiguousarray(sample), xf1, K, threads)
+
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -24,7 +24,10 @@ LLAMA3_8B_UP = (14336, 4096)
 def f32_to_bf16_bits(a) -> np.ndarray:
     """float32 -> bf16 bit patterns (uint16), round to nearest even."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    r = (u.astype(np.uint64) + 0x7FFF + ((u >> 16) & 1)) >> 16
+    r = (u >> 16) & 1            # finite inputs only: the uint32 sum below cannot wrap for them
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= 16
     return r.astype(np.uint16)
 
 
@@ -113,3 +116,26 @@ def adversarial_groups(n_groups: int, D: int, seed: int) -> np.ndarray:
         s = rng.integers(0, 2, size=D) * 2 - 1
         out[g] = (np.asarray(v, dtype=np.float64) * s).astype(np.float32)
     return out
+
+
+def gaussian_weights_device(rows: int, cols: int, sigma: float, seed: int, device):
+    """The same recipe as gaussian_weights(bf16=True), generated on a torch device (for matrices
+    too large to build quickly with numpy): i.i.d. N(0, sigma^2), random signs and a block
+    Walsh-Hadamard transform along each row, scaled by 1/sqrt(block), rounded to bf16.
+    Returns a bfloat16 tensor [rows][cols].  The random stream differs from the numpy recipe."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    w = torch.randn((rows, cols), generator=gen, device=device, dtype=torch.float32) * sigma
+    signs = torch.randint(0, 2, (cols,), generator=gen, device=device, dtype=torch.int32)
+    w *= (signs * 2 - 1).to(torch.float32)[None, :]
+    n = cols & (-cols)
+    h = 1
+    while h < n:
+        v = w.view(rows, cols // (2 * h), 2, h)
+        a, b = v[:, :, 0, :], v[:, :, 1, :]
+        w = torch.stack((a + b, a - b), dim=2).reshape(rows, cols)
+        h *= 2
+    w *= 1.0 / float(np.sqrt(n))
+    return w.to(torch.bfloat16)

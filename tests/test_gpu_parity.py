@@ -146,7 +146,7 @@ def test_empty_inputs_and_argument_errors():
     yy = torch.zeros((17, 4), device="cuda")
     assert L.pvq_decode_gemv(h, p.index.data_ptr(), p.scale.data_ptr(), None, 4, 512, x.data_ptr(), 17,
                              512, yy.data_ptr(), 4, None) == -2
-    for D, K in [(7, 5), (8, 0), (8, 128), (32, 100)]:
+    for D, K in [(7, 5), (8, 0), (8, 128), (32, 127)]:
         with pytest.raises(pvq.PvqError):
             pvq.pvq_ctx_create(D, K)
     with pytest.raises(pvq.PvqError):

@@ -39,6 +39,9 @@ def lib():
         path = _build.LIB_PATH
         if not os.path.exists(path):
             _build.build()
+        # PyTorch ships its own HIP runtime; load it first so that the process holds one runtime
+        # and the library's streams and pointers are the ones torch hands out.
+        import torch  # noqa: F401
         L = C.CDLL(path)
         i32, i64, vp = C.c_int, C.c_int64, C.c_void_p
         L.pvq_strerror.restype = C.c_char_p

@@ -87,6 +87,15 @@ int pvq_max_k(int D, int bit_budget, int *K);
  */
 int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, double *centers);
 
+/*
+ * Host-only diagnostic of the table-driven decoder that the kernels use for D = 8 when N(8,K) fits a
+ * 32-bit word and the tables fit LDS: rebuilds those tables and replays the kernels' table walk on the
+ * host for the indices [first, first + count) (clipped to N(8,K)), comparing every decoded point with
+ * the coordinate-by-coordinate walk of App. B.3.  *mismatches (host) receives the number of indices
+ * that differ (0 when the tables are right).  PVQ_E_UNSUPPORTED if (8,K) has no such tables.
+ */
+int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mismatches);
+
 /* ---- context ------------------------------------------------------------------------------- */
 
 /*

@@ -14,6 +14,7 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables",
+    "pvq_fast_tables_selftest",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
 ]
@@ -50,6 +51,7 @@ def lib():
         L.pvq_count.argtypes = [i32, i32, vp, vp]
         L.pvq_max_k.argtypes = [i32, i32, vp]
         L.pvq_beta_tables.argtypes = [i32, i64, i32, vp, vp]
+        L.pvq_fast_tables_selftest.argtypes = [i32, C.c_uint64, C.c_uint64, vp]
         L.pvq_ctx_create.argtypes = [vp, i32, i32, i32, vp, vp]
         L.pvq_ctx_destroy.argtypes = [vp]
         L.pvq_ctx_info.argtypes = [vp, vp, vp, vp, vp]
@@ -94,6 +96,14 @@ def pvq_beta_tables(D: int, G: int, scale_bits: int):
     _check(lib().pvq_beta_tables(D, G, scale_bits, edges.ctypes.data, centers.ctypes.data),
            "pvq_beta_tables")
     return edges[: n - 1], centers
+
+
+def pvq_fast_tables_selftest(K: int, first: int = 0, count: int = 1 << 40) -> int:
+    """Number of indices in [first, first+count) that the table-driven D=8 decoder gets wrong
+    (host replay).  Raises PvqError(-2) if (8, K) has no such tables."""
+    bad = C.c_uint64()
+    _check(lib().pvq_fast_tables_selftest(K, first, count, C.byref(bad)), "pvq_fast_tables_selftest")
+    return bad.value
 
 
 # ------------------------------------------------------------------ context

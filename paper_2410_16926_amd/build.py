@@ -9,7 +9,7 @@ _CSRC = os.path.join(_HERE, "csrc")
 _INC = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libpvq.so")
 
-SOURCES = ["pvq_host.cpp", "pvq_kernels.hip"]
+SOURCES = ["pvq_host.cpp", "pvq_fast8_tables.cpp", "pvq_kernels.hip", "pvq_fast8.hip"]
 
 # -ffp-contract=off: the encoder's float32 results are part of the format (no fused multiply-adds
 # unless written as fmaf); correctly rounded float32 division and square root likewise.
@@ -30,7 +30,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(_CSRC, "pvq_internal.h"), os.path.join(_INC, "pvq.h")]
+    deps = sources() + [os.path.join(_CSRC, "pvq_internal.h"), os.path.join(_CSRC, "pvq_fast8.h"),
+                        os.path.join(_INC, "pvq.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

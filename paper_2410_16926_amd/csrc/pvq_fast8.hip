@@ -1,0 +1,409 @@
+// gfx950 kernels built on the D = 8 table-driven decoder (pvq_fast8.h): decode to a matrix, and
+// decode fused into y = W_hat x.
+//
+// One workgroup per compute unit keeps the whole table blob (up to 156 KiB) in LDS and walks many
+// rows, so the copy is paid once per launch and unit.  A lane owns four consecutive groups of a row:
+// their 24-bit indices are three aligned dwords, their outputs 64 contiguous bytes.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "pvq_internal.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kMaxThreads = 1024;
+constexpr int kGroupsPerLane = 4;
+constexpr int kSliceGroups = kWave * kGroupsPerLane;  // groups one wave covers in a row: 256
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+struct fast8_launch {
+    pvq_fast8_params p;
+    const unsigned char *blob;
+    const float *sqrtc;  // 2^scale_bits entries, or nullptr
+    int index_bits, scale_bits;
+};
+
+__device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, float *sqrtc_l)
+{
+    const int nthreads = blockDim.x;
+    for (uint32_t i = threadIdx.x * 16u; i < f.p.blob_bytes; i += nthreads * 16u)
+        *reinterpret_cast<uint4 *>(lds + i) = *reinterpret_cast<const uint4 *>(f.blob + i);
+    if (f.scale_bits > 0)
+        for (int i = threadIdx.x; i < (1 << f.scale_bits); i += nthreads) sqrtc_l[i] = f.sqrtc[i];
+    __syncthreads();
+}
+
+// What a lane fetches for its four groups of one row: index bits and amplitude information.
+template <bool CODES>
+struct item_t {
+    uint32_t w[3];                       // 24-bit path: three dwords; generic path: unused
+    uint32_t c[kGroupsPerLane];          // generic path: the four indices
+    float amp[CODES ? 1 : kGroupsPerLane];
+    uint32_t codes;                      // CODES: the four codes, lowest group in the low bits
+};
+
+template <bool CODES, bool B24>
+__device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int g0,
+                                  bool live, item_t<CODES> &it)
+{
+    if (!live) {
+        it.w[0] = it.w[1] = it.w[2] = 0;
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) it.c[j] = 0;
+#pragma unroll
+        for (int j = 0; j < (CODES ? 1 : kGroupsPerLane); j++) it.amp[j] = 0.0f;
+        it.codes = 0;
+        return;
+    }
+    const uint32_t *irow = a.index + row * a.index_row_words;
+    if constexpr (B24) {
+        const uint32_t *p = irow + (g0 >> 2) * 3;
+        it.w[0] = p[0]; it.w[1] = p[1]; it.w[2] = p[2];
+    } else {
+        const uint32_t b = (uint32_t)f.index_bits;
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) {
+            const uint32_t pos = (uint32_t)(g0 + j) * b, w0 = pos >> 5, sh = pos & 31;
+            uint64_t v = irow[w0];
+            if (sh + b > 32) v |= (uint64_t)irow[w0 + 1] << 32;
+            it.c[j] = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
+        }
+    }
+    if constexpr (CODES) {
+        const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
+        const uint32_t pos = (uint32_t)g0 * (uint32_t)f.scale_bits;  // 4 codes never straddle a word
+        it.codes = srow[pos >> 5] >> (pos & 31);
+    } else {
+        const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(a.scale) + row * a.groups + g0);
+        it.amp[0] = v.x; it.amp[1] = v.y; it.amp[2] = v.z; it.amp[3] = v.w;
+    }
+}
+
+template <bool CODES, bool B24>
+__device__ inline void split_indices(item_t<CODES> &it)
+{
+    if constexpr (B24) {
+        it.c[0] = it.w[0] & 0xFFFFFFu;
+        it.c[1] = __builtin_amdgcn_alignbit(it.w[1], it.w[0], 24) & 0xFFFFFFu;
+        it.c[2] = __builtin_amdgcn_alignbit(it.w[2], it.w[1], 16) & 0xFFFFFFu;
+        it.c[3] = it.w[2] >> 8;
+    }
+}
+
+// amplitude factor of group j without the row normaliser: sqrt(center[q]) or the stored amplitude
+template <bool CODES>
+__device__ inline float amp_factor(const fast8_launch &f, const item_t<CODES> &it, int j, const float *sqrtc_l)
+{
+    if constexpr (CODES) {
+        const uint32_t q = (it.codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
+        return sqrtc_l[q];
+    } else {
+        return it.amp[j];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// y = W_hat x
+// ---------------------------------------------------------------------------------------------
+
+// Waves are arranged as nsl column slices (256 groups each) x rl row lanes.  Per batch of 4*rl rows
+// every wave handles 4 rows of its slice; lanes keep their 32 activations per vector in registers.
+// Row sums: xor butterfly inside the wave, then the slices' partial sums meet in LDS in slice order.
+template <int NB, bool CODES, bool B24>
+__global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_decode_args a, int b0,
+                                                             int nsl, int rl, int rows_per_block)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
+    float *part = sqrtc_l + 256;
+    load_tables(lds, f, sqrtc_l);
+
+    const int G = (int)a.groups;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int slice = wave % nsl, rowlane = wave / nsl;
+    const int g0 = slice * kSliceGroups + lane * kGroupsPerLane;
+    const bool in_row = g0 < G;
+    constexpr int RI = 4;              // rows per wave per batch
+    const int RB = RI * rl;            // rows per batch
+
+    uint32_t xr[NB][16];
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        const uint16_t *xp = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + b) * a.ldx + (int64_t)g0 * 8;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (in_row) v = *reinterpret_cast<const uint4 *>(xp + 8 * j);
+            xr[b][4 * j] = v.x; xr[b][4 * j + 1] = v.y; xr[b][4 * j + 2] = v.z; xr[b][4 * j + 3] = v.w;
+        }
+    }
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
+
+    item_t<CODES> cur[RI], nxt[RI];
+#pragma unroll
+    for (int i = 0; i < RI; i++) {
+        const int64_t row = r_begin + i * rl + rowlane;
+        fetch_item<CODES, B24>(f, a, row, g0, in_row && row < r_end, cur[i]);
+    }
+
+    for (int64_t batch = r_begin; batch < r_end; batch += RB) {
+#pragma unroll
+        for (int i = 0; i < RI; i++) {
+            const int64_t row = batch + RB + i * rl + rowlane;
+            fetch_item<CODES, B24>(f, a, row, g0, in_row && row < r_end, nxt[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < RI; i++) {
+            split_indices<CODES, B24>(cur[i]);
+            float acc[NB];
+#pragma unroll
+            for (int b = 0; b < NB; b++) acc[b] = 0.0f;
+            uint32_t pr[kGroupsPerLane][4], n2x4[kGroupsPerLane];
+            pvq_fast8_decode<kGroupsPerLane>(lds, f.p, cur[i].c, pr, n2x4);
+#pragma unroll
+            for (int j = 0; j < kGroupsPerLane; j++) {
+                const float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
+                                   amp_factor<CODES>(f, cur[i], j, sqrtc_l);
+#pragma unroll
+                for (int b = 0; b < NB; b++) {
+                    float s = dot2_bf16(pr[j][0], xr[b][4 * j], 0.0f);
+                    s = dot2_bf16(pr[j][1], xr[b][4 * j + 1], s);
+                    s = dot2_bf16(pr[j][2], xr[b][4 * j + 2], s);
+                    s = dot2_bf16(pr[j][3], xr[b][4 * j + 3], s);
+                    acc[b] = fmaf(gain, s, acc[b]);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                float v = acc[b];
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+                if (lane == 0) part[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < RB * NB) {
+            const int rloc = threadIdx.x / NB, b = threadIdx.x % NB;
+            const int64_t row = batch + rloc;
+            if (row < r_end) {
+                float v = 0.0f;
+                for (int s = 0; s < nsl; s++) v += part[(rloc * nsl + s) * NB + b];
+                if constexpr (CODES) v *= sqrtf(a.rownorm[row]);
+                a.y[(int64_t)(b0 + b) * a.ldy + row] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < RI; i++) cur[i] = nxt[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// decode to a matrix
+// ---------------------------------------------------------------------------------------------
+
+template <int OUT>
+__device__ inline void store_group(void *W_out, int64_t elem, const uint32_t (&pr)[4], float gain)
+{
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        v[2 * j] = gain * __uint_as_float(pr[j] << 16);
+        v[2 * j + 1] = gain * __uint_as_float(pr[j] & 0xFFFF0000u);
+    }
+    if constexpr (OUT == PVQ_F32) {
+        float *o = reinterpret_cast<float *>(W_out) + elem;
+        *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4 *>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+        uint32_t q[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if constexpr (OUT == PVQ_F16) {
+                q[j] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v[2 * j]) |
+                       ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v[2 * j + 1]) << 16);
+            } else {
+                const uint32_t u0 = __float_as_uint(v[2 * j]), u1 = __float_as_uint(v[2 * j + 1]);
+                q[j] = ((u0 + 0x7FFFu + ((u0 >> 16) & 1u)) >> 16) | ((u1 + 0x7FFFu + ((u1 >> 16) & 1u)) & 0xFFFF0000u);
+            }
+        }
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(W_out) + elem) = make_uint4(q[0], q[1], q[2], q[3]);
+    }
+}
+
+// Items = (row, quad of four groups); a block takes a contiguous range of items and its lanes stride it.
+template <int OUT, bool CODES, bool B24>
+__global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a,
+                                                               int64_t items_per_block)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
+    load_tables(lds, f, sqrtc_l);
+
+    const uint32_t Q = (uint32_t)(a.groups / kGroupsPerLane);
+    const int64_t total = a.rows * (int64_t)Q;
+    const int64_t i_begin = (int64_t)blockIdx.x * items_per_block;
+    const int64_t i_end = std::min(total, i_begin + items_per_block);
+    for (int64_t it0 = i_begin + threadIdx.x; it0 < i_end; it0 += blockDim.x) {
+        const int64_t row = it0 / Q;
+        const int g0 = (int)(it0 - row * Q) * kGroupsPerLane;
+        item_t<CODES> it;
+        fetch_item<CODES, B24>(f, a, row, g0, true, it);
+        split_indices<CODES, B24>(it);
+        float srn = 1.0f;
+        if constexpr (CODES) srn = sqrtf(a.rownorm[row]);
+        uint32_t prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
+        pvq_fast8_decode<kGroupsPerLane>(lds, f.p, it.c, prs, n2x4s);
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) {
+            const uint32_t(&pr)[4] = prs[j];
+            const uint32_t n2x4 = n2x4s[j];
+            // amp / sqrt(n2): the amplitude first (as in sqrt(center) * sqrt(row normaliser)), then the
+            // tabulated 1/sqrt(n2)
+            const float amp = CODES ? amp_factor<CODES>(f, it, j, sqrtc_l) * srn : amp_factor<CODES>(f, it, j, sqrtc_l);
+            const float gain = amp * *reinterpret_cast<const float *>(lds + f.p.invs + n2x4);
+            store_group<OUT>(a.W_out, row * a.ldw + (int64_t)(g0 + j) * 8, pr, gain);
+        }
+    }
+}
+
+fast8_launch make_launch(const pvq_ctx *c)
+{
+    fast8_launch f;
+    f.p = c->fast8; f.blob = c->fast8_blob; f.sqrtc = c->sqrtc;
+    f.index_bits = c->index_bits; f.scale_bits = c->scale_bits;
+    return f;
+}
+
+int g_num_cus = 0;
+
+template <typename Kern>
+hipError_t allow_big_lds(Kern k)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+template <int NB>
+hipError_t prepare_gemv()
+{
+    hipError_t e = allow_big_lds(gemv8_kernel<NB, true, true>);
+    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, true, false>);
+    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, false, true>);
+    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, false, false>);
+    return e;
+}
+
+template <int OUT>
+hipError_t prepare_decode()
+{
+    hipError_t e = allow_big_lds(decode8_kernel<OUT, true, true>);
+    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, true, false>);
+    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, false, true>);
+    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, false, false>);
+    return e;
+}
+
+template <int NB>
+hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b0, int nsl, int rl,
+                          int rows_per_block, dim3 grid, dim3 block, size_t lds, hipStream_t s)
+{
+    const bool codes = f.scale_bits > 0, b24 = f.index_bits == 24;
+    if (codes && b24) hipLaunchKernelGGL((gemv8_kernel<NB, true, true>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
+    else if (codes) hipLaunchKernelGGL((gemv8_kernel<NB, true, false>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
+    else if (b24) hipLaunchKernelGGL((gemv8_kernel<NB, false, true>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
+    else hipLaunchKernelGGL((gemv8_kernel<NB, false, false>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
+    return hipGetLastError();
+}
+
+template <int OUT>
+hipError_t launch_decode_out(const fast8_launch &f, const pvq_decode_args &a, int64_t ipb, dim3 grid,
+                             dim3 block, size_t lds, hipStream_t s)
+{
+    const bool codes = f.scale_bits > 0, b24 = f.index_bits == 24;
+    if (codes && b24) hipLaunchKernelGGL((decode8_kernel<OUT, true, true>), grid, block, lds, s, f, a, ipb);
+    else if (codes) hipLaunchKernelGGL((decode8_kernel<OUT, true, false>), grid, block, lds, s, f, a, ipb);
+    else if (b24) hipLaunchKernelGGL((decode8_kernel<OUT, false, true>), grid, block, lds, s, f, a, ipb);
+    else hipLaunchKernelGGL((decode8_kernel<OUT, false, false>), grid, block, lds, s, f, a, ipb);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t pvq_fast8_prepare(void)
+{
+    static hipError_t once = [] {
+        hipError_t e = prepare_gemv<1>();
+        if (e == hipSuccess) e = prepare_gemv<2>();
+        if (e == hipSuccess) e = prepare_gemv<4>();
+        if (e == hipSuccess) e = prepare_decode<PVQ_F32>();
+        if (e == hipSuccess) e = prepare_decode<PVQ_F16>();
+        if (e == hipSuccess) e = prepare_decode<PVQ_BF16>();
+        int dev = 0;
+        if (e == hipSuccess) e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&g_num_cus, hipDeviceAttributeMultiprocessorCount, dev);
+        return e;
+    }();
+    return once;
+}
+
+bool pvq_fast8_decode_usable(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    return c->fast8_blob != nullptr && a.groups % kGroupsPerLane == 0;
+}
+
+bool pvq_fast8_gemv_usable(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    // a row must fit the waves of one workgroup: at most 16 slices of 256 groups
+    return c->fast8_blob != nullptr && a.groups % kGroupsPerLane == 0 &&
+           (a.groups + kSliceGroups - 1) / kSliceGroups <= kMaxThreads / kWave;
+}
+
+hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
+{
+    const fast8_launch f = make_launch(c);
+    const size_t lds = f.p.blob_bytes + 256 * sizeof(float);
+    const int64_t total = a.rows * (a.groups / kGroupsPerLane);
+    // every block pays the table copy, so blocks get at least a few thousand items each
+    const int64_t want_blocks = std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, (total + 4095) / 4096);
+    const int64_t nblocks = std::max<int64_t>(1, want_blocks);
+    const int64_t ipb = (total + nblocks - 1) / nblocks;
+    const dim3 grid((unsigned)nblocks), block(kMaxThreads);
+    switch (out_dtype) {
+    case PVQ_F32: return launch_decode_out<PVQ_F32>(f, a, ipb, grid, block, lds, s);
+    case PVQ_F16: return launch_decode_out<PVQ_F16>(f, a, ipb, grid, block, lds, s);
+    default: return launch_decode_out<PVQ_BF16>(f, a, ipb, grid, block, lds, s);
+    }
+}
+
+hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
+{
+    const fast8_launch f = make_launch(c);
+    const int nsl = (int)((a.groups + kSliceGroups - 1) / kSliceGroups);
+    const int rl = std::max(1, (kMaxThreads / kWave) / nsl);
+    const int RB = 4 * rl;
+    const size_t lds = f.p.blob_bytes + 256 * sizeof(float) + (size_t)RB * nsl * 4 * sizeof(float);
+    const int64_t batches = (a.rows + RB - 1) / RB;
+    const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
+    const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);
+    const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)(kWave * nsl * rl));
+    int b0 = 0;
+    while (b0 < a.batch) {
+        const int left = a.batch - b0;
+        hipError_t e;
+        if (left >= 4) { e = launch_gemv_nb<4>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 4; }
+        else if (left >= 2) { e = launch_gemv_nb<2>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 2; }
+        else { e = launch_gemv_nb<1>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 1; }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}

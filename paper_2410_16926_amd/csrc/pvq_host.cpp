@@ -247,7 +247,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
-    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr;
+    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = nullptr;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -263,6 +263,14 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
         if (e == hipSuccess) e = hipMemcpy(c->edges, e32.data(), sizeof(float) * n, hipMemcpyHostToDevice);
         if (e == hipSuccess) e = hipMemcpy(c->sqrtc, sc32.data(), sizeof(float) * n, hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && D == 8 && words == 1) {
+        std::vector<unsigned char> blob;
+        if (pvq_fast8_build(K, kFast8MaxBytes, blob, c->fast8)) {
+            e = pvq_fast8_prepare();
+            if (e == hipSuccess) e = hipMalloc((void **)&c->fast8_blob, blob.size());
+            if (e == hipSuccess) e = hipMemcpy(c->fast8_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+        }
+    }
     if (e != hipSuccess) {
         pvq_ctx_destroy(c);
         return hip_fail(e);
@@ -275,7 +283,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[4] = {c->tab_n, c->tab_u, c->edges, c->sqrtc};
+    void *ptrs[5] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);
@@ -388,7 +396,8 @@ extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *s
     if ((rc = fill_decode_args(c, a, index, scale, rownorm, rows, cols))) return rc;
     if ((rc = check_device(c))) return rc;
     a.W_out = W_out; a.ldw = ldw;
-    hipError_t e = pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
+    hipError_t e = pvq_fast8_decode_usable(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
+                                                 : pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
@@ -416,6 +425,7 @@ extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const vo
     if ((rc = fill_decode_args(c, a, index, scale, rownorm, rows, cols))) return rc;
     if ((rc = check_device(c))) return rc;
     a.x = x; a.batch = batch; a.ldx = ldx; a.y = y; a.ldy = ldy;
-    hipError_t e = pvq_launch_decode_gemv(c, a, (hipStream_t)stream);
+    hipError_t e = pvq_fast8_gemv_usable(c, a) ? pvq_fast8_launch_gemv(c, a, (hipStream_t)stream)
+                                               : pvq_launch_decode_gemv(c, a, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "pvq.h"
+#include "pvq_fast8.h"
 
 struct pvq_ctx {
     int D, K;
@@ -22,6 +23,10 @@ struct pvq_ctx {
     float *edges;   // 2^scale_bits - 1 float32 edges (or nullptr)
     float *sqrtc;   // 2^scale_bits float32 sqrt(centers) (or nullptr)
     size_t tab_n_bytes, tab_u_bytes;
+    // Table-driven decoder (D = 8, one-word indices, tables that fit LDS); fast8_blob == nullptr
+    // when the configuration has none.
+    unsigned char *fast8_blob;
+    pvq_fast8_params fast8;
 };
 
 struct pvq_encode_args {
@@ -53,3 +58,10 @@ struct pvq_decode_args {
 hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
 hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
+
+// D = 8 table-driven kernels (pvq_fast8.hip).  `*_usable` says whether the shape qualifies.
+bool pvq_fast8_decode_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
+bool pvq_fast8_gemv_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
+hipError_t pvq_fast8_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
+hipError_t pvq_fast8_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
+hipError_t pvq_fast8_prepare(void);  // one-time kernel attributes (large dynamic LDS)

@@ -96,3 +96,16 @@ def test_pvq_beta_tables_errors():
         pvq.pvq_beta_tables(8, 16, 3)     # unsupported width
     with pytest.raises(pvq.PvqError):
         pvq.pvq_beta_tables(8, 1, 2)      # a single group has no distribution
+
+
+@pytest.mark.parametrize("K", [1, 2, 5, 9, 13, 16, 17])
+def test_table_driven_decoder_tables_replay_every_index(K):
+    # host logic: the pair/bucket tables the D=8 kernels walk, replayed on the CPU over ALL indices
+    # of P(8,K) against the plain coordinate-by-coordinate decoding
+    assert pvq.pvq_fast_tables_selftest(K) == 0
+
+
+def test_table_driven_decoder_limits():
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_fast_tables_selftest(40)
+    assert e.value.status == -2

@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's sample (0 = auto)")
     ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
+    ap.add_argument("--only", default="", help="comma-separated subset of encode,decode,gemv_b1,gemv_b4,"
+                    "gemv_b16 to run in the timed steps (profiling aid; the JSON line is then partial)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (rows would shard across "
@@ -121,17 +123,26 @@ def main():
     ys = {B: torch.empty((B, ROWS), dtype=torch.float32, device=dev) for B in BATCHES}
 
     names = ["encode", "decode"] + [f"gemv_b{B}" for B in BATCHES]
+    only = set(filter(None, args.only.split(",")))
+    if only - set(names):
+        sys.exit(f"bench.py: --only takes names from {names}")
+    if only:   # every set must hold valid codes before a partial step can run
+        for p in sets:
+            pvq.pvq_encode(ctx, W, out=p)
 
     def step(i, events=None):
         p = sets[i % len(sets)]
         ev = events
         if ev: ev[0].record()
-        pvq.pvq_encode(ctx, W, out=p)
+        if not only or "encode" in only:
+            pvq.pvq_encode(ctx, W, out=p)
         if ev: ev[1].record()
-        pvq.pvq_decode(ctx, p, out=Wout)
+        if not only or "decode" in only:
+            pvq.pvq_decode(ctx, p, out=Wout)
         if ev: ev[2].record()
         for j, B in enumerate(BATCHES):
-            pvq.pvq_decode_gemv(ctx, p, xs[B], out=ys[B])
+            if not only or f"gemv_b{B}" in only:
+                pvq.pvq_decode_gemv(ctx, p, xs[B], out=ys[B])
             if ev: ev[3 + j].record()
 
     for i in range(args.warmup):
@@ -153,6 +164,8 @@ def main():
             ms[n] += ev[j].elapsed_time(ev[j + 1])
     for n in names:
         ms[n] /= args.steps
+        if only and n not in only:
+            ms[n] = float("nan")
 
     weights = ROWS * COLS
     ab = {B: algorithmic_bytes(ROWS, COLS, ctx.index_bits, SCALE_BITS, B) for B in BATCHES}

@@ -31,6 +31,14 @@
 #define PVQ_HD inline
 #endif
 
+// Keeps a 16-byte table entry together: without it the compiler reads the one field a loop tests
+// first and the other three later, which costs a second LDS round trip per stage.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define PVQ_KEEP_TOGETHER(q) asm volatile("" : "+v"((q).x), "+v"((q).y), "+v"((q).z), "+v"((q).w))
+#else
+#define PVQ_KEEP_TOGETHER(q) ((void)0)
+#endif
+
 struct pvq_fast8_params {
     uint32_t blob_bytes;
     uint32_t n_minus_1;   // N(8,K) - 1: stored indices are clamped to it
@@ -62,9 +70,10 @@ struct pvq_fast8_block {
 // `row[j]` = byte offset of the bucket row for group j's current k; r[j] is replaced by the residual
 // inside the block found; the block is returned in b[j].
 // E is the bucket entry type (uint32_t or uint16_t) with THR / DB bits for its first two fields.
+// `blmem` is the memory the block table is read from (the LDS copy of the blob or the blob itself).
 template <int NG, typename E, uint32_t THR, uint32_t DB>
-PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG], uint32_t shift,
-                            uint32_t bl, uint32_t (&r)[NG], pvq_fast8_block (&b)[NG])
+PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const unsigned char *blmem, const uint32_t (&row)[NG],
+                            uint32_t shift, uint32_t bl, uint32_t (&r)[NG], pvq_fast8_block (&b)[NG])
 {
     uint32_t e[NG], addr[NG];
 #pragma unroll
@@ -79,22 +88,24 @@ PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
         addr[j] = bl + (idx << 4);
     }
     bool miss = false;
+    uint4 q[NG];
+#pragma unroll
+    for (int j = 0; j < NG; j++) q[j] = *reinterpret_cast<const uint4 *>(blmem + addr[j]);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(lds + addr[j]);
-        b[j].start = q.x; b[j].end = q.y; b[j].values = q.z; b[j].meta = q.w;
-        miss = miss || r[j] >= q.y;
+        PVQ_KEEP_TOGETHER(q[j]);
+        b[j].start = q[j].x; b[j].end = q[j].y; b[j].values = q[j].z; b[j].meta = q[j].w;
+        miss = miss || r[j] >= q[j].y;
     }
-    // a bucket with several small blocks: move on block by block (rare)
-    while (miss) {
-        miss = false;
+    // a bucket with several small blocks: the few lanes concerned move on block by block
+    if (miss) {
 #pragma unroll
         for (int j = 0; j < NG; j++) {
-            if (r[j] >= b[j].end) {
+            while (r[j] >= b[j].end) {
                 addr[j] += 16;
-                const uint4 q = *reinterpret_cast<const uint4 *>(lds + addr[j]);
-                b[j].start = q.x; b[j].end = q.y; b[j].values = q.z; b[j].meta = q.w;
-                miss = miss || r[j] >= q.y;
+                uint4 n = *reinterpret_cast<const uint4 *>(blmem + addr[j]);
+                PVQ_KEEP_TOGETHER(n);
+                b[j].start = n.x; b[j].end = n.y; b[j].values = n.z; b[j].meta = n.w;
             }
         }
     }
@@ -103,9 +114,12 @@ PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
 }
 
 // NG indices -> per index four bf16 pairs (y0,y1) (y2,y3) (y4,y5) (y6,y7) and n2x4 = 4 * sum y^2.
+// `lds` holds the blob; `bl0mem` is where S0's block table is read from: either `lds` again, or the
+// blob in global memory, which moves one 16-byte lookup per group from LDS to the vector cache (S0's
+// block table is small enough to stay there).
 template <int NG>
-PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const pvq_fast8_params &p, const uint32_t (&c)[NG],
-                             uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
+PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const unsigned char *bl0mem, const pvq_fast8_params &p,
+                             const uint32_t (&c)[NG], uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
 {
     uint32_t r[NG], row[NG];
     pvq_fast8_block b0[NG], b1[NG], b2[NG];
@@ -114,13 +128,13 @@ PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const pvq_fast8_params &p
         r[j] = c[j] < p.n_minus_1 ? c[j] : p.n_minus_1;
         row[j] = p.bk0;
     }
-    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, row, p.s0, p.bl0, r, b0);
+    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, bl0mem, row, p.s0, p.bl0, r, b0);
 #pragma unroll
     for (int j = 0; j < NG; j++) row[j] = b0[j].meta >> 14;
-    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, row, p.s1, p.bl1, r, b1);
+    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, lds, row, p.s1, p.bl1, r, b1);
 #pragma unroll
     for (int j = 0; j < NG; j++) row[j] = b1[j].meta >> 14;
-    pvq_fast8_stage<NG, uint16_t, kFast8S2ThrBits, kFast8S2DbBits>(lds, row, p.s2, p.bl2, r, b2);
+    pvq_fast8_stage<NG, uint16_t, kFast8S2ThrBits, kFast8S2DbBits>(lds, lds, row, p.s2, p.bl2, r, b2);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         const uint2 t = *reinterpret_cast<const uint2 *>(lds + (b2[j].meta >> 14) + (r[j] << 3));

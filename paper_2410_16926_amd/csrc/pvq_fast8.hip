@@ -16,6 +16,7 @@ constexpr int kWave = 64;
 constexpr int kMaxThreads = 1024;
 constexpr int kGroupsPerLane = 4;
 constexpr int kSliceGroups = kWave * kGroupsPerLane;  // groups one wave covers in a row: 256
+constexpr int kLdsBytes = 160 * 1024;                 // the whole LDS of a compute unit
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
@@ -31,13 +32,26 @@ struct fast8_launch {
     int index_bits, scale_bits;
 };
 
+// Copies the blob into LDS.  Behind it: with FUSED (amplitude codes of at most 2 bits) the table
+// gain[q][n2] = (1/sqrt(n2)) * sqrt(center[q]), (K*K+1) floats per code, so that one lookup gives a
+// group's whole gain; otherwise the 2^scale_bits values sqrt(center[q]).
+template <bool FUSED>
 __device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, float *sqrtc_l)
 {
     const int nthreads = blockDim.x;
+    // (issuing several loads per lane before the first LDS write measured slower: all units ask for
+    // the same lines at once)
     for (uint32_t i = threadIdx.x * 16u; i < f.p.blob_bytes; i += nthreads * 16u)
         *reinterpret_cast<uint4 *>(lds + i) = *reinterpret_cast<const uint4 *>(f.blob + i);
-    if (f.scale_bits > 0)
+    if constexpr (FUSED) {
+        const int n = (int)f.p.k2max + 1;
+        for (int i = threadIdx.x; i < (n << f.scale_bits); i += nthreads) {
+            const int q = i / n, n2 = i - q * n;
+            sqrtc_l[i] = reinterpret_cast<const float *>(f.blob + f.p.invs)[n2] * f.sqrtc[q];
+        }
+    } else if (f.scale_bits > 0) {
         for (int i = threadIdx.x; i < (1 << f.scale_bits); i += nthreads) sqrtc_l[i] = f.sqrtc[i];
+    }
     __syncthreads();
 }
 
@@ -80,7 +94,8 @@ __device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &
     if constexpr (CODES) {
         const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
         const uint32_t pos = (uint32_t)g0 * (uint32_t)f.scale_bits;  // 4 codes never straddle a word
-        it.codes = srow[pos >> 5] >> (pos & 31);
+        it.codes = srow[pos >> 5];   // shifted into place in split_indices: no arithmetic on loaded
+                                     // data here, so that fetches can stay in flight
     } else {
         const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(a.scale) + row * a.groups + g0);
         it.amp[0] = v.x; it.amp[1] = v.y; it.amp[2] = v.z; it.amp[3] = v.w;
@@ -88,8 +103,9 @@ __device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &
 }
 
 template <bool CODES, bool B24>
-__device__ inline void split_indices(item_t<CODES> &it)
+__device__ inline void split_indices(const fast8_launch &f, int g0, item_t<CODES> &it)
 {
+    if constexpr (CODES) it.codes >>= ((uint32_t)g0 * (uint32_t)f.scale_bits) & 31u;
     if constexpr (B24) {
         it.c[0] = it.w[0] & 0xFFFFFFu;
         it.c[1] = __builtin_amdgcn_alignbit(it.w[1], it.w[0], 24) & 0xFFFFFFu;
@@ -117,14 +133,18 @@ __device__ inline float amp_factor(const fast8_launch &f, const item_t<CODES> &i
 // Waves are arranged as nsl column slices (256 groups each) x rl row lanes.  Per batch of 4*rl rows
 // every wave handles 4 rows of its slice; lanes keep their 32 activations per vector in registers.
 // Row sums: xor butterfly inside the wave, then the slices' partial sums meet in LDS in slice order.
-template <int NB, bool CODES, bool B24>
+// AMP: 0 = float32 amplitudes, 1 = amplitude codes, 2 = amplitude codes with the fused gain table.
+template <int NB, int AMP, bool B24>
 __global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_decode_args a, int b0,
                                                              int nsl, int rl, int rows_per_block)
 {
-    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr bool CODES = AMP != 0;
+    // static, so that table offsets fold into the LDS instructions' immediate fields
+    __shared__ __align__(16) unsigned char lds[kLdsBytes];
     float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
-    float *part = sqrtc_l + 256;
-    load_tables(lds, f, sqrtc_l);
+    const uint32_t gain_stride = (f.p.k2max + 1) * 4;   // bytes per code in the fused table
+    float *part = sqrtc_l + (AMP == 2 ? ((f.p.k2max + 1) << f.scale_bits) : 256);
+    load_tables<AMP == 2>(lds, f, sqrtc_l);
 
     const int G = (int)a.groups;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
@@ -164,16 +184,23 @@ __global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_
         }
 #pragma unroll
         for (int i = 0; i < RI; i++) {
-            split_indices<CODES, B24>(cur[i]);
+            split_indices<CODES, B24>(f, g0, cur[i]);
             float acc[NB];
 #pragma unroll
             for (int b = 0; b < NB; b++) acc[b] = 0.0f;
             uint32_t pr[kGroupsPerLane][4], n2x4[kGroupsPerLane];
-            pvq_fast8_decode<kGroupsPerLane>(lds, f.p, cur[i].c, pr, n2x4);
+            pvq_fast8_decode<kGroupsPerLane>(lds, f.blob, f.p, cur[i].c, pr, n2x4);
 #pragma unroll
             for (int j = 0; j < kGroupsPerLane; j++) {
-                const float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
-                                   amp_factor<CODES>(f, cur[i], j, sqrtc_l);
+                float gain;
+                if constexpr (AMP == 2) {
+                    const uint32_t q = (cur[i].codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
+                    gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
+                                                            q * gain_stride + n2x4[j]);
+                } else {
+                    gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
+                           amp_factor<CODES>(f, cur[i], j, sqrtc_l);
+                }
 #pragma unroll
                 for (int b = 0; b < NB; b++) {
                     float s = dot2_bf16(pr[j][0], xr[b][4 * j], 0.0f);
@@ -246,9 +273,10 @@ template <int OUT, bool CODES, bool B24>
 __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a,
                                                                int64_t items_per_block)
 {
-    extern __shared__ __align__(16) unsigned char lds[];
+    // static, so that table offsets fold into the LDS instructions' immediate fields
+    __shared__ __align__(16) unsigned char lds[kLdsBytes];
     float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
-    load_tables(lds, f, sqrtc_l);
+    load_tables<false>(lds, f, sqrtc_l);
 
     const uint32_t Q = (uint32_t)(a.groups / kGroupsPerLane);
     const int64_t total = a.rows * (int64_t)Q;
@@ -259,11 +287,11 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
         const int g0 = (int)(it0 - row * Q) * kGroupsPerLane;
         item_t<CODES> it;
         fetch_item<CODES, B24>(f, a, row, g0, true, it);
-        split_indices<CODES, B24>(it);
+        split_indices<CODES, B24>(f, g0, it);
         float srn = 1.0f;
         if constexpr (CODES) srn = sqrtf(a.rownorm[row]);
         uint32_t prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
-        pvq_fast8_decode<kGroupsPerLane>(lds, f.p, it.c, prs, n2x4s);
+        pvq_fast8_decode<kGroupsPerLane>(lds, lds, f.p, it.c, prs, n2x4s);
 #pragma unroll
         for (int j = 0; j < kGroupsPerLane; j++) {
             const uint32_t(&pr)[4] = prs[j];
@@ -287,41 +315,22 @@ fast8_launch make_launch(const pvq_ctx *c)
 
 int g_num_cus = 0;
 
-template <typename Kern>
-hipError_t allow_big_lds(Kern k)
-{
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-}
-
-template <int NB>
-hipError_t prepare_gemv()
-{
-    hipError_t e = allow_big_lds(gemv8_kernel<NB, true, true>);
-    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, true, false>);
-    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, false, true>);
-    if (e == hipSuccess) e = allow_big_lds(gemv8_kernel<NB, false, false>);
-    return e;
-}
-
-template <int OUT>
-hipError_t prepare_decode()
-{
-    hipError_t e = allow_big_lds(decode8_kernel<OUT, true, true>);
-    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, true, false>);
-    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, false, true>);
-    if (e == hipSuccess) e = allow_big_lds(decode8_kernel<OUT, false, false>);
-    return e;
-}
-
 template <int NB>
 hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b0, int nsl, int rl,
                           int rows_per_block, dim3 grid, dim3 block, size_t lds, hipStream_t s)
 {
-    const bool codes = f.scale_bits > 0, b24 = f.index_bits == 24;
-    if (codes && b24) hipLaunchKernelGGL((gemv8_kernel<NB, true, true>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
-    else if (codes) hipLaunchKernelGGL((gemv8_kernel<NB, true, false>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
-    else if (b24) hipLaunchKernelGGL((gemv8_kernel<NB, false, true>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
-    else hipLaunchKernelGGL((gemv8_kernel<NB, false, false>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block);
+    const bool b24 = f.index_bits == 24;
+    // the fused gain table must fit behind the blob together with the partial-sum buffer
+    const size_t fused_bytes = ((size_t)(f.p.k2max + 1) << f.scale_bits) * 4;
+    const bool fused = f.scale_bits > 0 && f.scale_bits <= 2 &&
+                       f.p.blob_bytes + fused_bytes + 64 * 4 * sizeof(float) <= (size_t)kLdsBytes;
+    const int amp = f.scale_bits == 0 ? 0 : (fused ? 2 : 1);
+#define PVQ_GEMV_CASE(AMP, B24) \
+    hipLaunchKernelGGL((gemv8_kernel<NB, AMP, B24>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block)
+    if (amp == 2) { if (b24) PVQ_GEMV_CASE(2, true); else PVQ_GEMV_CASE(2, false); }
+    else if (amp == 1) { if (b24) PVQ_GEMV_CASE(1, true); else PVQ_GEMV_CASE(1, false); }
+    else { if (b24) PVQ_GEMV_CASE(0, true); else PVQ_GEMV_CASE(0, false); }
+#undef PVQ_GEMV_CASE
     return hipGetLastError();
 }
 
@@ -342,14 +351,8 @@ hipError_t launch_decode_out(const fast8_launch &f, const pvq_decode_args &a, in
 hipError_t pvq_fast8_prepare(void)
 {
     static hipError_t once = [] {
-        hipError_t e = prepare_gemv<1>();
-        if (e == hipSuccess) e = prepare_gemv<2>();
-        if (e == hipSuccess) e = prepare_gemv<4>();
-        if (e == hipSuccess) e = prepare_decode<PVQ_F32>();
-        if (e == hipSuccess) e = prepare_decode<PVQ_F16>();
-        if (e == hipSuccess) e = prepare_decode<PVQ_BF16>();
         int dev = 0;
-        if (e == hipSuccess) e = hipGetDevice(&dev);
+        hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&g_num_cus, hipDeviceAttributeMultiprocessorCount, dev);
         return e;
     }();
@@ -371,7 +374,7 @@ bool pvq_fast8_gemv_usable(const pvq_ctx *c, const pvq_decode_args &a)
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
 {
     const fast8_launch f = make_launch(c);
-    const size_t lds = f.p.blob_bytes + 256 * sizeof(float);
+    const size_t lds = 0;  // the kernels own the whole LDS statically
     const int64_t total = a.rows * (a.groups / kGroupsPerLane);
     // every block pays the table copy, so blocks get at least a few thousand items each
     const int64_t want_blocks = std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, (total + 4095) / 4096);
@@ -391,7 +394,7 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
     const int nsl = (int)((a.groups + kSliceGroups - 1) / kSliceGroups);
     const int rl = std::max(1, (kMaxThreads / kWave) / nsl);
     const int RB = 4 * rl;
-    const size_t lds = f.p.blob_bytes + 256 * sizeof(float) + (size_t)RB * nsl * 4 * sizeof(float);
+    const size_t lds = 0;  // the kernels own the whole LDS statically
     const int64_t batches = (a.rows + RB - 1) / RB;
     const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
     const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);

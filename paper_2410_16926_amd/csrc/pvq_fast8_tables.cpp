@@ -240,7 +240,7 @@ extern "C" int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, u
     uint64_t bad = 0;
     for (uint64_t c = first; c < first + count && c < total; c++) {
         uint32_t cc[1] = {(uint32_t)c}, pr[1][4], nn[1];
-        pvq_fast8_decode<1>(blob.data(), p, cc, pr, nn);
+        pvq_fast8_decode<1>(blob.data(), blob.data(), p, cc, pr, nn);
         const uint32_t *pairs = pr[0];
         const uint32_t n2x4 = nn[0];
         // plain walk

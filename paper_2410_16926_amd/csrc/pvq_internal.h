@@ -64,4 +64,4 @@ bool pvq_fast8_decode_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
 bool pvq_fast8_gemv_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
-hipError_t pvq_fast8_prepare(void);  // one-time kernel attributes (large dynamic LDS)
+hipError_t pvq_fast8_prepare(void);  // one-time device queries

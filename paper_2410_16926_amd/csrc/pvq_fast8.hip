@@ -2,8 +2,7 @@
 // decode fused into y = W_hat x.
 //
 // One workgroup per compute unit keeps the whole table blob (up to 156 KiB) in LDS and walks many
-// rows, so the copy is paid once per launch and unit.  A lane owns four consecutive groups of a row:
-// their 24-bit indices are three aligned dwords, their outputs 64 contiguous bytes.
+// rows, so the copy is paid once per launch and unit.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -15,10 +14,11 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kMaxThreads = 1024;
 constexpr int kGroupsPerLane = 4;
-constexpr int kSliceGroups = kWave * kGroupsPerLane;  // groups one wave covers in a row: 256
+constexpr int kTileGroups = kWave * kGroupsPerLane;   // groups one wave covers in a row: 256
 constexpr int kLdsBytes = 160 * 1024;                 // the whole LDS of a compute unit
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 
 __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
 {
@@ -55,9 +55,78 @@ __device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, fl
     __syncthreads();
 }
 
-// What a lane fetches for its four groups of one row: index bits and amplitude information.
-template <bool CODES>
+// Work mapping.  A wave works on a tile of 256 consecutive groups of one row; lane l owns the groups
+// tile*256 + 64*j + l, j = 0..3.  So for every j the 64 lanes touch 64 consecutive groups: the index
+// reads of one j cover 192 contiguous bytes and, in the decode kernel, the stores of one j cover one
+// contiguous KiB (a lane that kept four neighbouring groups would write 16 bytes out of every 64 per
+// store instruction, which measured 2.5x slower).
+
+// What a lane fetches for its four groups of one row.  Raw words only: no arithmetic touches loaded
+// data until the item is consumed, so that the loads stay in flight behind the previous item's work.
 struct item_t {
+    uint32_t w[kGroupsPerLane];   // index: the dword at byte 3g-1 of the row (24-bit path) or the index itself
+    uint32_t a[kGroupsPerLane];   // amplitude: the code word holding group g's code, or the float's bits
+};
+
+template <bool CODES, bool B24>
+__device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int gbase,
+                                  bool live, item_t &it)
+{
+    const int G = (int)a.groups;
+    const uint32_t *irow = a.index + row * a.index_row_words;
+#pragma unroll
+    for (int j = 0; j < kGroupsPerLane; j++) {
+        const int g = gbase + kWave * j;
+        it.w[j] = 0;
+        it.a[j] = 0;
+        if (live && g < G) {
+            if constexpr (B24) {
+                // the 3 bytes of group g start at byte 3g; one dword load from byte 3g-1 (3g for g = 0)
+                // holds them and stays inside the row
+                const unsigned char *p = reinterpret_cast<const unsigned char *>(irow) + 3 * g - (g > 0 ? 1 : 0);
+                uint32_t v;
+                __builtin_memcpy(&v, p, 4);
+                it.w[j] = v;
+            } else {
+                const uint32_t b = (uint32_t)f.index_bits;
+                const uint32_t pos = (uint32_t)g * b, w0 = pos >> 5, sh = pos & 31;
+                uint64_t v = irow[w0];
+                if (sh + b > 32) v |= (uint64_t)irow[w0 + 1] << 32;
+                it.w[j] = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
+            }
+            if constexpr (CODES) {
+                const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
+                it.a[j] = srow[((uint32_t)g * (uint32_t)f.scale_bits) >> 5];
+            } else {
+                it.a[j] = __float_as_uint(reinterpret_cast<const float *>(a.scale)[row * a.groups + g]);
+            }
+        }
+    }
+}
+
+// the four indices of an item
+template <bool B24>
+__device__ inline void item_indices(const item_t &it, int gbase, uint32_t (&c)[kGroupsPerLane])
+{
+#pragma unroll
+    for (int j = 0; j < kGroupsPerLane; j++) {
+        if constexpr (B24) c[j] = (gbase + kWave * j > 0) ? it.w[j] >> 8 : it.w[j] & 0xFFFFFFu;
+        else c[j] = it.w[j];
+    }
+}
+
+// amplitude code of group j of an item
+__device__ inline uint32_t item_code(const fast8_launch &f, const item_t &it, int gbase, int j)
+{
+    const uint32_t pos = (uint32_t)(gbase + kWave * j) * (uint32_t)f.scale_bits;
+    return (it.a[j] >> (pos & 31u)) & ((1u << f.scale_bits) - 1u);
+}
+
+// The fused product writes nothing per group, so there a lane takes four NEIGHBOURING groups
+// (4*lane .. 4*lane+3 of its wave's 256): their 24-bit indices are three aligned dwords and their
+// amplitude codes sit in one word, two loads per row instead of eight.
+template <bool CODES>
+struct quad_item_t {
     uint32_t w[3];                       // 24-bit path: three dwords; generic path: unused
     uint32_t c[kGroupsPerLane];          // generic path: the four indices
     float amp[CODES ? 1 : kGroupsPerLane];
@@ -65,8 +134,8 @@ struct item_t {
 };
 
 template <bool CODES, bool B24>
-__device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int g0,
-                                  bool live, item_t<CODES> &it)
+__device__ inline void fetch_quad(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int g0,
+                                  bool live, quad_item_t<CODES> &it)
 {
     if (!live) {
         it.w[0] = it.w[1] = it.w[2] = 0;
@@ -94,7 +163,7 @@ __device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &
     if constexpr (CODES) {
         const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
         const uint32_t pos = (uint32_t)g0 * (uint32_t)f.scale_bits;  // 4 codes never straddle a word
-        it.codes = srow[pos >> 5];   // shifted into place in split_indices: no arithmetic on loaded
+        it.codes = srow[pos >> 5];   // shifted into place in split_quad: no arithmetic on loaded
                                      // data here, so that fetches can stay in flight
     } else {
         const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(a.scale) + row * a.groups + g0);
@@ -103,7 +172,7 @@ __device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &
 }
 
 template <bool CODES, bool B24>
-__device__ inline void split_indices(const fast8_launch &f, int g0, item_t<CODES> &it)
+__device__ inline void split_quad(const fast8_launch &f, int g0, quad_item_t<CODES> &it)
 {
     if constexpr (CODES) it.codes >>= ((uint32_t)g0 * (uint32_t)f.scale_bits) & 31u;
     if constexpr (B24) {
@@ -116,7 +185,7 @@ __device__ inline void split_indices(const fast8_launch &f, int g0, item_t<CODES
 
 // amplitude factor of group j without the row normaliser: sqrt(center[q]) or the stored amplitude
 template <bool CODES>
-__device__ inline float amp_factor(const fast8_launch &f, const item_t<CODES> &it, int j, const float *sqrtc_l)
+__device__ inline float amp_factor(const fast8_launch &f, const quad_item_t<CODES> &it, int j, const float *sqrtc_l)
 {
     if constexpr (CODES) {
         const uint32_t q = (it.codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
@@ -149,7 +218,7 @@ __global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_
     const int G = (int)a.groups;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int slice = wave % nsl, rowlane = wave / nsl;
-    const int g0 = slice * kSliceGroups + lane * kGroupsPerLane;
+    const int g0 = slice * kTileGroups + lane * kGroupsPerLane;
     const bool in_row = g0 < G;
     constexpr int RI = 4;              // rows per wave per batch
     const int RB = RI * rl;            // rows per batch
@@ -169,22 +238,22 @@ __global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
 
-    item_t<CODES> cur[RI], nxt[RI];
+    quad_item_t<CODES> cur[RI], nxt[RI];
 #pragma unroll
     for (int i = 0; i < RI; i++) {
         const int64_t row = r_begin + i * rl + rowlane;
-        fetch_item<CODES, B24>(f, a, row, g0, in_row && row < r_end, cur[i]);
+        fetch_quad<CODES, B24>(f, a, row, g0, in_row && row < r_end, cur[i]);
     }
 
     for (int64_t batch = r_begin; batch < r_end; batch += RB) {
 #pragma unroll
         for (int i = 0; i < RI; i++) {
             const int64_t row = batch + RB + i * rl + rowlane;
-            fetch_item<CODES, B24>(f, a, row, g0, in_row && row < r_end, nxt[i]);
+            fetch_quad<CODES, B24>(f, a, row, g0, in_row && row < r_end, nxt[i]);
         }
 #pragma unroll
         for (int i = 0; i < RI; i++) {
-            split_indices<CODES, B24>(f, g0, cur[i]);
+            split_quad<CODES, B24>(f, g0, cur[i]);
             float acc[NB];
 #pragma unroll
             for (int b = 0; b < NB; b++) acc[b] = 0.0f;
@@ -260,15 +329,17 @@ __device__ inline void store_group(void *W_out, int64_t elem, const uint32_t (&p
                 q[j] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v[2 * j]) |
                        ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v[2 * j + 1]) << 16);
             } else {
-                const uint32_t u0 = __float_as_uint(v[2 * j]), u1 = __float_as_uint(v[2 * j + 1]);
-                q[j] = ((u0 + 0x7FFFu + ((u0 >> 16) & 1u)) >> 16) | ((u1 + 0x7FFFu + ((u1 >> 16) & 1u)) & 0xFFFF0000u);
+                // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
+                const f32x2_t pair = {v[2 * j], v[2 * j + 1]};
+                q[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t));
             }
         }
         *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(W_out) + elem) = make_uint4(q[0], q[1], q[2], q[3]);
     }
 }
 
-// Items = (row, quad of four groups); a block takes a contiguous range of items and its lanes stride it.
+// Wave items = (row, tile of 256 groups).  A block takes a contiguous range of them; its waves
+// stride the range and fetch one item ahead.
 template <int OUT, bool CODES, bool B24>
 __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a,
                                                                int64_t items_per_block)
@@ -278,30 +349,49 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
     float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
     load_tables<false>(lds, f, sqrtc_l);
 
-    const uint32_t Q = (uint32_t)(a.groups / kGroupsPerLane);
-    const int64_t total = a.rows * (int64_t)Q;
+    const int G = (int)a.groups;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x / kWave;
+    const uint32_t T = (uint32_t)((a.groups + kTileGroups - 1) / kTileGroups);   // tiles per row
+    const int64_t total = a.rows * (int64_t)T;
     const int64_t i_begin = (int64_t)blockIdx.x * items_per_block;
     const int64_t i_end = std::min(total, i_begin + items_per_block);
-    for (int64_t it0 = i_begin + threadIdx.x; it0 < i_end; it0 += blockDim.x) {
-        const int64_t row = it0 / Q;
-        const int g0 = (int)(it0 - row * Q) * kGroupsPerLane;
-        item_t<CODES> it;
-        fetch_item<CODES, B24>(f, a, row, g0, true, it);
-        split_indices<CODES, B24>(f, g0, it);
-        float srn = 1.0f;
-        if constexpr (CODES) srn = sqrtf(a.rownorm[row]);
-        uint32_t prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
-        pvq_fast8_decode<kGroupsPerLane>(lds, lds, f.p, it.c, prs, n2x4s);
+    // (row, tile) of this wave's item, advanced by nwaves items per step without dividing again
+    const uint32_t step_rows = nwaves / T, step_tiles = nwaves % T;
+    int64_t item = i_begin + wave;
+    int64_t row = item / T;
+    uint32_t tile = (uint32_t)(item - row * T);
+
+    item_t cur, nxt;
+    float cur_rn = 1.0f, nxt_rn = 1.0f;
+    bool live = item < i_end;     // uniform in the wave
+    fetch_item<CODES, B24>(f, a, row, (int)tile * kTileGroups + lane, live, cur);
+    if constexpr (CODES) cur_rn = live ? a.rownorm[row] : 1.0f;
+    while (live) {
+        int64_t nrow = row + step_rows;
+        uint32_t ntile = tile + step_tiles;
+        if (ntile >= T) { ntile -= T; nrow += 1; }
+        const bool nlive = item + nwaves < i_end;
+        fetch_item<CODES, B24>(f, a, nrow, (int)ntile * kTileGroups + lane, nlive, nxt);
+        if constexpr (CODES) nxt_rn = nlive ? a.rownorm[nrow] : 1.0f;
+
+        const int gbase = (int)tile * kTileGroups + lane;
+        const float srn = CODES ? sqrtf(cur_rn) : 1.0f;
+        uint32_t c[kGroupsPerLane], prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
+        item_indices<B24>(cur, gbase, c);
+        pvq_fast8_decode<kGroupsPerLane>(lds, lds, f.p, c, prs, n2x4s);
 #pragma unroll
         for (int j = 0; j < kGroupsPerLane; j++) {
-            const uint32_t(&pr)[4] = prs[j];
-            const uint32_t n2x4 = n2x4s[j];
-            // amp / sqrt(n2): the amplitude first (as in sqrt(center) * sqrt(row normaliser)), then the
-            // tabulated 1/sqrt(n2)
-            const float amp = CODES ? amp_factor<CODES>(f, it, j, sqrtc_l) * srn : amp_factor<CODES>(f, it, j, sqrtc_l);
-            const float gain = amp * *reinterpret_cast<const float *>(lds + f.p.invs + n2x4);
-            store_group<OUT>(a.W_out, row * a.ldw + (int64_t)(g0 + j) * 8, pr, gain);
+            const int g = gbase + kWave * j;
+            if (g < G) {
+                // amp / sqrt(n2): the amplitude first (sqrt(center) * sqrt(row normaliser), or the stored
+                // float), then the tabulated 1/sqrt(n2)
+                const float amp = CODES ? sqrtc_l[item_code(f, cur, gbase, j)] * srn : __uint_as_float(cur.a[j]);
+                const float gain = amp * *reinterpret_cast<const float *>(lds + f.p.invs + n2x4s[j]);
+                store_group<OUT>(a.W_out, row * a.ldw + (int64_t)g * 8, prs[j], gain);
+            }
         }
+        cur = nxt; cur_rn = nxt_rn; row = nrow; tile = ntile; live = nlive; item += nwaves;
     }
 }
 
@@ -361,23 +451,25 @@ hipError_t pvq_fast8_prepare(void)
 
 bool pvq_fast8_decode_usable(const pvq_ctx *c, const pvq_decode_args &a)
 {
-    return c->fast8_blob != nullptr && a.groups % kGroupsPerLane == 0;
+    (void)a;
+    return c->fast8_blob != nullptr;
 }
 
 bool pvq_fast8_gemv_usable(const pvq_ctx *c, const pvq_decode_args &a)
 {
     // a row must fit the waves of one workgroup: at most 16 slices of 256 groups
+    // lanes take whole quads of groups
     return c->fast8_blob != nullptr && a.groups % kGroupsPerLane == 0 &&
-           (a.groups + kSliceGroups - 1) / kSliceGroups <= kMaxThreads / kWave;
+           (a.groups + kTileGroups - 1) / kTileGroups <= kMaxThreads / kWave;
 }
 
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
 {
     const fast8_launch f = make_launch(c);
     const size_t lds = 0;  // the kernels own the whole LDS statically
-    const int64_t total = a.rows * (a.groups / kGroupsPerLane);
-    // every block pays the table copy, so blocks get at least a few thousand items each
-    const int64_t want_blocks = std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, (total + 4095) / 4096);
+    const int64_t total = a.rows * ((a.groups + kTileGroups - 1) / kTileGroups);   // wave items
+    // every block pays the table copy, so blocks get at least 64 wave items (16K groups) each
+    const int64_t want_blocks = std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, (total + 63) / 64);
     const int64_t nblocks = std::max<int64_t>(1, want_blocks);
     const int64_t ipb = (total + nblocks - 1) / nblocks;
     const dim3 grid((unsigned)nblocks), block(kMaxThreads);
@@ -391,7 +483,7 @@ hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, i
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
 {
     const fast8_launch f = make_launch(c);
-    const int nsl = (int)((a.groups + kSliceGroups - 1) / kSliceGroups);
+    const int nsl = (int)((a.groups + kTileGroups - 1) / kTileGroups);
     const int rl = std::max(1, (kMaxThreads / kWave) / nsl);
     const int RB = 4 * rl;
     const size_t lds = 0;  // the kernels own the whole LDS statically

@@ -1,0 +1,259 @@
+// Encoder specialised for D = 8 with 24-bit indices (the 3 bits/weight setting).
+//
+// Same arithmetic, in the same order, as the generic encoder (pvq_kernels.hip) — results are bit for
+// bit the same — but organised for throughput:
+//   * one lane per group, one workgroup of up to 1024 lanes per row tile, so a row of 8192 weights is
+//     one pass;
+//   * the pulse-count repair (Sec. 2.5) is branch-free: every coordinate's place in the order of
+//     deviations is counted with 28 comparisons, and the |sum - K| first places are adjusted.  This
+//     equals the one-at-a-time repair because no coordinate is ever adjusted twice (for finite
+//     input the |sum - K| largest deviations are all positive, an adjusted coordinate drops below
+//     -1/2);
+//   * the index (App. B.2) is a sum of seven table entries, one per coordinate, from a table of
+//     per-coordinate offsets indexed by (coordinate, pulses left, magnitude, sign);
+//   * four neighbouring lanes assemble their 24-bit indices into three dwords with DPP moves and write
+//     them straight to global memory; amplitude codes are OR-reduced across lanes the same way;
+//   * the row normaliser's pairwise sum is a wave butterfly followed by a small tree over wave sums
+//     (adding +0.0 for absent groups is exact, so padding a row to a power of two does not change
+//     the pair-level sum).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "pvq_internal.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int D = 8;
+
+struct enc8_launch {
+    const uint32_t *offs;   // [7][K+1][K+1][2]
+    const float *edges;     // 2^scale_bits entries, last = +inf (or nullptr)
+    int K, scale_bits;
+};
+
+// Position of every coordinate in the order of keys (largest first, lower coordinate first on
+// ties): wins[i] = number of coordinates that i comes before.
+__device__ inline void count_wins(const float (&key)[D], int (&wins)[D])
+{
+#pragma unroll
+    for (int i = 0; i < D; i++) wins[i] = 0;
+#pragma unroll
+    for (int i = 0; i < D; i++)
+#pragma unroll
+        for (int j = i + 1; j < D; j++) {
+            const bool first = key[i] >= key[j];
+            wins[i] += first ? 1 : 0;
+            wins[j] += first ? 0 : 1;
+        }
+}
+
+// Sum over adjacent pairs, level by level (fixed order, float32).
+__device__ inline float tree8(float (&v)[D])
+{
+#pragma unroll
+    for (int s = 1; s < D; s *= 2)
+#pragma unroll
+        for (int i = 0; i < D; i += 2 * s) v[i] = v[i] + v[i + s];
+    return v[0];
+}
+
+template <typename TIn>
+__device__ inline void load8(const TIn *__restrict__ p, float (&w)[D])
+{
+    if constexpr (sizeof(TIn) == 4) {
+        const float4 q0 = *reinterpret_cast<const float4 *>(p), q1 = *reinterpret_cast<const float4 *>(p + 4);
+        w[0] = q0.x; w[1] = q0.y; w[2] = q0.z; w[3] = q0.w; w[4] = q1.x; w[5] = q1.y; w[6] = q1.z; w[7] = q1.w;
+    } else {
+        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            w[2 * j] = __uint_as_float(u[j] << 16);
+            w[2 * j + 1] = __uint_as_float(u[j] & 0xFFFF0000u);
+        }
+    }
+}
+
+// One group: returns its 24-bit index, the sum of squares, and the signed point in y.
+__device__ inline uint32_t encode_group8(const float (&w)[D], int K, const uint32_t *offs, float &ss_out,
+                                         int (&y)[D])
+{
+    float a[D], tmp[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) { a[i] = fabsf(w[i]); tmp[i] = a[i]; }
+    const float l1 = tree8(tmp);
+#pragma unroll
+    for (int i = 0; i < D; i++) tmp[i] = w[i] * w[i];
+    ss_out = tree8(tmp);
+
+    const float g = (float)K / l1;
+    const bool degenerate = !(l1 > 0.0f) || !(fabsf(g) < INFINITY);
+    // from here on every t is finite and within [0, K(1+eps)] unless `degenerate`
+    float t[D], yf[D];
+    float S = 0.0f;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        t[i] = a[i] * g;
+        yf[i] = rintf(t[i]);
+        S += yf[i];                       // small integers: exact in any order
+    }
+    const float m = (float)K - S;         // > 0: pulses to add, < 0: pulses to take away
+    float key[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        const float d = t[i] - yf[i];     // how far below its projected value
+        key[i] = m < 0.0f ? -d : d;
+    }
+    int wins[D];
+    count_wins(key, wins);
+    const int need = (int)fabsf(m);       // coordinates to adjust; they hold the places 0 .. need-1
+    const float unit = m < 0.0f ? -1.0f : 1.0f;
+    uint32_t c = 0;
+    int k = K;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        const bool adjust = wins[i] + need >= D;      // place = D-1-wins < need
+        int mag = (int)(yf[i] + (adjust ? unit : 0.0f));
+        const int neg = w[i] < 0.0f ? 1 : 0;
+        if (degenerate) mag = (i == D - 1) ? K : 0;
+        // table bounds and a point on the pyramid whatever the input was: the last coordinate takes
+        // what is left (for finite input that is what it holds anyway)
+        mag = (i == D - 1) ? k : max(0, min(mag, k));
+        y[i] = (neg && !degenerate) ? -mag : mag;
+        if (i < D - 1) {
+            // offs[i][k][mag][neg]: what coordinate i adds to the index with k pulses left (App. B.2)
+            c += offs[(((i * (K + 1) + k) * (K + 1)) + mag) * 2 + (degenerate ? 0 : neg)];
+            k -= mag;
+        } else {
+            c += (neg && !degenerate && k > 0) ? 1u : 0u;
+        }
+    }
+    return c;
+}
+
+// TIn: float or uint16_t (bf16 bits).  A block of kBlock lanes takes whole rows, kBlock groups at a
+// time; several blocks share a compute unit, so one block's loads and barriers hide behind the
+// others' arithmetic.
+constexpr int kBlock = 256;
+constexpr int kMaxGroups = 4096;   // groups per row this kernel takes (their sums of squares sit in LDS)
+
+template <typename TIn, bool CODES>
+__global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_encode_args a)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int K = f.K, sb = f.scale_bits;
+    const int ntab = 7 * (K + 1) * (K + 1) * 2;
+    uint32_t *offs = smem;
+    float *edges = reinterpret_cast<float *>(smem + ntab);       // 256 floats
+    float *wsum = edges + 256;                                    // 64 wave sums of the row (zero padded)
+    float *ss_row = wsum + 64;                                    // the row's sums of squares (CODES)
+    for (int i = threadIdx.x; i < ntab; i += kBlock) offs[i] = f.offs[i];
+    if constexpr (CODES)
+        for (int i = threadIdx.x; i < (1 << sb); i += kBlock) edges[i] = f.edges[i];
+    if (threadIdx.x < 64) wsum[threadIdx.x] = 0.0f;
+    __syncthreads();
+
+    const int G = (int)a.groups;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int quad_pos = lane & 3;
+    const int tiles = (G + kBlock - 1) / kBlock;
+
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        const TIn *wrow = reinterpret_cast<const TIn *>(a.W) + row * a.ldw;
+        uint32_t *irow = a.index_out + row * a.index_row_words;
+        for (int tix = 0; tix < tiles; tix++) {
+            const int g = tix * kBlock + (int)threadIdx.x;
+            uint32_t c = 0;
+            float ss = 0.0f;
+            if (g < G) {
+                float w[D];
+                int y[D];
+                load8<TIn>(wrow + (int64_t)g * D, w);
+                c = encode_group8(w, K, offs, ss, y);
+                if (a.pulses_out) {
+                    uint32_t lo = 0, hi = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        lo |= ((uint32_t)y[j] & 0xFFu) << (8 * j);
+                        hi |= ((uint32_t)y[4 + j] & 0xFFu) << (8 * j);
+                    }
+                    *reinterpret_cast<uint2 *>(a.pulses_out + row * a.cols + (int64_t)g * D) = make_uint2(lo, hi);
+                }
+                if constexpr (CODES) ss_row[g] = ss;
+                else reinterpret_cast<float *>(a.scale_out)[row * G + g] = sqrtf(ss);
+            }
+            // four neighbouring 24-bit indices -> three dwords: lane j of a quad (j < 3) builds dword j
+            // from its own index and the next lane's
+            const uint32_t cn = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xF9, 0xF, 0xF, false);
+            const uint32_t lo = c | (cn << 24), hi = cn >> 8;
+            const uint32_t word = __builtin_amdgcn_alignbit(hi, lo, 8 * quad_pos);
+            if (quad_pos < 3 && g < G) irow[3 * (g >> 2) + quad_pos] = word;
+            if constexpr (CODES) {
+                // pairwise sum over the wave's 64 groups (absent groups add +0.0, which is exact)
+                float v = ss;
+#pragma unroll
+                for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+                if (lane == 0) wsum[tix * (kBlock / kWave) + wave] = v;
+            }
+        }
+        if constexpr (CODES) {
+            __syncthreads();
+            // the pairwise tree continues over the (at most 64, zero padded) wave sums
+            float rowss = wsum[lane];
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) rowss += __shfl_xor(rowss, off, kWave);
+            if (threadIdx.x == 0) a.rownorm_out[row] = rowss;
+            // Sec. 3.3 Step 5: code = number of quantile edges <= u, u = ss_g / rowss (bisection over
+            // the ascending edges), packed 32/sb lanes to a dword by an OR butterfly
+            uint32_t *srow = reinterpret_cast<uint32_t *>(a.scale_out) + row * a.scale_row_words;
+            const int nedges = (1 << sb) - 1;
+            const int lanes_per_word = 32 / sb;
+            for (int tix = 0; tix < tiles; tix++) {
+                const int g = tix * kBlock + (int)threadIdx.x;
+                uint32_t v = 0;
+                if (g < G) {
+                    const float u = ss_row[g] / rowss;
+                    int lo = 0, hi = nedges;
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (edges[mid] <= u) lo = mid + 1; else hi = mid;
+                    }
+                    v = (uint32_t)lo << ((lane * sb) & 31);
+                }
+                for (int off = 1; off < lanes_per_word; off <<= 1) v |= __shfl_xor(v, off, kWave);
+                if ((lane & (lanes_per_word - 1)) == 0 && g < G) srow[((uint32_t)g * (uint32_t)sb) >> 5] = v;
+            }
+            __syncthreads();   // ss_row and wsum are rewritten by the next row
+        }
+    }
+}
+
+}  // namespace
+
+bool pvq_encode8_usable(const pvq_ctx *c, const pvq_encode_args &a)
+{
+    // quads of lanes write whole dword triples; a row's sums of squares must fit the LDS buffer
+    return c->enc8_offs != nullptr && a.groups % 4 == 0 && a.groups <= kMaxGroups;
+}
+
+hipError_t pvq_encode8_launch(const pvq_ctx *c, const pvq_encode_args &a, int dtype, hipStream_t s)
+{
+    enc8_launch f;
+    f.offs = c->enc8_offs; f.edges = c->edges; f.K = c->K; f.scale_bits = c->scale_bits;
+    const dim3 block(kBlock);
+    const bool with_codes = c->scale_bits > 0;
+    const size_t lds = ((size_t)7 * (c->K + 1) * (c->K + 1) * 2 + 256 + 64 + (with_codes ? (size_t)a.groups : 0)) * 4;
+    // rows are strided over the blocks; enough blocks to fill every unit several times over
+    const unsigned grid = (unsigned)std::min<int64_t>(a.rows, 8192);
+    const bool codes = c->scale_bits > 0;
+    if (dtype == PVQ_F32) {
+        if (codes) hipLaunchKernelGGL((encode8_kernel<float, true>), dim3(grid), dim3(block), lds, s, f, a);
+        else hipLaunchKernelGGL((encode8_kernel<float, false>), dim3(grid), dim3(block), lds, s, f, a);
+    } else {
+        if (codes) hipLaunchKernelGGL((encode8_kernel<uint16_t, true>), dim3(grid), dim3(block), lds, s, f, a);
+        else hipLaunchKernelGGL((encode8_kernel<uint16_t, false>), dim3(grid), dim3(block), lds, s, f, a);
+    }
+    return hipGetLastError();
+}

@@ -247,7 +247,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
-    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = nullptr;
+    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = nullptr; c->enc8_offs = nullptr;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -271,6 +271,24 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
             if (e == hipSuccess) e = hipMemcpy(c->fast8_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
         }
     }
+    if (e == hipSuccess && D == 8 && bits == 24) {
+        // What coordinate i (7-i dimensions after it) adds to the index when k pulses are left and it
+        // takes magnitude m with the given sign (App. B.2):
+        //   N(7-i,k) [m>0] + 2 sum_{j=1}^{m-1} N(7-i,k-j) + [negative] N(7-i,k-m)
+        const int K1 = K + 1;
+        std::vector<uint32_t> offs((size_t)7 * K1 * K1 * 2, 0u);
+        for (int i = 0; i < 7; i++)
+            for (int k = 0; k <= K; k++)
+                for (int m = 1; m <= k; m++) {
+                    uint64_t v = t.at(7 - i, k).limb[0];
+                    for (int j = 1; j < m; j++) v += 2 * t.at(7 - i, k - j).limb[0];
+                    const size_t at = (((size_t)i * K1 + k) * K1 + m) * 2;
+                    offs[at] = (uint32_t)v;
+                    offs[at + 1] = (uint32_t)(v + t.at(7 - i, k - m).limb[0]);
+                }
+        e = hipMalloc((void **)&c->enc8_offs, offs.size() * 4);
+        if (e == hipSuccess) e = hipMemcpy(c->enc8_offs, offs.data(), offs.size() * 4, hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         pvq_ctx_destroy(c);
         return hip_fail(e);
@@ -283,7 +301,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[5] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob};
+    void *ptrs[6] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob, c->enc8_offs};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);
@@ -353,7 +371,7 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
     if (c->scale_bits > 0 && !rownorm_out) return PVQ_E_INVALID_ARG;
     size_t esz = dtype == PVQ_F32 ? 4 : 2;
     if (!aligned(W, 16) || (ldw * esz) % 16 || !aligned(index_out, 4) || !aligned(scale_out, 4) ||
-        (rownorm_out && !aligned(rownorm_out, 4)))
+        (rownorm_out && !aligned(rownorm_out, 4)) || (pulses_out && !aligned(pulses_out, 16)))
         return PVQ_E_ALIGNMENT;
     if ((rc = check_device(c))) return rc;
 
@@ -363,7 +381,8 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
     a.pulses_out = pulses_out;
     a.index_row_words = stream_words(a.groups, c->index_bits);
     a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
-    hipError_t e = pvq_launch_encode(c, a, dtype, (hipStream_t)stream);
+    hipError_t e = pvq_encode8_usable(c, a) ? pvq_encode8_launch(c, a, dtype, (hipStream_t)stream)
+                                            : pvq_launch_encode(c, a, dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 

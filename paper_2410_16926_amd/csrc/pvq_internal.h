@@ -27,6 +27,9 @@ struct pvq_ctx {
     // when the configuration has none.
     unsigned char *fast8_blob;
     pvq_fast8_params fast8;
+    // Per-coordinate index offsets for the D = 8 / 24-bit encoder: [7][K+1][K+1][2] words
+    // (coordinate, pulses left, magnitude, sign); nullptr when the configuration has none.
+    uint32_t *enc8_offs;
 };
 
 struct pvq_encode_args {
@@ -58,6 +61,10 @@ struct pvq_decode_args {
 hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
 hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
+
+// D = 8 / 24-bit encoder (pvq_encode8.hip)
+bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);
+hipError_t pvq_encode8_launch(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
 
 // D = 8 table-driven kernels (pvq_fast8.hip).  `*_usable` says whether the shape qualifies.
 bool pvq_fast8_decode_usable(const pvq_ctx *ctx, const pvq_decode_args &a);

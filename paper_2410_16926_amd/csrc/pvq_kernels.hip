@@ -56,7 +56,6 @@ __device__ inline typename wide<W>::type load_field(const uint32_t *__restrict__
 template <int W>
 __device__ inline void stage_field(uint32_t *stage, uint32_t pos, int bits, typename wide<W>::type v)
 {
-    using T = typename wide<W>::type;
     const uint32_t w0 = pos >> 5, sh = pos & 31;
     const int span = (int)sh + bits;
     atomicOr(&stage[w0], (uint32_t)v << sh);

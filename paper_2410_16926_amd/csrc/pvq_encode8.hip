@@ -34,19 +34,23 @@ struct enc8_launch {
 };
 
 // Position of every coordinate in the order of keys (largest first, lower coordinate first on
-// ties): wins[i] = number of coordinates that i comes before.
+// ties): wins[i] = number of coordinates that i comes before.  One comparison per pair feeds two
+// counters through its carry: i's wins over later coordinates and j's losses against earlier ones.
 __device__ inline void count_wins(const float (&key)[D], int (&wins)[D])
 {
+    int lose[D];
 #pragma unroll
-    for (int i = 0; i < D; i++) wins[i] = 0;
+    for (int i = 0; i < D; i++) { wins[i] = 0; lose[i] = 0; }
 #pragma unroll
     for (int i = 0; i < D; i++)
 #pragma unroll
         for (int j = i + 1; j < D; j++) {
-            const bool first = key[i] >= key[j];
-            wins[i] += first ? 1 : 0;
-            wins[j] += first ? 0 : 1;
+            const int first = key[i] >= key[j] ? 1 : 0;
+            wins[i] += first;
+            lose[j] += first;
         }
+#pragma unroll
+    for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
 }
 
 // Sum over adjacent pairs, level by level (fixed order, float32).

@@ -64,15 +64,18 @@ def cpu_baseline(wf_rows, xf, K, threads):
     }
 
 
-def read_traffic():
-    """HBM bytes per launch of the batch-1 fused kernel from the committed counter summary
-    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs), or None if there is none."""
-    path = os.path.join(ROOT, "profiles", "gemv_b1_gate_70b_hbm_traffic.json")
+def read_traffic(kernel="gemv_b1"):
+    """HBM bytes per launch of a kernel from the committed counter summary (rocprofv3 --pmc FETCH_SIZE
+    and WRITE_SIZE runs, scaled by a copy of known size; see the file), or None if it is not there."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_gate_70b.txt")
     try:
         with open(path) as f:
-            return json.load(f).get("traffic_bytes_per_launch")
+            for line in f:
+                if line.startswith(f"{kernel}_traffic_bytes_per_launch"):
+                    return int(line.split("=")[1])
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def main():
@@ -85,6 +88,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
     ap.add_argument("--only", default="", help="comma-separated subset of encode,decode,gemv_b1,gemv_b4,"
                     "gemv_b16 to run in the timed steps (profiling aid; the JSON line is then partial)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of a known size (256 MiB read + 256 MiB written), so "
+                    "that a counter run can scale FETCH_SIZE / WRITE_SIZE against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (rows would shard across "
@@ -144,6 +150,14 @@ def main():
             if not only or f"gemv_b{B}" in only:
                 pvq.pvq_decode_gemv(ctx, p, xs[B], out=ys[B])
             if ev: ev[3 + j].record()
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

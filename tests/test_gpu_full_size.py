@@ -1,0 +1,67 @@
+"""GPU parity at the full sizes of the measured workloads, in the launch configurations bench.py
+times: whole-matrix bit-exact comparison of the encoder's outputs, whole-matrix 1-ulp comparison
+of decoded bf16 weights, and the fused product against a float64 matmul of the oracle's weights.
+The oracle runs on the host cores (16 threads); matrices are generated on the GPU from a seed."""
+import numpy as np
+import pytest
+
+import paper_2410_16926_amd as pvq
+import synth_inputs as si
+from oracle import pvq_oracle as oracle
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+THREADS = 16
+
+
+def device_matrix(rows, cols, seed):
+    W = si.gaussian_weights_device(rows, cols, 0.015, seed, torch.device("cuda:0"))
+    return W, W.to(torch.float32).cpu().numpy()          # bf16 tensor, the same values as float32
+
+
+def encode_decode_case(rows, cols, D, budget, scale_bits, seed, batches=()):
+    K = pvq.pvq_max_k(D, budget)
+    G = cols // D
+    ctx, oe, oc = gu.make_ctx(D, K, scale_bits, G)
+    W, wf = device_matrix(rows, cols, seed)
+    packed = pvq.pvq_encode(ctx, W, want_pulses=True)
+    torch.cuda.synchronize()
+    enc = oracle.encode(wf, D, K, scale_bits, oe, want_pulses=True, nthreads=THREADS)
+    gu.assert_encode_equal(packed, enc)
+    del wf
+    ref, _, _ = oracle.decode(enc, oc, nthreads=THREADS)
+    got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
+    want = oracle.to_bf16_bits(ref)
+    assert gu.ulp_f16(want, got) <= 1
+    assert np.mean(want != got) < 1e-3                    # one-ulp cases are double-rounding cases: rare
+    del got, want
+    for B in batches:
+        xf, xb = si.activations(B, cols, seed=seed + B)
+        y = pvq.pvq_decode_gemv(ctx, packed, gu.to_dev_bf16(xb)).cpu().numpy()
+        gu.assert_gemv_close(y, xf.astype(np.float64) @ ref.T)
+    ctx.close()
+
+
+def test_llama3_8b_up_projection_8bit_amplitudes():
+    # 14336 x 4096 bf16, D=8, 24-bit indices, 8-bit Beta amplitude codes
+    encode_decode_case(14336, 4096, 8, 24, 8, si.BASE_SEED + 1001)
+
+
+@pytest.mark.parametrize("D,budget", [(16, 52), (32, 104)])
+def test_llama3_8b_up_projection_wide_indices(D, budget):
+    # the same matrix family with 52-bit (2 words) and 104-bit (4 words) indices, float32 amplitudes
+    encode_decode_case(14336, 4096, D, budget, 0, si.BASE_SEED + 1002 + D)
+
+
+@pytest.mark.parametrize("name", ["k", "q", "down"])
+def test_llama3_70b_layer_shapes_2bit_amplitudes(name):
+    # 3.25 bits/weight: D=8, 24-bit index + 2-bit amplitude code; k/v, q/o and down shapes
+    rows, cols = si.LLAMA3_70B_SHAPES[name]
+    encode_decode_case(rows, cols, 8, 24, 2, si.BASE_SEED + 1100 + rows % 97)
+
+
+def test_llama3_70b_gate_projection_with_fused_product():
+    # the benchmark's matrix shape (28672 x 8192) end to end, and the fused product at batch 1, 4, 16
+    rows, cols = si.LLAMA3_70B_SHAPES["gate"]
+    encode_decode_case(rows, cols, 8, 24, 2, si.BASE_SEED + 1200, batches=(1, 4, 16))

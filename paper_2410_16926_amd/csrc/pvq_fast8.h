@@ -14,8 +14,8 @@
 //   S2  (d=4, k2)    single y4     -> residual in (3, k3)
 //   T3  (d=3, k3)    direct table over every (k3, r): y5, y6, y7
 // Finding a block: a bucket table indexed by (row k, r >> shift) names the block that holds the
-// bucket's first index (candidate A) and the block starting inside the bucket that covers most of it
-// (candidate B, with its start relative to the bucket).  The block table entry carries the block's
+// bucket's first index (candidate A) and a second block starting inside the bucket (candidate B, with
+// its start relative to the bucket).  The block table entry carries the block's
 // start and end; if r lies beyond the end (a bucket with several small blocks) the walk moves on
 // block by block.  All tables sit in one blob that a workgroup copies into LDS.
 //
@@ -40,7 +40,8 @@
 #endif
 
 struct pvq_fast8_params {
-    uint32_t blob_bytes;
+    uint32_t blob_bytes;  // whole blob
+    uint32_t lds_bytes;   // the blob without its last table, 1/sqrt(n2) (a kernel with its own gain table leaves it out)
     uint32_t n_minus_1;   // N(8,K) - 1: stored indices are clamped to it
     uint32_t bk0, bl0;    // byte offsets of S0's bucket table and block table
     uint32_t bl1, bl2;    // S1 / S2 block tables (their bucket rows are reached through meta)
@@ -49,18 +50,27 @@ struct pvq_fast8_params {
     uint32_t k2max;       // n2 <= K*K
 };
 
-// 32-bit bucket entry (S0, S1): bits 0..12 start of candidate B inside the bucket, bits 13..16 index
-// distance from A to B (0 = no B), bits 17..31 index of A in the stage's block table.
-// 16-bit bucket entry (S2, few blocks): 5 / 2 / 9 bits.
+// Two bucket-entry forms.
+// "two-candidate" (S1, 32 bits): bits 0..12 start of candidate B inside the bucket, bits 13..16 index
+// distance from A to B (0 = no B), bits 17..31 index of A in the stage's block table.  B is the block
+// starting inside the bucket that covers most of it.
+// "next-block" (S0 32 bits, S2 16 bits): B is always the block after A, which lets one addition do
+// the whole selection: entry = ((index of A - bucket number) << shift) + (2^shift - start of B inside
+// the bucket), so that (entry + r) >> shift = index of A, plus one exactly when r has reached B (the
+// low parts carry).  In the 16-bit form the arithmetic is modulo 2^16.
 constexpr uint32_t kFast8ThrBits = 13;
 constexpr uint32_t kFast8DbBits = 4;
-constexpr uint32_t kFast8S2ThrBits = 5;
-constexpr uint32_t kFast8S2DbBits = 2;
-// LDS left for the blob: the 160 KiB of a compute unit minus 4 KiB for the kernels' own buffers
-constexpr uint32_t kFast8MaxBytes = 160 * 1024 - 4096;
+constexpr uint32_t kFast8MaxShift = 13;
+#ifndef PVQ_FAST8_S0_MODE
+#define PVQ_FAST8_S0_MODE 1   // form of S0's bucket entries: 0 two-candidate, 1 next-block
+#endif    // all bucket shifts stay at or below this
+// LDS left for the blob: the 160 KiB of a compute unit minus 5 KiB for the kernels' own buffers
+// (partial sums: 2 KiB; amplitude table: 1 KiB, or a fused gain table in place of 1/sqrt(n2))
+constexpr uint32_t kFast8MaxBytes = 160 * 1024 - 5120;
 
-// block entry (16 bytes): start, end (0xFFFFFFFF for the last block of a row), values as bf16 pair,
-// meta = 4*(a^2+b^2) in bits 0..10 | byte offset of the next stage's row << 14
+// block entry (16 bytes, read as one uint4): x = start, y = end (0xFFFFFFFF for the last block of a
+// row), z = values as bf16 pair, w = meta = 4*(a^2+b^2) in bits 0..10 | byte offset of the next
+// stage's row << 14
 struct pvq_fast8_block {
     uint32_t start, end, values, meta;
 };
@@ -68,82 +78,99 @@ struct pvq_fast8_block {
 // One searched stage for NG independent groups at once: all bucket reads are issued together, then
 // all block reads, so that the LDS latencies of the groups overlap instead of adding up.
 // `row[j]` = byte offset of the bucket row for group j's current k; r[j] is replaced by the residual
-// inside the block found; the block is returned in b[j].
-// E is the bucket entry type (uint32_t or uint16_t) with THR / DB bits for its first two fields.
-// `blmem` is the memory the block table is read from (the LDS copy of the blob or the blob itself).
-template <int NG, typename E, uint32_t THR, uint32_t DB>
-PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const unsigned char *blmem, const uint32_t (&row)[NG],
-                            uint32_t shift, uint32_t bl, uint32_t (&r)[NG], pvq_fast8_block (&b)[NG])
+// inside the block found; the block entry is returned in b[j].
+// MODE 0: two-candidate 32-bit entries; 1: next-block 32-bit entries; 2: next-block 16-bit entries.
+template <int NG, int MODE>
+PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
+                            uint32_t shift, uint32_t bl, uint32_t (&r)[NG], uint4 (&b)[NG])
 {
     uint32_t e[NG], addr[NG];
 #pragma unroll
-    for (int j = 0; j < NG; j++)
-        e[j] = *reinterpret_cast<const E *>(lds + row[j] + (r[j] >> shift) * (uint32_t)sizeof(E));
+    for (int j = 0; j < NG; j++) {
+        if constexpr (MODE == 2) e[j] = *reinterpret_cast<const uint16_t *>(lds + row[j] + (r[j] >> shift) * 2u);
+        else e[j] = *reinterpret_cast<const uint32_t *>(lds + row[j] + (r[j] >> shift) * 4u);
+    }
 #pragma unroll
     for (int j = 0; j < NG; j++) {
-        const uint32_t rlow = r[j] & ((1u << shift) - 1u);
-        const uint32_t thr = e[j] & ((1u << THR) - 1u);
-        const uint32_t db = (e[j] >> THR) & ((1u << DB) - 1u);
-        const uint32_t idx = (e[j] >> (THR + DB)) + (rlow >= thr ? db : 0u);
+        uint32_t idx;
+        if constexpr (MODE == 0) {
+            const uint32_t rlow = r[j] & ((1u << shift) - 1u);
+            const uint32_t thr = e[j] & ((1u << kFast8ThrBits) - 1u);
+            const uint32_t db = (e[j] >> kFast8ThrBits) & ((1u << kFast8DbBits) - 1u);
+            idx = (e[j] >> (kFast8ThrBits + kFast8DbBits)) + (rlow >= thr ? db : 0u);
+        } else if constexpr (MODE == 1) {
+            idx = (e[j] + r[j]) >> shift;
+        } else {
+            idx = (uint32_t)(uint16_t)(e[j] + r[j]) >> shift;
+        }
         addr[j] = bl + (idx << 4);
     }
     bool miss = false;
-    uint4 q[NG];
 #pragma unroll
-    for (int j = 0; j < NG; j++) q[j] = *reinterpret_cast<const uint4 *>(blmem + addr[j]);
+    for (int j = 0; j < NG; j++) b[j] = *reinterpret_cast<const uint4 *>(lds + addr[j]);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
-        PVQ_KEEP_TOGETHER(q[j]);
-        b[j].start = q[j].x; b[j].end = q[j].y; b[j].values = q[j].z; b[j].meta = q[j].w;
-        miss = miss || r[j] >= q[j].y;
+        PVQ_KEEP_TOGETHER(b[j]);
+        miss = miss || r[j] >= b[j].y;
     }
     // a bucket with several small blocks: the few lanes concerned move on block by block
     if (miss) {
 #pragma unroll
         for (int j = 0; j < NG; j++) {
-            while (r[j] >= b[j].end) {
+            while (r[j] >= b[j].y) {
                 addr[j] += 16;
-                uint4 n = *reinterpret_cast<const uint4 *>(blmem + addr[j]);
-                PVQ_KEEP_TOGETHER(n);
-                b[j].start = n.x; b[j].end = n.y; b[j].values = n.z; b[j].meta = n.w;
+                b[j] = *reinterpret_cast<const uint4 *>(lds + addr[j]);
+                PVQ_KEEP_TOGETHER(b[j]);
             }
         }
     }
 #pragma unroll
-    for (int j = 0; j < NG; j++) r[j] -= b[j].start;
+    for (int j = 0; j < NG; j++) r[j] -= b[j].x;
 }
 
 // NG indices -> per index four bf16 pairs (y0,y1) (y2,y3) (y4,y5) (y6,y7) and n2x4 = 4 * sum y^2.
-// `lds` holds the blob; `bl0mem` is where S0's block table is read from: either `lds` again, or the
-// blob in global memory, which moves one 16-byte lookup per group from LDS to the vector cache (S0's
-// block table is small enough to stay there).
-template <int NG>
-PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const unsigned char *bl0mem, const pvq_fast8_params &p,
-                             const uint32_t (&c)[NG], uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
+// Each pair is handed to `emit(j, pair number, word)` as soon as its stage has found it, so that a
+// consumer that folds pairs into sums (the fused product) keeps one accumulator per group alive
+// instead of the block entries.
+// `lds` holds the blob (on the device: its copy in LDS).  All lookups stay there: reading S0's block
+// table through the vector cache instead was measured 13 % slower in the fused product.
+template <int NG, typename Emit>
+PVQ_HD void pvq_fast8_decode_emit(const unsigned char *lds, const pvq_fast8_params &p,
+                                  const uint32_t (&c)[NG], Emit &&emit, uint32_t (&n2x4)[NG])
 {
-    uint32_t r[NG], row[NG];
-    pvq_fast8_block b0[NG], b1[NG], b2[NG];
+    uint32_t r[NG], row[NG], acc[NG], y4[NG];
+    uint4 b[NG];
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         r[j] = c[j] < p.n_minus_1 ? c[j] : p.n_minus_1;
         row[j] = p.bk0;
     }
-    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, bl0mem, row, p.s0, p.bl0, r, b0);
+    pvq_fast8_stage<NG, PVQ_FAST8_S0_MODE>(lds, row, p.s0, p.bl0, r, b);
 #pragma unroll
-    for (int j = 0; j < NG; j++) row[j] = b0[j].meta >> 14;
-    pvq_fast8_stage<NG, uint32_t, kFast8ThrBits, kFast8DbBits>(lds, lds, row, p.s1, p.bl1, r, b1);
+    for (int j = 0; j < NG; j++) { emit(j, 0, b[j].z); acc[j] = b[j].w; row[j] = b[j].w >> 14; }
+    pvq_fast8_stage<NG, 0>(lds, row, p.s1, p.bl1, r, b);
 #pragma unroll
-    for (int j = 0; j < NG; j++) row[j] = b1[j].meta >> 14;
-    pvq_fast8_stage<NG, uint16_t, kFast8S2ThrBits, kFast8S2DbBits>(lds, lds, row, p.s2, p.bl2, r, b2);
+    for (int j = 0; j < NG; j++) { emit(j, 1, b[j].z); acc[j] += b[j].w; row[j] = b[j].w >> 14; }
+    pvq_fast8_stage<NG, 2>(lds, row, p.s2, p.bl2, r, b);
+#pragma unroll
+    for (int j = 0; j < NG; j++) { y4[j] = b[j].z; acc[j] += b[j].w; row[j] = (b[j].w >> 14) + (r[j] << 3); }
+    uint2 t[NG];
+#pragma unroll
+    for (int j = 0; j < NG; j++) t[j] = *reinterpret_cast<const uint2 *>(lds + row[j]);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
-        const uint2 t = *reinterpret_cast<const uint2 *>(lds + (b2[j].meta >> 14) + (r[j] << 3));
-        pairs[j][0] = b0[j].values;
-        pairs[j][1] = b1[j].values;
-        pairs[j][2] = (t.x & 0xFFFF0000u) | b2[j].values;
-        pairs[j][3] = t.y;
-        n2x4[j] = (b0[j].meta + b1[j].meta + b2[j].meta + t.x) & 0x7FFu;
+        emit(j, 2, (t[j].x & 0xFFFF0000u) | y4[j]);
+        emit(j, 3, t[j].y);
+        n2x4[j] = (acc[j] + t[j].x) & 0x7FFu;
     }
+}
+
+// The same with the pairs stored.
+template <int NG>
+PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const pvq_fast8_params &p,
+                             const uint32_t (&c)[NG], uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
+{
+    pvq_fast8_decode_emit<NG>(lds, p, c, [&](int j, int pair, uint32_t w) { pairs[j][pair] = w; }, n2x4);
 }
 
 // Host side: builds the blob for (8, K) if it fits `max_bytes`; returns false otherwise.

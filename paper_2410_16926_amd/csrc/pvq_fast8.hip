@@ -13,6 +13,10 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kMaxThreads = 1024;
+#ifndef PVQ_GEMV_THREADS
+#define PVQ_GEMV_THREADS 1024
+#endif
+constexpr int kGemvThreads = PVQ_GEMV_THREADS;   // lanes of a fused-product workgroup
 constexpr int kGroupsPerLane = 4;
 constexpr int kTileGroups = kWave * kGroupsPerLane;   // groups one wave covers in a row: 256
 constexpr int kLdsBytes = 160 * 1024;                 // the whole LDS of a compute unit
@@ -32,16 +36,18 @@ struct fast8_launch {
     int index_bits, scale_bits;
 };
 
-// Copies the blob into LDS.  Behind it: with FUSED (amplitude codes of at most 2 bits) the table
-// gain[q][n2] = (1/sqrt(n2)) * sqrt(center[q]), (K*K+1) floats per code, so that one lookup gives a
-// group's whole gain; otherwise the 2^scale_bits values sqrt(center[q]).
+// Copies the blob into LDS.  With FUSED (amplitude codes of at most 2 bits) the blob's last table,
+// 1/sqrt(n2), is left out and its place taken by gain[q][n2] = (1/sqrt(n2)) * sqrt(center[q]),
+// (K*K+1) floats per code, so that one lookup gives a group's whole gain; otherwise the
+// 2^scale_bits values sqrt(center[q]) follow the blob.
 template <bool FUSED>
 __device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, float *sqrtc_l)
 {
     const int nthreads = blockDim.x;
+    const uint32_t bytes = FUSED ? f.p.lds_bytes : f.p.blob_bytes;
     // (issuing several loads per lane before the first LDS write measured slower: all units ask for
     // the same lines at once)
-    for (uint32_t i = threadIdx.x * 16u; i < f.p.blob_bytes; i += nthreads * 16u)
+    for (uint32_t i = threadIdx.x * 16u; i < bytes; i += nthreads * 16u)
         *reinterpret_cast<uint4 *>(lds + i) = *reinterpret_cast<const uint4 *>(f.blob + i);
     if constexpr (FUSED) {
         const int n = (int)f.p.k2max + 1;
@@ -130,98 +136,173 @@ struct quad_item_t {
     uint32_t w[3];                       // 24-bit path: three dwords; generic path: unused
     uint32_t c[kGroupsPerLane];          // generic path: the four indices
     float amp[CODES ? 1 : kGroupsPerLane];
-    uint32_t codes;                      // CODES: the four codes, lowest group in the low bits
+    uint32_t codes;                      // CODES: the word that holds the four codes
+};
+
+// Per-lane byte offsets into a row of the planes; rows differ only in a wave-uniform base, so the
+// loads take a scalar base and these offsets.  Lanes beyond the row's last group read the row's
+// first quad: what they decode meets activations of zero.
+struct quad_offsets {
+    uint32_t index, scale;
 };
 
 template <bool CODES, bool B24>
-__device__ inline void fetch_quad(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int g0,
-                                  bool live, quad_item_t<CODES> &it)
+__device__ inline quad_offsets make_quad_offsets(const fast8_launch &f, int g0, bool in_row)
 {
-    if (!live) {
-        it.w[0] = it.w[1] = it.w[2] = 0;
-#pragma unroll
-        for (int j = 0; j < kGroupsPerLane; j++) it.c[j] = 0;
-#pragma unroll
-        for (int j = 0; j < (CODES ? 1 : kGroupsPerLane); j++) it.amp[j] = 0.0f;
-        it.codes = 0;
-        return;
-    }
-    const uint32_t *irow = a.index + row * a.index_row_words;
+    const uint32_t g = in_row ? (uint32_t)g0 : 0u;
+    quad_offsets o;
+    o.index = B24 ? (g >> 2) * 12u : 0u;
+    o.scale = CODES ? ((g * (uint32_t)f.scale_bits) >> 5) * 4u : g * 4u;  // 4 codes never straddle a word
+    return o;
+}
+
+// `row` must be uniform in the wave.  No arithmetic on loaded data here, so that fetches stay in
+// flight until the item is split.
+template <bool CODES, bool B24>
+__device__ inline void fetch_quad(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int g0, bool in_row,
+                                  const quad_offsets &o, quad_item_t<CODES> &it)
+{
+    const unsigned char *irow = reinterpret_cast<const unsigned char *>(a.index + row * a.index_row_words);
     if constexpr (B24) {
-        const uint32_t *p = irow + (g0 >> 2) * 3;
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(irow + o.index);
         it.w[0] = p[0]; it.w[1] = p[1]; it.w[2] = p[2];
     } else {
         const uint32_t b = (uint32_t)f.index_bits;
+        const uint32_t g = in_row ? (uint32_t)g0 : 0u;
 #pragma unroll
         for (int j = 0; j < kGroupsPerLane; j++) {
-            const uint32_t pos = (uint32_t)(g0 + j) * b, w0 = pos >> 5, sh = pos & 31;
-            uint64_t v = irow[w0];
-            if (sh + b > 32) v |= (uint64_t)irow[w0 + 1] << 32;
+            const uint32_t pos = (g + j) * b, w0 = pos >> 5, sh = pos & 31;
+            uint64_t v = reinterpret_cast<const uint32_t *>(irow)[w0];
+            if (sh + b > 32) v |= (uint64_t)reinterpret_cast<const uint32_t *>(irow)[w0 + 1] << 32;
             it.c[j] = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
         }
     }
     if constexpr (CODES) {
-        const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
-        const uint32_t pos = (uint32_t)g0 * (uint32_t)f.scale_bits;  // 4 codes never straddle a word
-        it.codes = srow[pos >> 5];   // shifted into place in split_quad: no arithmetic on loaded
-                                     // data here, so that fetches can stay in flight
+        const unsigned char *srow = reinterpret_cast<const unsigned char *>(
+            reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words);
+        it.codes = *reinterpret_cast<const uint32_t *>(srow + o.scale);
     } else {
-        const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(a.scale) + row * a.groups + g0);
+        const unsigned char *srow = reinterpret_cast<const unsigned char *>(
+            reinterpret_cast<const float *>(a.scale) + row * a.groups);
+        const float4 v = *reinterpret_cast<const float4 *>(srow + o.scale);
         it.amp[0] = v.x; it.amp[1] = v.y; it.amp[2] = v.z; it.amp[3] = v.w;
     }
 }
 
+// What the decoder needs of an item, copied out so that the item's registers can take the next fetch.
+template <bool CODES>
+struct quad_split_t {
+    uint32_t c[kGroupsPerLane];
+    uint32_t codes;                      // the four codes, lowest group in the low bits
+    float amp[CODES ? 1 : kGroupsPerLane];
+};
+
 template <bool CODES, bool B24>
-__device__ inline void split_quad(const fast8_launch &f, int g0, quad_item_t<CODES> &it)
+__device__ inline void split_quad(const fast8_launch &f, int g0, const quad_item_t<CODES> &it, quad_split_t<CODES> &q)
 {
-    if constexpr (CODES) it.codes >>= ((uint32_t)g0 * (uint32_t)f.scale_bits) & 31u;
+    q.codes = 0;
+    if constexpr (CODES) q.codes = it.codes >> (((uint32_t)g0 * (uint32_t)f.scale_bits) & 31u);
+    else {
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) q.amp[j] = it.amp[j];
+    }
     if constexpr (B24) {
-        it.c[0] = it.w[0] & 0xFFFFFFu;
-        it.c[1] = __builtin_amdgcn_alignbit(it.w[1], it.w[0], 24) & 0xFFFFFFu;
-        it.c[2] = __builtin_amdgcn_alignbit(it.w[2], it.w[1], 16) & 0xFFFFFFu;
-        it.c[3] = it.w[2] >> 8;
+        q.c[0] = it.w[0] & 0xFFFFFFu;
+        q.c[1] = __builtin_amdgcn_alignbit(it.w[1], it.w[0], 24) & 0xFFFFFFu;
+        q.c[2] = __builtin_amdgcn_alignbit(it.w[2], it.w[1], 16) & 0xFFFFFFu;
+        q.c[3] = it.w[2] >> 8;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) q.c[j] = it.c[j];
     }
 }
 
 // amplitude factor of group j without the row normaliser: sqrt(center[q]) or the stored amplitude
 template <bool CODES>
-__device__ inline float amp_factor(const fast8_launch &f, const quad_item_t<CODES> &it, int j, const float *sqrtc_l)
+__device__ inline float amp_factor(const fast8_launch &f, const quad_split_t<CODES> &q, int j, const float *sqrtc_l)
 {
     if constexpr (CODES) {
-        const uint32_t q = (it.codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
-        return sqrtc_l[q];
+        const uint32_t code = (q.codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
+        return sqrtc_l[code];
     } else {
-        return it.amp[j];
+        return q.amp[j];
     }
+}
+
+// v + (v moved across lanes by one data-parallel-primitive pattern); lanes outside ROWS add zero
+template <int CTRL, int ROWS = 0xF>
+__device__ inline float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xF, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+// Sum over the 64 lanes in a fixed order, valid in lane 63: pairs, quads, eights, rows of 16 (mirror
+// patterns), then row 0 into 1 and row 2 into 3, then rows 0..1 into 2..3.  Pure vector-ALU work:
+// no LDS traffic, unlike a shuffle butterfly.
+__device__ inline float wave_sum_lane63(float v)
+{
+    v = dpp_add<0xB1>(v);          // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);          // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);         // row_half_mirror
+    v = dpp_add<0x140>(v);         // row_mirror
+    v = dpp_add<0x142, 0xA>(v);    // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);    // row_bcast31 into rows 2 and 3
+    return v;
 }
 
 // ---------------------------------------------------------------------------------------------
 // y = W_hat x
 // ---------------------------------------------------------------------------------------------
 
+constexpr int kGemvRowsPerWave = 4;    // rows a wave decodes per batch of rows
+// partial sums of one batch of rows: 64 (row, slice) pairs x 4 vectors, two buffers
+constexpr size_t kPartBytes = 2 * 64 * 4 * sizeof(float);
+
 // Waves are arranged as nsl column slices (256 groups each) x rl row lanes.  Per batch of 4*rl rows
 // every wave handles 4 rows of its slice; lanes keep their 32 activations per vector in registers.
-// Row sums: xor butterfly inside the wave, then the slices' partial sums meet in LDS in slice order.
+// Row sums: fixed-order sum inside the wave, then the slices' partial sums meet in LDS in slice order.
 // AMP: 0 = float32 amplitudes, 1 = amplitude codes, 2 = amplitude codes with the fused gain table.
 template <int NB, int AMP, bool B24>
-__global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_decode_args a, int b0,
+__global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq_decode_args a, int b0,
                                                              int nsl, int rl, int rows_per_block)
 {
     constexpr bool CODES = AMP != 0;
+    constexpr int RI = kGemvRowsPerWave;
+#ifndef PVQ_GEMV_IR
+#define PVQ_GEMV_IR 1
+#endif
+    constexpr int IR = NB == 1 ? PVQ_GEMV_IR : 1;   // rows decoded together
     // static, so that table offsets fold into the LDS instructions' immediate fields
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
-    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
+    // the fused gain table replaces the 1/sqrt(n2) table at the end of the blob
+    float *sqrtc_l = reinterpret_cast<float *>(lds + (AMP == 2 ? f.p.lds_bytes : f.p.blob_bytes));
     const uint32_t gain_stride = (f.p.k2max + 1) * 4;   // bytes per code in the fused table
     float *part = sqrtc_l + (AMP == 2 ? ((f.p.k2max + 1) << f.scale_bits) : 256);
-    load_tables<AMP == 2>(lds, f, sqrtc_l);
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
 
     const int G = (int)a.groups;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & (kWave - 1);
+    // the wave's number as a scalar, so that row addresses are computed once per wave, not per lane
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int slice = wave % nsl, rowlane = wave / nsl;
     const int g0 = slice * kTileGroups + lane * kGroupsPerLane;
     const bool in_row = g0 < G;
-    constexpr int RI = 4;              // rows per wave per batch
     const int RB = RI * rl;            // rows per batch
+    const quad_offsets qo = make_quad_offsets<CODES, B24>(f, g0, in_row);
+    const int64_t r_last = r_end - 1;  // rows beyond the range re-read the last one; their sums are dropped
+
+    // first fetches go out before the table copy
+    quad_item_t<CODES> item[RI];
+    if (r_begin < r_end) {
+#pragma unroll
+        for (int i = 0; i < RI; i++)
+            fetch_quad<CODES, B24>(f, a, std::min<int64_t>(r_begin + i * rl + rowlane, r_last), g0, in_row, qo, item[i]);
+    }
+    load_tables<AMP == 2>(lds, f, sqrtc_l);
+    if (r_begin >= r_end) return;
 
     uint32_t xr[NB][16];
 #pragma unroll
@@ -235,72 +316,72 @@ __global__ __launch_bounds__(kMaxThreads) void gemv8_kernel(fast8_launch f, pvq_
         }
     }
 
-    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
-
-    quad_item_t<CODES> cur[RI], nxt[RI];
-#pragma unroll
-    for (int i = 0; i < RI; i++) {
-        const int64_t row = r_begin + i * rl + rowlane;
-        fetch_quad<CODES, B24>(f, a, row, g0, in_row && row < r_end, cur[i]);
-    }
-
+    int parity = 0;
     for (int64_t batch = r_begin; batch < r_end; batch += RB) {
+        float *pbuf = part + parity * (64 * NB);
 #pragma unroll
-        for (int i = 0; i < RI; i++) {
-            const int64_t row = batch + RB + i * rl + rowlane;
-            fetch_quad<CODES, B24>(f, a, row, g0, in_row && row < r_end, nxt[i]);
-        }
+        for (int i0 = 0; i0 < RI; i0 += IR) {
+            // IR rows are decoded together: 4*IR independent table walks per lane overlap their latencies
+            quad_split_t<CODES> q[IR];
+            uint32_t c[IR * kGroupsPerLane], n2x4[IR * kGroupsPerLane];
+            float dot[IR * kGroupsPerLane][NB];
 #pragma unroll
-        for (int i = 0; i < RI; i++) {
-            split_quad<CODES, B24>(f, g0, cur[i]);
-            float acc[NB];
+            for (int r = 0; r < IR; r++) {
+                const int i = i0 + r;
+                split_quad<CODES, B24>(f, g0, item[i], q[r]);
+                // the same registers take this wave's row of the next batch while the current one is decoded
+                fetch_quad<CODES, B24>(f, a, std::min<int64_t>(batch + RB + i * rl + rowlane, r_last), g0, in_row, qo, item[i]);
 #pragma unroll
-            for (int b = 0; b < NB; b++) acc[b] = 0.0f;
-            uint32_t pr[kGroupsPerLane][4], n2x4[kGroupsPerLane];
-            pvq_fast8_decode<kGroupsPerLane>(lds, f.blob, f.p, cur[i].c, pr, n2x4);
+                for (int j = 0; j < kGroupsPerLane; j++) c[r * kGroupsPerLane + j] = q[r].c[j];
+            }
+            // every pair goes into the groups' dot products the moment its stage has found it
+            pvq_fast8_decode_emit<IR * kGroupsPerLane>(lds, f.p, c, [&](int e, int pair, uint32_t w) {
 #pragma unroll
-            for (int j = 0; j < kGroupsPerLane; j++) {
-                float gain;
-                if constexpr (AMP == 2) {
-                    const uint32_t q = (cur[i].codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
-                    gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
-                                                            q * gain_stride + n2x4[j]);
-                } else {
-                    gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
-                           amp_factor<CODES>(f, cur[i], j, sqrtc_l);
+                for (int b = 0; b < NB; b++)
+                    dot[e][b] = dot2_bf16(w, xr[b][4 * (e % kGroupsPerLane) + pair], pair == 0 ? 0.0f : dot[e][b]);
+            }, n2x4);
+#pragma unroll
+            for (int r = 0; r < IR; r++) {
+                const int i = i0 + r;
+                float acc[NB];
+#pragma unroll
+                for (int b = 0; b < NB; b++) acc[b] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < kGroupsPerLane; j++) {
+                    const int e = r * kGroupsPerLane + j;
+                    float gain;
+                    if constexpr (AMP == 2) {
+                        const uint32_t code = (q[r].codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
+                        gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
+                                                                code * gain_stride + n2x4[e]);
+                    } else {
+                        gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[e]) *
+                               amp_factor<CODES>(f, q[r], j, sqrtc_l);
+                    }
+#pragma unroll
+                    for (int b = 0; b < NB; b++) acc[b] = fmaf(gain, dot[e][b], acc[b]);
                 }
 #pragma unroll
                 for (int b = 0; b < NB; b++) {
-                    float s = dot2_bf16(pr[j][0], xr[b][4 * j], 0.0f);
-                    s = dot2_bf16(pr[j][1], xr[b][4 * j + 1], s);
-                    s = dot2_bf16(pr[j][2], xr[b][4 * j + 2], s);
-                    s = dot2_bf16(pr[j][3], xr[b][4 * j + 3], s);
-                    acc[b] = fmaf(gain, s, acc[b]);
+                    const float v = wave_sum_lane63(acc[b]);
+                    if (lane == kWave - 1) pbuf[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
                 }
             }
-#pragma unroll
-            for (int b = 0; b < NB; b++) {
-                float v = acc[b];
-#pragma unroll
-                for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-                if (lane == 0) part[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
-            }
         }
+        // one barrier per batch: the next batch writes the other buffer, and a buffer is written
+        // again only after the barrier that follows its readers
         __syncthreads();
         if ((int)threadIdx.x < RB * NB) {
             const int rloc = threadIdx.x / NB, b = threadIdx.x % NB;
             const int64_t row = batch + rloc;
             if (row < r_end) {
                 float v = 0.0f;
-                for (int s = 0; s < nsl; s++) v += part[(rloc * nsl + s) * NB + b];
+                for (int s = 0; s < nsl; s++) v += pbuf[(rloc * nsl + s) * NB + b];
                 if constexpr (CODES) v *= sqrtf(a.rownorm[row]);
                 a.y[(int64_t)(b0 + b) * a.ldy + row] = v;
             }
         }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < RI; i++) cur[i] = nxt[i];
+        parity ^= 1;
     }
 }
 
@@ -379,7 +460,7 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
         const float srn = CODES ? sqrtf(cur_rn) : 1.0f;
         uint32_t c[kGroupsPerLane], prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
         item_indices<B24>(cur, gbase, c);
-        pvq_fast8_decode<kGroupsPerLane>(lds, lds, f.p, c, prs, n2x4s);
+        pvq_fast8_decode<kGroupsPerLane>(lds, f.p, c, prs, n2x4s);
 #pragma unroll
         for (int j = 0; j < kGroupsPerLane; j++) {
             const int g = gbase + kWave * j;
@@ -413,7 +494,7 @@ hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b
     // the fused gain table must fit behind the blob together with the partial-sum buffer
     const size_t fused_bytes = ((size_t)(f.p.k2max + 1) << f.scale_bits) * 4;
     const bool fused = f.scale_bits > 0 && f.scale_bits <= 2 &&
-                       f.p.blob_bytes + fused_bytes + 64 * 4 * sizeof(float) <= (size_t)kLdsBytes;
+                       f.p.lds_bytes + fused_bytes + kPartBytes <= (size_t)kLdsBytes;
     const int amp = f.scale_bits == 0 ? 0 : (fused ? 2 : 1);
 #define PVQ_GEMV_CASE(AMP, B24) \
     hipLaunchKernelGGL((gemv8_kernel<NB, AMP, B24>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block)
@@ -460,7 +541,7 @@ bool pvq_fast8_gemv_usable(const pvq_ctx *c, const pvq_decode_args &a)
     // a row must fit the waves of one workgroup: at most 16 slices of 256 groups
     // lanes take whole quads of groups
     return c->fast8_blob != nullptr && a.groups % kGroupsPerLane == 0 &&
-           (a.groups + kTileGroups - 1) / kTileGroups <= kMaxThreads / kWave;
+           (a.groups + kTileGroups - 1) / kTileGroups <= kGemvThreads / kWave;
 }
 
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
@@ -484,7 +565,7 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
 {
     const fast8_launch f = make_launch(c);
     const int nsl = (int)((a.groups + kTileGroups - 1) / kTileGroups);
-    const int rl = std::max(1, (kMaxThreads / kWave) / nsl);
+    const int rl = std::max(1, (kGemvThreads / kWave) / nsl);
     const int RB = 4 * rl;
     const size_t lds = 0;  // the kernels own the whole LDS statically
     const int64_t batches = (a.rows + RB - 1) / RB;

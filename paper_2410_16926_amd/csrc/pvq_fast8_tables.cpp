@@ -71,6 +71,25 @@ void build_bucket_row(const std::vector<Block> &blocks, uint32_t first_index, ui
     }
 }
 
+// Bucket row in the next-block form: (index of A - bucket number) << shift, plus 2^shift minus the
+// start of the block after A inside the bucket (nothing if it starts beyond the bucket).
+template <typename E>
+void build_next_bucket_row(const std::vector<Block> &blocks, uint32_t first_index, uint64_t total, int shift,
+                           std::vector<E> &out)
+{
+    const uint64_t width = (uint64_t)1 << shift;
+    const uint64_t nb = (total + width - 1) / width;
+    size_t a = 0;
+    for (uint64_t j = 0; j < nb; j++) {
+        const uint64_t lo = j * width, hi = lo + width;
+        while (a + 1 < blocks.size() && blocks[a + 1].start <= lo) a++;
+        uint64_t low = 0;
+        if (a + 1 < blocks.size() && blocks[a + 1].start < hi) low = width - (blocks[a + 1].start - lo);
+        const uint64_t high = (uint64_t)first_index + a - j;   // modulo the entry width
+        out.push_back((E)((high << shift) + low));
+    }
+}
+
 void align16(std::vector<unsigned char> &blob) { blob.resize((blob.size() + 15) & ~(size_t)15); }
 
 template <typename T>
@@ -135,8 +154,8 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     std::vector<uint32_t> bk0, bk1;
     std::vector<uint16_t> bk2;
     std::vector<uint32_t> bk1_row(K + 1), bk2_row(K + 1);
-    build_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, kFast8ThrBits, kFast8DbBits, bk0);
-    // pad S0's bucket table so that every clamped index has an entry (it has: c <= N-1)
+    if (PVQ_FAST8_S0_MODE == 1) build_next_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, bk0);
+    else build_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, kFast8ThrBits, kFast8DbBits, bk0);
     uint32_t first = 0;
     for (int k = 0; k <= K; k++) {
         bk1_row[k] = (uint32_t)bk1.size() * 4;
@@ -146,10 +165,10 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     first = 0;
     for (int k = 0; k <= K; k++) {
         bk2_row[k] = (uint32_t)bk2.size() * 2;
-        build_bucket_row<uint16_t>(rows2[k], first, N.at(4, k), s2, kFast8S2ThrBits, kFast8S2DbBits, bk2);
+        build_next_bucket_row<uint16_t>(rows2[k], first, N.at(4, k), s2, bk2);
         first += (uint32_t)rows2[k].size();
     }
-    if (first >= (1u << (16 - kFast8S2ThrBits - kFast8S2DbBits))) return false;
+    if (first >= (1u << (16 - s2))) return false;   // S2's block numbers must fit the 16-bit entries
 
     // ---- lay the blob out ---------------------------------------------------------------------
     // sizes are known now; offsets of the rows that `meta` words point to must be fixed before the
@@ -166,6 +185,8 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     const size_t o_bl0 = off; off = up16(off + nblk0 * 16);
     const size_t o_bl1 = off; off = up16(off + nblk1 * 16);
     const size_t o_bl2 = off; off = up16(off + nblk2 * 16);
+    // 1/sqrt(n2) comes last: a kernel that builds its own gain table leaves it out of its LDS copy
+    const size_t lds_bytes = off;
     const size_t o_invs = off; off = up16(off + (size_t)(K * K + 1) * 4);
     if (off > max_bytes || off >= ((size_t)1 << 18)) return false;
 
@@ -197,6 +218,7 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     if (!ok || blob.size() != off) return false;
 
     p.blob_bytes = (uint32_t)blob.size();
+    p.lds_bytes = (uint32_t)lds_bytes;
     p.n_minus_1 = (uint32_t)(N.at(8, K) - 1);
     p.bk0 = (uint32_t)o_bk0; p.bl0 = (uint32_t)o_bl0; p.bl1 = (uint32_t)o_bl1; p.bl2 = (uint32_t)o_bl2;
     p.invs = (uint32_t)o_invs;
@@ -217,11 +239,11 @@ bool pvq_fast8_build(int K, uint32_t max_bytes, std::vector<unsigned char> &blob
     // Finer buckets mean fewer block-by-block steps; take the finest combination that fits.  The
     // base shifts follow the index width (for 24 bits: 12 / 8 / 3); S2 is coarsened first (its
     // blocks are the most regular), then S0, and S1 last.
-    static const int steps[][3] = {{0, 0, 0}, {1, 0, 0}, {1, 0, 1}, {1, 0, 2}, {1, 1, 2}, {2, 1, 2}, {2, 2, 2}, {3, 3, 2}};
+    static const int steps[][3] = {{0, 0, 0}, {0, 0, 1}, {1, 0, 1}, {1, 0, 2}, {1, 1, 2}, {2, 1, 2}, {2, 2, 2}, {3, 3, 2}};
     for (const auto &st : steps) {
-        const int s0 = std::min(std::max(1, bits - 12) + st[0], (int)kFast8ThrBits);
-        const int s1 = std::min(std::max(1, bits - 16) + st[1], (int)kFast8ThrBits);
-        const int s2 = std::min(std::max(1, bits - 21) + st[2], (int)kFast8S2ThrBits);
+        const int s0 = std::min(std::max(1, bits - 12) + st[0], (int)kFast8MaxShift);
+        const int s1 = std::min(std::max(1, bits - 16) + st[1], (int)kFast8MaxShift);
+        const int s2 = std::min(std::max(1, bits - 21) + st[2], 6);
         if (build_with_shifts(K, N, s0, s1, s2, max_bytes, blob, p)) return true;
     }
     return false;
@@ -240,7 +262,7 @@ extern "C" int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, u
     uint64_t bad = 0;
     for (uint64_t c = first; c < first + count && c < total; c++) {
         uint32_t cc[1] = {(uint32_t)c}, pr[1][4], nn[1];
-        pvq_fast8_decode<1>(blob.data(), blob.data(), p, cc, pr, nn);
+        pvq_fast8_decode<1>(blob.data(), p, cc, pr, nn);
         const uint32_t *pairs = pr[0];
         const uint32_t n2x4 = nn[0];
         // plain walk

@@ -34,14 +34,22 @@
 // Keeps a 16-byte table entry together: without it the compiler reads the one field a loop tests
 // first and the other three later, which costs a second LDS round trip per stage.
 #if defined(__HIP_DEVICE_COMPILE__)
-#define PVQ_KEEP_TOGETHER(q) asm volatile("" : "+v"((q).x), "+v"((q).y), "+v"((q).z), "+v"((q).w))
+#define PVQ_KEEP_TOGETHER(q) asm volatile("" : "+v"(q))
 #else
 #define PVQ_KEEP_TOGETHER(q) ((void)0)
 #endif
 
+// a block entry as one 16-byte value (one register tuple on the device)
+typedef uint32_t pvq_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t pvq_u32x2 __attribute__((ext_vector_type(2)));
+
 struct pvq_fast8_params {
     uint32_t blob_bytes;  // whole blob
-    uint32_t lds_bytes;   // the blob without its last table, 1/sqrt(n2) (a kernel with its own gain table leaves it out)
+    uint32_t tab_bytes;   // what a workgroup copies into LDS: all but an S0 block table kept outside
+    uint32_t lds_bytes;   // tab_bytes without its last table, 1/sqrt(n2) (a kernel with its own gain
+                          // table leaves that out)
+    uint32_t s0_outside;  // 1: S0's block table lies behind tab_bytes and is read from the blob in
+                          // device memory (and S0's bucket entries are two-candidate ones)
     uint32_t n_minus_1;   // N(8,K) - 1: stored indices are clamped to it
     uint32_t bk0, bl0;    // byte offsets of S0's bucket table and block table
     uint32_t bl1, bl2;    // S1 / S2 block tables (their bucket rows are reached through meta)
@@ -61,9 +69,7 @@ struct pvq_fast8_params {
 constexpr uint32_t kFast8ThrBits = 13;
 constexpr uint32_t kFast8DbBits = 4;
 constexpr uint32_t kFast8MaxShift = 13;
-#ifndef PVQ_FAST8_S0_MODE
-#define PVQ_FAST8_S0_MODE 1   // form of S0's bucket entries: 0 two-candidate, 1 next-block
-#endif    // all bucket shifts stay at or below this
+    // all bucket shifts stay at or below this
 // LDS left for the blob: the 160 KiB of a compute unit minus 5 KiB for the kernels' own buffers
 // (partial sums: 2 KiB; amplitude table: 1 KiB, or a fused gain table in place of 1/sqrt(n2))
 constexpr uint32_t kFast8MaxBytes = 160 * 1024 - 5120;
@@ -75,16 +81,17 @@ struct pvq_fast8_block {
     uint32_t start, end, values, meta;
 };
 
-// One searched stage for NG independent groups at once: all bucket reads are issued together, then
-// all block reads, so that the LDS latencies of the groups overlap instead of adding up.
-// `row[j]` = byte offset of the bucket row for group j's current k; r[j] is replaced by the residual
-// inside the block found; the block entry is returned in b[j].
+// A searched stage for NG independent groups at once, in two halves so that all bucket reads are
+// issued together and then all block reads (the latencies of the groups overlap instead of adding up).
+//
+// First half: the bucket lookups.  `row[j]` = byte offset of the bucket row for group j's current
+// k; returns in addr[j] the byte offset of the block entry chosen for r[j].
 // MODE 0: two-candidate 32-bit entries; 1: next-block 32-bit entries; 2: next-block 16-bit entries.
 template <int NG, int MODE>
-PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
-                            uint32_t shift, uint32_t bl, uint32_t (&r)[NG], uint4 (&b)[NG])
+PVQ_HD void pvq_fast8_find(const unsigned char *lds, const uint32_t (&row)[NG], uint32_t shift, uint32_t bl,
+                           const uint32_t (&r)[NG], uint32_t (&addr)[NG])
 {
-    uint32_t e[NG], addr[NG];
+    uint32_t e[NG];
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         if constexpr (MODE == 2) e[j] = *reinterpret_cast<const uint16_t *>(lds + row[j] + (r[j] >> shift) * 2u);
@@ -105,21 +112,32 @@ PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
         }
         addr[j] = bl + (idx << 4);
     }
+}
+
+// Second half, after b[j] has been read from `mem + addr[j]`: a bucket with several small blocks
+// makes the few lanes concerned move on block by block; then r[j] becomes the residual inside the
+// block found.  `mem` is the memory that holds the block table (the LDS copy of the blob, or the
+// blob in device memory).  `addr_of(addr)` fills in the entries' addresses when they are needed: a
+// caller that did not keep them looks them up again, which only the rare groups that move on pay for.
+template <int NG, typename AddrOf>
+PVQ_HD void pvq_fast8_settle(const unsigned char *mem, uint32_t (&r)[NG], pvq_u32x4 (&b)[NG], AddrOf &&addr_of)
+{
     bool miss = false;
-#pragma unroll
-    for (int j = 0; j < NG; j++) b[j] = *reinterpret_cast<const uint4 *>(lds + addr[j]);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         PVQ_KEEP_TOGETHER(b[j]);
         miss = miss || r[j] >= b[j].y;
     }
-    // a bucket with several small blocks: the few lanes concerned move on block by block
     if (miss) {
+        // (stepping all NG groups together, one round trip per step of the furthest group, measured
+        // slower than one short loop per group)
+        uint32_t addr[NG];
+        addr_of(addr);
 #pragma unroll
         for (int j = 0; j < NG; j++) {
             while (r[j] >= b[j].y) {
                 addr[j] += 16;
-                b[j] = *reinterpret_cast<const uint4 *>(lds + addr[j]);
+                b[j] = *reinterpret_cast<const pvq_u32x4 *>(mem + addr[j]);
                 PVQ_KEEP_TOGETHER(b[j]);
             }
         }
@@ -128,24 +146,52 @@ PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG],
     for (int j = 0; j < NG; j++) r[j] -= b[j].x;
 }
 
-// NG indices -> per index four bf16 pairs (y0,y1) (y2,y3) (y4,y5) (y6,y7) and n2x4 = 4 * sum y^2.
-// Each pair is handed to `emit(j, pair number, word)` as soon as its stage has found it, so that a
-// consumer that folds pairs into sums (the fused product) keeps one accumulator per group alive
-// instead of the block entries.
-// `lds` holds the blob (on the device: its copy in LDS).  All lookups stay there: reading S0's block
-// table through the vector cache instead was measured 13 % slower in the fused product.
-template <int NG, typename Emit>
-PVQ_HD void pvq_fast8_decode_emit(const unsigned char *lds, const pvq_fast8_params &p,
-                                  const uint32_t (&c)[NG], Emit &&emit, uint32_t (&n2x4)[NG])
+// both halves, block table in LDS
+template <int NG, int MODE>
+PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG], uint32_t shift, uint32_t bl,
+                            uint32_t (&r)[NG], pvq_u32x4 (&b)[NG])
 {
-    uint32_t r[NG], row[NG], acc[NG], y4[NG];
-    uint4 b[NG];
+    uint32_t addr[NG];
+    pvq_fast8_find<NG, MODE>(lds, row, shift, bl, r, addr);
+#pragma unroll
+    for (int j = 0; j < NG; j++) b[j] = *reinterpret_cast<const pvq_u32x4 *>(lds + addr[j]);
+    pvq_fast8_settle<NG>(lds, r, b, [&](uint32_t (&out)[NG]) {
+#pragma unroll
+        for (int j = 0; j < NG; j++) out[j] = addr[j];
+    });
+}
+
+// S0 for NG stored indices, up to the addresses of the block entries (in `blob` when OUTSIDE, else in
+// `lds`): a caller that reads those entries from device memory can start S0 of its next indices
+// while it still decodes the current ones.  r = the indices, clamped to the last valid one.
+template <int NG, bool OUTSIDE>
+PVQ_HD void pvq_fast8_s0_find(const unsigned char *lds, const pvq_fast8_params &p, const uint32_t (&c)[NG],
+                              uint32_t (&r)[NG], uint32_t (&addr)[NG])
+{
+    uint32_t row[NG];
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         r[j] = c[j] < p.n_minus_1 ? c[j] : p.n_minus_1;
         row[j] = p.bk0;
     }
-    pvq_fast8_stage<NG, PVQ_FAST8_S0_MODE>(lds, row, p.s0, p.bl0, r, b);
+    pvq_fast8_find<NG, OUTSIDE ? 0 : 1>(lds, row, p.s0, p.bl0, r, addr);
+}
+
+// The rest of the decoder, from S0's block entries b (as read from the addresses that
+// pvq_fast8_s0_find gave for the clamped indices r) on.  Per index:
+// four bf16 pairs (y0,y1) (y2,y3) (y4,y5) (y6,y7) and n2x4 = 4 * sum y^2.  Each pair is handed to
+// `emit(j, pair number, word)` as soon as its stage has found it, so that a consumer that folds
+// pairs into sums (the fused product) keeps one accumulator per group alive instead of the block
+// entries.
+template <int NG, bool OUTSIDE, typename Emit>
+PVQ_HD void pvq_fast8_rest(const unsigned char *lds, const unsigned char *blob, const pvq_fast8_params &p,
+                           uint32_t (&r)[NG], pvq_u32x4 (&b)[NG], Emit &&emit, uint32_t (&n2x4)[NG])
+{
+    uint32_t row[NG], acc[NG], y4[NG];
+    pvq_fast8_settle<NG>(OUTSIDE ? blob : lds, r, b, [&](uint32_t (&out)[NG]) {
+        uint32_t same[NG];
+        pvq_fast8_s0_find<NG, OUTSIDE>(lds, p, r, same, out);
+    });
 #pragma unroll
     for (int j = 0; j < NG; j++) { emit(j, 0, b[j].z); acc[j] = b[j].w; row[j] = b[j].w >> 14; }
     pvq_fast8_stage<NG, 0>(lds, row, p.s1, p.bl1, r, b);
@@ -154,9 +200,9 @@ PVQ_HD void pvq_fast8_decode_emit(const unsigned char *lds, const pvq_fast8_para
     pvq_fast8_stage<NG, 2>(lds, row, p.s2, p.bl2, r, b);
 #pragma unroll
     for (int j = 0; j < NG; j++) { y4[j] = b[j].z; acc[j] += b[j].w; row[j] = (b[j].w >> 14) + (r[j] << 3); }
-    uint2 t[NG];
+    pvq_u32x2 t[NG];
 #pragma unroll
-    for (int j = 0; j < NG; j++) t[j] = *reinterpret_cast<const uint2 *>(lds + row[j]);
+    for (int j = 0; j < NG; j++) t[j] = *reinterpret_cast<const pvq_u32x2 *>(lds + row[j]);
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         emit(j, 2, (t[j].x & 0xFFFF0000u) | y4[j]);
@@ -165,14 +211,31 @@ PVQ_HD void pvq_fast8_decode_emit(const unsigned char *lds, const pvq_fast8_para
     }
 }
 
-// The same with the pairs stored.
-template <int NG>
-PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const pvq_fast8_params &p,
-                             const uint32_t (&c)[NG], uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
+// Whole decoder, one index set after the other.  `lds` holds the first tab_bytes of the blob (on the
+// device: their copy in LDS), `blob` the whole blob (used for S0's block table when OUTSIDE).
+template <int NG, bool OUTSIDE, typename Emit>
+PVQ_HD void pvq_fast8_decode_emit(const unsigned char *lds, const unsigned char *blob, const pvq_fast8_params &p,
+                                  const uint32_t (&c)[NG], Emit &&emit, uint32_t (&n2x4)[NG])
 {
-    pvq_fast8_decode_emit<NG>(lds, p, c, [&](int j, int pair, uint32_t w) { pairs[j][pair] = w; }, n2x4);
+    uint32_t r[NG], addr[NG];
+    pvq_u32x4 b[NG];
+    const unsigned char *s0mem = OUTSIDE ? blob : lds;
+    pvq_fast8_s0_find<NG, OUTSIDE>(lds, p, c, r, addr);
+#pragma unroll
+    for (int j = 0; j < NG; j++) b[j] = *reinterpret_cast<const pvq_u32x4 *>(s0mem + addr[j]);
+    pvq_fast8_rest<NG, OUTSIDE>(lds, blob, p, r, b, emit, n2x4);
 }
 
-// Host side: builds the blob for (8, K) if it fits `max_bytes`; returns false otherwise.
+// The same with the pairs stored.
+template <int NG, bool OUTSIDE>
+PVQ_HD void pvq_fast8_decode(const unsigned char *lds, const unsigned char *blob, const pvq_fast8_params &p,
+                             const uint32_t (&c)[NG], uint32_t (&pairs)[NG][4], uint32_t (&n2x4)[NG])
+{
+    pvq_fast8_decode_emit<NG, OUTSIDE>(lds, blob, p, c, [&](int j, int pair, uint32_t w) { pairs[j][pair] = w; }, n2x4);
+}
+
+// Host side: builds the blob for (8, K) if what goes to LDS fits `max_bytes`; returns false otherwise.
+// s0_outside: keep S0's block table behind the part copied to LDS.
 #include <vector>
-bool pvq_fast8_build(int K, uint32_t max_bytes, std::vector<unsigned char> &blob, pvq_fast8_params &p);
+bool pvq_fast8_build(int K, uint32_t max_bytes, bool s0_outside, std::vector<unsigned char> &blob,
+                     pvq_fast8_params &p);

@@ -13,10 +13,8 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kMaxThreads = 1024;
-#ifndef PVQ_GEMV_THREADS
-#define PVQ_GEMV_THREADS 1024
-#endif
-constexpr int kGemvThreads = PVQ_GEMV_THREADS;   // lanes of a fused-product workgroup
+constexpr int kGemvThreads = 1024;   // lanes of a fused-product workgroup (half as many with twice the
+                                     // groups in flight per lane measured 30 % slower)
 constexpr int kGroupsPerLane = 4;
 constexpr int kTileGroups = kWave * kGroupsPerLane;   // groups one wave covers in a row: 256
 constexpr int kLdsBytes = 160 * 1024;                 // the whole LDS of a compute unit
@@ -37,14 +35,14 @@ struct fast8_launch {
 };
 
 // Copies the blob into LDS.  With FUSED (amplitude codes of at most 2 bits) the blob's last table,
-// 1/sqrt(n2), is left out and its place taken by gain[q][n2] = (1/sqrt(n2)) * sqrt(center[q]),
-// (K*K+1) floats per code, so that one lookup gives a group's whole gain; otherwise the
+// 1/sqrt(n2), is left out and its place taken by gain[n2][q] = (1/sqrt(n2)) * sqrt(center[q]),
+// 2^scale_bits floats per n2, so that one lookup gives a group's whole gain; otherwise the
 // 2^scale_bits values sqrt(center[q]) follow the blob.
 template <bool FUSED>
 __device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, float *sqrtc_l)
 {
     const int nthreads = blockDim.x;
-    const uint32_t bytes = FUSED ? f.p.lds_bytes : f.p.blob_bytes;
+    const uint32_t bytes = FUSED ? f.p.lds_bytes : f.p.tab_bytes;
     // (issuing several loads per lane before the first LDS write measured slower: all units ask for
     // the same lines at once)
     for (uint32_t i = threadIdx.x * 16u; i < bytes; i += nthreads * 16u)
@@ -52,7 +50,7 @@ __device__ inline void load_tables(unsigned char *lds, const fast8_launch &f, fl
     if constexpr (FUSED) {
         const int n = (int)f.p.k2max + 1;
         for (int i = threadIdx.x; i < (n << f.scale_bits); i += nthreads) {
-            const int q = i / n, n2 = i - q * n;
+            const int n2 = i >> f.scale_bits, q = i & ((1 << f.scale_bits) - 1);
             sqrtc_l[i] = reinterpret_cast<const float *>(f.blob + f.p.invs)[n2] * f.sqrtc[q];
         }
     } else if (f.scale_bits > 0) {
@@ -255,7 +253,9 @@ __device__ inline float wave_sum_lane63(float v)
 // y = W_hat x
 // ---------------------------------------------------------------------------------------------
 
-constexpr int kGemvRowsPerWave = 4;    // rows a wave decodes per batch of rows
+// rows a wave decodes per batch of rows (= how far ahead it fetches), with and without S0 running
+// a row ahead (whose state takes the registers of two more fetched rows)
+constexpr int kGemvRowsPerWave = 4, kGemvRowsPerWaveAhead = 2;
 // partial sums of one batch of rows: 64 (row, slice) pairs x 4 vectors, two buffers
 constexpr size_t kPartBytes = 2 * 64 * 4 * sizeof(float);
 
@@ -263,21 +263,18 @@ constexpr size_t kPartBytes = 2 * 64 * 4 * sizeof(float);
 // every wave handles 4 rows of its slice; lanes keep their 32 activations per vector in registers.
 // Row sums: fixed-order sum inside the wave, then the slices' partial sums meet in LDS in slice order.
 // AMP: 0 = float32 amplitudes, 1 = amplitude codes, 2 = amplitude codes with the fused gain table.
-template <int NB, int AMP, bool B24>
+// AHEAD: S0 of a wave's next row is started before the current row is decoded, with S0's block
+// entries read from device memory (tables in the flavour that keeps that table outside LDS).
+template <int NB, int AMP, bool B24, bool AHEAD>
 __global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq_decode_args a, int b0,
                                                              int nsl, int rl, int rows_per_block)
 {
     constexpr bool CODES = AMP != 0;
-    constexpr int RI = kGemvRowsPerWave;
-#ifndef PVQ_GEMV_IR
-#define PVQ_GEMV_IR 1
-#endif
-    constexpr int IR = NB == 1 ? PVQ_GEMV_IR : 1;   // rows decoded together
+    constexpr int RI = AHEAD ? kGemvRowsPerWaveAhead : kGemvRowsPerWave;
     // static, so that table offsets fold into the LDS instructions' immediate fields
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
     // the fused gain table replaces the 1/sqrt(n2) table at the end of the blob
-    float *sqrtc_l = reinterpret_cast<float *>(lds + (AMP == 2 ? f.p.lds_bytes : f.p.blob_bytes));
-    const uint32_t gain_stride = (f.p.k2max + 1) * 4;   // bytes per code in the fused table
+    float *sqrtc_l = reinterpret_cast<float *>(lds + (AMP == 2 ? f.p.lds_bytes : f.p.tab_bytes));
     float *part = sqrtc_l + (AMP == 2 ? ((f.p.k2max + 1) << f.scale_bits) : 256);
 
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
@@ -316,56 +313,78 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq
         }
     }
 
+    // S0 runs one row ahead.  Its block entries come from the table's copy in device memory, through
+    // the vector cache: that takes one 16-byte lookup per group off the LDS, which is the busiest
+    // unit of this kernel, and the cache's latency passes while the row before is decoded.
+    struct ahead_t {
+        quad_split_t<CODES> q;
+        uint32_t r[kGroupsPerLane];
+        pvq_u32x4 b[kGroupsPerLane];
+    };
+    // takes the item in `slot`, refills the slot with `refill_row`, and starts S0 for the item taken
+    auto start_row = [&](int slot, int64_t refill_row, ahead_t &n) {
+        split_quad<CODES, B24>(f, g0, item[slot], n.q);
+        fetch_quad<CODES, B24>(f, a, std::min<int64_t>(refill_row, r_last), g0, in_row, qo, item[slot]);
+        uint32_t addr[kGroupsPerLane];
+        pvq_fast8_s0_find<kGroupsPerLane, true>(lds, f.p, n.q.c, n.r, addr);
+#pragma unroll
+        for (int j = 0; j < kGroupsPerLane; j++) n.b[j] = *reinterpret_cast<const pvq_u32x4 *>(f.blob + addr[j]);
+    };
+    ahead_t nx;
+    if constexpr (AHEAD) start_row(0, r_begin + RB + rowlane, nx);
+
     int parity = 0;
     for (int64_t batch = r_begin; batch < r_end; batch += RB) {
         float *pbuf = part + parity * (64 * NB);
 #pragma unroll
-        for (int i0 = 0; i0 < RI; i0 += IR) {
-            // IR rows are decoded together: 4*IR independent table walks per lane overlap their latencies
-            quad_split_t<CODES> q[IR];
-            uint32_t c[IR * kGroupsPerLane], n2x4[IR * kGroupsPerLane];
-            float dot[IR * kGroupsPerLane][NB];
-#pragma unroll
-            for (int r = 0; r < IR; r++) {
-                const int i = i0 + r;
-                split_quad<CODES, B24>(f, g0, item[i], q[r]);
+        for (int i = 0; i < RI; i++) {
+            ahead_t cu;
+            if constexpr (AHEAD) {
+                cu = nx;
+                // the slot after this one holds the next row: of this batch, or (last slot) of the following one
+                const int slot = (i + 1) % RI;
+                const int64_t held = i + 1 < RI ? batch : batch + RB;
+                start_row(slot, held + RB + slot * rl + rowlane, nx);
+            } else {
+                split_quad<CODES, B24>(f, g0, item[i], cu.q);
                 // the same registers take this wave's row of the next batch while the current one is decoded
                 fetch_quad<CODES, B24>(f, a, std::min<int64_t>(batch + RB + i * rl + rowlane, r_last), g0, in_row, qo, item[i]);
-#pragma unroll
-                for (int j = 0; j < kGroupsPerLane; j++) c[r * kGroupsPerLane + j] = q[r].c[j];
             }
+
+            uint32_t n2x4[kGroupsPerLane];
+            float dot[kGroupsPerLane][NB];
             // every pair goes into the groups' dot products the moment its stage has found it
-            pvq_fast8_decode_emit<IR * kGroupsPerLane>(lds, f.p, c, [&](int e, int pair, uint32_t w) {
+            auto emit = [&](int j, int pair, uint32_t w) {
 #pragma unroll
                 for (int b = 0; b < NB; b++)
-                    dot[e][b] = dot2_bf16(w, xr[b][4 * (e % kGroupsPerLane) + pair], pair == 0 ? 0.0f : dot[e][b]);
-            }, n2x4);
+                    dot[j][b] = dot2_bf16(w, xr[b][4 * j + pair], pair == 0 ? 0.0f : dot[j][b]);
+            };
+            if constexpr (AHEAD) pvq_fast8_rest<kGroupsPerLane, true>(lds, f.blob, f.p, cu.r, cu.b, emit, n2x4);
+            else pvq_fast8_decode_emit<kGroupsPerLane, false>(lds, f.blob, f.p, cu.q.c, emit, n2x4);
+            float acc[NB];
 #pragma unroll
-            for (int r = 0; r < IR; r++) {
-                const int i = i0 + r;
-                float acc[NB];
+            for (int b = 0; b < NB; b++) acc[b] = 0.0f;
+            const uint32_t codes4 = cu.q.codes << 2;
 #pragma unroll
-                for (int b = 0; b < NB; b++) acc[b] = 0.0f;
-#pragma unroll
-                for (int j = 0; j < kGroupsPerLane; j++) {
-                    const int e = r * kGroupsPerLane + j;
-                    float gain;
-                    if constexpr (AMP == 2) {
-                        const uint32_t code = (q[r].codes >> (j * f.scale_bits)) & ((1u << f.scale_bits) - 1u);
-                        gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
-                                                                code * gain_stride + n2x4[e]);
-                    } else {
-                        gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[e]) *
-                               amp_factor<CODES>(f, q[r], j, sqrtc_l);
-                    }
-#pragma unroll
-                    for (int b = 0; b < NB; b++) acc[b] = fmaf(gain, dot[e][b], acc[b]);
+            for (int j = 0; j < kGroupsPerLane; j++) {
+                float gain;
+                if constexpr (AMP == 2) {
+                    // byte offset of gain[n2][q]: 4 * (n2 * 2^bits + q), from 4*n2 and the code word
+                    // shifted left by two
+                    const uint32_t code4 = (codes4 >> (j * f.scale_bits)) & (((1u << f.scale_bits) - 1u) << 2);
+                    gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
+                                                            ((n2x4[j] << f.scale_bits) + code4));
+                } else {
+                    gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
+                           amp_factor<CODES>(f, cu.q, j, sqrtc_l);
                 }
 #pragma unroll
-                for (int b = 0; b < NB; b++) {
-                    const float v = wave_sum_lane63(acc[b]);
-                    if (lane == kWave - 1) pbuf[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
-                }
+                for (int b = 0; b < NB; b++) acc[b] = fmaf(gain, dot[j][b], acc[b]);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                const float v = wave_sum_lane63(acc[b]);
+                if (lane == kWave - 1) pbuf[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
             }
         }
         // one barrier per batch: the next batch writes the other buffer, and a buffer is written
@@ -427,7 +446,7 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
 {
     // static, so that table offsets fold into the LDS instructions' immediate fields
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
-    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.blob_bytes);
+    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.tab_bytes);
     load_tables<false>(lds, f, sqrtc_l);
 
     const int G = (int)a.groups;
@@ -460,7 +479,7 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
         const float srn = CODES ? sqrtf(cur_rn) : 1.0f;
         uint32_t c[kGroupsPerLane], prs[kGroupsPerLane][4], n2x4s[kGroupsPerLane];
         item_indices<B24>(cur, gbase, c);
-        pvq_fast8_decode<kGroupsPerLane>(lds, f.p, c, prs, n2x4s);
+        pvq_fast8_decode<kGroupsPerLane, false>(lds, f.blob, f.p, c, prs, n2x4s);
 #pragma unroll
         for (int j = 0; j < kGroupsPerLane; j++) {
             const int g = gbase + kWave * j;
@@ -476,17 +495,17 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
     }
 }
 
-fast8_launch make_launch(const pvq_ctx *c)
+fast8_launch make_launch(const pvq_ctx *c, bool gemv)
 {
     fast8_launch f;
-    f.p = c->fast8; f.blob = c->fast8_blob; f.sqrtc = c->sqrtc;
+    f.p = gemv ? c->fast8g : c->fast8; f.blob = gemv ? c->fast8g_blob : c->fast8_blob; f.sqrtc = c->sqrtc;
     f.index_bits = c->index_bits; f.scale_bits = c->scale_bits;
     return f;
 }
 
 int g_num_cus = 0;
 
-template <int NB>
+template <int NB, bool AHEAD>
 hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b0, int nsl, int rl,
                           int rows_per_block, dim3 grid, dim3 block, size_t lds, hipStream_t s)
 {
@@ -497,7 +516,7 @@ hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b
                        f.p.lds_bytes + fused_bytes + kPartBytes <= (size_t)kLdsBytes;
     const int amp = f.scale_bits == 0 ? 0 : (fused ? 2 : 1);
 #define PVQ_GEMV_CASE(AMP, B24) \
-    hipLaunchKernelGGL((gemv8_kernel<NB, AMP, B24>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block)
+    hipLaunchKernelGGL((gemv8_kernel<NB, AMP, B24, AHEAD>), grid, block, lds, s, f, a, b0, nsl, rl, rows_per_block)
     if (amp == 2) { if (b24) PVQ_GEMV_CASE(2, true); else PVQ_GEMV_CASE(2, false); }
     else if (amp == 1) { if (b24) PVQ_GEMV_CASE(1, true); else PVQ_GEMV_CASE(1, false); }
     else { if (b24) PVQ_GEMV_CASE(0, true); else PVQ_GEMV_CASE(0, false); }
@@ -546,7 +565,7 @@ bool pvq_fast8_gemv_usable(const pvq_ctx *c, const pvq_decode_args &a)
 
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
 {
-    const fast8_launch f = make_launch(c);
+    const fast8_launch f = make_launch(c, false);
     const size_t lds = 0;  // the kernels own the whole LDS statically
     const int64_t total = a.rows * ((a.groups + kTileGroups - 1) / kTileGroups);   // wave items
     // every block pays the table copy, so blocks get at least 64 wave items (16K groups) each
@@ -561,24 +580,38 @@ hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, i
     }
 }
 
-hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
+namespace {
+
+// one launch of the fused product for vectors [b0, b0 + NB)
+template <int NB, bool AHEAD>
+hipError_t launch_gemv_pass(const pvq_ctx *c, const pvq_decode_args &a, int b0, hipStream_t s)
 {
-    const fast8_launch f = make_launch(c);
+    const fast8_launch f = make_launch(c, AHEAD);
     const int nsl = (int)((a.groups + kTileGroups - 1) / kTileGroups);
     const int rl = std::max(1, (kGemvThreads / kWave) / nsl);
-    const int RB = 4 * rl;
+    const int RB = (AHEAD ? kGemvRowsPerWaveAhead : kGemvRowsPerWave) * rl;
     const size_t lds = 0;  // the kernels own the whole LDS statically
     const int64_t batches = (a.rows + RB - 1) / RB;
     const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
     const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);
     const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)(kWave * nsl * rl));
+    return launch_gemv_nb<NB, AHEAD>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s);
+}
+
+}  // namespace
+
+hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
+{
+    // a single vector runs S0 a row ahead (if the tables exist in that flavour); with more vectors
+    // the registers go to the activations instead
+    const bool ahead = c->fast8g_blob != nullptr;
     int b0 = 0;
     while (b0 < a.batch) {
         const int left = a.batch - b0;
         hipError_t e;
-        if (left >= 4) { e = launch_gemv_nb<4>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 4; }
-        else if (left >= 2) { e = launch_gemv_nb<2>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 2; }
-        else { e = launch_gemv_nb<1>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s); b0 += 1; }
+        if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
+        else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
+        else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -102,7 +102,7 @@ uint32_t append(std::vector<unsigned char> &blob, const std::vector<T> &v)
     return off;
 }
 
-bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint32_t max_bytes,
+bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint32_t max_bytes, bool s0_outside,
                        std::vector<unsigned char> &blob, pvq_fast8_params &p)
 {
     // ---- block lists --------------------------------------------------------------------
@@ -154,7 +154,9 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     std::vector<uint32_t> bk0, bk1;
     std::vector<uint16_t> bk2;
     std::vector<uint32_t> bk1_row(K + 1), bk2_row(K + 1);
-    if (PVQ_FAST8_S0_MODE == 1) build_next_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, bk0);
+    // S0's blocks read from LDS: next-block entries (a step to the following block is cheap there);
+    // read through the vector cache: two-candidate entries, which need such steps five times less often
+    if (!s0_outside) build_next_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, bk0);
     else build_bucket_row<uint32_t>(rows0[0], 0, N.at(8, K), s0, kFast8ThrBits, kFast8DbBits, bk0);
     uint32_t first = 0;
     for (int k = 0; k <= K; k++) {
@@ -182,13 +184,16 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     size_t nblk0 = rows0[0].size(), nblk1 = 0, nblk2 = 0;
     for (auto &r : rows1) nblk1 += r.size();
     for (auto &r : rows2) nblk2 += r.size();
-    const size_t o_bl0 = off; off = up16(off + nblk0 * 16);
+    size_t o_bl0 = 0;
+    if (!s0_outside) { o_bl0 = off; off = up16(off + nblk0 * 16); }
     const size_t o_bl1 = off; off = up16(off + nblk1 * 16);
     const size_t o_bl2 = off; off = up16(off + nblk2 * 16);
-    // 1/sqrt(n2) comes last: a kernel that builds its own gain table leaves it out of its LDS copy
+    // 1/sqrt(n2) comes last of what goes to LDS: a kernel that builds its own gain table leaves it out
     const size_t lds_bytes = off;
     const size_t o_invs = off; off = up16(off + (size_t)(K * K + 1) * 4);
-    if (off > max_bytes || off >= ((size_t)1 << 18)) return false;
+    const size_t tab_bytes = off;
+    if (s0_outside) { o_bl0 = off; off = up16(off + nblk0 * 16); }
+    if (tab_bytes > max_bytes || off >= ((size_t)1 << 18)) return false;
 
     auto write_blocks = [&](const std::vector<std::vector<Block>> &rows, auto next_row_offset) {
         std::vector<pvq_fast8_block> v;
@@ -212,13 +217,17 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
 
     blob.clear();
     bool ok = append(blob, bk0) == o_bk0 && append(blob, bk1) == o_bk1 && append(blob, bk2) == o_bk2 &&
-              append(blob, t3) == o_t3 && append(blob, bl0) == o_bl0 && append(blob, bl1) == o_bl1 &&
-              append(blob, bl2) == o_bl2 && append(blob, invs) == o_invs;
+              append(blob, t3) == o_t3;
+    if (!s0_outside) ok = ok && append(blob, bl0) == o_bl0;
+    ok = ok && append(blob, bl1) == o_bl1 && append(blob, bl2) == o_bl2 && append(blob, invs) == o_invs;
+    if (s0_outside) ok = ok && append(blob, bl0) == o_bl0;
     align16(blob);
     if (!ok || blob.size() != off) return false;
 
     p.blob_bytes = (uint32_t)blob.size();
     p.lds_bytes = (uint32_t)lds_bytes;
+    p.tab_bytes = (uint32_t)tab_bytes;
+    p.s0_outside = s0_outside ? 1u : 0u;
     p.n_minus_1 = (uint32_t)(N.at(8, K) - 1);
     p.bk0 = (uint32_t)o_bk0; p.bl0 = (uint32_t)o_bl0; p.bl1 = (uint32_t)o_bl1; p.bl2 = (uint32_t)o_bl2;
     p.invs = (uint32_t)o_invs;
@@ -229,7 +238,8 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
 
 }  // namespace
 
-bool pvq_fast8_build(int K, uint32_t max_bytes, std::vector<unsigned char> &blob, pvq_fast8_params &p)
+bool pvq_fast8_build(int K, uint32_t max_bytes, bool s0_outside, std::vector<unsigned char> &blob,
+                     pvq_fast8_params &p)
 {
     if (K < 1 || K > 22) return false;  // 4*K*K must stay below 2^11
     SmallTable N(K);
@@ -244,7 +254,7 @@ bool pvq_fast8_build(int K, uint32_t max_bytes, std::vector<unsigned char> &blob
         const int s0 = std::min(std::max(1, bits - 12) + st[0], (int)kFast8MaxShift);
         const int s1 = std::min(std::max(1, bits - 16) + st[1], (int)kFast8MaxShift);
         const int s2 = std::min(std::max(1, bits - 21) + st[2], 6);
-        if (build_with_shifts(K, N, s0, s1, s2, max_bytes, blob, p)) return true;
+        if (build_with_shifts(K, N, s0, s1, s2, max_bytes, s0_outside, blob, p)) return true;
     }
     return false;
 }
@@ -254,15 +264,19 @@ bool pvq_fast8_build(int K, uint32_t max_bytes, std::vector<unsigned char> &blob
 extern "C" int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mismatches)
 {
     if (!mismatches) return PVQ_E_INVALID_ARG;
-    std::vector<unsigned char> blob;
-    pvq_fast8_params p;
-    if (!pvq_fast8_build(K, kFast8MaxBytes, blob, p)) return PVQ_E_UNSUPPORTED;
     SmallTable N(K);
     const uint64_t total = N.at(8, K);
     uint64_t bad = 0;
+    // both table flavours: everything in one place, and S0's block table kept apart
+    for (int flavour = 0; flavour < 2; flavour++)
+    {
+    std::vector<unsigned char> blob;
+    pvq_fast8_params p;
+    if (!pvq_fast8_build(K, kFast8MaxBytes, flavour == 1, blob, p)) return PVQ_E_UNSUPPORTED;
     for (uint64_t c = first; c < first + count && c < total; c++) {
         uint32_t cc[1] = {(uint32_t)c}, pr[1][4], nn[1];
-        pvq_fast8_decode<1>(blob.data(), p, cc, pr, nn);
+        if (flavour == 0) pvq_fast8_decode<1, false>(blob.data(), blob.data(), p, cc, pr, nn);
+        else pvq_fast8_decode<1, true>(blob.data(), blob.data(), p, cc, pr, nn);
         const uint32_t *pairs = pr[0];
         const uint32_t n2x4 = nn[0];
         // plain walk
@@ -289,6 +303,7 @@ extern "C" int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, u
         }
         same = same && n2x4 == (uint32_t)(4 * n2);
         bad += !same;
+    }
     }
     *mismatches = bad;
     return PVQ_OK;

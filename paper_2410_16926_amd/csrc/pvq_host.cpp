@@ -247,7 +247,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
-    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = nullptr; c->enc8_offs = nullptr;
+    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -265,10 +265,14 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     }
     if (e == hipSuccess && D == 8 && words == 1) {
         std::vector<unsigned char> blob;
-        if (pvq_fast8_build(K, kFast8MaxBytes, blob, c->fast8)) {
+        if (pvq_fast8_build(K, kFast8MaxBytes, false, blob, c->fast8)) {
             e = pvq_fast8_prepare();
             if (e == hipSuccess) e = hipMalloc((void **)&c->fast8_blob, blob.size());
             if (e == hipSuccess) e = hipMemcpy(c->fast8_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+            if (e == hipSuccess && pvq_fast8_build(K, kFast8MaxBytes, true, blob, c->fast8g)) {
+                e = hipMalloc((void **)&c->fast8g_blob, blob.size());
+                if (e == hipSuccess) e = hipMemcpy(c->fast8g_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+            }
         }
     }
     if (e == hipSuccess && D == 8 && bits == 24) {
@@ -301,7 +305,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[6] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob, c->enc8_offs};
+    void *ptrs[7] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->enc8_offs};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);

@@ -24,9 +24,11 @@ struct pvq_ctx {
     float *sqrtc;   // 2^scale_bits float32 sqrt(centers) (or nullptr)
     size_t tab_n_bytes, tab_u_bytes;
     // Table-driven decoder (D = 8, one-word indices, tables that fit LDS); fast8_blob == nullptr
-    // when the configuration has none.
-    unsigned char *fast8_blob;
-    pvq_fast8_params fast8;
+    // when the configuration has none.  Two flavours of the tables: all of them in one LDS copy (the
+    // decode kernel), and S0's block table kept in device memory (the fused product; nullptr if
+    // that flavour does not fit).
+    unsigned char *fast8_blob, *fast8g_blob;
+    pvq_fast8_params fast8, fast8g;
     // Per-coordinate index offsets for the D = 8 / 24-bit encoder: [7][K+1][K+1][2] words
     // (coordinate, pulses left, magnitude, sign); nullptr when the configuration has none.
     uint32_t *enc8_offs;

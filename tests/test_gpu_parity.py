@@ -67,6 +67,14 @@ def test_wide_indices(D, budget):
     run_case(wf, D, K, 0, src_bits=wb, batches=(1, 2))
 
 
+@pytest.mark.parametrize("K,bits", [(5, 0), (9, 2), (13, 8), (17, 2), (17, 0)])
+def test_d8_other_pulse_counts(K, bits):
+    # D = 8 with index widths other than 24 bits (13, 18, 22 and 25): the table-driven kernels with
+    # indices that straddle words at varying offsets
+    wf, wb = si.gaussian_weights(160, 2048, 0.015, seed=si.BASE_SEED + 60 + K, bf16=True)
+    run_case(wf, 8, K, bits, src_bits=wb, batches=(1, 2, 5))
+
+
 @pytest.mark.parametrize("D,budget,bits", [(16, 52, 4), (32, 104, 8)])
 def test_wide_indices_with_codes(D, budget, bits):
     K = pvq.pvq_max_k(D, budget)

@@ -13,6 +13,7 @@
  *   - pyramid encoding  (point -> integer index)                (App. B.2, Alg. 2)
  *   - pyramid decoding  (integer index -> point), corrected     (App. B.3, Alg. 3)
  *   - the group amplitude s = ||w||_2                            (Sec. 2.3)
+ *     or the least-squares amplitude for the quantised direction (Sec. 3.3 Step 4)
  *   - amplitude codes against Beta quantile edges               (Sec. 3.3 Step 5, Sec. 3.4)
  *   - dequantisation: point -> unit sphere -> times amplitude   (Sec. 2.4 eq. for S(D,K), Sec. 3.4)
  *   - the reference product  out = W_hat x                       (float64 textbook matmul)
@@ -469,6 +470,7 @@ typedef struct {
     const float *W;
     int64_t rows, cols, r0, r1;
     int D, K, index_bits, scale_bits;
+    int amp_mode;       /* 0: s_g = ||w_g||_2; 1: least-squares amplitude */
     const float *edges; /* 2^scale_bits - 1 ascending float32 edges, or NULL */
     uint32_t *index_out;
     void *scale_out;
@@ -477,9 +479,34 @@ typedef struct {
 } enc_job_t;
 
 /*
+ * Least-squares amplitude of a group for its quantised direction (Sec. 3.3 Step 4).
+ * The group is rebuilt as s * y / ||y||_2; the s that minimises ||w - s y/||y||_2||_2 is
+ *     s = (y . w) / ||y||_2 .
+ * Reading: the section prints the ratio of the two inner products upside down; the
+ * minimiser of the stated distance is the one above (a test checks it against a
+ * least-squares solve).
+ * float32, fixed order: products (float)y_i * w_i rounded one by one, summed over pair
+ * levels; sum of y_i^2 as an integer; one square root, one division.
+ */
+float pvqo_ls_amplitude(const float *w, const int32_t *y, int D)
+{
+    float *buf = malloc(sizeof(float) * D);
+    int32_t n2 = 0;
+    for (int i = 0; i < D; i++) {
+        buf[i] = (float)y[i] * w[i];
+        n2 += y[i] * y[i];
+    }
+    float dot = sum_pair_levels(buf, D);
+    free(buf);
+    return dot / sqrtf((float)n2);
+}
+
+/*
  * Rows r0..r1-1 of W (row-major float32, cols = G*D; a bf16 source is widened exactly
- * by the caller).  Per group: quantise, rank, pack, and the amplitude.
- *   scale_bits == 0: the amplitude s_g = sqrtf(ss_g) is stored as float32 [rows][G].
+ * by the caller).  Per group: quantise, rank, pack, and the amplitude s_g: sqrtf(ss_g)
+ * with ss_g the group's sum of squares, or (amp_mode 1) the least-squares amplitude, for
+ * which ss_g = s_g * s_g below.
+ *   scale_bits == 0: s_g is stored as float32 [rows][G].
  *   scale_bits  > 0 (Sec. 3.3 Step 5 / Sec. 3.4): rowss = sum_g ss_g (pair levels),
  *       u_g = ss_g / rowss, code q_g = number of edges <= u_g, which is
  *       floor(CDF(u_g) * 2^b) when edges[j-1] = PPF(j / 2^b); codes are packed like the
@@ -494,6 +521,7 @@ static void *encode_rows(void *arg)
     int64_t sw = J->scale_bits ? row_words(G, J->scale_bits) : 0;
     int32_t *y = malloc(sizeof(int32_t) * D);
     float *ss = malloc(sizeof(float) * G);
+    float *amp = malloc(sizeof(float) * G);
     float *buf = malloc(sizeof(float) * G);
     int nedges = J->scale_bits ? (1 << J->scale_bits) - 1 : 0;
 
@@ -504,6 +532,12 @@ static void *encode_rows(void *arg)
         for (int64_t g = 0; g < G; g++) {
             big_t c;
             pvqo_quantize_group(wrow + g * D, D, K, y, &ss[g]);
+            if (J->amp_mode == 1) {
+                amp[g] = pvqo_ls_amplitude(wrow + g * D, y, D);
+                ss[g] = amp[g] * amp[g];
+            } else {
+                amp[g] = sqrtf(ss[g]);
+            }
             rank_point(J->tab, y, &c);
             put_bits(irow, g * J->index_bits, J->index_bits, c.w);
             if (J->pulses_out)
@@ -511,7 +545,7 @@ static void *encode_rows(void *arg)
         }
         if (J->scale_bits == 0) {
             float *srow = (float *)J->scale_out + r * G;
-            for (int64_t g = 0; g < G; g++) srow[g] = sqrtf(ss[g]);
+            for (int64_t g = 0; g < G; g++) srow[g] = amp[g];
             if (J->rowss_out) {
                 memcpy(buf, ss, sizeof(float) * G);
                 J->rowss_out[r] = sum_pair_levels(buf, (int)G);
@@ -531,16 +565,17 @@ static void *encode_rows(void *arg)
             }
         }
     }
-    free(y); free(ss); free(buf);
+    free(y); free(ss); free(amp); free(buf);
     return NULL;
 }
 
 /* Rows are split into nthreads contiguous blocks (plain static split; 1 = serial). */
 int pvqo_encode(const float *W, int64_t rows, int64_t cols, int D, int K, int scale_bits,
-                const float *edges, uint32_t *index_out, void *scale_out, float *rowss_out,
-                int8_t *pulses_out, int nthreads)
+                int amp_mode, const float *edges, uint32_t *index_out, void *scale_out,
+                float *rowss_out, int8_t *pulses_out, int nthreads)
 {
     if (D < 1 || K < 1 || K > 127 || cols % D || scale_bits < 0 || scale_bits > 8) return -1;
+    if (amp_mode != 0 && amp_mode != 1) return -1;
     if (scale_bits > 0 && (!edges || !rowss_out)) return -1;
     table_t *t = tab_build(D, K);
     if (t->overflow) { tab_free(t); return -1; }
@@ -551,7 +586,7 @@ int pvqo_encode(const float *W, int64_t rows, int64_t cols, int D, int K, int sc
     enc_job_t *jobs = malloc(sizeof(enc_job_t) * nthreads);
     for (int i = 0; i < nthreads; i++) {
         enc_job_t j = { t, W, rows, cols, rows * i / nthreads, rows * (i + 1) / nthreads,
-                        D, K, ib, scale_bits, edges, index_out, scale_out, rowss_out,
+                        D, K, ib, scale_bits, amp_mode, edges, index_out, scale_out, rowss_out,
                         pulses_out };
         jobs[i] = j;
         if (nthreads == 1) encode_rows(&jobs[i]);

@@ -51,7 +51,9 @@ def lib():
         L.pvqo_quantize_group.restype = None
         L.pvqo_rank_many.argtypes = [i32, i32, i64, vp, vp]
         L.pvqo_unrank_many.argtypes = [i32, i32, i64, vp, vp, i32]
-        L.pvqo_encode.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+        L.pvqo_encode.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+        L.pvqo_ls_amplitude.argtypes = [vp, vp, i32]
+        L.pvqo_ls_amplitude.restype = C.c_float
         L.pvqo_decode.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, i32,
                                   vp, i32]
         _lib = L
@@ -118,6 +120,14 @@ def quantize_group(w, K: int):
     return y, ss[0]
 
 
+def ls_amplitude(w, y) -> float:
+    """Least-squares amplitude of one group w (float32) for its quantised point y (Sec. 3.3 Step 4)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    assert w.shape == y.shape and w.ndim == 1
+    return float(lib().pvqo_ls_amplitude(_p(w), _p(y), int(w.size)))
+
+
 def rank(points, K: int):
     """points int [n][D] on P(D,K) -> list of Python-int indices."""
     x = np.ascontiguousarray(np.atleast_2d(points), dtype=np.int32)
@@ -180,8 +190,9 @@ class Encoded:
 
 
 def encode(W, D: int, K: int, scale_bits: int = 0, edges=None, want_pulses: bool = True,
-           nthreads: int = 1) -> Encoded:
-    """W: float32 [rows][cols] (widen bf16 with bf16_bits_to_f32 first)."""
+           nthreads: int = 1, amplitude: str = "l2") -> Encoded:
+    """W: float32 [rows][cols] (widen bf16 with bf16_bits_to_f32 first).
+    amplitude: "l2" = the group's norm (Sec. 2.3), "ls" = least-squares amplitude (Sec. 3.3 Step 4)."""
     W = np.ascontiguousarray(W, dtype=np.float32)
     rows, cols = W.shape
     G = cols // D
@@ -196,8 +207,8 @@ def encode(W, D: int, K: int, scale_bits: int = 0, edges=None, want_pulses: bool
         e32 = np.ascontiguousarray(np.asarray(edges, dtype=np.float64).astype(np.float32))
         assert e32.size == (1 << scale_bits) - 1
     pulses = np.zeros((rows, cols), dtype=np.int8) if want_pulses else None
-    rc = lib().pvqo_encode(_p(W), rows, cols, D, K, scale_bits, _p(e32), _p(index), _p(scale),
-                           _p(rowss), _p(pulses), nthreads)
+    rc = lib().pvqo_encode(_p(W), rows, cols, D, K, scale_bits, {"l2": 0, "ls": 1}[amplitude], _p(e32),
+                           _p(index), _p(scale), _p(rowss), _p(pulses), nthreads)
     if rc != 0:
         raise ValueError("pvqo_encode rejected its arguments")
     return Encoded(rows, cols, D, K, scale_bits, index, scale, rowss, pulses)

@@ -100,3 +100,85 @@ def test_dequantised_amplitude_is_sqrt_center_times_row_normaliser():
     # and it approximates the true group norm to within the bin width
     true = np.sqrt((W.astype(np.float64).reshape(rows, G, D) ** 2).sum(axis=2))
     assert np.median(np.abs(amp - true) / true) < 0.08
+
+
+# ---- least-squares amplitude (Sec. 3.3 Step 4) ------------------------------------------------
+
+def _groups(n, D, seed):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, D)) * 0.02).astype(np.float32)
+
+
+@pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (4, 3)])
+def test_ls_amplitude_is_the_least_squares_solution(D, K):
+    # s minimises ||w - s d||_2 for the unit direction d = y/||y||_2: compare with a least-squares solve
+    for w in _groups(200, D, seed=11 + D):
+        y, _ = o.quantize_group(w, K)
+        d = y.astype(np.float64) / np.linalg.norm(y.astype(np.float64))
+        s_ref = np.linalg.lstsq(d[:, None], w.astype(np.float64), rcond=None)[0][0]
+        s = o.ls_amplitude(w, y)
+        assert abs(s - s_ref) <= 2e-6 * abs(s_ref) + 1e-12
+        # it is the norm times the cosine of the angle between w and y, hence never above the norm
+        wn = np.linalg.norm(w.astype(np.float64))
+        assert s <= wn * (1 + 1e-6)
+        assert abs(s - wn * float(d @ w.astype(np.float64)) / wn) <= 2e-6 * wn
+        # and no other amplitude rebuilds the group better: not the norm, not the printed (inverted) ratio
+        err = lambda a: np.linalg.norm(w.astype(np.float64) - a * d)
+        assert err(s) <= err(wn) + 1e-12
+        printed = float(y.astype(np.float64) @ y.astype(np.float64)) / float(y.astype(np.float64) @ w.astype(np.float64))
+        assert err(s) <= err(printed * np.linalg.norm(y.astype(np.float64))) + 1e-12
+
+
+def test_ls_amplitude_special_cases():
+    # a group that lies exactly along a pyramid point: the amplitude is its norm
+    y = np.array([3, -2, 0, 1, 0, -4, 5, 1], dtype=np.int32)
+    w = (0.125 * y).astype(np.float32)
+    yq, _ = o.quantize_group(w, int(np.abs(y).sum()))
+    assert np.array_equal(yq, y)
+    assert o.ls_amplitude(w, yq) == pytest.approx(float(np.linalg.norm(w.astype(np.float64))), rel=1e-6)
+    # one-hot direction: the amplitude is that coordinate of the group
+    w = np.array([0.5, 0.01, -0.02, 0.0, 0.0, 0.0, 0.0, 0.0], dtype=np.float32)
+    y = np.array([1, 0, 0, 0, 0, 0, 0, 0], dtype=np.int32)
+    assert o.ls_amplitude(w, y) == np.float32(0.5)
+    # zero group -> point (0,...,0,+K), amplitude 0
+    z = np.zeros(8, dtype=np.float32)
+    yz, _ = o.quantize_group(z, 16)
+    assert o.ls_amplitude(z, yz) == 0.0
+
+
+@pytest.mark.parametrize("bits", [0, 2])
+def test_ls_amplitude_in_the_matrix_encoder(bits):
+    # the matrix encoder stores exactly the per-group values, and decoding with them rebuilds the
+    # matrix at least as well as with the norms
+    D, K = 8, 16
+    W = si.gaussian_weights(24, 512, 0.02, seed=5)
+    G = W.shape[1] // D
+    edges, centers = o.beta_tables(D, G, bits) if bits else (None, None)
+    e_ls = o.encode(W, D, K, bits, edges, amplitude="ls")
+    e_l2 = o.encode(W, D, K, bits, edges, amplitude="l2")
+    assert np.array_equal(e_ls.index, e_l2.index) and np.array_equal(e_ls.pulses, e_l2.pulses)
+    amps = np.array([[o.ls_amplitude(W[r, g * D:(g + 1) * D], e_ls.pulses[r, g * D:(g + 1) * D].astype(np.int32))
+                      for g in range(G)] for r in range(W.shape[0])], dtype=np.float32)
+    if bits == 0:
+        assert np.array_equal(e_ls.scale, amps)
+        d_ls, _, _ = o.decode(e_ls)
+        d_l2, _, _ = o.decode(e_l2)
+        assert np.linalg.norm(W - d_ls) < np.linalg.norm(W - d_l2)
+    else:
+        ss = amps * amps
+        # row normaliser = pair-level sum of the squared amplitudes; codes count the edges below ss/rowss
+        for r in range(W.shape[0]):
+            buf = ss[r].copy()
+            n = buf.size
+            while n > 1:
+                half = n // 2
+                nxt = buf[0:2 * half:2] + buf[1:2 * half:2]
+                if n % 2:
+                    nxt = np.append(nxt, buf[n - 1])
+                buf = nxt.astype(np.float32)
+                n = buf.size
+            assert e_ls.rowss[r] == buf[0]
+            u = (ss[r] / e_ls.rowss[r]).astype(np.float32)
+            want = (np.asarray(edges, dtype=np.float64).astype(np.float32)[None, :] <= u[:, None]).sum(axis=1)
+            got = o.unpack_fields(e_ls.scale[r:r + 1], G, bits)[0]
+            assert np.array_equal(np.array(got), want)

@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
     ap.add_argument("--only", default="", help="comma-separated subset of encode,decode,gemv_b1,gemv_b4,"
                     "gemv_b16 to run in the timed steps (profiling aid; the JSON line is then partial)")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed steps also time, on the same matrix: pvq_encode with least-squares "
+                    "amplitudes, and the D=16 / 52-bit index / 4-bit amplitude setting (generic kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (256 MiB read + 256 MiB written), so "
                     "that a counter run can scale FETCH_SIZE / WRITE_SIZE against a kernel of known traffic")
@@ -224,6 +227,31 @@ def main():
         },
         "input_generation_s": round(t_gen, 1),
     }
+
+    if args.extras:
+        def timed(fn, reps=5):
+            fn(); torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            for i in range(reps):
+                ev[i].record(); fn()
+            ev[reps].record(); torch.cuda.synchronize()
+            return sum(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) / reps
+        ex = {}
+        ctx.set_amplitude("ls")
+        ex["encode_ls_ms"] = round(timed(lambda: pvq.pvq_encode(ctx, W, out=sets[0])), 4)
+        ctx.set_amplitude("norm")
+        K16 = pvq.pvq_max_k(16, 52)
+        e16, c16 = pvq.pvq_beta_tables(16, COLS // 16, 4)
+        ctx16 = pvq.pvq_ctx_create(16, K16, 4, e16, c16)
+        ctx16.set_amplitude("ls")
+        p16 = pvq.alloc_packed(ctx16, ROWS, COLS, dev)
+        ex["d16_k33_4bit"] = {
+            "encode_ms": round(timed(lambda: pvq.pvq_encode(ctx16, W, out=p16)), 4),
+            "decode_ms": round(timed(lambda: pvq.pvq_decode(ctx16, p16, out=Wout)), 4),
+            "gemv_b1_ms": round(timed(lambda: pvq.pvq_decode_gemv(ctx16, p16, xs[1], out=ys[1])), 4),
+        }
+        ctx16.close()
+        result["extras"] = ex
 
     if not args.no_cpu_baseline:
         threads = min(os.cpu_count() or 1, 16)

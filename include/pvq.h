@@ -116,6 +116,20 @@ int pvq_ctx_destroy(pvq_ctx *ctx);
 int pvq_ctx_info(const pvq_ctx *ctx, int *D, int *K, int *index_bits, int *scale_bits);
 
 /*
+ * Which amplitude pvq_encode gives a group (host call, takes effect for later pvq_encode calls on
+ * this context; not to be changed while an encode of this context is being enqueued by another thread):
+ *   PVQ_AMP_NORM  the group's Euclidean norm (Sec. 2.3); the default.
+ *   PVQ_AMP_LS    the least-squares amplitude for the quantised direction, s = (y . w) / ||y||_2
+ *                 (Sec. 3.3 Step 4: the s that minimises ||w - s y/||y||_2||_2; the section prints the
+ *                 ratio of the two inner products upside down).  float32: the products y_i * w_i rounded
+ *                 one by one and summed over adjacent pairs, one square root, one division.
+ * With amplitude codes the quantised quantity is s^2 over the row's sum of s^2 in both cases
+ * (Sec. 3.3 Step 5), so decoding is the same.  PVQ_E_INVALID_ARG for another value.
+ */
+typedef enum { PVQ_AMP_NORM = 0, PVQ_AMP_LS = 1 } pvq_amplitude;
+int pvq_ctx_set_amplitude(pvq_ctx *ctx, int amplitude);
+
+/*
  * Sizes in bytes of the three planes for a rows x cols matrix (host out pointers, may be NULL):
  * index plane rows*ceil(G*index_bits/32)*4; scale plane rows*G*4 (scale_bits == 0) or
  * rows*ceil(G*scale_bits/32)*4; row normaliser rows*4.

@@ -15,7 +15,7 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables",
     "pvq_fast_tables_selftest",
-    "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_packed_sizes",
+    "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
 ]
 
@@ -55,6 +55,7 @@ def lib():
         L.pvq_ctx_create.argtypes = [vp, i32, i32, i32, vp, vp]
         L.pvq_ctx_destroy.argtypes = [vp]
         L.pvq_ctx_info.argtypes = [vp, vp, vp, vp, vp]
+        L.pvq_ctx_set_amplitude.argtypes = [vp, i32]
         L.pvq_packed_sizes.argtypes = [vp, i64, i64, vp, vp, vp]
         L.pvq_encode.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
@@ -132,6 +133,10 @@ class PvqContext:
     def handle(self):
         return self._h
 
+    def set_amplitude(self, kind: str):
+        """"norm": group norms (default); "ls": least-squares amplitudes (pvq_ctx_set_amplitude)."""
+        _check(lib().pvq_ctx_set_amplitude(self._h, {"norm": 0, "ls": 1}[kind]), "pvq_ctx_set_amplitude")
+
     def close(self):
         if self._h:
             h, self._h = self._h, C.c_void_p()
@@ -150,6 +155,10 @@ def pvq_ctx_create(D, K, scale_bits=0, edges=None, centers=None) -> PvqContext:
 
 def pvq_ctx_destroy(ctx: PvqContext):
     ctx.close()
+
+
+def pvq_ctx_set_amplitude(ctx: PvqContext, kind: str):
+    ctx.set_amplitude(kind)
 
 
 def pvq_packed_sizes(ctx: PvqContext, rows: int, cols: int):

@@ -143,7 +143,8 @@ __device__ inline uint32_t encode_group8(const float (&w)[D], int K, const uint3
 constexpr int kBlock = 256;
 constexpr int kMaxGroups = 4096;   // groups per row this kernel takes (their sums of squares sit in LDS)
 
-template <typename TIn, bool CODES>
+// LS: least-squares amplitudes (Sec. 3.3 Step 4) instead of norms.
+template <typename TIn, bool CODES, bool LS>
 __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_encode_args a)
 {
     extern __shared__ __align__(16) uint32_t smem[];
@@ -176,6 +177,9 @@ __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_enco
                 int y[D];
                 load8<TIn>(wrow + (int64_t)g * D, w);
                 c = encode_group8(w, K, offs, ss, y);
+                float amp;
+                if constexpr (LS) { amp = pvq_ls_amplitude<D>(w, y); ss = amp * amp; }
+                else amp = sqrtf(ss);
                 if (a.pulses_out) {
                     uint32_t lo = 0, hi = 0;
 #pragma unroll
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_enco
                     *reinterpret_cast<uint2 *>(a.pulses_out + row * a.cols + (int64_t)g * D) = make_uint2(lo, hi);
                 }
                 if constexpr (CODES) ss_row[g] = ss;
-                else reinterpret_cast<float *>(a.scale_out)[row * G + g] = sqrtf(ss);
+                else reinterpret_cast<float *>(a.scale_out)[row * G + g] = amp;
             }
             // four neighbouring 24-bit indices -> three dwords: lane j of a quad (j < 3) builds dword j
             // from its own index and the next lane's
@@ -252,12 +256,15 @@ hipError_t pvq_encode8_launch(const pvq_ctx *c, const pvq_encode_args &a, int dt
     // rows are strided over the blocks; enough blocks to fill every unit several times over
     const unsigned grid = (unsigned)std::min<int64_t>(a.rows, 8192);
     const bool codes = c->scale_bits > 0;
+#define PVQ_ENC8_CASE(T, C, L) hipLaunchKernelGGL((encode8_kernel<T, C, L>), dim3(grid), dim3(block), lds, s, f, a)
+    const bool ls = a.ls_amplitude != 0;
     if (dtype == PVQ_F32) {
-        if (codes) hipLaunchKernelGGL((encode8_kernel<float, true>), dim3(grid), dim3(block), lds, s, f, a);
-        else hipLaunchKernelGGL((encode8_kernel<float, false>), dim3(grid), dim3(block), lds, s, f, a);
+        if (codes) { if (ls) PVQ_ENC8_CASE(float, true, true); else PVQ_ENC8_CASE(float, true, false); }
+        else { if (ls) PVQ_ENC8_CASE(float, false, true); else PVQ_ENC8_CASE(float, false, false); }
     } else {
-        if (codes) hipLaunchKernelGGL((encode8_kernel<uint16_t, true>), dim3(grid), dim3(block), lds, s, f, a);
-        else hipLaunchKernelGGL((encode8_kernel<uint16_t, false>), dim3(grid), dim3(block), lds, s, f, a);
+        if (codes) { if (ls) PVQ_ENC8_CASE(uint16_t, true, true); else PVQ_ENC8_CASE(uint16_t, true, false); }
+        else { if (ls) PVQ_ENC8_CASE(uint16_t, false, true); else PVQ_ENC8_CASE(uint16_t, false, false); }
     }
+#undef PVQ_ENC8_CASE
     return hipGetLastError();
 }

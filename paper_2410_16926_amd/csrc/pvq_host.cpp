@@ -247,7 +247,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
-    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr;
+    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -325,6 +325,13 @@ extern "C" int pvq_ctx_info(const pvq_ctx *c, int *D, int *K, int *index_bits, i
     return PVQ_OK;
 }
 
+extern "C" int pvq_ctx_set_amplitude(pvq_ctx *c, int amplitude)
+{
+    if (!c || (amplitude != PVQ_AMP_NORM && amplitude != PVQ_AMP_LS)) return PVQ_E_INVALID_ARG;
+    c->amplitude = amplitude;
+    return PVQ_OK;
+}
+
 static int64_t stream_words(int64_t groups, int bits) { return (groups * bits + 31) / 32; }
 
 static int check_shape(const pvq_ctx *c, int64_t rows, int64_t cols)
@@ -380,6 +387,7 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
     if ((rc = check_device(c))) return rc;
 
     pvq_encode_args a;
+    a.ls_amplitude = c->amplitude == PVQ_AMP_LS ? 1 : 0;
     a.W = W; a.rows = rows; a.cols = cols; a.ldw = ldw; a.groups = cols / c->D;
     a.index_out = index_out; a.scale_out = scale_out; a.rownorm_out = rownorm_out;
     a.pulses_out = pulses_out;

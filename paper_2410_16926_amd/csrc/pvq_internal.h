@@ -29,12 +29,14 @@ struct pvq_ctx {
     // that flavour does not fit).
     unsigned char *fast8_blob, *fast8g_blob;
     pvq_fast8_params fast8, fast8g;
+    int amplitude;   // PVQ_AMP_NORM or PVQ_AMP_LS
     // Per-coordinate index offsets for the D = 8 / 24-bit encoder: [7][K+1][K+1][2] words
     // (coordinate, pulses left, magnitude, sign); nullptr when the configuration has none.
     uint32_t *enc8_offs;
 };
 
 struct pvq_encode_args {
+    int ls_amplitude;   // 1: least-squares amplitudes instead of norms
     const void *W;
     int64_t rows, cols, ldw, groups;
     uint32_t *index_out;
@@ -58,6 +60,25 @@ struct pvq_decode_args {
     float *y;
     int64_t ldy;
 };
+
+// Least-squares amplitude of a group for its point y (Sec. 3.3 Step 4): (y . w) / ||y||_2 in float32,
+// products rounded one by one and summed over adjacent pairs, level by level.
+template <int D>
+__device__ inline float pvq_ls_amplitude(const float (&w)[D], const int (&y)[D])
+{
+    float p[D];
+    int n2 = 0;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        p[i] = (float)y[i] * w[i];
+        n2 += y[i] * y[i];
+    }
+#pragma unroll
+    for (int s = 1; s < D; s *= 2)
+#pragma unroll
+        for (int i = 0; i < D; i += 2 * s) p[i] = p[i] + p[i + s];
+    return p[0] / sqrtf((float)n2);
+}
 
 // Each returns a hipError_t from the launch (hipSuccess if enqueued).
 hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);

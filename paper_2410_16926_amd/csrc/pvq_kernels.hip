@@ -258,11 +258,16 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(tables_t tb, pvq_encod
                 float w[D];
                 int y[D];
                 load_group<D, TIn>(wrow + (int64_t)g * D, w);
-                const float ss = quantize_group<D>(w, K, y);
+                float ss = quantize_group<D>(w, K, y);
                 const T c = rank_point<D, W>(y, K, tab_u);
                 stage_field<W>(stage, (uint32_t)tid * (uint32_t)b, b, c);
+                // the amplitude: the norm, or the least-squares one, whose square then stands for
+                // the sum of squares in the codes (Sec. 3.3 Steps 4 and 5)
+                float amp;
+                if (a.ls_amplitude) { amp = pvq_ls_amplitude<D>(w, y); ss = amp * amp; }
+                else amp = sqrtf(ss);
                 if (sb > 0) ss_row[g] = ss;
-                else reinterpret_cast<float *>(a.scale_out)[row * G + g] = sqrtf(ss);
+                else reinterpret_cast<float *>(a.scale_out)[row * G + g] = amp;
                 if (a.pulses_out) {
                     int8_t *p = a.pulses_out + row * a.cols + (int64_t)g * D;
 #pragma unroll

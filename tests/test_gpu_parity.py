@@ -14,14 +14,17 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def run_case(W32, D, K, scale_bits, src_bits=None, batches=(1, 4), out_dtypes=("f32", "f16", "bf16"), seed=1):
+def run_case(W32, D, K, scale_bits, src_bits=None, batches=(1, 4), out_dtypes=("f32", "f16", "bf16"), seed=1,
+             amplitude="l2"):
     rows, cols = W32.shape
     G = cols // D
     ctx, oe, oc = gu.make_ctx(D, K, scale_bits, G)
+    if amplitude == "ls":
+        ctx.set_amplitude("ls")
     Wd = gu.to_dev_bf16(src_bits) if src_bits is not None else gu.to_dev_f32(W32)
     packed = pvq.pvq_encode(ctx, Wd, want_pulses=True)
     torch.cuda.synchronize()
-    enc = oracle.encode(W32, D, K, scale_bits, oe, nthreads=8)
+    enc = oracle.encode(W32, D, K, scale_bits, oe, nthreads=8, amplitude=amplitude)
     gu.assert_encode_equal(packed, enc)
 
     ref, _, _ = oracle.decode(enc, oc, nthreads=8)
@@ -73,6 +76,28 @@ def test_d8_other_pulse_counts(K, bits):
     # indices that straddle words at varying offsets
     wf, wb = si.gaussian_weights(160, 2048, 0.015, seed=si.BASE_SEED + 60 + K, bf16=True)
     run_case(wf, 8, K, bits, src_bits=wb, batches=(1, 2, 5))
+
+
+@pytest.mark.parametrize("D,budget,bits,bf16", [(8, 24, 0, True), (8, 24, 2, True), (8, 24, 8, False),
+                                                (16, 52, 0, False), (16, 52, 4, True), (32, 104, 0, True)])
+def test_least_squares_amplitudes(D, budget, bits, bf16):
+    # Sec. 3.3 Step 4 amplitudes (and their codes) instead of group norms; D = 16 with 4-bit codes is
+    # the paper's 3.25 bits/weight setting
+    K = pvq.pvq_max_k(D, budget)
+    if bf16:
+        wf, wb = si.gaussian_weights(128, 2048, 0.015, seed=si.BASE_SEED + 70 + D + bits, bf16=True)
+        run_case(wf, D, K, bits, src_bits=wb, batches=(1, 4), amplitude="ls")
+    else:
+        W = si.gaussian_weights(128, 2048, 0.02, seed=si.BASE_SEED + 70 + D + bits)
+        run_case(W, D, K, bits, batches=(1,), amplitude="ls")
+
+
+def test_least_squares_amplitudes_adversarial():
+    # ties, zeros (amplitude 0), one-hot groups, wide dynamic range
+    n = 1 << 14
+    W = si.adversarial_groups(n, 8, seed=91).reshape(n * 8 // 2048, 2048)
+    run_case(W, 8, 16, 0, batches=(1,), out_dtypes=("f32",), amplitude="ls")
+    run_case(W, 8, 16, 2, batches=(1,), out_dtypes=("f32",), amplitude="ls")
 
 
 @pytest.mark.parametrize("D,budget,bits", [(16, 52, 4), (32, 104, 8)])

@@ -2,8 +2,9 @@
 //
 // Same arithmetic, in the same order, as the generic encoder (pvq_kernels.hip) — results are bit for
 // bit the same — but organised for throughput:
-//   * one lane per group, one workgroup of up to 1024 lanes per row tile, so a row of 8192 weights is
-//     one pass;
+//   * one lane per group, workgroups of 256 lanes that take whole rows, 256 groups at a time (several
+//     workgroups share a compute unit, so one's loads and barriers hide behind the others' arithmetic;
+//     1024-lane workgroups measured twice as slow);
 //   * the pulse-count repair (Sec. 2.5) is branch-free: every coordinate's place in the order of
 //     deviations is counted with 28 comparisons, and the |sum - K| first places are adjusted.  This
 //     equals the one-at-a-time repair because no coordinate is ever adjusted twice (for finite

@@ -51,8 +51,8 @@ struct pvq_fast8_params {
     uint32_t s0_outside;  // 1: S0's block table lies behind tab_bytes and is read from the blob in
                           // device memory (and S0's bucket entries are two-candidate ones)
     uint32_t n_minus_1;   // N(8,K) - 1: stored indices are clamped to it
-    uint32_t bk0, bl0;    // byte offsets of S0's bucket table and block table
-    uint32_t bl1, bl2;    // S1 / S2 block tables (their bucket rows are reached through meta)
+    uint32_t bk0, bk1, bk2, t3;   // byte offsets of the three bucket tables and of T3
+    uint32_t bl0, bl1, bl2;       // ... and of the three block tables
     uint32_t invs;        // float [K*K + 1]: 1 / sqrt(n2), indexed by n2 (entry 0 = 0)
     uint32_t s0, s1, s2;  // bucket shifts of the three searched stages
     uint32_t k2max;       // n2 <= K*K
@@ -75,8 +75,9 @@ constexpr uint32_t kFast8MaxShift = 13;
 constexpr uint32_t kFast8MaxBytes = 160 * 1024 - 5120;
 
 // block entry (16 bytes, read as one uint4): x = start, y = end (0xFFFFFFFF for the last block of a
-// row), z = values as bf16 pair, w = meta = 4*(a^2+b^2) in bits 0..10 | byte offset of the next
-// stage's row << 14
+// row), z = values as bf16 pair, w = meta = 4*(a^2+b^2).  start and end are biased: a residual is
+// carried as r + (its row's first bucket in the stage's bucket table) << shift, so that r >> shift
+// finds the bucket without a row offset; x = start + this row's bias - the next stage's row bias.
 struct pvq_fast8_block {
     uint32_t start, end, values, meta;
 };
@@ -84,18 +85,18 @@ struct pvq_fast8_block {
 // A searched stage for NG independent groups at once, in two halves so that all bucket reads are
 // issued together and then all block reads (the latencies of the groups overlap instead of adding up).
 //
-// First half: the bucket lookups.  `row[j]` = byte offset of the bucket row for group j's current
-// k; returns in addr[j] the byte offset of the block entry chosen for r[j].
+// First half: the bucket lookups in the stage's bucket table at byte offset `bk` (r is biased with
+// its row, see the block entry); returns in addr[j] the byte offset of the block entry chosen for r[j].
 // MODE 0: two-candidate 32-bit entries; 1: next-block 32-bit entries; 2: next-block 16-bit entries.
 template <int NG, int MODE>
-PVQ_HD void pvq_fast8_find(const unsigned char *lds, const uint32_t (&row)[NG], uint32_t shift, uint32_t bl,
+PVQ_HD void pvq_fast8_find(const unsigned char *lds, uint32_t bk, uint32_t shift, uint32_t bl,
                            const uint32_t (&r)[NG], uint32_t (&addr)[NG])
 {
     uint32_t e[NG];
 #pragma unroll
     for (int j = 0; j < NG; j++) {
-        if constexpr (MODE == 2) e[j] = *reinterpret_cast<const uint16_t *>(lds + row[j] + (r[j] >> shift) * 2u);
-        else e[j] = *reinterpret_cast<const uint32_t *>(lds + row[j] + (r[j] >> shift) * 4u);
+        if constexpr (MODE == 2) e[j] = *reinterpret_cast<const uint16_t *>(lds + bk + (r[j] >> shift) * 2u);
+        else e[j] = *reinterpret_cast<const uint32_t *>(lds + bk + (r[j] >> shift) * 4u);
     }
 #pragma unroll
     for (int j = 0; j < NG; j++) {
@@ -122,11 +123,12 @@ PVQ_HD void pvq_fast8_find(const unsigned char *lds, const uint32_t (&row)[NG], 
 template <int NG, typename AddrOf>
 PVQ_HD void pvq_fast8_settle(const unsigned char *mem, uint32_t (&r)[NG], pvq_u32x4 (&b)[NG], AddrOf &&addr_of)
 {
-    bool miss = false;
+    bool miss = false, mj[NG];
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         PVQ_KEEP_TOGETHER(b[j]);
-        miss = miss || r[j] >= b[j].y;
+        mj[j] = r[j] >= b[j].y;
+        miss = miss || mj[j];
     }
     if (miss) {
         // (stepping all NG groups together, one round trip per step of the furthest group, measured
@@ -135,10 +137,12 @@ PVQ_HD void pvq_fast8_settle(const unsigned char *mem, uint32_t (&r)[NG], pvq_u3
         addr_of(addr);
 #pragma unroll
         for (int j = 0; j < NG; j++) {
-            while (r[j] >= b[j].y) {
-                addr[j] += 16;
-                b[j] = *reinterpret_cast<const pvq_u32x4 *>(mem + addr[j]);
-                PVQ_KEEP_TOGETHER(b[j]);
+            if (mj[j]) {
+                do {
+                    addr[j] += 16;
+                    b[j] = *reinterpret_cast<const pvq_u32x4 *>(mem + addr[j]);
+                    PVQ_KEEP_TOGETHER(b[j]);
+                } while (r[j] >= b[j].y);
             }
         }
     }
@@ -148,11 +152,11 @@ PVQ_HD void pvq_fast8_settle(const unsigned char *mem, uint32_t (&r)[NG], pvq_u3
 
 // both halves, block table in LDS
 template <int NG, int MODE>
-PVQ_HD void pvq_fast8_stage(const unsigned char *lds, const uint32_t (&row)[NG], uint32_t shift, uint32_t bl,
+PVQ_HD void pvq_fast8_stage(const unsigned char *lds, uint32_t bk, uint32_t shift, uint32_t bl,
                             uint32_t (&r)[NG], pvq_u32x4 (&b)[NG])
 {
     uint32_t addr[NG];
-    pvq_fast8_find<NG, MODE>(lds, row, shift, bl, r, addr);
+    pvq_fast8_find<NG, MODE>(lds, bk, shift, bl, r, addr);
 #pragma unroll
     for (int j = 0; j < NG; j++) b[j] = *reinterpret_cast<const pvq_u32x4 *>(lds + addr[j]);
     pvq_fast8_settle<NG>(lds, r, b, [&](uint32_t (&out)[NG]) {
@@ -168,13 +172,9 @@ template <int NG, bool OUTSIDE>
 PVQ_HD void pvq_fast8_s0_find(const unsigned char *lds, const pvq_fast8_params &p, const uint32_t (&c)[NG],
                               uint32_t (&r)[NG], uint32_t (&addr)[NG])
 {
-    uint32_t row[NG];
 #pragma unroll
-    for (int j = 0; j < NG; j++) {
-        r[j] = c[j] < p.n_minus_1 ? c[j] : p.n_minus_1;
-        row[j] = p.bk0;
-    }
-    pvq_fast8_find<NG, OUTSIDE ? 0 : 1>(lds, row, p.s0, p.bl0, r, addr);
+    for (int j = 0; j < NG; j++) r[j] = c[j] < p.n_minus_1 ? c[j] : p.n_minus_1;
+    pvq_fast8_find<NG, OUTSIDE ? 0 : 1>(lds, p.bk0, p.s0, p.bl0, r, addr);
 }
 
 // The rest of the decoder, from S0's block entries b (as read from the addresses that
@@ -187,22 +187,22 @@ template <int NG, bool OUTSIDE, typename Emit>
 PVQ_HD void pvq_fast8_rest(const unsigned char *lds, const unsigned char *blob, const pvq_fast8_params &p,
                            uint32_t (&r)[NG], pvq_u32x4 (&b)[NG], Emit &&emit, uint32_t (&n2x4)[NG])
 {
-    uint32_t row[NG], acc[NG], y4[NG];
+    uint32_t acc[NG], y4[NG];
     pvq_fast8_settle<NG>(OUTSIDE ? blob : lds, r, b, [&](uint32_t (&out)[NG]) {
         uint32_t same[NG];
         pvq_fast8_s0_find<NG, OUTSIDE>(lds, p, r, same, out);
     });
 #pragma unroll
-    for (int j = 0; j < NG; j++) { emit(j, 0, b[j].z); acc[j] = b[j].w; row[j] = b[j].w >> 14; }
-    pvq_fast8_stage<NG, 0>(lds, row, p.s1, p.bl1, r, b);
+    for (int j = 0; j < NG; j++) { emit(j, 0, b[j].z); acc[j] = b[j].w; }
+    pvq_fast8_stage<NG, 0>(lds, p.bk1, p.s1, p.bl1, r, b);
 #pragma unroll
-    for (int j = 0; j < NG; j++) { emit(j, 1, b[j].z); acc[j] += b[j].w; row[j] = b[j].w >> 14; }
-    pvq_fast8_stage<NG, 2>(lds, row, p.s2, p.bl2, r, b);
+    for (int j = 0; j < NG; j++) { emit(j, 1, b[j].z); acc[j] += b[j].w; }
+    pvq_fast8_stage<NG, 2>(lds, p.bk2, p.s2, p.bl2, r, b);
 #pragma unroll
-    for (int j = 0; j < NG; j++) { y4[j] = b[j].z; acc[j] += b[j].w; row[j] = (b[j].w >> 14) + (r[j] << 3); }
+    for (int j = 0; j < NG; j++) { y4[j] = b[j].z; acc[j] += b[j].w; }
     pvq_u32x2 t[NG];
 #pragma unroll
-    for (int j = 0; j < NG; j++) t[j] = *reinterpret_cast<const pvq_u32x2 *>(lds + row[j]);
+    for (int j = 0; j < NG; j++) t[j] = *reinterpret_cast<const pvq_u32x2 *>(lds + p.t3 + (r[j] << 3));
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         emit(j, 2, (t[j].x & 0xFFFF0000u) | y4[j]);

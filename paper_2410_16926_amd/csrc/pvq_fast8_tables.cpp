@@ -72,11 +72,13 @@ void build_bucket_row(const std::vector<Block> &blocks, uint32_t first_index, ui
 }
 
 // Bucket row in the next-block form: (index of A - bucket number) << shift, plus 2^shift minus the
-// start of the block after A inside the bucket (nothing if it starts beyond the bucket).
+// start of the block after A inside the bucket (nothing if it starts beyond the bucket).  The bucket
+// number counts over all rows of the stage, as the biased residuals do (see write_blocks).
 template <typename E>
 void build_next_bucket_row(const std::vector<Block> &blocks, uint32_t first_index, uint64_t total, int shift,
                            std::vector<E> &out)
 {
+    const uint64_t row_bucket = out.size();   // the row's first bucket, counted over the whole stage
     const uint64_t width = (uint64_t)1 << shift;
     const uint64_t nb = (total + width - 1) / width;
     size_t a = 0;
@@ -85,7 +87,7 @@ void build_next_bucket_row(const std::vector<Block> &blocks, uint32_t first_inde
         while (a + 1 < blocks.size() && blocks[a + 1].start <= lo) a++;
         uint64_t low = 0;
         if (a + 1 < blocks.size() && blocks[a + 1].start < hi) low = width - (blocks[a + 1].start - lo);
-        const uint64_t high = (uint64_t)first_index + a - j;   // modulo the entry width
+        const uint64_t high = (uint64_t)first_index + a - (row_bucket + j);   // modulo the entry width
         out.push_back((E)((high << shift) + low));
     }
 }
@@ -195,22 +197,34 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     if (s0_outside) { o_bl0 = off; off = up16(off + nblk0 * 16); }
     if (tab_bytes > max_bytes || off >= ((size_t)1 << 18)) return false;
 
-    auto write_blocks = [&](const std::vector<std::vector<Block>> &rows, auto next_row_offset) {
+    // Residuals travel biased: inside stage S a residual r of row k is kept as r + (first bucket of
+    // row k, counted over the stage) << shift_S, so that r >> shift_S is the bucket's place in the
+    // stage's whole bucket table and no row offset has to be carried or added.  A block entry's
+    // `start` therefore holds start + this row's bias - the next stage's row bias, and `end` holds
+    // end + this row's bias.  For T3 the bias is the row's first entry (shift 0).
+    auto write_blocks = [&](const std::vector<std::vector<Block>> &rows, auto row_bias, auto next_bias) {
         std::vector<pvq_fast8_block> v;
-        for (auto &row : rows)
+        for (size_t k = 0; k < rows.size(); k++) {
+            const auto &row = rows[k];
+            // S0 has a single row, reached with k = K pulses and no bias
+            const uint32_t bias = row_bias((int)k);
             for (size_t i = 0; i < row.size(); i++) {
                 pvq_fast8_block e;
-                e.start = (uint32_t)row[i].start;
-                e.end = i + 1 < row.size() ? (uint32_t)(row[i].start + row[i].size) : 0xFFFFFFFFu;
+                e.start = (uint32_t)row[i].start + bias - next_bias(row[i].next_k);
+                e.end = i + 1 < row.size() ? (uint32_t)(row[i].start + row[i].size) + bias : 0xFFFFFFFFu;
                 e.values = row[i].values;
-                e.meta = row[i].n2x4 | ((uint32_t)next_row_offset(row[i].next_k) << 14);
+                e.meta = row[i].n2x4;
                 v.push_back(e);
             }
+        }
         return v;
     };
-    const auto bl0 = write_blocks(rows0, [&](int k) { return o_bk1 + bk1_row[k]; });
-    const auto bl1 = write_blocks(rows1, [&](int k) { return o_bk2 + bk2_row[k]; });
-    const auto bl2 = write_blocks(rows2, [&](int k) { return o_t3 + t3_row[k]; });
+    auto bias1 = [&](int k) { return (bk1_row[k] / 4u) << s1; };
+    auto bias2 = [&](int k) { return (bk2_row[k] / 2u) << s2; };
+    auto bias3 = [&](int k) { return t3_row[k] / 8u; };
+    const auto bl0 = write_blocks(rows0, [&](int) { return 0u; }, bias1);
+    const auto bl1 = write_blocks(rows1, bias1, bias2);
+    const auto bl2 = write_blocks(rows2, bias2, bias3);
     std::vector<float> invs((size_t)K * K + 1);
     invs[0] = 0.0f;
     for (int n2 = 1; n2 <= K * K; n2++) invs[n2] = (float)(1.0 / std::sqrt((double)n2));
@@ -229,7 +243,8 @@ bool build_with_shifts(int K, const SmallTable &N, int s0, int s1, int s2, uint3
     p.tab_bytes = (uint32_t)tab_bytes;
     p.s0_outside = s0_outside ? 1u : 0u;
     p.n_minus_1 = (uint32_t)(N.at(8, K) - 1);
-    p.bk0 = (uint32_t)o_bk0; p.bl0 = (uint32_t)o_bl0; p.bl1 = (uint32_t)o_bl1; p.bl2 = (uint32_t)o_bl2;
+    p.bk0 = (uint32_t)o_bk0; p.bk1 = (uint32_t)o_bk1; p.bk2 = (uint32_t)o_bk2; p.t3 = (uint32_t)o_t3;
+    p.bl0 = (uint32_t)o_bl0; p.bl1 = (uint32_t)o_bl1; p.bl2 = (uint32_t)o_bl2;
     p.invs = (uint32_t)o_invs;
     p.s0 = s0; p.s1 = s1; p.s2 = s2;
     p.k2max = (uint32_t)(K * K);

@@ -94,7 +94,8 @@ __device__ inline uint32_t encode_group8(const float (&w)[D], int K, const uint3
     ss_out = tree8(tmp);
 
     const float g = (float)K / l1;
-    const bool degenerate = !(l1 > 0.0f) || !(fabsf(g) < INFINITY);
+    // no direction: all zeros, a norm whose reciprocal overflows, or anything not finite
+    const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(g < INFINITY);
     // from here on every t is finite and within [0, K(1+eps)] unless `degenerate`
     float t[D], yf[D];
     float S = 0.0f;
@@ -121,15 +122,19 @@ __device__ inline uint32_t encode_group8(const float (&w)[D], int K, const uint3
     for (int i = 0; i < D; i++) {
         const bool adjust = wins[i] + need >= D;      // place = D-1-wins < need
         int mag = (int)(yf[i] + (adjust ? unit : 0.0f));
-        const int neg = w[i] < 0.0f ? 1 : 0;
+        // sign bit of the weight; a degenerate group takes +K.  (-0.0 never carries a pulse: a
+        // coordinate whose projection is zero is not among the ones raised.)
+        const uint32_t neg = __float_as_uint(w[i]) >> 31;
         if (degenerate) mag = (i == D - 1) ? K : 0;
-        // table bounds and a point on the pyramid whatever the input was: the last coordinate takes
-        // what is left (for finite input that is what it holds anyway)
-        mag = (i == D - 1) ? k : max(0, min(mag, k));
+        // the magnitudes of the adjusted point lie in [0, k] and sum to K (a degenerate group was
+        // given its point just above); the last coordinate takes what is left
+        if (i == D - 1) mag = k;
         y[i] = (neg && !degenerate) ? -mag : mag;
         if (i < D - 1) {
-            // offs[i][k][mag][neg]: what coordinate i adds to the index with k pulses left (App. B.2)
-            c += offs[(((i * (K + 1) + k) * (K + 1)) + mag) * 2 + (degenerate ? 0 : neg)];
+            // offs[i][k][mag][neg]: what coordinate i adds to the index with k pulses left (App. B.2);
+            // with mag = 0 both signs hold 0
+            // (24-bit multiplies: everything here is far below 2^24)
+            c += offs[(__mul24(i * (K + 1) + k, K + 1) + mag) * 2 + neg];
             k -= mag;
         } else {
             c += (neg && !degenerate && k > 0) ? 1u : 0u;

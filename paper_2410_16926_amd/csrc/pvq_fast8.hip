@@ -404,6 +404,125 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq
     }
 }
 
+// Sixteen activation vectors in one pass over the codes.  With four neighbouring groups per lane the
+// activations of 16 vectors would need 256 registers, so here a lane owns ONE group column (a wave
+// covers 64 consecutive groups of a row, 64 registers of activations) and keeps four ROWS in flight
+// instead: the four table walks overlap as in the other kernels, and every decoded group is used for
+// 16 dot products.  Waves: nsl slices of 64 groups x rl row lanes.  Per row and vector the wave's
+// sum goes to LDS, where the slices' partial sums meet in slice order (deterministic).
+// AMP: 0 = float32 amplitudes, 1 = amplitude codes.
+constexpr int kWide = 16;            // vectors per pass
+constexpr int kWideRows = 4;         // rows a wave keeps in flight
+constexpr size_t kWidePartBytes = 64 * kWide * sizeof(float);   // (row, slice) pairs of a batch x vectors
+
+template <int AMP, bool B24>
+__global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f, pvq_decode_args a, int b0,
+                                                                  int nsl, int rl, int rows_per_block)
+{
+    constexpr bool CODES = AMP != 0;
+    constexpr int RI = kWideRows, NB = kWide;
+    __shared__ __align__(16) unsigned char lds[kLdsBytes];
+    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.tab_bytes);
+    float *part = sqrtc_l + 256;
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
+    const int64_t r_last = r_end - 1;
+    const int G = (int)a.groups;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int slice = wave % nsl, rowlane = wave / nsl;
+    const int g = slice * kWave + lane;
+    const bool in_row = g < G;
+    const uint32_t gc = in_row ? (uint32_t)g : 0u;     // lanes beyond the row decode its first group against zeros
+    const int RB = RI * rl;
+
+    // what a lane fetches per row: the dword that holds its index, and its amplitude (code word or float)
+    struct item { uint32_t w, s; };
+    auto fetch = [&](int64_t row, item &it) {
+        row = std::min<int64_t>(row, r_last);
+        const unsigned char *irow = reinterpret_cast<const unsigned char *>(a.index + row * a.index_row_words);
+        if constexpr (B24) {
+            // the 3 bytes of group g start at byte 3g; one dword load from byte 3g-1 (3g for g = 0)
+            // holds them and stays inside the row
+            uint32_t v;
+            __builtin_memcpy(&v, irow + 3u * gc - (gc > 0 ? 1u : 0u), 4);
+            it.w = v;
+        } else {
+            const uint32_t b = (uint32_t)f.index_bits;
+            const uint32_t pos = gc * b, w0 = pos >> 5, sh = pos & 31;
+            uint64_t v = reinterpret_cast<const uint32_t *>(irow)[w0];
+            if (sh + b > 32) v |= (uint64_t)reinterpret_cast<const uint32_t *>(irow)[w0 + 1] << 32;
+            it.w = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
+        }
+        if constexpr (CODES)
+            it.s = (reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words)[(gc * (uint32_t)f.scale_bits) >> 5];
+        else
+            it.s = __float_as_uint(reinterpret_cast<const float *>(a.scale)[row * a.groups + gc]);
+    };
+
+    item cur[RI];
+    if (r_begin < r_end) {
+#pragma unroll
+        for (int i = 0; i < RI; i++) fetch(r_begin + i * rl + rowlane, cur[i]);
+    }
+    load_tables<false>(lds, f, sqrtc_l);
+    if (r_begin >= r_end) return;
+
+    uint32_t xr[NB][4];
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (in_row)
+            v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + b) * a.ldx + (int64_t)g * 8);
+        xr[b][0] = v.x; xr[b][1] = v.y; xr[b][2] = v.z; xr[b][3] = v.w;
+    }
+
+    for (int64_t batch = r_begin; batch < r_end; batch += RB) {
+        uint32_t c[RI], pr[RI][4], n2x4[RI];
+        float amp[RI];
+#pragma unroll
+        for (int i = 0; i < RI; i++) {
+            if constexpr (B24) c[i] = gc > 0 ? cur[i].w >> 8 : cur[i].w & 0xFFFFFFu;
+            else c[i] = cur[i].w;
+            if constexpr (CODES) {
+                const uint32_t code = (cur[i].s >> ((gc * (uint32_t)f.scale_bits) & 31u)) & ((1u << f.scale_bits) - 1u);
+                amp[i] = sqrtc_l[code];
+            } else {
+                amp[i] = __uint_as_float(cur[i].s);
+            }
+            // the registers of the consumed row take this wave's row of the next batch
+            fetch(batch + RB + i * rl + rowlane, cur[i]);
+        }
+        pvq_fast8_decode<RI, false>(lds, f.blob, f.p, c, pr, n2x4);
+#pragma unroll
+        for (int i = 0; i < RI; i++) {
+            const float gain = amp[i] * *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[i]);
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                float s = dot2_bf16(pr[i][0], xr[b][0], 0.0f);
+                s = dot2_bf16(pr[i][1], xr[b][1], s);
+                s = dot2_bf16(pr[i][2], xr[b][2], s);
+                s = dot2_bf16(pr[i][3], xr[b][3], s);
+                const float v = wave_sum_lane63(gain * s);
+                if (lane == kWave - 1) part[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < RB * NB) {
+            const int rloc = threadIdx.x / NB, b = threadIdx.x % NB;
+            const int64_t row = batch + rloc;
+            if (row < r_end) {
+                float v = 0.0f;
+                for (int s = 0; s < nsl; s++) v += part[(rloc * nsl + s) * NB + b];
+                if constexpr (CODES) v *= sqrtf(a.rownorm[row]);
+                a.y[(int64_t)(b0 + b) * a.ldy + row] = v;
+            }
+        }
+        __syncthreads();   // `part` is rewritten by the next batch
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // decode to a matrix
 // ---------------------------------------------------------------------------------------------
@@ -600,6 +719,38 @@ hipError_t launch_gemv_pass(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
 
 }  // namespace
 
+namespace {
+
+// one launch of the 16-vector kernel for vectors [b0, b0 + 16)
+hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, hipStream_t s)
+{
+    const fast8_launch f = make_launch(c, false);
+    const int nsl = (int)((a.groups + kWave - 1) / kWave);
+    const int rl = std::max(1, (kGemvThreads / kWave) / nsl);
+    const int RB = kWideRows * rl;
+    const int64_t batches = (a.rows + RB - 1) / RB;
+    const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
+    const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);
+    const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)(kWave * nsl * rl));
+    const bool b24 = f.index_bits == 24, codes = f.scale_bits > 0;
+#define PVQ_WIDE_CASE(AMP, B24) \
+    hipLaunchKernelGGL((gemv8_wide_kernel<AMP, B24>), grid, block, 0, s, f, a, b0, nsl, rl, rows_per_block)
+    if (codes) { if (b24) PVQ_WIDE_CASE(1, true); else PVQ_WIDE_CASE(1, false); }
+    else { if (b24) PVQ_WIDE_CASE(0, true); else PVQ_WIDE_CASE(0, false); }
+#undef PVQ_WIDE_CASE
+    return hipGetLastError();
+}
+
+// the 16-vector kernel takes rows of at most 16 slices of 64 groups whose tables, amplitude table and
+// partial sums fit LDS together
+bool wide_usable(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    return (a.groups + kWave - 1) / kWave <= kGemvThreads / kWave &&
+           (size_t)c->fast8.tab_bytes + 256 * sizeof(float) + kWidePartBytes <= (size_t)kLdsBytes;
+}
+
+}  // namespace
+
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
 {
     // a single vector runs S0 a row ahead (if the tables exist in that flavour); with more vectors
@@ -609,7 +760,8 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
     while (b0 < a.batch) {
         const int left = a.batch - b0;
         hipError_t e;
-        if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
+        if (left >= kWide && wide_usable(c, a)) { e = launch_gemv_wide(c, a, b0, s); b0 += kWide; }
+        else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
         else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }
         if (e != hipSuccess) return e;

@@ -58,7 +58,7 @@ def test_config0_512x512_fp32_amplitudes():
 def test_amplitude_codes_bf16_source(bits):
     # the Llama-3-8B up-projection family (bf16 source, N(0, 0.015^2), 4096 inputs), a row slice
     wf, wb = si.gaussian_weights(192, 4096, 0.015, seed=si.BASE_SEED + 1, bf16=True)
-    run_case(wf, 8, 16, bits, src_bits=wb, batches=(1, 4))
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(1, 4, 16) if bits in (2, 8) else (1, 4))
 
 
 @pytest.mark.parametrize("D,budget", [(16, 52), (32, 104), (16, 64), (8, 40), (16, 30), (32, 32)])

@@ -404,6 +404,37 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq
     }
 }
 
+// Sums of 16 per-lane values over the 64 lanes, all 16 at once: at each of the first four steps a lane
+// hands half of its values to the partner lane (lane ^ 1, 2, 4, 8) and adds the partner's other half
+// to the ones it keeps, so the work halves every step (8 + 4 + 2 + 1 additions instead of 16 per
+// step); two more steps add the four rows of 16 lanes.  Returns, in every lane, the total of vector
+// number  8*(lane&1) + 4*((lane>>1)&1) + 2*((lane>>2)&1) + ((lane>>3)&1).  Fixed order.
+__device__ inline float wave_sum16(const float (&a)[16], int lane)
+{
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+    float n8[8], n4[4], n2[2];
+#pragma unroll
+    for (int c = 0; c < 8; c++) {
+        const float keep = b0 ? a[c + 8] : a[c], send = b0 ? a[c] : a[c + 8];
+        n8[c] = keep + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));
+    }
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const float keep = b1 ? n8[c + 4] : n8[c], send = b1 ? n8[c] : n8[c + 4];
+        n4[c] = keep + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x4E, 0xF, 0xF, false));
+    }
+#pragma unroll
+    for (int c = 0; c < 2; c++) {
+        const float keep = b2 ? n4[c + 2] : n4[c], send = b2 ? n4[c] : n4[c + 2];
+        n2[c] = keep + __shfl_xor(send, 4, kWave);
+    }
+    const float keep = b3 ? n2[1] : n2[0], send = b3 ? n2[0] : n2[1];
+    float v = keep + __shfl_xor(send, 8, kWave);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
 // Sixteen activation vectors in one pass over the codes.  With four neighbouring groups per lane the
 // activations of 16 vectors would need 256 registers, so here a lane owns ONE group column (a wave
 // covers 64 consecutive groups of a row, 64 registers of activations) and keeps four ROWS in flight
@@ -436,6 +467,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
     const bool in_row = g < G;
     const uint32_t gc = in_row ? (uint32_t)g : 0u;     // lanes beyond the row decode its first group against zeros
     const int RB = RI * rl;
+    // the vector whose wave total wave_sum16 leaves in this lane
+    const int my_vector = 8 * (lane & 1) + 4 * ((lane >> 1) & 1) + 2 * ((lane >> 2) & 1) + ((lane >> 3) & 1);
 
     // what a lane fetches per row: the dword that holds its index, and its amplitude (code word or float)
     struct item { uint32_t w, s; };
@@ -498,15 +531,17 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
 #pragma unroll
         for (int i = 0; i < RI; i++) {
             const float gain = amp[i] * *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[i]);
+            float acc[NB];
 #pragma unroll
             for (int b = 0; b < NB; b++) {
                 float s = dot2_bf16(pr[i][0], xr[b][0], 0.0f);
                 s = dot2_bf16(pr[i][1], xr[b][1], s);
                 s = dot2_bf16(pr[i][2], xr[b][2], s);
                 s = dot2_bf16(pr[i][3], xr[b][3], s);
-                const float v = wave_sum_lane63(gain * s);
-                if (lane == kWave - 1) part[((i * rl + rowlane) * nsl + slice) * NB + b] = v;
+                acc[b] = gain * s;
             }
+            const float v = wave_sum16(acc, lane);
+            if (lane < NB) part[((i * rl + rowlane) * nsl + slice) * NB + my_vector] = v;
         }
         __syncthreads();
         if ((int)threadIdx.x < RB * NB) {

@@ -437,13 +437,13 @@ __device__ inline float wave_sum16(const float (&a)[16], int lane)
 
 // Sixteen activation vectors in one pass over the codes.  With four neighbouring groups per lane the
 // activations of 16 vectors would need 256 registers, so here a lane owns ONE group column (a wave
-// covers 64 consecutive groups of a row, 64 registers of activations) and keeps four ROWS in flight
-// instead: the four table walks overlap as in the other kernels, and every decoded group is used for
+// covers 64 consecutive groups of a row, 64 registers of activations) and keeps three ROWS in flight
+// instead (a fourth spills registers and measured slower): the table walks overlap as in the other kernels, and every decoded group is used for
 // 16 dot products.  Waves: nsl slices of 64 groups x rl row lanes.  Per row and vector the wave's
 // sum goes to LDS, where the slices' partial sums meet in slice order (deterministic).
 // AMP: 0 = float32 amplitudes, 1 = amplitude codes.
 constexpr int kWide = 16;            // vectors per pass
-constexpr int kWideRows = 4;         // rows a wave keeps in flight
+constexpr int kWideRows = 3;         // rows a wave keeps in flight
 constexpr size_t kWidePartBytes = 64 * kWide * sizeof(float);   // (row, slice) pairs of a batch x vectors
 
 template <int AMP, bool B24>

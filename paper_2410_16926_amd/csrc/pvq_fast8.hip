@@ -72,38 +72,39 @@ struct item_t {
     uint32_t a[kGroupsPerLane];   // amplitude: the code word holding group g's code, or the float's bits
 };
 
+// Branch-free on purpose: every lane loads (lanes beyond the row re-read its first group, a wave
+// past its last item re-reads a valid one).  With loads under conditions the compiler cannot count
+// how many are in flight and makes every use of an item wait for ALL outstanding memory operations,
+// the stores of the previous item included.
 template <bool CODES, bool B24>
 __device__ inline void fetch_item(const fast8_launch &f, const pvq_decode_args &a, int64_t row, int gbase,
-                                  bool live, item_t &it)
+                                  item_t &it)
 {
     const int G = (int)a.groups;
     const uint32_t *irow = a.index + row * a.index_row_words;
 #pragma unroll
     for (int j = 0; j < kGroupsPerLane; j++) {
-        const int g = gbase + kWave * j;
-        it.w[j] = 0;
-        it.a[j] = 0;
-        if (live && g < G) {
-            if constexpr (B24) {
-                // the 3 bytes of group g start at byte 3g; one dword load from byte 3g-1 (3g for g = 0)
-                // holds them and stays inside the row
-                const unsigned char *p = reinterpret_cast<const unsigned char *>(irow) + 3 * g - (g > 0 ? 1 : 0);
-                uint32_t v;
-                __builtin_memcpy(&v, p, 4);
-                it.w[j] = v;
-            } else {
-                const uint32_t b = (uint32_t)f.index_bits;
-                const uint32_t pos = (uint32_t)g * b, w0 = pos >> 5, sh = pos & 31;
-                uint64_t v = irow[w0];
-                if (sh + b > 32) v |= (uint64_t)irow[w0 + 1] << 32;
-                it.w[j] = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
-            }
-            if constexpr (CODES) {
-                const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
-                it.a[j] = srow[((uint32_t)g * (uint32_t)f.scale_bits) >> 5];
-            } else {
-                it.a[j] = __float_as_uint(reinterpret_cast<const float *>(a.scale)[row * a.groups + g]);
-            }
+        const int gj = gbase + kWave * j;
+        const int g = gj < G ? gj : 0;
+        if constexpr (B24) {
+            // the 3 bytes of group g start at byte 3g; one dword load from byte 3g-1 (3g for g = 0)
+            // holds them and stays inside the row
+            const unsigned char *p = reinterpret_cast<const unsigned char *>(irow) + 3 * g - (g > 0 ? 1 : 0);
+            uint32_t v;
+            __builtin_memcpy(&v, p, 4);
+            it.w[j] = v;
+        } else {
+            const uint32_t b = (uint32_t)f.index_bits;
+            const uint32_t pos = (uint32_t)g * b, w0 = pos >> 5, sh = pos & 31;
+            uint64_t v = irow[w0];
+            if (sh + b > 32) v |= (uint64_t)irow[w0 + 1] << 32;
+            it.w[j] = (uint32_t)(v >> sh) & (uint32_t)((1ull << b) - 1ull);
+        }
+        if constexpr (CODES) {
+            const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
+            it.a[j] = srow[((uint32_t)g * (uint32_t)f.scale_bits) >> 5];
+        } else {
+            it.a[j] = __float_as_uint(reinterpret_cast<const float *>(a.scale)[row * a.groups + g]);
         }
     }
 }
@@ -592,8 +593,9 @@ __device__ inline void store_group(void *W_out, int64_t elem, const uint32_t (&p
     }
 }
 
-// Wave items = (row, tile of 256 groups).  A block takes a contiguous range of them; its waves
-// stride the range and fetch one item ahead.
+// Wave items = (row, tile of 256 groups).  Items go round robin over all waves of the grid, so that at
+// any moment the grid writes one contiguous, advancing window of the output (a few MB) rather than one
+// window per block: DRAM pages are then filled by neighbours in time.  A wave fetches one item ahead.
 template <int OUT, bool CODES, bool B24>
 __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a,
                                                                int64_t items_per_block)
@@ -608,26 +610,31 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
     const int nwaves = blockDim.x / kWave;
     const uint32_t T = (uint32_t)((a.groups + kTileGroups - 1) / kTileGroups);   // tiles per row
     const int64_t total = a.rows * (int64_t)T;
-    const int64_t i_begin = (int64_t)blockIdx.x * items_per_block;
-    const int64_t i_end = std::min(total, i_begin + items_per_block);
-    // (row, tile) of this wave's item, advanced by nwaves items per step without dividing again
-    const uint32_t step_rows = nwaves / T, step_tiles = nwaves % T;
-    int64_t item = i_begin + wave;
+    (void)items_per_block;
+    const int64_t i_end = total;
+    // (row, tile) of this wave's item, advanced by one item of every wave of the grid per step
+    // without dividing again
+    const int64_t stride = (int64_t)gridDim.x * nwaves;
+    const int64_t step_rows = stride / T;
+    const uint32_t step_tiles = (uint32_t)(stride % T);
+    int64_t item = (int64_t)blockIdx.x * nwaves + wave;
     int64_t row = item / T;
     uint32_t tile = (uint32_t)(item - row * T);
 
     item_t cur, nxt;
     float cur_rn = 1.0f, nxt_rn = 1.0f;
     bool live = item < i_end;     // uniform in the wave
-    fetch_item<CODES, B24>(f, a, row, (int)tile * kTileGroups + lane, live, cur);
-    if constexpr (CODES) cur_rn = live ? a.rownorm[row] : 1.0f;
+    if (!live) return;            // (after the table copy's barrier; no barrier follows)
+    fetch_item<CODES, B24>(f, a, row, (int)tile * kTileGroups + lane, cur);
+    if constexpr (CODES) cur_rn = a.rownorm[row];
     while (live) {
         int64_t nrow = row + step_rows;
         uint32_t ntile = tile + step_tiles;
         if (ntile >= T) { ntile -= T; nrow += 1; }
-        const bool nlive = item + nwaves < i_end;
-        fetch_item<CODES, B24>(f, a, nrow, (int)ntile * kTileGroups + lane, nlive, nxt);
-        if constexpr (CODES) nxt_rn = nlive ? a.rownorm[nrow] : 1.0f;
+        const bool nlive = item + stride < i_end;
+        if (!nlive) { nrow = row; ntile = tile; }     // nothing follows: fetch this item again, unused
+        fetch_item<CODES, B24>(f, a, nrow, (int)ntile * kTileGroups + lane, nxt);
+        if constexpr (CODES) nxt_rn = a.rownorm[nrow];
 
         const int gbase = (int)tile * kTileGroups + lane;
         const float srn = CODES ? sqrtf(cur_rn) : 1.0f;
@@ -645,7 +652,7 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
                 store_group<OUT>(a.W_out, row * a.ldw + (int64_t)g * 8, prs[j], gain);
             }
         }
-        cur = nxt; cur_rn = nxt_rn; row = nrow; tile = ntile; live = nlive; item += nwaves;
+        cur = nxt; cur_rn = nxt_rn; row = nrow; tile = ntile; live = nlive; item += stride;
     }
 }
 

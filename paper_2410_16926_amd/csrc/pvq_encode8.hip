@@ -54,6 +54,28 @@ __device__ inline void count_wins(const float (&key)[D], int (&wins)[D])
     for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
 }
 
+// v + (v moved across lanes by one data-parallel-primitive pattern); lanes outside ROWS add zero
+template <int CTRL, int ROWS = 0xF>
+__device__ inline float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xF, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+// Sum of the 64 lanes' values over adjacent pairs, level by level (lanes 2i and 2i+1, then pairs of
+// pairs, ...), valid in lane 63.  Each level adds the two halves' sums, in whichever operand order
+// the lane pattern gives (addition commutes exactly), so the result is the pair-level sum bit for bit.
+__device__ inline float wave_pair_sum(float v)
+{
+    v = dpp_add<0xB1>(v);          // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);          // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);         // row_half_mirror
+    v = dpp_add<0x140>(v);         // row_mirror
+    v = dpp_add<0x142, 0xA>(v);    // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);    // row_bcast31 into rows 2 and 3
+    return v;
+}
+
 // Sum over adjacent pairs, level by level (fixed order, float32).
 __device__ inline float tree8(float (&v)[D])
 {
@@ -206,10 +228,8 @@ __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_enco
             if (quad_pos < 3 && g < G) irow[3 * (g >> 2) + quad_pos] = word;
             if constexpr (CODES) {
                 // pairwise sum over the wave's 64 groups (absent groups add +0.0, which is exact)
-                float v = ss;
-#pragma unroll
-                for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-                if (lane == 0) wsum[tix * (kBlock / kWave) + wave] = v;
+                const float v = wave_pair_sum(ss);
+                if (lane == kWave - 1) wsum[tix * (kBlock / kWave) + wave] = v;
             }
         }
         if constexpr (CODES) {

@@ -15,12 +15,14 @@
 //   T3  (d=3, k3)    direct table over every (k3, r): y5, y6, y7
 // Finding a block: a bucket table indexed by (row k, r >> shift) names the block that holds the
 // bucket's first index (candidate A) and a second block starting inside the bucket (candidate B, with
-// its start relative to the bucket).  The block table entry carries the block's
-// start and end; if r lies beyond the end (a bucket with several small blocks) the walk moves on
-// block by block.  All tables sit in one blob that a workgroup copies into LDS.
+// its start relative to the bucket).  The block table entry carries the block's start and end; if
+// r lies beyond the end (a bucket with several small blocks) the lane steps on block by block.
+// Residuals are carried with a per-row bias that makes r >> shift the bucket's place in the stage's
+// whole bucket table (see the block entry).  All tables sit in one blob that a workgroup copies into
+// LDS; a second flavour keeps S0's block table outside for a kernel that reads it from device memory.
 //
 // Values are emitted as packed bf16 pairs (exact for |y| <= 256) ready for v_dot2_f32_bf16, plus
-// 4 * sum(y^2) accumulated in the low bits of the block entries' `meta` words.
+// 4 * sum(y^2) accumulated from the block entries' `meta` words.
 #pragma once
 
 #include <stdint.h>
@@ -68,8 +70,7 @@ struct pvq_fast8_params {
 // low parts carry).  In the 16-bit form the arithmetic is modulo 2^16.
 constexpr uint32_t kFast8ThrBits = 13;
 constexpr uint32_t kFast8DbBits = 4;
-constexpr uint32_t kFast8MaxShift = 13;
-    // all bucket shifts stay at or below this
+constexpr uint32_t kFast8MaxShift = 13;   // all bucket shifts stay at or below this
 // LDS left for the blob: the 160 KiB of a compute unit minus 5 KiB for the kernels' own buffers
 // (partial sums: 2 KiB; amplitude table: 1 KiB, or a fused gain table in place of 1/sqrt(n2))
 constexpr uint32_t kFast8MaxBytes = 160 * 1024 - 5120;

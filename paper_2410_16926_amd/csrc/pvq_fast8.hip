@@ -597,8 +597,7 @@ __device__ inline void store_group(void *W_out, int64_t elem, const uint32_t (&p
 // any moment the grid writes one contiguous, advancing window of the output (a few MB) rather than one
 // window per block: DRAM pages are then filled by neighbours in time.  A wave fetches one item ahead.
 template <int OUT, bool CODES, bool B24>
-__global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a,
-                                                               int64_t items_per_block)
+__global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pvq_decode_args a)
 {
     // static, so that table offsets fold into the LDS instructions' immediate fields
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
@@ -610,7 +609,6 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
     const int nwaves = blockDim.x / kWave;
     const uint32_t T = (uint32_t)((a.groups + kTileGroups - 1) / kTileGroups);   // tiles per row
     const int64_t total = a.rows * (int64_t)T;
-    (void)items_per_block;
     const int64_t i_end = total;
     // (row, tile) of this wave's item, advanced by one item of every wave of the grid per step
     // without dividing again
@@ -686,14 +684,14 @@ hipError_t launch_gemv_nb(const fast8_launch &f, const pvq_decode_args &a, int b
 }
 
 template <int OUT>
-hipError_t launch_decode_out(const fast8_launch &f, const pvq_decode_args &a, int64_t ipb, dim3 grid,
+hipError_t launch_decode_out(const fast8_launch &f, const pvq_decode_args &a, dim3 grid,
                              dim3 block, size_t lds, hipStream_t s)
 {
     const bool codes = f.scale_bits > 0, b24 = f.index_bits == 24;
-    if (codes && b24) hipLaunchKernelGGL((decode8_kernel<OUT, true, true>), grid, block, lds, s, f, a, ipb);
-    else if (codes) hipLaunchKernelGGL((decode8_kernel<OUT, true, false>), grid, block, lds, s, f, a, ipb);
-    else if (b24) hipLaunchKernelGGL((decode8_kernel<OUT, false, true>), grid, block, lds, s, f, a, ipb);
-    else hipLaunchKernelGGL((decode8_kernel<OUT, false, false>), grid, block, lds, s, f, a, ipb);
+    if (codes && b24) hipLaunchKernelGGL((decode8_kernel<OUT, true, true>), grid, block, lds, s, f, a);
+    else if (codes) hipLaunchKernelGGL((decode8_kernel<OUT, true, false>), grid, block, lds, s, f, a);
+    else if (b24) hipLaunchKernelGGL((decode8_kernel<OUT, false, true>), grid, block, lds, s, f, a);
+    else hipLaunchKernelGGL((decode8_kernel<OUT, false, false>), grid, block, lds, s, f, a);
     return hipGetLastError();
 }
 
@@ -732,12 +730,11 @@ hipError_t pvq_fast8_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, i
     // every block pays the table copy, so blocks get at least 64 wave items (16K groups) each
     const int64_t want_blocks = std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, (total + 63) / 64);
     const int64_t nblocks = std::max<int64_t>(1, want_blocks);
-    const int64_t ipb = (total + nblocks - 1) / nblocks;
     const dim3 grid((unsigned)nblocks), block(kMaxThreads);
     switch (out_dtype) {
-    case PVQ_F32: return launch_decode_out<PVQ_F32>(f, a, ipb, grid, block, lds, s);
-    case PVQ_F16: return launch_decode_out<PVQ_F16>(f, a, ipb, grid, block, lds, s);
-    default: return launch_decode_out<PVQ_BF16>(f, a, ipb, grid, block, lds, s);
+    case PVQ_F32: return launch_decode_out<PVQ_F32>(f, a, grid, block, lds, s);
+    case PVQ_F16: return launch_decode_out<PVQ_F16>(f, a, grid, block, lds, s);
+    default: return launch_decode_out<PVQ_BF16>(f, a, grid, block, lds, s);
     }
 }
 

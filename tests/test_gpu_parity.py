@@ -118,6 +118,15 @@ def test_ragged_shapes(rows, cols, D):
         run_case(W, D, K, 2, batches=(1,), out_dtypes=("f32",))
 
 
+@pytest.mark.parametrize("rows,cols,bits", [(1, 8 * 4, 0), (5, 8 * 296, 2), (37, 8 * 1000, 8), (3, 8 * 3584, 2),
+                                            (130, 8 * 64, 0)])
+def test_many_vectors_on_ragged_shapes(rows, cols, bits):
+    # the 16-vector pass (one group column per lane) with partial slices, few rows, rows that do not
+    # fill a batch; and a batch size that the narrower passes share (4 + 2 + 1)
+    wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 80 + rows, rotate=False, bf16=True)
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 7), out_dtypes=("bf16",))
+
+
 @pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])
 def test_adversarial_groups(D, K):
     # rounding ties, repair ties, zeros, one-hot, wide dynamic range; 64k groups

@@ -449,7 +449,7 @@ constexpr size_t kWidePartBytes = 64 * kWide * sizeof(float);   // (row, slice) 
 
 template <int AMP, bool B24>
 __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f, pvq_decode_args a, int b0,
-                                                                  int nsl, int rl, int rows_per_block)
+                                                                  int nvec, int nsl, int rl, int rows_per_block)
 {
     constexpr bool CODES = AMP != 0;
     constexpr int RI = kWideRows, NB = kWide;
@@ -507,7 +507,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
 #pragma unroll
     for (int b = 0; b < NB; b++) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (in_row)
+        if (in_row && b < nvec)     // fewer than 16 vectors: the missing ones are zeros and are not written
             v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + b) * a.ldx + (int64_t)g * 8);
         xr[b][0] = v.x; xr[b][1] = v.y; xr[b][2] = v.z; xr[b][3] = v.w;
     }
@@ -548,7 +548,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
         if ((int)threadIdx.x < RB * NB) {
             const int rloc = threadIdx.x / NB, b = threadIdx.x % NB;
             const int64_t row = batch + rloc;
-            if (row < r_end) {
+            if (row < r_end && b < nvec) {
                 float v = 0.0f;
                 for (int s = 0; s < nsl; s++) v += part[(rloc * nsl + s) * NB + b];
                 if constexpr (CODES) v *= sqrtf(a.rownorm[row]);
@@ -760,8 +760,8 @@ hipError_t launch_gemv_pass(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
 
 namespace {
 
-// one launch of the 16-vector kernel for vectors [b0, b0 + 16)
-hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, hipStream_t s)
+// one launch of the 16-vector kernel for vectors [b0, b0 + nvec), nvec <= 16
+hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, int nvec, hipStream_t s)
 {
     const fast8_launch f = make_launch(c, false);
     const int nsl = (int)((a.groups + kWave - 1) / kWave);
@@ -773,7 +773,7 @@ hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
     const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)(kWave * nsl * rl));
     const bool b24 = f.index_bits == 24, codes = f.scale_bits > 0;
 #define PVQ_WIDE_CASE(AMP, B24) \
-    hipLaunchKernelGGL((gemv8_wide_kernel<AMP, B24>), grid, block, 0, s, f, a, b0, nsl, rl, rows_per_block)
+    hipLaunchKernelGGL((gemv8_wide_kernel<AMP, B24>), grid, block, 0, s, f, a, b0, nvec, nsl, rl, rows_per_block)
     if (codes) { if (b24) PVQ_WIDE_CASE(1, true); else PVQ_WIDE_CASE(1, false); }
     else { if (b24) PVQ_WIDE_CASE(0, true); else PVQ_WIDE_CASE(0, false); }
 #undef PVQ_WIDE_CASE
@@ -799,7 +799,9 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
     while (b0 < a.batch) {
         const int left = a.batch - b0;
         hipError_t e;
-        if (left >= kWide && wide_usable(c, a)) { e = launch_gemv_wide(c, a, b0, s); b0 += kWide; }
+        // from eight vectors on, one 16-vector pass (about 215 us on the benchmark shape whatever the
+        // count) beats two or more 4-vector passes (111 us each)
+        if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
         else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
         else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }

@@ -124,7 +124,7 @@ def test_many_vectors_on_ragged_shapes(rows, cols, bits):
     # the 16-vector pass (one group column per lane) with partial slices, few rows, rows that do not
     # fill a batch; and a batch size that the narrower passes share (4 + 2 + 1)
     wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 80 + rows, rotate=False, bf16=True)
-    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 7), out_dtypes=("bf16",))
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 11, 8, 7), out_dtypes=("bf16",))
 
 
 @pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])

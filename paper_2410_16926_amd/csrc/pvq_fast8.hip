@@ -605,7 +605,9 @@ __global__ __launch_bounds__(kMaxThreads) void decode8_kernel(fast8_launch f, pv
     load_tables<false>(lds, f, sqrtc_l);
 
     const int G = (int)a.groups;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & (kWave - 1);
+    // the wave's number as a scalar, so that rows, tiles and row addresses are computed once per wave
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int nwaves = blockDim.x / kWave;
     const uint32_t T = (uint32_t)((a.groups + kTileGroups - 1) / kTileGroups);   // tiles per row
     const int64_t total = a.rows * (int64_t)T;

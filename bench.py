@@ -81,8 +81,8 @@ def read_traffic(kernel="gemv_b1"):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's sample (0 = auto)")
     ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
@@ -175,14 +175,12 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    ms = {n: 0.0 for n in names}
-    for ev in all_events:
-        for j, n in enumerate(names):
-            ms[n] += ev[j].elapsed_time(ev[j + 1])
+    per_step = {n: [ev[j].elapsed_time(ev[j + 1]) for ev in all_events] for j, n in enumerate(names)}
+    ms = {n: sum(v) / len(v) for n, v in per_step.items()}
     for n in names:
-        ms[n] /= args.steps
         if only and n not in only:
             ms[n] = float("nan")
+    g1 = sorted(per_step["gemv_b1"])
 
     weights = ROWS * COLS
     ab = {B: algorithmic_bytes(ROWS, COLS, ctx.index_bits, SCALE_BITS, B) for B in BATCHES}
@@ -203,6 +201,16 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         b2b = e0.elapsed_time(e1) / n
+        # and with one set of packed planes only (95 MB: it stays in the last-level cache)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            pvq.pvq_decode_gemv(ctx, sets[0], xs[1], out=ys[1])
+        e1.record()
+        torch.cuda.synchronize()
+        warm = e0.elapsed_time(e1) / n
+    else:
+        warm = float("nan")
     gemv1 = gbps(ab[1]["gemv"], ms["gemv_b1"] if ms["gemv_b1"] == ms["gemv_b1"] else b2b)
 
     result = {
@@ -225,7 +233,12 @@ def main():
             "scale_bits": SCALE_BITS, "packed_sets": len(sets),
         },
         "kernel_ms": {n: round(v, 4) for n, v in ms.items()},
+        "gemv_b1_ms_median_min": [round(g1[len(g1) // 2], 4), round(g1[0], 4)],
         "gemv_b1_back_to_back_ms": round(b2b, 4),
+        "gemv_b1_single_set_cache_warm_ms": round(warm, 4),
+        # the products' arithmetic against the vector ALU (2*rows*cols*batch flop; fp32 vector peak 157.3 TFLOP/s):
+        # far below it at every batch size, the kernels are bound by decoding, not by HBM or by the products
+        "gemv_tflops": {f"b{B}": round(2.0 * weights * B / (ms[f"gemv_b{B}"] * 1e-3) / 1e12, 2) for B in BATCHES},
         "pct_of_hbm_peak": round(100 * gemv1 / HBM_PEAK_GBPS, 2),
         "encode_gweights_per_s": round(weights / (ms["encode"] * 1e-3) / 1e9, 2),
         "decode_gweights_per_s": round(weights / (ms["decode"] * 1e-3) / 1e9, 2),
@@ -276,9 +289,22 @@ def main():
         rows = min(rows, ROWS)
         sample = W[:rows].to(torch.float32).cpu().numpy()      # the bf16 values, widened exactly
         result["cpu_baseline"] = cpu_baseline(np.ascontiguousarray(sample), xf1, K, threads)
+        one = cpu_baseline(np.ascontiguousarray(sample[:max(1, rows // threads)]), xf1, K, 1)
+        result["cpu_baseline"]["one_core"] = {k: one[k] for k in ("value", "decode_gemv_gweights_per_s",
+                                                                   "encode_gweights_per_s", "seconds")}
 
     ctx.close()
-    print(json.dumps(result))
+
+    def clean(v):   # a partial run (--only) leaves figures undefined: null, not NaN, in the JSON line
+        if isinstance(v, float) and v != v:
+            return None
+        if isinstance(v, dict):
+            return {k: clean(x) for k, x in v.items()}
+        if isinstance(v, list):
+            return [clean(x) for x in v]
+        return v
+
+    print(json.dumps(clean(result)))
 
 
 if __name__ == "__main__":

@@ -281,6 +281,12 @@ def main():
             "gemv_b1_ms": round(timed(lambda: pvq.pvq_decode_gemv(ctx16, p16, xs[1], out=ys[1])), 4),
         }
         ctx16.close()
+        # App. C.2: the size table on the GPU (one workgroup, a latency-bound scan), and the oracle's beside it
+        from oracle import pvq_oracle as oracle
+        for (d_, k_, w_) in ((32, 60, 4), (128, 187, 12)):
+            t_gpu = timed(lambda: pvq.pvq_size_table_device(d_, k_, w_, dev), reps=20)
+            t0 = time.perf_counter(); oracle.size_table(d_, k_); t_cpu = time.perf_counter() - t0
+            ex[f"size_table_D{d_}_K{k_}"] = {"gpu_ms": round(t_gpu, 4), "oracle_cpu_ms": round(t_cpu * 1e3, 3)}
         result["extras"] = ex
 
     if not args.no_cpu_baseline:

@@ -73,6 +73,17 @@ int pvq_last_hip_error(void);
 int pvq_count(int D, int K, uint32_t *count_words, int *index_bits);
 
 /*
+ * The whole size table on the GPU (App. C.2: every row is a prefix sum over k of the row before; one
+ * workgroup, a multi-word scan through LDS): N(d,k) for d = 0..D, k = 0..K, written to
+ * table[(d*(K+1) + k)*words + i], i = 0..words-1 little-endian 32-bit words (device memory,
+ * (D+1)*(K+1)*words words, owned by the caller).  *overflow (device, one word) is set to 0, or to 1 if
+ * some entry did not fit `words` words (the entries are then the true values modulo 2^(32*words)).
+ * Asynchronous on `stream`; uses no memset, so it may be captured.  0 <= D <= 1024, 0 <= K <= 1023,
+ * 1 <= words <= 16, else PVQ_E_UNSUPPORTED; NULL pointers PVQ_E_INVALID_ARG.
+ */
+int pvq_size_table_device(int D, int K, int words, uint32_t *table, uint32_t *overflow, void *stream);
+
+/*
  * Sec. 3.3 Step 2: the largest K >= 1 whose index fits in bit_budget bits (1..255).
  * PVQ_E_UNSUPPORTED if not even K = 1 fits.
  */

@@ -14,7 +14,7 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables",
-    "pvq_fast_tables_selftest",
+    "pvq_fast_tables_selftest", "pvq_size_table_device",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
 ]
@@ -52,6 +52,7 @@ def lib():
         L.pvq_max_k.argtypes = [i32, i32, vp]
         L.pvq_beta_tables.argtypes = [i32, i64, i32, vp, vp]
         L.pvq_fast_tables_selftest.argtypes = [i32, C.c_uint64, C.c_uint64, vp]
+        L.pvq_size_table_device.argtypes = [i32, i32, i32, vp, vp, vp]
         L.pvq_ctx_create.argtypes = [vp, i32, i32, i32, vp, vp]
         L.pvq_ctx_destroy.argtypes = [vp]
         L.pvq_ctx_info.argtypes = [vp, vp, vp, vp, vp]
@@ -105,6 +106,18 @@ def pvq_fast_tables_selftest(K: int, first: int = 0, count: int = 1 << 40) -> in
     bad = C.c_uint64()
     _check(lib().pvq_fast_tables_selftest(K, first, count, C.byref(bad)), "pvq_fast_tables_selftest")
     return bad.value
+
+
+def pvq_size_table_device(D: int, K: int, words: int, device=None):
+    """The size table computed on the GPU: (int32 tensor [(D+1)][(K+1)][words] holding the unsigned
+    little-endian words, int32 tensor [1] = overflow flag), both on `device`; asynchronous."""
+    import torch
+    device = device or torch.device("cuda", torch.cuda.current_device())
+    table = torch.empty((D + 1, K + 1, words), dtype=torch.int32, device=device)
+    flag = torch.empty(1, dtype=torch.int32, device=device)
+    _check(lib().pvq_size_table_device(D, K, words, C.c_void_p(table.data_ptr()), C.c_void_p(flag.data_ptr()),
+                                       _stream_ptr()), "pvq_size_table_device")
+    return table, flag
 
 
 # ------------------------------------------------------------------ context

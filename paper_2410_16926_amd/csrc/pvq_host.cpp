@@ -325,6 +325,14 @@ extern "C" int pvq_ctx_info(const pvq_ctx *c, int *D, int *K, int *index_bits, i
     return PVQ_OK;
 }
 
+extern "C" int pvq_size_table_device(int D, int K, int words, uint32_t *table, uint32_t *overflow, void *stream)
+{
+    if (D < 0 || K < 0 || words < 1 || !table || !overflow) return PVQ_E_INVALID_ARG;
+    if (D > 1024 || K > 1023 || words > 16) return PVQ_E_UNSUPPORTED;
+    const hipError_t e = pvq_launch_size_table(D, K, words, table, overflow, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
 extern "C" int pvq_ctx_set_amplitude(pvq_ctx *c, int amplitude)
 {
     if (!c || (amplitude != PVQ_AMP_NORM && amplitude != PVQ_AMP_LS)) return PVQ_E_INVALID_ARG;

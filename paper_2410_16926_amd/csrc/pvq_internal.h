@@ -85,6 +85,9 @@ hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int d
 hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
 
+// size table on the GPU (pvq_size_table.hip): (D+1) x (K+1) entries of `words` words, one workgroup
+hipError_t pvq_launch_size_table(int D, int K, int words, uint32_t *table, uint32_t *overflow, hipStream_t s);
+
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);
 hipError_t pvq_encode8_launch(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);

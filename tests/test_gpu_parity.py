@@ -222,3 +222,30 @@ def test_corrupt_indices_do_not_fault():
     torch.cuda.synchronize()
     assert out.shape == (16, 1024)
     ctx.close()
+
+
+@pytest.mark.parametrize("D,K,words", [(8, 16, 1), (16, 33, 2), (32, 60, 4), (128, 187, 12), (64, 127, 16),
+                                       (5, 0, 1), (0, 7, 1), (200, 1023, 16)])
+def test_size_table_on_the_gpu(D, K, words):
+    # App. C.2: every entry must equal the oracle's table, word for word
+    table, flag = pvq.pvq_size_table_device(D, K, words)
+    got = table.cpu().numpy().view(np.uint32)
+    want = oracle.size_table(D, K) if (D, K, words) != (200, 1023, 16) else None
+    if want is None:
+        # far beyond 512 bits: only the flag and the rows that still fit are checked
+        assert int(flag.cpu()[0]) == 1
+        want = oracle.size_table(6, 1023)
+        D = 6
+    else:
+        assert int(flag.cpu()[0]) == 0
+    for d in range(D + 1):
+        for k in range(0, K + 1, max(1, K // 37)):
+            assert oracle.words_to_int(got[d, k]) == want[d][k], (d, k)
+
+
+def test_size_table_overflow_flag():
+    # N(16,33) needs 52 bits: one word is not enough, two are
+    _, flag1 = pvq.pvq_size_table_device(16, 33, 1)
+    t2, flag2 = pvq.pvq_size_table_device(16, 33, 2)
+    assert int(flag1.cpu()[0]) == 1 and int(flag2.cpu()[0]) == 0
+    assert oracle.words_to_int(t2.cpu().numpy().view(np.uint32)[16, 33]) == oracle.size_table(16, 33)[16][33]

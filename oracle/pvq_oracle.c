@@ -16,6 +16,7 @@
  *     or the least-squares amplitude for the quantised direction (Sec. 3.3 Step 4)
  *   - amplitude codes against Beta quantile edges               (Sec. 3.3 Step 5, Sec. 3.4)
  *   - dequantisation: point -> unit sphere -> times amplitude   (Sec. 2.4 eq. for S(D,K), Sec. 3.4)
+ *   - the randomised Hadamard rotation along the rows           (Sec. 2.3, Sec. 3.3 Step 1)
  *   - the reference product  out = W_hat x                       (float64 textbook matmul)
  *
  * Arithmetic.  Index arithmetic uses the fixed-width multi-word integers below (NW 32-bit
@@ -596,6 +597,52 @@ int pvqo_encode(const float *W, int64_t rows, int64_t cols, int D, int K, int sc
         for (int i = 0; i < nthreads; i++) pthread_join(th[i], NULL);
     free(th); free(jobs);
     tab_free(t);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* randomised Hadamard rotation along the rows    (Sec. 2.3, Sec. 3.3 Step 1) */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Every row of X (float32 [rows][cols]) is cut into blocks of `block` consecutive values
+ * (block a power of two dividing cols) and each block x is replaced by
+ *     signs_after == 0:   H (s . x) / sqrt(block)        (the rotation applied before quantising)
+ *     signs_after == 1:   s . (H x) / sqrt(block)        (its inverse: H is symmetric, H H = block I)
+ * with H the Sylvester-Hadamard matrix in natural order and s_i = -1 where signs[i] != 0, else +1
+ * (signs has cols entries, NULL = all +1).
+ * float32 throughout: the transform is the in-place butterfly a,b -> a+b, a-b over strides
+ * 1, 2, 4, ..., block/2 in that order (every value of a stage is one rounded sum or difference
+ * of two values of the stage before, so the result does not depend on how a stage is scheduled),
+ * then one multiplication by the float32 nearest to 1/sqrt(block).
+ * Reading: the paper takes its rotation from the works it cites and gives no arithmetic; this
+ * is the plain fast Walsh-Hadamard transform, block diagonal when cols is not a power of two.
+ */
+int pvqo_hadamard_rows(const float *X, int64_t rows, int64_t cols, int64_t block,
+                       const uint8_t *signs, int signs_after, float *Y)
+{
+    if (block < 1 || (block & (block - 1)) || cols % block) return -1;
+    float scale = (float)(1.0 / sqrt((double)block));
+    float *v = malloc(sizeof(float) * block);
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t b0 = 0; b0 < cols; b0 += block) {
+            const float *x = X + r * cols + b0;
+            for (int64_t i = 0; i < block; i++)
+                v[i] = (!signs_after && signs && signs[b0 + i]) ? -x[i] : x[i];
+            for (int64_t h = 1; h < block; h *= 2)
+                for (int64_t i = 0; i < block; i += 2 * h)
+                    for (int64_t j = i; j < i + h; j++) {
+                        float a = v[j], b = v[j + h];
+                        v[j] = a + b;
+                        v[j + h] = a - b;
+                    }
+            float *y = Y + r * cols + b0;
+            for (int64_t i = 0; i < block; i++) {
+                float t = v[i] * scale;
+                y[i] = (signs_after && signs && signs[b0 + i]) ? -t : t;
+            }
+        }
+    free(v);
     return 0;
 }
 

@@ -52,6 +52,7 @@ def lib():
         L.pvqo_rank_many.argtypes = [i32, i32, i64, vp, vp]
         L.pvqo_unrank_many.argtypes = [i32, i32, i64, vp, vp, i32]
         L.pvqo_encode.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+        L.pvqo_hadamard_rows.argtypes = [vp, i64, i64, i64, vp, i32, vp]
         L.pvqo_ls_amplitude.argtypes = [vp, vp, i32]
         L.pvqo_ls_amplitude.restype = C.c_float
         L.pvqo_decode.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, i32,
@@ -240,6 +241,19 @@ def decode(enc: Encoded, centers=None, x=None, want_weights: bool = True,
     if rc != 0:
         raise ValueError("pvqo_decode rejected its arguments")
     return Wd, pulses, out
+
+
+def hadamard_rows(X, block: int, signs=None, signs_after: bool = False) -> np.ndarray:
+    """Block-diagonal randomised Hadamard rotation of every row (float32), or its inverse
+    (signs_after=True).  signs: uint8 [cols], non-zero = -1."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    rows, cols = X.shape
+    sg = None if signs is None else np.ascontiguousarray(signs, dtype=np.uint8)
+    assert sg is None or sg.size == cols
+    Y = np.empty_like(X)
+    if lib().pvqo_hadamard_rows(_p(X), rows, cols, int(block), _p(sg), 1 if signs_after else 0, _p(Y)) != 0:
+        raise ValueError("pvqo_hadamard_rows rejected its arguments")
+    return Y
 
 
 def unpack_fields(words, groups: int, bits: int):

@@ -148,6 +148,28 @@ int pvq_ctx_set_amplitude(pvq_ctx *ctx, int amplitude);
 int pvq_packed_sizes(const pvq_ctx *ctx, int64_t rows, int64_t cols, size_t *index_bytes,
                      size_t *scale_bytes, size_t *rownorm_bytes);
 
+/*
+ * Randomised Hadamard rotation along the rows (Sec. 2.3 "Hadamard coherence processing", Sec. 3.3
+ * Step 1), the step in front of pvq_encode, and its inverse, the step behind pvq_decode.
+ * Every row of X is cut into blocks of `block` consecutive values and each block x becomes
+ *     inverse == 0:   H (s . x) / sqrt(block)
+ *     inverse != 0:   s . (H x) / sqrt(block)        (undoes the former: H is symmetric, H H = block I)
+ * with H the Sylvester-Hadamard matrix in natural order and s_i = -1 where signs[i] != 0, else +1.
+ * float32 arithmetic in a fixed order (butterflies over strides 1, 2, 4, ..., then one multiplication
+ * by float32(1/sqrt(block))), one rounding to out_dtype at the end.
+ *   X      device, [rows][ldx] of dtype (PVQ_F32 or PVQ_BF16), 16-byte aligned rows (ldx*size % 16 == 0)
+ *   Y      device, [rows][ldy] of out_dtype (PVQ_F32 or PVQ_BF16), aligned likewise; Y may be X when the
+ *          two types are the same
+ *   block  a power of two, 8 <= block <= 8192, dividing cols (a block-diagonal rotation when cols is not
+ *          a power of two, e.g. 7 blocks of 4096 for 28672 columns)
+ *   signs  device, cols bytes, 8-byte aligned, or NULL for all +1
+ * PVQ_E_INVALID_ARG: negative sizes, ldx/ldy < cols, NULL X or Y (unless rows or cols is 0: nothing is
+ * done then); PVQ_E_UNSUPPORTED: block or a dtype outside the above, cols not a multiple of block;
+ * PVQ_E_ALIGNMENT.
+ */
+int pvq_hadamard(const void *X, int dtype, int64_t rows, int64_t cols, int64_t ldx, int block,
+                 const uint8_t *signs, int inverse, void *Y, int out_dtype, int64_t ldy, void *stream);
+
 /* ---- the hot path --------------------------------------------------------------------------- */
 
 /*

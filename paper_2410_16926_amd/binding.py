@@ -14,7 +14,7 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables",
-    "pvq_fast_tables_selftest", "pvq_size_table_device",
+    "pvq_fast_tables_selftest", "pvq_size_table_device", "pvq_hadamard",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
 ]
@@ -53,6 +53,7 @@ def lib():
         L.pvq_beta_tables.argtypes = [i32, i64, i32, vp, vp]
         L.pvq_fast_tables_selftest.argtypes = [i32, C.c_uint64, C.c_uint64, vp]
         L.pvq_size_table_device.argtypes = [i32, i32, i32, vp, vp, vp]
+        L.pvq_hadamard.argtypes = [vp, i32, i64, i64, i64, i32, vp, i32, vp, i32, i64, vp]
         L.pvq_ctx_create.argtypes = [vp, i32, i32, i32, vp, vp]
         L.pvq_ctx_destroy.argtypes = [vp]
         L.pvq_ctx_info.argtypes = [vp, vp, vp, vp, vp]
@@ -118,6 +119,19 @@ def pvq_size_table_device(D: int, K: int, words: int, device=None):
     _check(lib().pvq_size_table_device(D, K, words, C.c_void_p(table.data_ptr()), C.c_void_p(flag.data_ptr()),
                                        _stream_ptr()), "pvq_size_table_device")
     return table, flag
+
+
+def pvq_hadamard(X, block: int, signs=None, inverse: bool = False, out=None, out_dtype=None):
+    """Randomised Hadamard rotation of every row of the 2-D device tensor X (float32 or bfloat16) in
+    blocks of `block` columns, or its inverse.  signs: uint8 device tensor [cols] (non-zero = -1) or None."""
+    import torch
+    rows, cols = X.shape
+    if out is None:
+        out = torch.empty((rows, cols), dtype=out_dtype or X.dtype, device=X.device)
+    _check(lib().pvq_hadamard(_ptr(X), _dtype_code(X), rows, cols, X.stride(0) if rows > 1 else cols, block,
+                              _ptr(signs), 1 if inverse else 0, _ptr(out), _dtype_code(out),
+                              out.stride(0) if rows > 1 else cols, _stream_ptr()), "pvq_hadamard")
+    return out
 
 
 # ------------------------------------------------------------------ context

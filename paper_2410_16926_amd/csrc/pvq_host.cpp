@@ -333,6 +333,24 @@ extern "C" int pvq_size_table_device(int D, int K, int words, uint32_t *table, u
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
+extern "C" int pvq_hadamard(const void *X, int dtype, int64_t rows, int64_t cols, int64_t ldx, int block,
+                            const uint8_t *signs, int inverse, void *Y, int out_dtype, int64_t ldy, void *stream)
+{
+    if (rows < 0 || cols < 0 || ldx < cols || ldy < cols) return PVQ_E_INVALID_ARG;
+    if ((dtype != PVQ_F32 && dtype != PVQ_BF16) || (out_dtype != PVQ_F32 && out_dtype != PVQ_BF16))
+        return PVQ_E_UNSUPPORTED;
+    if (block < 8 || block > 8192 || (block & (block - 1)) || cols % block) return PVQ_E_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return PVQ_OK;
+    if (!X || !Y) return PVQ_E_INVALID_ARG;
+    const int64_t isz = dtype == PVQ_F32 ? 4 : 2, osz = out_dtype == PVQ_F32 ? 4 : 2;
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15) || (ldx * isz) % 16 || (ldy * osz) % 16 || ((uintptr_t)signs & 7))
+        return PVQ_E_ALIGNMENT;
+    if (rows * ((cols + 511) / 512) > 0x7FFFFFFF) return PVQ_E_UNSUPPORTED;
+    const hipError_t e = pvq_launch_hadamard(X, dtype, rows, cols, ldx, block, signs, inverse ? 1 : 0, Y, out_dtype,
+                                             ldy, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
 extern "C" int pvq_ctx_set_amplitude(pvq_ctx *c, int amplitude)
 {
     if (!c || (amplitude != PVQ_AMP_NORM && amplitude != PVQ_AMP_LS)) return PVQ_E_INVALID_ARG;

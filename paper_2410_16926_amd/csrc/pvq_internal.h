@@ -88,6 +88,11 @@ hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, 
 // size table on the GPU (pvq_size_table.hip): (D+1) x (K+1) entries of `words` words, one workgroup
 hipError_t pvq_launch_size_table(int D, int K, int words, uint32_t *table, uint32_t *overflow, hipStream_t s);
 
+// randomised Hadamard rotation of rows (pvq_hadamard.hip); arguments already validated
+hipError_t pvq_launch_hadamard(const void *X, int in_dtype, int64_t rows, int64_t cols, int64_t ldx, int block,
+                               const uint8_t *signs, int signs_after, void *Y, int out_dtype, int64_t ldy,
+                               hipStream_t s);
+
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);
 hipError_t pvq_encode8_launch(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);

@@ -249,3 +249,40 @@ def test_size_table_overflow_flag():
     t2, flag2 = pvq.pvq_size_table_device(16, 33, 2)
     assert int(flag1.cpu()[0]) == 1 and int(flag2.cpu()[0]) == 0
     assert oracle.words_to_int(t2.cpu().numpy().view(np.uint32)[16, 33]) == oracle.size_table(16, 33)[16][33]
+
+
+@pytest.mark.parametrize("rows,cols,block", [(3, 8, 8), (5, 64, 16), (4, 8 * 37 * 8, 64), (7, 512, 512), (6, 3584, 512),
+                                             (9, 2048, 2048), (5, 4096, 4096), (3, 8192, 8192), (2, 28672, 4096),
+                                             (130, 1024, 128)])
+def test_hadamard_rotation(rows, cols, block):
+    # Sec. 3.3 Step 1: float32 butterflies in a fixed order, so float32 results are the oracle's bit for
+    # bit and bf16 results are its values rounded once; the inverse undoes the rotation
+    rng = np.random.default_rng(rows * 131 + cols)
+    X = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+    sg = rng.integers(0, 2, size=cols).astype(np.uint8)
+    want = oracle.hadamard_rows(X, block, sg)
+    Xd, sd = gu.to_dev_f32(X), torch.from_numpy(sg).cuda()
+    got = pvq.pvq_hadamard(Xd, block, sd)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    got_bf = pvq.pvq_hadamard(Xd, block, sd, out_dtype=torch.bfloat16)
+    assert np.array_equal(gu.bf16_tensor_bits(got_bf), oracle.to_bf16_bits(want.astype(np.float64)))
+    # bf16 source, no signs
+    xb = si.f32_to_bf16_bits(X)
+    xf = si.bf16_bits_to_f32(xb)
+    got2 = pvq.pvq_hadamard(gu.to_dev_bf16(xb), block, None, out_dtype=torch.float32)
+    assert np.array_equal(got2.cpu().numpy().view(np.uint32), oracle.hadamard_rows(xf, block).view(np.uint32))
+    # inverse, in place
+    back = pvq.pvq_hadamard(got, block, sd, inverse=True, out=got)
+    want_back = oracle.hadamard_rows(want, block, sg, signs_after=True)
+    assert np.array_equal(back.cpu().numpy().view(np.uint32), want_back.view(np.uint32))
+    assert np.allclose(back.cpu().numpy(), X, rtol=0, atol=4e-6 * np.abs(X).max() * np.log2(block))
+
+
+def test_hadamard_argument_errors():
+    X = torch.zeros((4, 96), dtype=torch.float32, device="cuda")
+    for block in (4, 64, 48, 16384):       # too small, not dividing 96, not a power of two, too large
+        with pytest.raises(pvq.PvqError):
+            pvq.pvq_hadamard(X, block)
+    with pytest.raises(pvq.PvqError):
+        pvq.pvq_hadamard(X.to(torch.float16), 32)
+    assert pvq.pvq_hadamard(torch.zeros((0, 96), dtype=torch.float32, device="cuda"), 32).shape == (0, 96)

@@ -65,8 +65,41 @@ __device__ inline void stage_across_lanes(float (&v)[8], int lane)
     }
 }
 
-// TIn / OUT: 0 = float32, 2 = bf16 (pvq_dtype values)
-template <int IN, int OUT>
+// Ownership (P, R): the lane holds the 8 values of its chunk whose index differs in bits 3P .. 3P+R-1 (the
+// R low bits of the register number) and, for R < 3, in bits 0 .. 2-R (the other bits of the register
+// number); the lane number fills the remaining index bits in order.  (0, 3) is 8 consecutive values.
+// The index of register q is own_base(lane) | own_offset(q): the two never share a bit, so the padded
+// address splits the same way and the register's part is a compile-time constant.
+template <int P, int R>
+__device__ inline uint32_t own_base(uint32_t lane)
+{
+    const uint32_t rest = lane << (3 - R);
+    return (rest & ((1u << (3 * P)) - 1u)) | ((rest >> (3 * P)) << (3 * P + R));
+}
+template <int P, int R>
+__device__ constexpr uint32_t own_offset(int q)
+{
+    return ((uint32_t)q >> R) + (((uint32_t)q & ((1u << R) - 1u)) << (3 * P));
+}
+
+// Through LDS from ownership (P0, R0) to (P1, R1); the caller alternates two buffers, so that one barrier
+// per exchange is enough (a buffer is written again only after a barrier that every wave reaches after
+// its reads of it).
+template <int P0, int R0, int P1, int R1>
+__device__ inline void exchange(float (&v)[8], float *buf, uint32_t lane)
+{
+    float *w = buf + pad(own_base<P0, R0>(lane));
+#pragma unroll
+    for (int q = 0; q < 8; q++) w[pad(own_offset<P0, R0>(q))] = v[q];
+    __syncthreads();
+    const float *r = buf + pad(own_base<P1, R1>(lane));
+#pragma unroll
+    for (int q = 0; q < 8; q++) v[q] = r[pad(own_offset<P1, R1>(q))];
+}
+
+// IN / OUT: 0 = float32, 2 = bf16 (pvq_dtype values).  LOG2N: 9 stands for every block of up to 512 values
+// (log2n says which), 10 .. 13 for that block size.
+template <int IN, int OUT, int LOG2N>
 __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t ldx, void *Y, int64_t ldy,
                                                         int64_t cols, int log2n, const uint8_t *signs,
                                                         int signs_after, float scale, int chunks_per_row)
@@ -114,6 +147,7 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
     }
 
     // index bits 0..2 are the register number, bits 3..8 the lane number inside the wave
+    if constexpr (LOG2N > 9) log2n = LOG2N;
     stages_in_registers(v, min(3, log2n));
     if (log2n > 3) stage_across_lanes<1>(v, lane);
     if (log2n > 4) stage_across_lanes<2>(v, lane);
@@ -121,38 +155,19 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
     if (log2n > 6) stage_across_lanes<8>(v, lane);
     if (log2n > 7) stage_across_lanes<16>(v, lane);
     if (log2n > 8) stage_across_lanes<32>(v, lane);
-    // from bit 9 on the partners sit in other waves.  Phase p >= 3: the lane owns the 8 values whose index
-    // differs in bits 3p .. 3p+r-1 (r = 3, or what is left of log2n).  own(p, r, q) is the index, inside
-    // the chunk, of the lane's q-th value; two LDS buffers alternate, so one barrier per exchange.
-    int owned_p = 0, owned_r = 3;   // how the registers are laid out now (phase, bits)
-    auto own = [&](int p, int r, int q) -> uint32_t {
-        // the r low bits of q go to index bits 3p .. 3p+r-1; the lane number and the other bits of q fill
-        // the remaining index bits in order
-        const uint32_t span = 1u << (3 * p);                       // 8^p
-        const uint32_t qa = (uint32_t)q & ((1u << r) - 1u), qb = (uint32_t)q >> r;
-        const uint32_t rest = ((uint32_t)lane << (3 - r)) + qb;
-        return (rest & (span - 1)) + qa * span + (rest >> (3 * p)) * (span << r);
-    };
-    float *buf = smem;
-    const uint32_t buf_words = pad(8u * (uint32_t)L) + 1u;
-    for (int p = 3; 3 * p < log2n; p++) {
-        const int r = min(3, log2n - 3 * p);
-#pragma unroll
-        for (int q = 0; q < 8; q++) buf[pad(own(owned_p, owned_r, q))] = v[q];
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 8; q++) v[q] = buf[pad(own(p, r, q))];
-        stages_in_registers(v, r);
-        owned_p = p; owned_r = r;
-        buf = (buf == smem) ? smem + buf_words : smem;
-    }
-    // back to 8 consecutive values per lane
-    if (owned_p != 0) {
-#pragma unroll
-        for (int q = 0; q < 8; q++) buf[pad(own(owned_p, owned_r, q))] = v[q];
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 8; q++) v[q] = buf[pad(8u * (uint32_t)lane + (uint32_t)q)];
+    // from bit 9 on the partners sit in other waves
+    if constexpr (LOG2N > 9) {
+        constexpr int R3 = LOG2N - 9 < 3 ? LOG2N - 9 : 3;
+        float *buf0 = smem, *buf1 = smem + pad(8u * (uint32_t)L) + 1u;
+        exchange<0, 3, 3, R3>(v, buf0, lane);
+        stages_in_registers(v, R3);
+        if constexpr (LOG2N > 12) {
+            exchange<3, R3, 4, LOG2N - 12>(v, buf1, lane);
+            stages_in_registers(v, LOG2N - 12);
+            exchange<4, LOG2N - 12, 0, 3>(v, buf0, lane);
+        } else {
+            exchange<3, R3, 0, 3>(v, buf1, lane);
+        }
     }
 
 #pragma unroll
@@ -191,10 +206,19 @@ hipError_t pvq_launch_hadamard(const void *X, int in_dtype, int64_t rows, int64_
     // two buffers for the exchanges between waves (none for blocks that fit a wave's 512 values)
     const size_t lds = log2n > 9 ? 2 * (size_t)(chunk + chunk / 32 + 1) * sizeof(float) : 0;
     const dim3 grid((unsigned)(rows * chunks_per_row)), blk((unsigned)L);
-#define PVQ_HAD_CASE(I, O) \
-    hipLaunchKernelGGL((hadamard_kernel<I, O>), grid, blk, lds, s, X, ldx, Y, ldy, cols, log2n, signs, signs_after, scale, chunks_per_row)
-    if (in_dtype == PVQ_F32) { if (out_dtype == PVQ_F32) PVQ_HAD_CASE(PVQ_F32, PVQ_F32); else PVQ_HAD_CASE(PVQ_F32, PVQ_BF16); }
-    else { if (out_dtype == PVQ_F32) PVQ_HAD_CASE(PVQ_BF16, PVQ_F32); else PVQ_HAD_CASE(PVQ_BF16, PVQ_BF16); }
+#define PVQ_HAD_LAUNCH(I, O, N) \
+    hipLaunchKernelGGL((hadamard_kernel<I, O, N>), grid, blk, lds, s, X, ldx, Y, ldy, cols, log2n, signs, signs_after, scale, chunks_per_row)
+#define PVQ_HAD_CASE(I, O)                                   \
+    switch (log2n) {                                         \
+    case 13: PVQ_HAD_LAUNCH(I, O, 13); break;                \
+    case 12: PVQ_HAD_LAUNCH(I, O, 12); break;                \
+    case 11: PVQ_HAD_LAUNCH(I, O, 11); break;                \
+    case 10: PVQ_HAD_LAUNCH(I, O, 10); break;                \
+    default: PVQ_HAD_LAUNCH(I, O, 9); break;                 \
+    }
+    if (in_dtype == PVQ_F32) { if (out_dtype == PVQ_F32) PVQ_HAD_CASE(PVQ_F32, PVQ_F32) else PVQ_HAD_CASE(PVQ_F32, PVQ_BF16) }
+    else { if (out_dtype == PVQ_F32) PVQ_HAD_CASE(PVQ_BF16, PVQ_F32) else PVQ_HAD_CASE(PVQ_BF16, PVQ_BF16) }
+#undef PVQ_HAD_LAUNCH
 #undef PVQ_HAD_CASE
     return hipGetLastError();
 }

@@ -253,7 +253,7 @@ def test_size_table_overflow_flag():
 
 @pytest.mark.parametrize("rows,cols,block", [(3, 8, 8), (5, 64, 16), (4, 8 * 37 * 8, 64), (7, 512, 512), (6, 3584, 512),
                                              (9, 2048, 2048), (5, 4096, 4096), (3, 8192, 8192), (2, 28672, 4096),
-                                             (130, 1024, 128)])
+                                             (130, 1024, 128), (4, 3072, 1024), (2, 16384, 8192)])
 def test_hadamard_rotation(rows, cols, block):
     # Sec. 3.3 Step 1: float32 butterflies in a fixed order, so float32 results are the oracle's bit for
     # bit and bf16 results are its values rounded once; the inverse undoes the rotation

@@ -287,6 +287,14 @@ def main():
             t_gpu = timed(lambda: pvq.pvq_size_table_device(d_, k_, w_, dev), reps=20)
             t0 = time.perf_counter(); oracle.size_table(d_, k_); t_cpu = time.perf_counter() - t0
             ex[f"size_table_D{d_}_K{k_}"] = {"gpu_ms": round(t_gpu, 4), "oracle_cpu_ms": round(t_cpu * 1e3, 3)}
+        # Sec. 3.3 Step 1: randomised Hadamard rotation of the rows, bf16 in and out (HBM-bound: one read,
+        # one write of the matrix)
+        sg = torch.randint(0, 2, (COLS,), dtype=torch.uint8, device=dev)
+        had = {}
+        for blk in (64, 512, 4096, 8192):
+            ms = timed(lambda: pvq.pvq_hadamard(W, blk, sg, out=Wout), reps=10)
+            had[f"block_{blk}"] = {"ms": round(ms, 4), "GBps": round(2 * W.numel() * W.element_size() / ms / 1e6, 1)}
+        ex["hadamard_bf16"] = had
         result["extras"] = ex
 
     if not args.no_cpu_baseline:

@@ -575,7 +575,8 @@ int pvqo_encode(const float *W, int64_t rows, int64_t cols, int D, int K, int sc
                 int amp_mode, const float *edges, uint32_t *index_out, void *scale_out,
                 float *rowss_out, int8_t *pulses_out, int nthreads)
 {
-    if (D < 1 || K < 1 || K > 127 || cols % D || scale_bits < 0 || scale_bits > 8) return -1;
+    if (D < 1 || K < 1 || K > 1023 || cols % D || scale_bits < 0 || scale_bits > 8) return -1;
+    if (K > 127 && pulses_out) return -1; /* the optional pulse plane is int8 */
     if (amp_mode != 0 && amp_mode != 1) return -1;
     if (scale_bits > 0 && (!edges || !rowss_out)) return -1;
     table_t *t = tab_build(D, K);
@@ -726,7 +727,8 @@ int pvqo_decode(const uint32_t *index, const void *scale, const float *rowss, in
                 double *W_out, int8_t *pulses_out, const double *x, int batch, double *out,
                 int nthreads)
 {
-    if (D < 1 || K < 1 || K > 127 || cols % D || scale_bits < 0 || scale_bits > 8) return -1;
+    if (D < 1 || K < 1 || K > 1023 || cols % D || scale_bits < 0 || scale_bits > 8) return -1;
+    if (K > 127 && pulses_out) return -1; /* the optional pulse plane is int8 */
     if (scale_bits > 0 && (!centers || !rowss)) return -1;
     if (batch > 0 && (!x || !out)) return -1;
     table_t *t = tab_build(D, K);

@@ -207,7 +207,7 @@ def encode(W, D: int, K: int, scale_bits: int = 0, edges=None, want_pulses: bool
         scale = np.zeros((rows, row_words(G, scale_bits)), dtype=np.uint32)
         e32 = np.ascontiguousarray(np.asarray(edges, dtype=np.float64).astype(np.float32))
         assert e32.size == (1 << scale_bits) - 1
-    pulses = np.zeros((rows, cols), dtype=np.int8) if want_pulses else None
+    pulses = np.zeros((rows, cols), dtype=np.int8) if want_pulses and K <= 127 else None   # int8 plane
     rc = lib().pvqo_encode(_p(W), rows, cols, D, K, scale_bits, {"l2": 0, "ls": 1}[amplitude], _p(e32),
                            _p(index), _p(scale), _p(rowss), _p(pulses), nthreads)
     if rc != 0:

@@ -35,6 +35,32 @@ def test_packed_layout_and_round_trip(D, budget, cols):
     assert np.array_equal(pulses, enc.pulses)
 
 
+@pytest.mark.parametrize("D,K,cols", [(128, 187, 512), (64, 40, 320)])
+def test_large_groups_round_trip(D, K, cols):
+    # the on-the-fly activation setting: groups of 64 / 128 values, indices of 123 / 384 bits, float32
+    # amplitudes; no int8 pulse plane exists for K > 127, so the stored fields are decoded instead
+    rows, G = 5, cols // D
+    rng = np.random.default_rng(D + K)
+    X = rng.standard_t(3.0, (rows, cols)).astype(np.float32)
+    enc = o.encode(X, D, K)
+    b = o.index_bits(D, K)
+    assert enc.index.shape == (rows, (G * b + 31) // 32)
+    fields = o.unpack_fields(enc.index, G, b)
+    What, _, _ = o.decode(enc)
+    for r in range(rows):
+        assert o.words_to_int(enc.index[r]) >> (G * b) == 0
+        pts = o.unrank(fields[r], D, K)
+        for g in range(G):
+            w = X[r, g * D:(g + 1) * D]
+            y, ss = o.quantize_group(w, K)
+            assert pts[g].tolist() == y.tolist()
+            assert fields[r][g] == pins.count_before(y.tolist(), K)
+            assert enc.scale[r, g] == np.sqrt(ss, dtype=np.float32)
+            yd = y.astype(np.float64)
+            want = float(enc.scale[r, g]) * yd / np.sqrt((yd * yd).sum())
+            assert np.allclose(What[r, g * D:(g + 1) * D], want, rtol=1e-15, atol=0)
+
+
 def test_dequantised_weights_are_amplitude_times_unit_direction():
     D, K = 8, 16
     rows, cols = 16, 256

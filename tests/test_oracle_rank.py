@@ -61,16 +61,20 @@ def _random_point(rng, D, K):
     return [m if rng.random() < 0.5 else -m for m in mags]
 
 
-@pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (7, 11)])
+@pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (7, 11), (64, 40), (128, 187)])
 def test_wide_indices_against_counting_with_python_integers(D, K):
     rng = random.Random(D * 1000 + K)
-    pts = [_random_point(rng, D, K) for _ in range(150)]
+    pts = [_random_point(rng, D, K) for _ in range(150 if D <= 32 else 24)]
     want = [pins.count_before(p, K) for p in pts]
     assert o.rank(pts, K) == want
     assert o.unrank(want, D, K).tolist() == pts
     assert max(want) < pins.n_binomial(D, K)
     if D == 32:
         assert max(want).bit_length() > 96      # the 4-word path is really exercised
+    if D == 128:
+        # the large-group setting of on-the-fly activation quantisation: 3 bits per value
+        assert o.index_bits(D, K) <= 384 < o.index_bits(D, K + 1)
+        assert max(want).bit_length() > 352     # twelve words
 
 
 def test_counting_yardstick_agrees_with_sorting():

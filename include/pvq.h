@@ -46,7 +46,7 @@ typedef struct pvq_ctx pvq_ctx;
 typedef enum {
     PVQ_OK = 0,
     PVQ_E_INVALID_ARG = -1, /* null pointer, negative size, ld < cols, bad enum value ...          */
-    PVQ_E_UNSUPPORTED = -2, /* D not in {8,16,32}; K out of range; index wider than 128 bits;
+    PVQ_E_UNSUPPORTED = -2, /* D not in {8,16,32,64,128}; K out of range; index wider than 128 (512) bits;
                                cols not a multiple of D; scale_bits not in {0,1,2,4,8}; batch > 16 */
     PVQ_E_ALIGNMENT = -3,   /* a device pointer or ld breaks the alignment stated at the call      */
     PVQ_E_HIP = -4,         /* a HIP runtime call failed; see pvq_last_hip_error()                 */
@@ -66,9 +66,9 @@ int pvq_last_hip_error(void);
 
 /*
  * N(D,K), the number of points of P(D,K) (Sec. 2.4: N(D,0)=1, N(0,K>=1)=0,
- * N(D,K) = N(D-1,K) + N(D,K-1) + N(D-1,K-1)), as 8 little-endian 32-bit words in count_words
+ * N(D,K) = N(D-1,K) + N(D,K-1) + N(D-1,K-1)), as 16 little-endian 32-bit words in count_words
  * (host, may be NULL), and the width of an index, bit_length(N-1), in index_bits (host, may be NULL).
- * 1 <= D <= 256, 0 <= K <= 1024; PVQ_E_UNSUPPORTED if N does not fit 256 bits.
+ * 1 <= D <= 256, 0 <= K <= 1024; PVQ_E_UNSUPPORTED if N does not fit 512 bits.
  */
 int pvq_count(int D, int K, uint32_t *count_words, int *index_bits);
 
@@ -84,7 +84,7 @@ int pvq_count(int D, int K, uint32_t *count_words, int *index_bits);
 int pvq_size_table_device(int D, int K, int words, uint32_t *table, uint32_t *overflow, void *stream);
 
 /*
- * Sec. 3.3 Step 2: the largest K >= 1 whose index fits in bit_budget bits (1..255).
+ * Sec. 3.3 Step 2: the largest K >= 1 whose index fits in bit_budget bits (1..511).
  * PVQ_E_UNSUPPORTED if not even K = 1 fits.
  */
 int pvq_max_k(int D, int bit_budget, int *K);
@@ -112,7 +112,11 @@ int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mi
 /*
  * Builds the size tables for (D,K) on the host, uploads them (and the amplitude tables) to the
  * current HIP device, and returns an immutable context usable from any thread and stream of that
- * device.  D in {8,16,32}; 1 <= K <= 127; index_bits <= 128.
+ * device.  D in {8,16,32}: 1 <= K <= 127, index_bits <= 128.
+ * D in {64,128} (long groups, the setting of on-the-fly quantisation of activations, Sec. 3.2 and
+ *   Sec. 4.3; e.g. D = 128, K = 187 for 3 bits per value): 1 <= K <= 1023, N(D,K) <= 2^512, float32
+ *   amplitudes only (scale_bits == 0; Sec. 3.3 Step 5 quantises amplitudes for small groups);
+ *   pvq_encode and pvq_decode work on such a context, pvq_decode_gemv returns PVQ_E_UNSUPPORTED.
  * scale_bits == 0: amplitudes are float32, edges/centers are ignored (may be NULL).
  * scale_bits in {1,2,4,8}: edges (2^b - 1 ascending values) and centers (2^b values), host float64,
  *   e.g. from pvq_beta_tables.  Encoding compares float32(u) with float32(edges[j]); decoding
@@ -185,7 +189,7 @@ int pvq_hadamard(const void *X, int dtype, int64_t rows, int64_t cols, int64_t l
  *   rownorm_out device, float32 [rows]; required and written when scale_bits > 0, ignored (may be
  *               NULL) otherwise.
  *   pulses_out  device, int8 [rows][cols], 16-byte aligned, or NULL: the integer points themselves,
- *               for checking.
+ *               for checking.  Must be NULL when K > 127 (PVQ_E_UNSUPPORTED otherwise).
  *
  * Arithmetic is float32 in a fixed order (pairwise sums of |w| and w*w over adjacent elements,
  * one correctly rounded division K/||w||_1, products, round-to-nearest-even; ties in the repair go
@@ -216,7 +220,7 @@ int pvq_decode(const pvq_ctx *ctx, const uint32_t *index, const void *scale, con
  * Decode fused into a matrix-vector product, without materialising the weights:
  *   y[b][r] = sum_c W_hat[r][c] * x[b][c],   W_hat as produced by pvq_decode in float32.
  * Not in the paper; it is the inference-side use of the decoder (Sec. 2.3: the rotated, quantised
- * weights multiply the activations directly).
+ * weights multiply the activations directly).  PVQ_E_UNSUPPORTED for contexts with D = 64 or 128.
  *
  *   x   device, bf16 [batch][ldx], 16-byte aligned, ldx >= cols, ldx a multiple of 8; 1 <= batch <= 16.
  *   y   device, float32 [batch][ldy], ldy >= rows.  Float32 accumulation in a fixed order

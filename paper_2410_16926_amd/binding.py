@@ -76,11 +76,11 @@ def _check(status: int, where: str):
 
 def pvq_count(D: int, K: int):
     """(N(D,K) as a Python int, index_bits)."""
-    words = (C.c_uint32 * 8)()
+    words = (C.c_uint32 * 16)()
     bits = C.c_int()
     _check(lib().pvq_count(D, K, words, C.byref(bits)), "pvq_count")
     n = 0
-    for i in range(8):
+    for i in range(16):
         n |= int(words[i]) << (32 * i)
     return n, bits.value
 

@@ -36,25 +36,25 @@ extern "C" const char *pvq_strerror(int status)
 extern "C" int pvq_last_hip_error(void) { return g_last_hip_error; }
 
 // ------------------------------------------------------------------------------------------
-// 256-bit unsigned integers (four 64-bit limbs) for the size tables
+// 512-bit unsigned integers (eight 64-bit limbs) for the size tables
 // ------------------------------------------------------------------------------------------
 
 namespace {
 
-struct U256 {
-    uint64_t limb[4] = {0, 0, 0, 0};
+struct U512 {
+    uint64_t limb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    static U256 of(uint64_t v)
+    static U512 of(uint64_t v)
     {
-        U256 r;
+        U512 r;
         r.limb[0] = v;
         return r;
     }
-    // returns true when the sum left 256 bits
-    bool add(const U256 &o)
+    // returns true when the sum left 512 bits
+    bool add(const U512 &o)
     {
         unsigned __int128 carry = 0;
-        for (int i = 0; i < 4; i++) {
+        for (int i = 0; i < 8; i++) {
             unsigned __int128 s = (unsigned __int128)limb[i] + o.limb[i] + carry;
             limb[i] = (uint64_t)s;
             carry = s >> 64;
@@ -63,12 +63,12 @@ struct U256 {
     }
     void decrement()  // value > 0
     {
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 8; i++)
             if (limb[i]-- != 0) break;
     }
     int bit_length() const
     {
-        for (int i = 3; i >= 0; i--)
+        for (int i = 7; i >= 0; i--)
             if (limb[i]) return 64 * i + 64 - __builtin_clzll(limb[i]);
         return 0;
     }
@@ -79,18 +79,18 @@ struct U256 {
 // but the kernels need every row, so the whole table is kept.
 struct SizeTable {
     int D, K;
-    int first_bad_k;      // smallest k with an entry that left 256 bits (K+1 if none); columns
+    int first_bad_k;      // smallest k with an entry that left 512 bits (K+1 if none); columns
                           // below it are exact, because N(d,k) only depends on columns <= k
     bool overflow;
-    std::vector<U256> n;  // (D+1) x (K+1)
+    std::vector<U512> n;  // (D+1) x (K+1)
 
     SizeTable(int D_, int K_) : D(D_), K(K_), first_bad_k(K_ + 1), n((size_t)(D_ + 1) * (K_ + 1))
     {
-        for (int k = 0; k <= K; k++) at(0, k) = U256::of(k == 0 ? 1 : 0);
+        for (int k = 0; k <= K; k++) at(0, k) = U512::of(k == 0 ? 1 : 0);
         for (int d = 1; d <= D; d++) {
-            at(d, 0) = U256::of(1);
+            at(d, 0) = U512::of(1);
             for (int k = 1; k <= K; k++) {
-                U256 v = at(d - 1, k);
+                U512 v = at(d - 1, k);
                 bool bad = v.add(at(d, k - 1));
                 bad |= v.add(at(d - 1, k - 1));
                 if (bad && k < first_bad_k) first_bad_k = k;
@@ -99,11 +99,11 @@ struct SizeTable {
         }
         overflow = first_bad_k <= K;
     }
-    U256 &at(int d, int k) { return n[(size_t)d * (K + 1) + k]; }
-    const U256 &at(int d, int k) const { return n[(size_t)d * (K + 1) + k]; }
+    U512 &at(int d, int k) { return n[(size_t)d * (K + 1) + k]; }
+    const U512 &at(int d, int k) const { return n[(size_t)d * (K + 1) + k]; }
     int index_bits() const
     {
-        U256 top = at(D, K);
+        U512 top = at(D, K);
         top.decrement();
         return top.bit_length();
     }
@@ -117,21 +117,21 @@ extern "C" int pvq_count(int D, int K, uint32_t *count_words, int *index_bits)
     SizeTable t(D, K);
     if (t.overflow) return PVQ_E_UNSUPPORTED;
     if (count_words)
-        for (int i = 0; i < 8; i++) count_words[i] = t.at(D, K).word(i);
+        for (int i = 0; i < 16; i++) count_words[i] = t.at(D, K).word(i);
     if (index_bits) *index_bits = t.index_bits();
     return PVQ_OK;
 }
 
 extern "C" int pvq_max_k(int D, int bit_budget, int *K)
 {
-    if (D < 1 || D > 256 || bit_budget < 1 || bit_budget > 255 || !K) return PVQ_E_INVALID_ARG;
+    if (D < 1 || D > 256 || bit_budget < 1 || bit_budget > 511 || !K) return PVQ_E_INVALID_ARG;
     // One table with a generous K bound; N(D,k) grows with k, so the first k that does not fit
-    // (or that left the 256-bit integers) ends the search.
+    // (or that left the 512-bit integers) ends the search.
     int kmax = 1024;
     SizeTable t(D, kmax);
     int best = 0;
     for (int k = 1; k <= kmax && k < t.first_bad_k; k++) {
-        U256 top = t.at(D, k);
+        U512 top = t.at(D, k);
         top.decrement();
         if (top.bit_length() > bit_budget) break;
         best = k;
@@ -203,16 +203,20 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
 {
     if (!out) return PVQ_E_INVALID_ARG;
     *out = nullptr;
-    if (D != 8 && D != 16 && D != 32) return PVQ_E_UNSUPPORTED;
-    if (K < 1 || K > 127) return PVQ_E_UNSUPPORTED;
-    if (!scale_bits_ok(scale_bits)) return PVQ_E_UNSUPPORTED;
+    // groups of 64 and 128 values (the on-the-fly activation setting) go to the kernels of pvq_wide.hip:
+    // a wave per group, tables of up to 16-word integers streamed from device memory
+    const bool wide = D == 64 || D == 128;
+    if (!wide && D != 8 && D != 16 && D != 32) return PVQ_E_UNSUPPORTED;
+    if (K < 1 || K > (wide ? 1023 : 127)) return PVQ_E_UNSUPPORTED;
+    if (!scale_bits_ok(scale_bits) || (wide && scale_bits != 0)) return PVQ_E_UNSUPPORTED;
     if (scale_bits > 0 && (!edges || !centers)) return PVQ_E_INVALID_ARG;
 
     SizeTable t(D, K);
     if (t.overflow) return PVQ_E_UNSUPPORTED;
     int bits = t.index_bits();
-    if (bits < 1 || bits > 128) return PVQ_E_UNSUPPORTED;
+    if (bits < 1 || bits > (wide ? 512 : 128)) return PVQ_E_UNSUPPORTED;
     int words = bits <= 32 ? 1 : (bits <= 64 ? 2 : 4);
+    if (wide) words = 4 * ((std::max(t.at(D, K).bit_length(), 1) + 127) / 128);   // N(D,K) itself is an entry
 
     int n = scale_bits ? (1 << scale_bits) : 0;
     std::vector<float> e32, sc32;
@@ -230,12 +234,33 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     // tab_n[dp][k] = N(dp,k); tab_u[dp][k+1] = N(dp,0) + ... + N(dp,k), tab_u[dp][0] = 0.
     // Every entry is below N(D,K) (the pyramid of one more dimension contains all of them), so it
     // fits `words` words.
-    std::vector<uint32_t> hn((size_t)D * (K + 1) * words), hu((size_t)D * (K + 2) * words);
-    for (int dp = 0; dp < D; dp++) {
-        U256 run;  // running sum
+    std::vector<uint32_t> hn, hu;
+    if (wide) {
+        // tab_n[d][k] = N(d,k), d = 0..D;  tab_u[d][k] = 2 (N(d,0) + ... + N(d,k)) mod 2^(32 words), d = 0..D-1
+        hn.resize((size_t)(D + 1) * (K + 1) * words);
+        hu.resize((size_t)D * (K + 1) * words);
+        for (int d = 0; d <= D; d++) {
+            U512 run;
+            for (int k = 0; k <= K; k++) {
+                const U512 &v = t.at(d, k);
+                run.add(v);
+                U512 twice = run;
+                twice.add(run);
+                for (int w = 0; w < words; w++) {
+                    hn[((size_t)d * (K + 1) + k) * words + w] = v.word(w);
+                    if (d < D) hu[((size_t)d * (K + 1) + k) * words + w] = twice.word(w);
+                }
+            }
+        }
+    } else {
+        hn.resize((size_t)D * (K + 1) * words);
+        hu.resize((size_t)D * (K + 2) * words);
+    }
+    for (int dp = 0; dp < D && !wide; dp++) {
+        U512 run;  // running sum
         for (int w = 0; w < words; w++) hu[((size_t)dp * (K + 2)) * words + w] = 0;
         for (int k = 0; k <= K; k++) {
-            const U256 &v = t.at(dp, k);
+            const U512 &v = t.at(dp, k);
             run.add(v);
             for (int w = 0; w < words; w++) {
                 hn[((size_t)dp * (K + 1) + k) * words + w] = v.word(w);
@@ -246,7 +271,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
 
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
-    c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits;
+    c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits; c->wide = wide ? 1 : 0;
     c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
@@ -419,8 +444,10 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
     a.pulses_out = pulses_out;
     a.index_row_words = stream_words(a.groups, c->index_bits);
     a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
-    hipError_t e = pvq_encode8_usable(c, a) ? pvq_encode8_launch(c, a, dtype, (hipStream_t)stream)
-                                            : pvq_launch_encode(c, a, dtype, (hipStream_t)stream);
+    if (c->wide && pulses_out && c->K > 127) return PVQ_E_UNSUPPORTED;   // int8 cannot hold such pulses
+    hipError_t e = c->wide ? pvq_wide_launch_encode(c, a, dtype, (hipStream_t)stream)
+                   : pvq_encode8_usable(c, a) ? pvq_encode8_launch(c, a, dtype, (hipStream_t)stream)
+                                              : pvq_launch_encode(c, a, dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
@@ -453,8 +480,9 @@ extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *s
     if ((rc = fill_decode_args(c, a, index, scale, rownorm, rows, cols))) return rc;
     if ((rc = check_device(c))) return rc;
     a.W_out = W_out; a.ldw = ldw;
-    hipError_t e = pvq_fast8_decode_usable(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
-                                                 : pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
+    hipError_t e = c->wide ? pvq_wide_launch_decode(c, a, out_dtype, (hipStream_t)stream)
+                   : pvq_fast8_decode_usable(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
+                                                   : pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
@@ -465,7 +493,7 @@ extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const vo
     int rc = check_shape(c, rows, cols);
     if (rc) return rc;
     if (batch < 0) return PVQ_E_INVALID_ARG;
-    if (batch > 16) return PVQ_E_UNSUPPORTED;
+    if (batch > 16 || (c && c->wide)) return PVQ_E_UNSUPPORTED;
     if (rows == 0 || batch == 0) return PVQ_OK;
     if (!y || ldy < rows) return PVQ_E_INVALID_ARG;
     if (!aligned(y, 4)) return PVQ_E_ALIGNMENT;

@@ -11,7 +11,9 @@
 struct pvq_ctx {
     int D, K;
     int index_bits;
-    int words;       // 32-bit words of one table entry / one index in registers: 1, 2 or 4
+    int words;       // 32-bit words of one table entry / one index in registers: 1, 2 or 4 (wide: 4..16)
+    int wide;        // 1: D = 64 or 128; tab_n[d][k] = N(d,k) for d = 0..D, tab_u[d][k] = 2 (N(d,0)+...+N(d,k))
+                     //    mod 2^(32 words) for d = 0..D-1, both [.][K+1][words]; kernels in pvq_wide.hip
     int scale_bits;  // 0 = float32 amplitudes
     int device;
     // Device tables.  Entries are `words` little-endian 32-bit words.
@@ -92,6 +94,10 @@ hipError_t pvq_launch_size_table(int D, int K, int words, uint32_t *table, uint3
 hipError_t pvq_launch_hadamard(const void *X, int in_dtype, int64_t rows, int64_t cols, int64_t ldx, int block,
                                const uint8_t *signs, int signs_after, void *Y, int out_dtype, int64_t ldy,
                                hipStream_t s);
+
+// groups of 64 / 128 values, indices of up to 512 bits (pvq_wide.hip); for contexts with wide == 1
+hipError_t pvq_wide_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
+hipError_t pvq_wide_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);

@@ -1,0 +1,480 @@
+// PVQ of long groups, D = 64 or 128 values with indices of up to 512 bits: the setting of on-the-fly
+// quantisation of activations (Sec. 3.2, Sec. 4.3), e.g. D = 128, K = 187 for
+// 3 bits per value (384-bit indices).  Amplitudes are float32 (Sec. 3.3 Step 5 quantises them only for
+// small groups).  The size table no longer fits LDS (1.2 MB for (128,187)); it is read from device
+// memory, where the L2 keeps it.
+//
+// Two tables of W-word integers (W = 4, 8, 12 or 16; arithmetic is modulo 2^(32W), every true result
+// fits):  N(d,k), and E(d,k) = 2 (N(d,0) + ... + N(d,k)).  With them the number of points of P(d,k)
+// whose first coordinate has magnitude below m >= 1 is  A(m) = N(d,k) - E(d-1,k-m)  (all points minus
+// those of magnitude m or more, two signs each), so that, in the order 0, +1, -1, +2, -2, ... of
+// App. B.2, a first coordinate +m has A(m) points before it and -m has A(m) + N(d-1,k-m).
+//
+// Encoding (Sec. 2.5 for the point, App. B.2 for its index): one wave per group, lane l holds coordinates
+// CP*l .. CP*l+CP-1 (CP = D/64).  The quantiser's sums run over adjacent pairs level by level (in the
+// lane, then lane^1, lane^2, ...), the repair of the pulse count picks one coordinate per step by a
+// wave-wide argmax (lowest coordinate on ties).  The index is a sum of per-coordinate terms that depend
+// on the coordinate's magnitude, sign and the pulses left before it only; a prefix sum over the
+// magnitudes gives the latter, every lane adds up its coordinates' terms from two table entries each,
+// and a butterfly of multi-word additions gives the total.  Because the pulses left after coordinate i
+// are those before coordinate i+1, the N(d-1,k-m) of a negative coordinate is the N(d,k) of the next
+// one and is read once.
+//
+// Decoding (App. B.3): one lane per group, coordinate by coordinate.  The lane keeps q = N(d,k) - 1 - r
+// for the residual r; the coordinate's magnitude is the smallest m with E(d-1,k-1-m) <= q (E(.,-1) = 0),
+// one table entry and one multi-word subtraction per step, and the difference of the last failed step
+// gives the next q.  Points go to LDS as int16, and the waves then write whole groups with consecutive
+// lanes on consecutive addresses.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "pvq_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+template <int W>
+struct wint {
+    uint32_t w[W];
+};
+
+template <int W>
+__device__ inline wint<W> load_entry(const uint32_t *tab, int64_t entry)
+{
+    wint<W> r;
+    const uint4 *p = reinterpret_cast<const uint4 *>(tab + entry * W);
+#pragma unroll
+    for (int i = 0; i < W / 4; i++) {
+        const uint4 v = p[i];
+        r.w[4 * i] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+    }
+    return r;
+}
+
+// a += b (modulo 2^(32W))
+template <int W>
+__device__ inline void add_to(wint<W> &a, const wint<W> &b)
+{
+    uint32_t carry = 0;
+#pragma unroll
+    for (int i = 0; i < W; i++) {
+        const uint64_t s = (uint64_t)a.w[i] + b.w[i] + carry;
+        a.w[i] = (uint32_t)s;
+        carry = (uint32_t)(s >> 32);
+    }
+}
+
+// a - b (modulo 2^(32W)); *borrow = 1 when b > a
+template <int W>
+__device__ inline wint<W> subtract(const wint<W> &a, const wint<W> &b, uint32_t *borrow)
+{
+    wint<W> r;
+    uint32_t br = 0;
+#pragma unroll
+    for (int i = 0; i < W; i++) {
+        const uint64_t s = (uint64_t)a.w[i] - b.w[i] - br;
+        r.w[i] = (uint32_t)s;
+        br = (uint32_t)(s >> 63);
+    }
+    *borrow = br;
+    return r;
+}
+
+__device__ inline float wave_sum_pairs(float v)
+{
+    // adjacent pairs, level by level; both lanes of a pair form the same sum
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = v + __shfl_xor(v, m, 64);
+    return v;
+}
+__device__ inline int wave_sum_int(int v)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+struct encode_wide_params {
+    const void *X;
+    int64_t ldx, groups, index_row_words;
+    int K, bits, tile_groups, tiles_per_row, ls;
+    const uint32_t *tab_n, *tab_e;
+    uint32_t *index_out;
+    float *scale_out;
+    int8_t *pulses_out;
+    int64_t cols;
+};
+
+// TIN: 0 = float32, 2 = bf16.  A workgroup takes tile_groups consecutive groups of one row, chosen so
+// that their indices fill whole words; the words are put together in LDS and stored once.
+template <int TIN, int CP, int W>
+__global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
+{
+    extern __shared__ __align__(16) uint32_t stream[];
+    constexpr int D = 64 * CP;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
+    const int64_t row = blockIdx.x / p.tiles_per_row;
+    const int tile = blockIdx.x - (int)(row * p.tiles_per_row);
+    const int64_t g0 = (int64_t)tile * p.tile_groups;
+    const int ng = (int)min((int64_t)p.tile_groups, p.groups - g0);
+    const int tile_words = (int)(((int64_t)ng * p.bits + 31) / 32);
+    const int64_t first_word = g0 * p.bits / 32;   // exact: tile_groups * bits is a multiple of 32
+    const int K = p.K;
+
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) stream[i] = 0;
+    __syncthreads();
+
+    for (int gi = wave; gi < ng; gi += nwaves) {
+        const int64_t g = g0 + gi;
+        float w[CP];
+        if constexpr (TIN == PVQ_F32) {
+            const float *src = reinterpret_cast<const float *>(p.X) + row * p.ldx + g * D + CP * lane;
+            if constexpr (CP == 2) {
+                const float2 v = *reinterpret_cast<const float2 *>(src);
+                w[0] = v.x; w[1] = v.y;
+            } else {
+                w[0] = src[0];
+            }
+        } else {
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(p.X) + row * p.ldx + g * D + CP * lane;
+            if constexpr (CP == 2) {
+                const uint32_t v = *reinterpret_cast<const uint32_t *>(src);
+                w[0] = __uint_as_float(v << 16); w[1] = __uint_as_float(v & 0xFFFF0000u);
+            } else {
+                w[0] = __uint_as_float((uint32_t)src[0] << 16);
+            }
+        }
+
+        // ---- the point (Sec. 2.5): project onto sum |t| = K, round, repair the pulse count
+        float a[CP], l1p, ssp;
+#pragma unroll
+        for (int j = 0; j < CP; j++) a[j] = fabsf(w[j]);
+        if constexpr (CP == 2) { l1p = a[0] + a[1]; ssp = w[0] * w[0] + w[1] * w[1]; }
+        else { l1p = a[0]; ssp = w[0] * w[0]; }
+        const float l1 = wave_sum_pairs(l1p), ss = wave_sum_pairs(ssp);
+        const float gain = (float)K / l1;
+        const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(gain < INFINITY);
+        float t[CP];
+        int m[CP];
+        int S = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            t[j] = a[j] * gain;
+            m[j] = degenerate ? 0 : (int)rintf(t[j]);
+            S += m[j];
+        }
+        S = wave_sum_int(S);
+        if (degenerate) {
+            if (lane == 63) m[CP - 1] = K;   // the point (0, ..., 0, +K): index 0
+            S = K;
+        }
+        // one pulse per step: off the coordinate that lies furthest above its projected value (among
+        // those that have one), or onto the one furthest below; ties go to the lowest coordinate.  A
+        // valid group needs at most D/2 steps.
+        for (int step = 0; step < D && S != K; step++) {
+            const bool down = S > K;
+            float be = -INFINITY;
+            int bi = 0x7FFFFFFF;
+#pragma unroll
+            for (int j = 0; j < CP; j++) {
+                const float e = down ? (float)m[j] - t[j] : t[j] - (float)m[j];
+                const bool can = !down || m[j] > 0;
+                if (can && (bi == 0x7FFFFFFF || e > be)) { be = e; bi = CP * lane + j; }
+            }
+#pragma unroll
+            for (int x = 1; x < 64; x <<= 1) {
+                const float oe = __shfl_xor(be, x, 64);
+                const int oi = __shfl_xor(bi, x, 64);
+                const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));
+                if (take) { be = oe; bi = oi; }
+            }
+#pragma unroll
+            for (int j = 0; j < CP; j++)
+                if (bi == CP * lane + j) m[j] += down ? -1 : 1;
+            S += down ? -1 : 1;
+        }
+
+        // ---- amplitude (Sec. 2.3, or Sec. 3.3 Step 4)
+        float amp;
+        if (p.ls) {
+            float dp;
+            int n2 = 0;
+            float pr[CP];
+#pragma unroll
+            for (int j = 0; j < CP; j++) {
+                const int ys = w[j] < 0.0f ? -m[j] : m[j];
+                pr[j] = (float)ys * w[j];
+                n2 += m[j] * m[j];
+            }
+            if constexpr (CP == 2) dp = pr[0] + pr[1]; else dp = pr[0];
+            amp = wave_sum_pairs(dp) / sqrtf((float)wave_sum_int(n2));
+        } else {
+            amp = sqrtf(ss);
+        }
+        if (lane == 0) p.scale_out[row * p.groups + g] = amp;
+        if (p.pulses_out) {
+#pragma unroll
+            for (int j = 0; j < CP; j++)
+                p.pulses_out[row * p.cols + g * D + CP * lane + j] = (int8_t)(w[j] < 0.0f ? -m[j] : m[j]);
+        }
+
+        // ---- the index (App. B.2): pulses left before each coordinate, then the terms
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) mine += m[j];
+        int incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        int k = K - (incl - mine);   // pulses left before this lane's first coordinate
+        bool neg_before;             // the coordinate before is negative
+        {
+            const int last_neg = (m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 1 : 0;
+            const int up = __shfl_up(last_neg, 1, 64);
+            neg_before = lane > 0 && up;
+        }
+        wint<W> acc;
+#pragma unroll
+        for (int i = 0; i < W; i++) acc.w[i] = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            const int d = D - (CP * lane + j);
+            const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
+            const int times = (mm > 0 ? 1 : 0) + (neg_before ? 1 : 0);      // how often N(d,k) counts
+            if (times) {
+                const wint<W> n = load_entry<W>(p.tab_n, (int64_t)d * (K + 1) + kk);
+                add_to(acc, n);
+                if (times == 2) add_to(acc, n);
+            }
+            if (mm > 0) {
+                const wint<W> e = load_entry<W>(p.tab_e, (int64_t)(d - 1) * (K + 1) + (kk - mm));
+                uint32_t br;
+                acc = subtract(acc, e, &br);
+            }
+            neg_before = mm > 0 && w[j] < 0.0f;
+            k = kk - mm;
+        }
+        if (lane == 63 && neg_before) {   // N(0,0) = 1 after a negative last coordinate
+            wint<W> one;
+#pragma unroll
+            for (int i = 0; i < W; i++) one.w[i] = 0;
+            one.w[0] = 1;
+            add_to(acc, one);
+        }
+#pragma unroll
+        for (int x = 1; x < 64; x <<= 1) {
+            wint<W> other;
+#pragma unroll
+            for (int i = 0; i < W; i++) other.w[i] = __shfl_xor(acc.w[i], x, 64);
+            add_to(acc, other);
+        }
+
+        // ---- into the tile's bit stream: lane i takes word i of the index, shifted to its place
+        uint32_t word = 0;
+#pragma unroll
+        for (int i = 0; i < W; i++) word = lane == i ? acc.w[i] : word;
+        const int off = gi * p.bits, sh = off & 31, w0 = off >> 5;
+        const uint32_t below = __shfl_up(word, 1, 64);
+        const uint32_t prev = lane > 0 ? below : 0u;
+        const uint32_t out = sh ? (word << sh) | (prev >> (32 - sh)) : word;
+        if (lane <= W && w0 + lane < tile_words && out) atomicOr(&stream[w0 + lane], out);
+    }
+    __syncthreads();
+    uint32_t *dst = p.index_out + row * p.index_row_words + first_word;
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) dst[i] = stream[i];
+}
+
+struct decode_wide_params {
+    const uint32_t *index;
+    const float *scale;
+    int64_t groups, total_groups, index_row_words, ldw;
+    int K, bits;
+    const uint32_t *tab_n, *tab_e;
+    void *W_out;
+};
+
+constexpr int kDecodeLanes = 128;
+
+// OUT: pvq_dtype of the result.  LDS: kDecodeLanes x (D + 2) int16 points, kDecodeLanes float32 gains.
+template <int OUT, int CP, int W>
+__global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_params p)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    constexpr int D = 64 * CP, LD = D + 2;   // int16 per group, odd number of words: lanes spread over the banks
+    int16_t *pts = reinterpret_cast<int16_t *>(lds_raw);
+    float *gains = reinterpret_cast<float *>(lds_raw + (size_t)kDecodeLanes * LD * 2);
+    const int K = p.K;
+    const int64_t gid = (int64_t)blockIdx.x * kDecodeLanes + threadIdx.x;
+    int16_t *mine = pts + (size_t)threadIdx.x * LD;
+
+    if (gid < p.total_groups) {
+        const int64_t row = gid / p.groups, g = gid - row * p.groups;
+        const uint32_t *src = p.index + row * p.index_row_words;
+        // the group's index: bits [g*bits, (g+1)*bits) of the row's stream
+        wint<W> r;
+#pragma unroll
+        for (int i = 0; i < W; i++) {
+            const int left = p.bits - 32 * i;
+            uint32_t v = 0;
+            if (left > 0) {
+                const int64_t at = g * p.bits + 32 * i;
+                const int64_t wi = at >> 5;
+                const int sh = (int)(at & 31);
+                v = src[wi] >> sh;
+                if (sh && wi + 1 < p.index_row_words) v |= src[wi + 1] << (32 - sh);
+                if (left < 32) v &= (1u << left) - 1u;
+            }
+            r.w[i] = v;
+        }
+        // q = N(D,K) - 1 - r; an index that is no codeword decodes to zeros
+        uint32_t br;
+        wint<W> q = subtract(load_entry<W>(p.tab_n, (int64_t)D * (K + 1) + K), r, &br);
+        bool valid = !br;
+        {
+            wint<W> one;
+#pragma unroll
+            for (int i = 0; i < W; i++) one.w[i] = 0;
+            one.w[0] = 1;
+            q = subtract(q, one, &br);
+            valid = valid && !br;
+        }
+        int k = valid ? K : 0;
+        int n2 = 0;
+        for (int i = 0; i < D; i++) {
+            const int d = D - i;
+            int y = 0;
+            if (k > 0) {
+                if (d == 1) {
+                    // the two points +k, -k of P(1,k): q = 1, 0
+                    bool zero = true;
+#pragma unroll
+                    for (int x = 0; x < W; x++) zero = zero && q.w[x] == 0;
+                    y = zero ? -k : k;
+                    k = 0;
+                } else {
+                    const uint32_t *erow = p.tab_e + (int64_t)(d - 1) * (K + 1) * W;
+                    int m = 0;
+                    wint<W> diff = q;       // q - E(d-1, k-m) of the last step that failed
+                    for (; m < k; m++) {
+                        uint32_t b;
+                        const wint<W> t = subtract(q, load_entry<W>(erow, k - 1 - m), &b);
+                        if (!b) { if (m == 0) q = t; break; }   // E <= q: magnitude m; for m = 0 the next q is q - E
+                        diff = t;
+                    }
+                    if (m > 0) {
+                        // inside the block of magnitude m: v = q - E(d-1,k-m) + N(d-1,k-m); negative means
+                        // the second half of the block (the coordinate is -m), whose q is v + N(d-1,k-m)
+                        const wint<W> n = load_entry<W>(p.tab_n, (int64_t)(d - 1) * (K + 1) + (k - m));
+                        add_to(diff, n);
+                        const bool negative = diff.w[W - 1] >> 31;
+                        if (negative) add_to(diff, n);
+                        q = diff;
+                        y = negative ? -m : m;
+                        k -= m;
+                    }
+                }
+            }
+            mine[i] = (int16_t)y;
+            n2 += y * y;
+        }
+        gains[threadIdx.x] = valid ? p.scale[gid] / sqrtf((float)n2) : 0.0f;
+    }
+    __syncthreads();
+
+    // whole groups out, a wave per group in turn
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int s = wave; s < kDecodeLanes; s += kDecodeLanes / 64) {
+        const int64_t og = (int64_t)blockIdx.x * kDecodeLanes + s;
+        if (og >= p.total_groups) break;
+        const int64_t row = og / p.groups, g = og - row * p.groups;
+        const float gain = gains[s];
+        const int16_t *pt = pts + (size_t)s * LD + CP * lane;
+        float v[CP];
+#pragma unroll
+        for (int j = 0; j < CP; j++) v[j] = gain * (float)pt[j];
+        const int64_t at = row * p.ldw + g * D + CP * lane;
+        if constexpr (OUT == PVQ_F32) {
+            float *o = reinterpret_cast<float *>(p.W_out) + at;
+            if constexpr (CP == 2) *reinterpret_cast<float2 *>(o) = make_float2(v[0], v[1]);
+            else o[0] = v[0];
+        } else if constexpr (OUT == PVQ_F16) {
+            __half *o = reinterpret_cast<__half *>(p.W_out) + at;
+            if constexpr (CP == 2) *reinterpret_cast<__half2 *>(o) = __halves2half2(__float2half_rn(v[0]), __float2half_rn(v[1]));
+            else o[0] = __float2half_rn(v[0]);
+        } else {
+            uint16_t *o = reinterpret_cast<uint16_t *>(p.W_out) + at;
+            if constexpr (CP == 2) {
+                const f32x2_t pair = {v[0], v[1]};
+                *reinterpret_cast<uint32_t *>(o) = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t));
+            } else {
+                const f32x2_t pair = {v[0], 0.0f};
+                o[0] = (uint16_t)__builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t));
+            }
+        }
+    }
+}
+
+int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
+
+}  // namespace
+
+hipError_t pvq_wide_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, int dtype, hipStream_t s)
+{
+    encode_wide_params p;
+    p.X = a.W; p.ldx = a.ldw; p.groups = a.groups; p.index_row_words = a.index_row_words;
+    p.K = c->K; p.bits = c->index_bits; p.ls = a.ls_amplitude;
+    p.tile_groups = 32 / gcd_int(c->index_bits, 32);
+    p.tiles_per_row = (int)((a.groups + p.tile_groups - 1) / p.tile_groups);
+    p.tab_n = c->tab_n; p.tab_e = c->tab_u;
+    p.index_out = a.index_out; p.scale_out = reinterpret_cast<float *>(a.scale_out); p.pulses_out = a.pulses_out;
+    p.cols = a.cols;
+    if (a.rows * p.tiles_per_row > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int waves = p.tile_groups < 8 ? p.tile_groups : 8;
+    const size_t lds = (size_t)(p.tile_groups * c->index_bits / 32) * 4;
+    const dim3 grid((unsigned)(a.rows * p.tiles_per_row)), blk(64u * waves);
+#define PVQ_WIDE_ENC(T, CP, W) hipLaunchKernelGGL((encode_wide_kernel<T, CP, W>), grid, blk, lds, s, p)
+#define PVQ_WIDE_ENC_W(T, CP)                                  \
+    switch (c->words) {                                        \
+    case 4: PVQ_WIDE_ENC(T, CP, 4); break;                     \
+    case 8: PVQ_WIDE_ENC(T, CP, 8); break;                     \
+    case 12: PVQ_WIDE_ENC(T, CP, 12); break;                   \
+    default: PVQ_WIDE_ENC(T, CP, 16); break;                   \
+    }
+    if (dtype == PVQ_F32) { if (c->D == 128) { PVQ_WIDE_ENC_W(PVQ_F32, 2) } else { PVQ_WIDE_ENC_W(PVQ_F32, 1) } }
+    else { if (c->D == 128) { PVQ_WIDE_ENC_W(PVQ_BF16, 2) } else { PVQ_WIDE_ENC_W(PVQ_BF16, 1) } }
+#undef PVQ_WIDE_ENC_W
+#undef PVQ_WIDE_ENC
+    return hipGetLastError();
+}
+
+hipError_t pvq_wide_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
+{
+    decode_wide_params p;
+    p.index = a.index; p.scale = reinterpret_cast<const float *>(a.scale);
+    p.groups = a.groups; p.total_groups = a.rows * a.groups; p.index_row_words = a.index_row_words; p.ldw = a.ldw;
+    p.K = c->K; p.bits = c->index_bits; p.tab_n = c->tab_n; p.tab_e = c->tab_u; p.W_out = a.W_out;
+    if ((p.total_groups + kDecodeLanes - 1) / kDecodeLanes > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const size_t lds = (size_t)kDecodeLanes * (c->D + 2) * 2 + (size_t)kDecodeLanes * 4;
+    const dim3 grid((unsigned)((p.total_groups + kDecodeLanes - 1) / kDecodeLanes)), blk(kDecodeLanes);
+#define PVQ_WIDE_DEC(O, CP, W) hipLaunchKernelGGL((decode_wide_kernel<O, CP, W>), grid, blk, lds, s, p)
+#define PVQ_WIDE_DEC_W(O, CP)                                  \
+    switch (c->words) {                                        \
+    case 4: PVQ_WIDE_DEC(O, CP, 4); break;                     \
+    case 8: PVQ_WIDE_DEC(O, CP, 8); break;                     \
+    case 12: PVQ_WIDE_DEC(O, CP, 12); break;                   \
+    default: PVQ_WIDE_DEC(O, CP, 16); break;                   \
+    }
+#define PVQ_WIDE_DEC_D(O) if (c->D == 128) { PVQ_WIDE_DEC_W(O, 2) } else { PVQ_WIDE_DEC_W(O, 1) }
+    if (out_dtype == PVQ_F32) { PVQ_WIDE_DEC_D(PVQ_F32) }
+    else if (out_dtype == PVQ_F16) { PVQ_WIDE_DEC_D(PVQ_F16) }
+    else { PVQ_WIDE_DEC_D(PVQ_BF16) }
+#undef PVQ_WIDE_DEC_D
+#undef PVQ_WIDE_DEC_W
+#undef PVQ_WIDE_DEC
+    return hipGetLastError();
+}

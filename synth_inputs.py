@@ -88,6 +88,25 @@ def activations(batch: int, cols: int, seed: int):
     return bf16_bits_to_f32(bits), bits
 
 
+def activation_matrix(tokens: int, hidden: int, seed: int, rotate: bool = True, bf16: bool = True):
+    """Stand-in for a batch of transformer activations [tokens][hidden]: i.i.d. N(0,1) with a few
+    channels (1 in 128, the same for every token) carrying 20x the magnitude and a per-token scale,
+    log-normal over tokens; then, as the method does before quantising (Sec. 3.3 Step 1), the randomised
+    Hadamard rotation along each row, which spreads the outlier channels.  With bf16=True returns
+    (float32 values equal to the bf16 numbers, uint16 bit patterns), else float32."""
+    rng = np.random.default_rng(seed + 300)
+    x = rng.standard_normal((tokens, hidden), dtype=np.float32)
+    outliers = rng.choice(hidden, size=max(1, hidden // 128), replace=False)
+    x[:, outliers] *= np.float32(20.0)
+    x *= np.exp(rng.standard_normal((tokens, 1)) * 0.5).astype(np.float32)
+    if rotate:
+        x = hadamard_rotate_rows(x, seed + 400)
+    if bf16:
+        bits = f32_to_bf16_bits(x)
+        return bf16_bits_to_f32(bits), bits
+    return x
+
+
 def adversarial_groups(n_groups: int, D: int, seed: int) -> np.ndarray:
     """Groups built to sit on rounding ties and fix-up ties: small-integer and half-integer
     multiples of a power of two, repeated magnitudes, zeros, mixed signs, one-hot and all-zero

@@ -34,7 +34,7 @@ def test_status_strings():
     assert L.pvq_strerror(-99) == b"unknown status"
 
 
-@pytest.mark.parametrize("D,K", [(2, 7), (8, 16), (16, 33), (32, 60), (64, 40), (3, 1), (5, 0)])
+@pytest.mark.parametrize("D,K", [(2, 7), (8, 16), (16, 33), (32, 60), (64, 40), (3, 1), (5, 0), (128, 187), (128, 382)])
 def test_pvq_count(D, K):
     n, bits = pvq.pvq_count(D, K)
     assert n == pins.n_binomial(D, K)
@@ -50,12 +50,12 @@ def test_pvq_count_rejects_what_it_cannot_hold():
     assert e.value.status == -1
 
 
-@pytest.mark.parametrize("D,budget,K", [(8, 24, 16), (16, 52, 33), (32, 104, 60)])
+@pytest.mark.parametrize("D,budget,K", [(8, 24, 16), (16, 52, 33), (32, 104, 60), (128, 384, 187), (64, 192, 96)])
 def test_pvq_max_k_on_the_measured_settings(D, budget, K):
     assert pvq.pvq_max_k(D, budget) == K
 
 
-@pytest.mark.parametrize("D,budget", [(4, 13), (8, 16), (16, 40), (24, 77), (128, 255), (256, 255)])
+@pytest.mark.parametrize("D,budget", [(4, 13), (8, 16), (16, 40), (24, 77), (128, 255), (256, 255), (128, 511), (64, 300)])
 def test_pvq_max_k_is_the_largest_that_fits(D, budget):
     K = pvq.pvq_max_k(D, budget)
     assert (pins.n_binomial(D, K) - 1).bit_length() <= budget < (pins.n_binomial(D, K + 1) - 1).bit_length()

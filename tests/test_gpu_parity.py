@@ -135,6 +135,81 @@ def test_adversarial_groups(D, K):
     run_case(W, D, K, 0, batches=(1,), out_dtypes=("f32",))
 
 
+def run_long_groups(X32, D, K, src_bits=None, amplitude="l2", want_pulses=False):
+    """Groups of 64 / 128 values (the on-the-fly activation setting): indices and float32 amplitudes
+    identical to the oracle's, decoded values within 1e-6 relative / 1 ulp; the fused product does
+    not exist for them."""
+    rows, cols = X32.shape
+    ctx = pvq.pvq_ctx_create(D, K)
+    assert ctx.index_bits == oracle.index_bits(D, K)
+    if amplitude == "ls":
+        ctx.set_amplitude("ls")
+    Xd = gu.to_dev_bf16(src_bits) if src_bits is not None else gu.to_dev_f32(X32)
+    packed = pvq.pvq_encode(ctx, Xd, want_pulses=want_pulses)
+    torch.cuda.synchronize()
+    enc = oracle.encode(X32, D, K, 0, None, nthreads=8, amplitude=amplitude)
+    gu.assert_encode_equal(packed, enc, check_pulses=want_pulses)
+    ref, _, _ = oracle.decode(enc, None, nthreads=8)
+    gu.assert_decode_close(pvq.pvq_decode(ctx, packed, torch.float32).cpu().numpy(), ref)
+    got = pvq.pvq_decode(ctx, packed, torch.float16).cpu().numpy()
+    assert gu.ulp_f16(oracle.to_f16(ref).view(np.uint16), got.view(np.uint16)) <= 1
+    got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
+    assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_decode_gemv(ctx, packed, torch.zeros((1, cols), dtype=torch.bfloat16, device="cuda"))
+    assert e.value.status == -2
+    ctx.close()
+
+
+@pytest.mark.parametrize("D,bits_per_value,tokens,hidden", [(128, 3, 48, 2048), (128, 2, 33, 1024), (128, 4, 9, 1024),
+                                                            (64, 3, 40, 1024), (64, 2, 17, 64 * 13), (128, 3, 1, 128)])
+def test_long_groups_bf16_activations(D, bits_per_value, tokens, hidden):
+    # D = 128 at 3 bits per value is K = 187 with 384-bit indices (12 words); 2 and 4 bits give 8- and
+    # 16-word integers; D = 64 likewise with 6, 4 words.  Index widths that are no multiple of 32 pack
+    # several groups into a tile of whole words (ragged last tile at 13 groups per row)
+    K = pvq.pvq_max_k(D, bits_per_value * D - (2 if bits_per_value == 4 else 0))
+    xf, xb = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + D + bits_per_value,
+                                  rotate=(hidden & (hidden - 1)) == 0)
+    run_long_groups(xf, D, K, src_bits=xb)
+
+
+@pytest.mark.parametrize("D,K", [(128, 187), (64, 40), (64, 127), (128, 1), (64, 2), (128, 382)])
+def test_long_groups_float32_and_odd_widths(D, K):
+    # float32 source without rotation (outlier channels stay: a few huge coordinates per group), index
+    # widths of 123 bits (64, 40) and others that straddle words, int8 pulse plane where K allows it
+    X = si.activation_matrix(21, D * 7, seed=si.BASE_SEED + D + K, rotate=False, bf16=False)
+    run_long_groups(X, D, K, want_pulses=K <= 127)
+    run_long_groups(X, D, K, amplitude="ls")
+
+
+@pytest.mark.parametrize("D,K", [(128, 187), (64, 40)])
+def test_long_groups_adversarial(D, K):
+    # rounding ties, repair ties, zeros (index 0, amplitude 0), one-hot groups, wide dynamic range
+    n = 1 << 11
+    X = si.adversarial_groups(n, D, seed=55 + D).reshape(n * D // 1024, 1024)
+    run_long_groups(X, D, K)
+    run_long_groups(X, D, K, amplitude="ls")
+
+
+def test_long_groups_argument_errors():
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_ctx_create(128, 400)              # N(128,400) needs more than 512 bits
+    assert e.value.status == -2
+    e2, c2 = pvq.pvq_beta_tables(128, 64, 2)
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_ctx_create(128, 187, 2, e2, c2)   # amplitude codes are for small groups only
+    assert e.value.status == -2
+    ctx = pvq.pvq_ctx_create(128, 187)
+    X = torch.zeros((2, 256), dtype=torch.float32, device="cuda")
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_encode(ctx, X, want_pulses=True)  # no int8 pulse plane above K = 127
+    assert e.value.status == -2
+    out = pvq.pvq_encode(ctx, X)                  # all-zero groups: index 0, amplitude 0
+    assert int(out.index.abs().sum()) == 0 and float(out.scale.abs().sum()) == 0.0
+    assert float(pvq.pvq_decode(ctx, out, torch.float32).abs().sum()) == 0.0
+    ctx.close()
+
+
 def test_leading_dimensions_and_views():
     D, K = 8, 16
     rows, cols, ld = 33, 512, 640

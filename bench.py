@@ -295,6 +295,26 @@ def main():
             ms = timed(lambda: pvq.pvq_hadamard(W, blk, sg, out=Wout), reps=10)
             had[f"block_{blk}"] = {"ms": round(ms, 4), "GBps": round(2 * W.numel() * W.element_size() / ms / 1e6, 1)}
         ex["hadamard_bf16"] = had
+        # on-the-fly activation quantisation (Sec. 3.2, Sec. 4.3): groups of 128 values, 3 bits per value
+        # (K = 187, 384-bit indices), a prefill batch and a decode batch of hidden size 8192
+        K128 = pvq.pvq_max_k(128, 384)
+        ctxa = pvq.pvq_ctx_create(128, K128)
+        act = {"D": 128, "K": K128, "index_bits": ctxa.index_bits}
+        for tokens in (4096, 16):
+            _, xb = si.activation_matrix(tokens, 8192, seed=7)
+            X = torch.from_numpy(xb.view(np.int16)).to(dev).view(torch.bfloat16)
+            pa = pvq.alloc_packed(ctxa, tokens, 8192, dev)
+            Xo = torch.empty_like(X)
+            te = timed(lambda: pvq.pvq_encode(ctxa, X, out=pa), reps=10)
+            td = timed(lambda: pvq.pvq_decode(ctxa, pa, out=Xo), reps=10)
+            act[f"tokens_{tokens}"] = {"encode_ms": round(te, 4), "decode_ms": round(td, 4),
+                                       "encode_Gvalues_per_s": round(tokens * 8192 / te / 1e6, 2)}
+            if tokens == 16:
+                xf = si.bf16_bits_to_f32(xb)
+                t0 = time.perf_counter(); oracle.encode(xf, 128, K128, nthreads=1); t_cpu = time.perf_counter() - t0
+                act["oracle_one_core_Gvalues_per_s"] = round(tokens * 8192 / t_cpu / 1e9, 5)
+        ctxa.close()
+        ex["activation_pvq"] = act
         result["extras"] = ex
 
     if not args.no_cpu_baseline:

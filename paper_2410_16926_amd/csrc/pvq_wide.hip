@@ -59,11 +59,7 @@ __device__ inline void add_to(wint<W> &a, const wint<W> &b)
 {
     uint32_t carry = 0;
 #pragma unroll
-    for (int i = 0; i < W; i++) {
-        const uint64_t s = (uint64_t)a.w[i] + b.w[i] + carry;
-        a.w[i] = (uint32_t)s;
-        carry = (uint32_t)(s >> 32);
-    }
+    for (int i = 0; i < W; i++) a.w[i] = __builtin_addc(a.w[i], b.w[i], carry, &carry);
 }
 
 // a - b (modulo 2^(32W)); *borrow = 1 when b > a
@@ -73,27 +69,39 @@ __device__ inline wint<W> subtract(const wint<W> &a, const wint<W> &b, uint32_t 
     wint<W> r;
     uint32_t br = 0;
 #pragma unroll
-    for (int i = 0; i < W; i++) {
-        const uint64_t s = (uint64_t)a.w[i] - b.w[i] - br;
-        r.w[i] = (uint32_t)s;
-        br = (uint32_t)(s >> 63);
-    }
+    for (int i = 0; i < W; i++) r.w[i] = __builtin_subc(a.w[i], b.w[i], br, &br);
     *borrow = br;
     return r;
 }
 
+// A lane's value moved by one data-parallel-primitive pattern; lanes whose row is not in ROWS, or whose
+// source lies outside their row, get `idle`.
+template <int CTRL, int ROWS = 0xF>
+__device__ inline uint32_t dpp_move(uint32_t v, uint32_t idle = 0)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)idle, (int)v, CTRL, ROWS, 0xF, false);
+}
+
+// The six steps that bring a combination of all 64 lanes' values to lane 63: lane^1, lane^2 (quad
+// permutations), the other quad of the half row and the other half of the row (mirror patterns: the
+// partner holds the same value as every lane of its group by then), row 0 into 1 and 2 into 3, rows 0..1
+// into 2..3.  For sums this is the adjacent-pair order, level by level.  No LDS traffic.
+#define PVQ_WAVE_STEPS(STEP)                                       \
+    STEP(0xB1, 0xF) STEP(0x4E, 0xF) STEP(0x141, 0xF) STEP(0x140, 0xF) STEP(0x142, 0xA) STEP(0x143, 0xC)
+
 __device__ inline float wave_sum_pairs(float v)
 {
-    // adjacent pairs, level by level; both lanes of a pair form the same sum
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v = v + __shfl_xor(v, m, 64);
-    return v;
+#define PVQ_STEP(CTRL, ROWS) v = v + __uint_as_float(dpp_move<CTRL, ROWS>(__float_as_uint(v)));
+    PVQ_WAVE_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+    return __uint_as_float(__builtin_amdgcn_readlane((int)__float_as_uint(v), 63));
 }
 __device__ inline int wave_sum_int(int v)
 {
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
-    return v;
+#define PVQ_STEP(CTRL, ROWS) v += (int)dpp_move<CTRL, ROWS>((uint32_t)v);
+    PVQ_WAVE_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 struct encode_wide_params {
@@ -184,13 +192,16 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
                 const bool can = !down || m[j] > 0;
                 if (can && (bi == 0x7FFFFFFF || e > be)) { be = e; bi = CP * lane + j; }
             }
-#pragma unroll
-            for (int x = 1; x < 64; x <<= 1) {
-                const float oe = __shfl_xor(be, x, 64);
-                const int oi = __shfl_xor(bi, x, 64);
-                const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));
-                if (take) { be = oe; bi = oi; }
-            }
+#define PVQ_STEP(CTRL, ROWS)                                                                             \
+    {                                                                                                    \
+        const float oe = __uint_as_float(dpp_move<CTRL, ROWS>(__float_as_uint(be), 0xFF800000u));        \
+        const int oi = (int)dpp_move<CTRL, ROWS>((uint32_t)bi, 0x7FFFFFFFu);                             \
+        const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));    \
+        if (take) { be = oe; bi = oi; }                                                                  \
+    }
+            PVQ_WAVE_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+            bi = __builtin_amdgcn_readlane(bi, 63);
 #pragma unroll
             for (int j = 0; j < CP; j++)
                 if (bi == CP * lane + j) m[j] += down ? -1 : 1;
@@ -225,12 +236,13 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
         int mine = 0;
 #pragma unroll
         for (int j = 0; j < CP; j++) mine += m[j];
-        int incl = mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int up = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += up;
-        }
+        int incl = mine;   // inclusive prefix sum over the lanes: inside the rows of 16, then across them
+        incl += (int)dpp_move<0x111>((uint32_t)incl);        // row_shr:1
+        incl += (int)dpp_move<0x112>((uint32_t)incl);        // row_shr:2
+        incl += (int)dpp_move<0x114>((uint32_t)incl);        // row_shr:4
+        incl += (int)dpp_move<0x118>((uint32_t)incl);        // row_shr:8
+        incl += (int)dpp_move<0x142, 0xA>((uint32_t)incl);   // lane 15 of rows 0, 2 into rows 1, 3
+        incl += (int)dpp_move<0x143, 0xC>((uint32_t)incl);   // lane 31 into rows 2, 3
         int k = K - (incl - mine);   // pulses left before this lane's first coordinate
         bool neg_before;             // the coordinate before is negative
         {
@@ -266,18 +278,23 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
             one.w[0] = 1;
             add_to(acc, one);
         }
-#pragma unroll
-        for (int x = 1; x < 64; x <<= 1) {
-            wint<W> other;
-#pragma unroll
-            for (int i = 0; i < W; i++) other.w[i] = __shfl_xor(acc.w[i], x, 64);
-            add_to(acc, other);
-        }
+#define PVQ_STEP(CTRL, ROWS)                                                           \
+    {                                                                                  \
+        wint<W> other;                                                                 \
+        _Pragma("unroll") for (int i = 0; i < W; i++) other.w[i] = dpp_move<CTRL, ROWS>(acc.w[i]); \
+        add_to(acc, other);                                                            \
+    }
+        PVQ_WAVE_STEPS(PVQ_STEP)
+#undef PVQ_STEP
 
-        // ---- into the tile's bit stream: lane i takes word i of the index, shifted to its place
+        // ---- into the tile's bit stream: lane i takes word i of the index (lane 63 has it), shifted to
+        // its place
         uint32_t word = 0;
 #pragma unroll
-        for (int i = 0; i < W; i++) word = lane == i ? acc.w[i] : word;
+        for (int i = 0; i < W; i++) {
+            const uint32_t wi = (uint32_t)__builtin_amdgcn_readlane((int)acc.w[i], 63);
+            word = lane == i ? wi : word;
+        }
         const int off = gi * p.bits, sh = off & 31, w0 = off >> 5;
         const uint32_t below = __shfl_up(word, 1, 64);
         const uint32_t prev = lane > 0 ? below : 0u;

@@ -12,11 +12,11 @@
 //
 // Encoding (Sec. 2.5 for the point, App. B.2 for its index): one wave per group, lane l holds coordinates
 // CP*l .. CP*l+CP-1 (CP = D/64).  The quantiser's sums run over adjacent pairs level by level (in the
-// lane, then lane^1, lane^2, ...), the repair of the pulse count picks one coordinate per step by a
-// wave-wide argmax (lowest coordinate on ties).  The index is a sum of per-coordinate terms that depend
+// lane, then across lanes by data-parallel-primitive moves, no LDS traffic), the repair of the pulse
+// count picks one coordinate per step by a wave-wide argmax (lowest coordinate on ties).  The index is a sum of per-coordinate terms that depend
 // on the coordinate's magnitude, sign and the pulses left before it only; a prefix sum over the
 // magnitudes gives the latter, every lane adds up its coordinates' terms from two table entries each,
-// and a butterfly of multi-word additions gives the total.  Because the pulses left after coordinate i
+// and six levels of multi-word additions across the lanes give the total.  Because the pulses left after coordinate i
 // are those before coordinate i+1, the N(d-1,k-m) of a negative coordinate is the N(d,k) of the next
 // one and is read once.
 //

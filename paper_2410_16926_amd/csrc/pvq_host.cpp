@@ -502,7 +502,7 @@ extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const vo
         // an empty sum: y = 0
         hipError_t e = hipSuccess;
         for (int b = 0; b < batch && e == hipSuccess; b++)
-            e = hipMemsetAsync(y + (int64_t)b * ldy, 0, sizeof(float) * rows, (hipStream_t)stream);
+            e = pvq_launch_fill_zero(y + (int64_t)b * ldy, rows, (hipStream_t)stream);
         return e == hipSuccess ? PVQ_OK : hip_fail(e);
     }
     if (!x || ldx < cols) return PVQ_E_INVALID_ARG;

@@ -618,3 +618,23 @@ hipError_t pvq_launch_decode_gemv(const pvq_ctx *c, const pvq_decode_args &a, hi
     if (c->words == 2) return launch_gemv_dw<32, 2>(c, a, s);
     return launch_gemv_dw<32, 4>(c, a, s);
 }
+
+// ---------------------------------------------------------------------------------------------
+// y = 0 for a product over zero columns (a kernel rather than a memset, so that a caller may
+// capture the call into a graph)
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+__global__ void fill_zero_kernel(float *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+}  // namespace
+
+hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}

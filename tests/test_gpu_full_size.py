@@ -65,3 +65,21 @@ def test_llama3_70b_gate_projection_with_fused_product():
     # the benchmark's matrix shape (28672 x 8192) end to end, and the fused product at batch 1, 4, 16
     rows, cols = si.LLAMA3_70B_SHAPES["gate"]
     encode_decode_case(rows, cols, 8, 24, 2, si.BASE_SEED + 1200, batches=(1, 4, 16))
+
+
+def test_prefill_batch_of_activations_long_groups():
+    # the on-the-fly activation setting at the size bench.py --extras times: 4096 tokens x 8192, D=128,
+    # K=187 (384-bit indices), float32 amplitudes; whole index plane and amplitudes identical to the
+    # oracle's, decoded bf16 values within 1 ulp
+    tokens, hidden, D = 4096, 8192, 128
+    K = pvq.pvq_max_k(D, 3 * D)
+    ctx = pvq.pvq_ctx_create(D, K)
+    xf, xb = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + 1300)
+    packed = pvq.pvq_encode(ctx, gu.to_dev_bf16(xb))
+    torch.cuda.synchronize()
+    enc = oracle.encode(xf, D, K, 0, None, nthreads=THREADS)
+    gu.assert_encode_equal(packed, enc, check_pulses=False)
+    ref, _, _ = oracle.decode(enc, None, nthreads=THREADS)
+    got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
+    assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
+    ctx.close()

@@ -560,6 +560,155 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
 }
 
 // ---------------------------------------------------------------------------------------------
+// Many activation vectors: the dot products on the matrix cores
+// ---------------------------------------------------------------------------------------------
+
+// With 5..16 vectors the dot products (8 x 16 multiply-adds per group) outweigh the decoding, and they
+// are a dense contraction: a tile of 16 rows x 32 columns of decoded weights times 32 x 16 activations
+// is one v_mfma_f32_16x16x32_bf16.  Lane l of a wave holds row l%16 of the tile and the k-block l/16 of
+// the instruction's 32 columns, which is exactly one decoded group (8 values) per lane and instruction.
+// A wave takes 16 rows x 64 consecutive groups: lane (m, kb) decodes the groups  slab + 16*q + 4*kb + j
+// of its row, quad q = 0..3 after quad (j = 0..3 through the table decoder at once), so that the four
+// k-blocks read 16 neighbouring groups (48 contiguous bytes of indices, one word of codes); the
+// activations of the same 8 columns, for vector l%16, are the other operand, loaded as they are (bf16)
+// from device memory, where the caches hold them.
+// Weights w = gain * y go in as two bf16 terms, hi = w cut to bf16 and lo = (w - hi) cut to bf16, one
+// instruction each: products with bf16 activations are exact in float32 and w is represented to
+// 2^-15, far inside the product's tolerance.  Float32 accumulation, in the instruction's own fixed
+// order.  The 16 x 16 results of the waves that share a row tile meet in LDS, four waves per phase,
+// and are added in wave order (deterministic).
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kMfmaRows = 16;                 // rows of a tile
+constexpr int kMfmaSlab = 64;                 // groups of a row that one wave takes
+constexpr int kMfmaSlots = 4;                 // waves whose results meet in LDS at a time
+constexpr size_t kMfmaPartBytes = kMfmaSlots * 256 * sizeof(float);
+
+// AMP: 0 = float32 amplitudes, 1 = amplitude codes.  24-bit indices.  nsl = slabs per row (a multiple
+// of 4, at most 16), rl = row tiles that the workgroup's waves work on at a time.
+template <int AMP>
+__global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f, pvq_decode_args a, int b0,
+                                                                  int nvec, int nsl, int rl, int rows_per_block)
+{
+    constexpr bool CODES = AMP != 0;
+    __shared__ __align__(16) unsigned char lds[kLdsBytes];
+    float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.tab_bytes);
+    float *part = sqrtc_l + 256;
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
+    const int64_t r_last = r_end - 1;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int nwaves = nsl * rl;
+    const int slice = wave % nsl, rowlane = wave / nsl;
+    const int m = lane & 15, kb = lane >> 4;
+    const uint32_t gl0 = (uint32_t)(slice * kMfmaSlab + 4 * kb);   // the lane's first group: quad q starts 16 q further
+    const uint32_t sb = (uint32_t)f.scale_bits;
+
+    load_tables<false>(lds, f, sqrtc_l);
+    if (r_begin >= r_end) return;
+
+    // the other operand: vector m, the 8 columns of the lane's group.  Lanes beyond the vectors given read
+    // the last vector again (no condition around the loads); their columns of the result are not stored.
+    const uint16_t *xrow = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + std::min(m, nvec - 1)) * a.ldx + (int64_t)gl0 * 8;
+
+    // what a lane reads per four groups: three index words, and the word with the four codes or four floats
+    struct quad_t { uint32_t w[3]; uint32_t s[CODES ? 1 : 4]; };
+    auto fetch = [&](int64_t row, int q, quad_t &it) {
+        const uint32_t g = gl0 + 16u * (uint32_t)q;
+        const uint3 iw = *reinterpret_cast<const uint3 *>(a.index + row * a.index_row_words + (g >> 2) * 3u);   // one 12-byte load
+        it.w[0] = iw.x; it.w[1] = iw.y; it.w[2] = iw.z;
+        if constexpr (CODES) {
+            it.s[0] = (reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words)[(g * sb) >> 5];
+        } else {
+            const float *sp = reinterpret_cast<const float *>(a.scale) + row * a.groups + g;
+#pragma unroll
+            for (int j = 0; j < 4; j++) it.s[j] = __float_as_uint(sp[j]);
+        }
+    };
+
+    const int64_t tiles = (r_end - r_begin + kMfmaRows - 1) / kMfmaRows;
+    for (int64_t t0 = 0; t0 < tiles; t0 += rl) {
+        const int64_t tile = t0 + rowlane;                           // uniform in the wave
+        const bool live = wave < nwaves && tile < tiles;
+        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (live) {
+            const int64_t row = std::min<int64_t>(r_begin + tile * kMfmaRows + m, r_last);
+            quad_t cur, nxt;
+            fetch(row, 0, cur);
+#pragma unroll 1
+            for (int q = 0; q < 4; q++) {
+                fetch(row, q < 3 ? q + 1 : 3, nxt);
+                uint4 bx[4];
+#pragma unroll
+                for (int j = 0; j < 4; j++) bx[j] = *reinterpret_cast<const uint4 *>(xrow + (16 * q + j) * 8);
+                uint32_t c[4], pr[4][4], n2x4[4];
+                c[0] = cur.w[0] & 0xFFFFFFu;
+                c[1] = __builtin_amdgcn_alignbit(cur.w[1], cur.w[0], 24) & 0xFFFFFFu;
+                c[2] = __builtin_amdgcn_alignbit(cur.w[2], cur.w[1], 16) & 0xFFFFFFu;
+                c[3] = cur.w[2] >> 8;
+                pvq_fast8_decode<4, false>(lds, f.blob, f.p, c, pr, n2x4);
+                const uint32_t codes = CODES ? cur.s[0] >> (((gl0 + 16u * (uint32_t)q) * sb) & 31u) : 0u;
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]);
+                    if constexpr (CODES) gain *= sqrtc_l[(codes >> (j * sb)) & ((1u << sb) - 1u)];
+                    else gain *= __uint_as_float(cur.s[j]);
+                    uint32_t hi[4], lo[4];
+#pragma unroll
+                    for (int p2 = 0; p2 < 4; p2++) {
+                        const float w0 = gain * __uint_as_float(pr[j][p2] << 16);
+                        const float w1 = gain * __uint_as_float(pr[j][p2] & 0xFFFF0000u);
+                        const uint32_t u0 = __float_as_uint(w0), u1 = __float_as_uint(w1);
+                        hi[p2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);      // upper halves: w cut to bf16
+                        const float l0 = w0 - __uint_as_float(u0 & 0xFFFF0000u);
+                        const float l1 = w1 - __uint_as_float(u1 & 0xFFFF0000u);
+                        lo[p2] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
+                    }
+                    const uint4 hv = make_uint4(hi[0], hi[1], hi[2], hi[3]), lv = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    const bf16x8_t xb = __builtin_bit_cast(bf16x8_t, bx[j]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hv), xb, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, lv), xb, acc, 0, 0, 0);
+                }
+                cur = nxt;
+            }
+        }
+        // acc[r] = partial sum for row 4*kb + r of the tile and vector m.  Phases of four waves: slices
+        // 4p..4p+3 of one row tile each; thread (tile row, vector) of the first 256 adds them in order.
+        float sum = 0.0f;
+        const int phases = (nwaves + kMfmaSlots - 1) / kMfmaSlots;
+        for (int ph = 0; ph < phases; ph++) {
+            if (wave / kMfmaSlots == ph && wave < nwaves) {
+                float *slot = part + (wave % kMfmaSlots) * 256;
+#pragma unroll
+                for (int r = 0; r < 4; r++) slot[(4 * kb + r) * 16 + m] = live ? acc[r] : 0.0f;
+            }
+            __syncthreads();
+            if (threadIdx.x < 256) {
+#pragma unroll
+                for (int sidx = 0; sidx < kMfmaSlots; sidx++)
+                    if (ph * kMfmaSlots + sidx < nwaves) sum += part[sidx * 256 + threadIdx.x];
+                // the last slices of a row tile: its sums are complete
+                if (((ph + 1) * kMfmaSlots) % nsl == 0) {
+                    const int64_t otile = t0 + (ph * kMfmaSlots) / nsl;
+                    const int64_t orow = r_begin + otile * kMfmaRows + (threadIdx.x >> 4);
+                    const int n = threadIdx.x & 15;
+                    if (otile < tiles && orow < r_end && n < nvec) {
+                        float v = sum;
+                        if constexpr (CODES) v *= sqrtf(a.rownorm[orow]);
+                        a.y[(int64_t)(b0 + n) * a.ldy + orow] = v;
+                    }
+                    sum = 0.0f;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // decode to a matrix
 // ---------------------------------------------------------------------------------------------
 
@@ -782,6 +931,31 @@ hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
     return hipGetLastError();
 }
 
+// one launch of the matrix-core kernel for vectors [b0, b0 + nvec), nvec <= 16
+hipError_t launch_gemv_mfma(const pvq_ctx *c, const pvq_decode_args &a, int b0, int nvec, hipStream_t s)
+{
+    const fast8_launch f = make_launch(c, false);
+    const int nsl = (int)(a.groups / kMfmaSlab);
+    const int rl = std::max(1, (kGemvThreads / kWave) / nsl);
+    const int RB = kMfmaRows * rl;
+    const int64_t batches = (a.rows + RB - 1) / RB;
+    const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
+    const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);
+    const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)kGemvThreads);
+    if (f.scale_bits > 0) hipLaunchKernelGGL((gemv8_mfma_kernel<1>), grid, block, 0, s, f, a, b0, nvec, nsl, rl, rows_per_block);
+    else hipLaunchKernelGGL((gemv8_mfma_kernel<0>), grid, block, 0, s, f, a, b0, nvec, nsl, rl, rows_per_block);
+    return hipGetLastError();
+}
+
+// the matrix-core kernel takes 24-bit indices and rows of 4, 8, 12 or 16 slabs of 64 groups, and needs
+// room in LDS for the tables, the amplitude table and four waves' results
+bool mfma_usable(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    const int64_t nsl = a.groups / kMfmaSlab;
+    return c->index_bits == 24 && a.groups % (4 * kMfmaSlab) == 0 && nsl <= kGemvThreads / kWave &&
+           (size_t)c->fast8.tab_bytes + 256 * sizeof(float) + kMfmaPartBytes <= (size_t)kLdsBytes;
+}
+
 // the 16-vector kernel takes rows of at most 16 slices of 64 groups whose tables, amplitude table and
 // partial sums fit LDS together
 bool wide_usable(const pvq_ctx *c, const pvq_decode_args &a)
@@ -803,7 +977,8 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
         hipError_t e;
         // from eight vectors on, one 16-vector pass (about 215 us on the benchmark shape whatever the
         // count) beats two or more 4-vector passes (111 us each)
-        if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
+        if (left >= 5 && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
+        else if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
         else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
         else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }

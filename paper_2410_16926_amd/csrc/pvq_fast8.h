@@ -131,11 +131,6 @@ PVQ_HD void pvq_fast8_settle(const unsigned char *mem, uint32_t (&r)[NG], pvq_u3
         mj[j] = r[j] >= b[j].y;
         miss = miss || mj[j];
     }
-#ifdef PVQ_PROBE_NOWALK
-#pragma unroll
-    for (int j = 0; j < NG; j++) r[j] = r[j] < b[j].y ? r[j] : b[j].y - 1u;
-    miss = false;
-#endif
     if (miss) {
         // (stepping all NG groups together, one round trip per step of the furthest group, measured
         // slower than one short loop per group)

@@ -74,12 +74,27 @@ def assert_decode_close(got_f32: np.ndarray, ref64: np.ndarray, rel=1e-6):
     assert ok.all(), f"{(~ok).sum()} weights off, worst rel {np.max(err / np.maximum(np.abs(ref64), 1e-300)):.3e}"
 
 
-def assert_gemv_close(y: np.ndarray, ref: np.ndarray, rel=1e-3):
-    """Per activation vector: ||y - ref||_2 <= rel ||ref||_2 and every element within
-    rel * (|ref_i| + rms(ref))."""
+def assert_gemv_close(y: np.ndarray, ref: np.ndarray, scale: np.ndarray = None, rel=1e-3):
+    """Per activation vector: ||y - ref||_2 <= rel * max(||ref||_2, ||scale||_2) and every element within
+    rel * (|ref_i| + max(rms(ref), scale_i)).  scale_i = sqrt(sum_c (w_ic x_c)^2), the root sum of squares
+    of the terms of output i: the size such a sum has when its terms do not cancel.  Without it (scale
+    None) the criterion is relative to ref alone, which a single output whose terms happen to cancel
+    cannot meet with any finite precision of the weights."""
     y = y.astype(np.float64)
     for b in range(ref.shape[0]):
         nrm = np.linalg.norm(ref[b])
-        assert np.linalg.norm(y[b] - ref[b]) <= rel * nrm, (b, np.linalg.norm(y[b] - ref[b]) / nrm)
         rms = nrm / np.sqrt(ref.shape[1])
-        assert np.all(np.abs(y[b] - ref[b]) <= rel * (np.abs(ref[b]) + rms))
+        s = np.zeros_like(ref[b]) if scale is None else scale[b]
+        bound = max(nrm, np.linalg.norm(s))
+        assert np.linalg.norm(y[b] - ref[b]) <= rel * bound, (b, np.linalg.norm(y[b] - ref[b]) / bound)
+        assert np.all(np.abs(y[b] - ref[b]) <= rel * (np.abs(ref[b]) + np.maximum(rms, s)))
+
+
+def product_scale(xf: np.ndarray, ref_weights: np.ndarray) -> np.ndarray:
+    """[batch][rows]: root sum of squares of the terms of every output of x @ W^T (float64)."""
+    x2 = xf.astype(np.float64) ** 2
+    out = np.empty((xf.shape[0], ref_weights.shape[0]))
+    step = 2048                                  # bound the temporaries
+    for r0 in range(0, ref_weights.shape[0], step):
+        out[:, r0:r0 + step] = np.sqrt(x2 @ (ref_weights[r0:r0 + step] ** 2).T)
+    return out

@@ -39,7 +39,7 @@ def encode_decode_case(rows, cols, D, budget, scale_bits, seed, batches=()):
     for B in batches:
         xf, xb = si.activations(B, cols, seed=seed + B)
         y = pvq.pvq_decode_gemv(ctx, packed, gu.to_dev_bf16(xb)).cpu().numpy()
-        gu.assert_gemv_close(y, xf.astype(np.float64) @ ref.T)
+        gu.assert_gemv_close(y, xf.astype(np.float64) @ ref.T, gu.product_scale(xf, ref))
     ctx.close()
 
 

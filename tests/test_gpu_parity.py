@@ -41,7 +41,7 @@ def run_case(W32, D, K, scale_bits, src_bits=None, batches=(1, 4), out_dtypes=("
         xf, xb = si.activations(B, cols, seed=seed + B)
         y = pvq.pvq_decode_gemv(ctx, packed, gu.to_dev_bf16(xb)).cpu().numpy()
         want = xf.astype(np.float64) @ ref.T
-        gu.assert_gemv_close(y, want)
+        gu.assert_gemv_close(y, want, gu.product_scale(xf, ref))
     ctx.close()
     return packed, enc
 

@@ -156,6 +156,11 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
     if (log2n > 7) stage_across_lanes<16>(v, lane);
     if (log2n > 8) stage_across_lanes<32>(v, lane);
     // from bit 9 on the partners sit in other waves
+    // Blocks of 1024 and 8192 values end with a single stage (index bit 9, or 12): its ownership (P, 1)
+    // still has runs of four consecutive values per lane, so the results are stored from there, as two
+    // runs 8^P apart, instead of going through LDS once more.
+    constexpr bool kSplitStore = LOG2N == 10 || LOG2N == 13;
+    constexpr int kSplitP = LOG2N == 13 ? 4 : 3;
     if constexpr (LOG2N > 9) {
         constexpr int R3 = LOG2N - 9 < 3 ? LOG2N - 9 : 3;
         float *buf0 = smem, *buf1 = smem + pad(8u * (uint32_t)L) + 1u;
@@ -164,10 +169,36 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
         if constexpr (LOG2N > 12) {
             exchange<3, R3, 4, LOG2N - 12>(v, buf1, lane);
             stages_in_registers(v, LOG2N - 12);
-            exchange<4, LOG2N - 12, 0, 3>(v, buf0, lane);
-        } else {
+        } else if constexpr (!kSplitStore) {
             exchange<3, R3, 0, 3>(v, buf1, lane);
         }
+    }
+
+    if constexpr (kSplitStore) {
+        // register q holds column  own_base(lane) + (q >> 1) + (q & 1) * 8^P  of the chunk
+        const int64_t cbase = (int64_t)chunk * 8 * L + own_base<kSplitP, 1>((uint32_t)lane);
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int64_t col = cbase + ((int64_t)h << (3 * kSplitP));
+            if (col >= cols) continue;            // whole blocks: a run is in or out
+            uint32_t sg = 0;
+            if (signs && signs_after) sg = *reinterpret_cast<const uint32_t *>(signs + col);
+            float w[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                w[i] = v[2 * i + h] * scale;
+                if ((sg >> (8 * i)) & 0xFFu) w[i] = -w[i];
+            }
+            if constexpr (OUT == PVQ_F32) {
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Y) + row * ldy + col) = make_float4(w[0], w[1], w[2], w[3]);
+            } else {
+                const f32x2_t p0 = {w[0], w[1]}, p1 = {w[2], w[3]};
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(Y) + row * ldy + col) =
+                    make_uint2(__builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2_t)),
+                               __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2_t)));
+            }
+        }
+        return;
     }
 
 #pragma unroll

@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
 #include "pvq_internal.h"
 
 namespace {
@@ -306,6 +308,219 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
     for (int i = threadIdx.x; i < tile_words; i += blockDim.x) dst[i] = stream[i];
 }
 
+// The same encoder with 16 lanes per group and four groups per wave (lane = 16 * group + sub, sub holds
+// coordinates CP*sub .. CP*sub+CP-1, CP = D/16): the sums, the argmax, the prefix sum and the multi-word
+// total then need four cross-lane levels instead of six, all of them permutations inside a row of 16
+// lanes after which every lane of the row holds the result, and a lane's own coordinates (four or eight)
+// are independent work in between.  That form remains for indices of more than 12 words, whose 17
+// stream words do not fit 16 lanes.
+#define PVQ_ROW_STEPS(STEP) STEP(0xB1) STEP(0x4E) STEP(0x141) STEP(0x140)
+
+__device__ inline float row_sum_pairs(float v)
+{
+#define PVQ_STEP(CTRL) v = v + __uint_as_float(dpp_move<CTRL>(__float_as_uint(v)));
+    PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+    return v;
+}
+__device__ inline int row_sum_int(int v)
+{
+#define PVQ_STEP(CTRL) v += (int)dpp_move<CTRL>((uint32_t)v);
+    PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+    return v;
+}
+
+// sum of CP values over adjacent pairs, level by level
+template <int CP>
+__device__ inline float tree_sum(const float (&x)[CP])
+{
+    float t[CP];
+#pragma unroll
+    for (int j = 0; j < CP; j++) t[j] = x[j];
+#pragma unroll
+    for (int st = 1; st < CP; st *= 2)
+#pragma unroll
+        for (int j = 0; j < CP; j += 2 * st) t[j] = t[j] + t[j + st];
+    return t[0];
+}
+
+template <int TIN, int CP, int W>
+__global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p)
+{
+    extern __shared__ __align__(16) uint32_t stream[];
+    constexpr int D = 16 * CP;
+    const int lane = threadIdx.x & 63, sub = lane & 15, quarter = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
+    const int64_t row = blockIdx.x / p.tiles_per_row;
+    const int tile = blockIdx.x - (int)(row * p.tiles_per_row);
+    const int64_t g0 = (int64_t)tile * p.tile_groups;
+    const int ng = (int)min((int64_t)p.tile_groups, p.groups - g0);
+    const int tile_words = (int)(((int64_t)ng * p.bits + 31) / 32);
+    const int64_t first_word = g0 * p.bits / 32;   // exact: tile_groups * bits is a multiple of 32
+    const int K = p.K;
+
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) stream[i] = 0;
+    __syncthreads();
+
+    for (int gi = 4 * wave; gi < ng; gi += 4 * nwaves) {
+        const int gl = gi + quarter;           // this quarter's group inside the tile
+        const bool on = gl < ng;               // quarters beyond the tile work on its first group again, unused
+        const int64_t g = g0 + (on ? gl : gi);
+        float w[CP];
+        if constexpr (TIN == PVQ_F32) {
+            const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(p.X) + row * p.ldx + g * D + CP * sub);
+#pragma unroll
+            for (int j = 0; j < CP / 4; j++) {
+                const float4 v = src[j];
+                w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+            }
+        } else {
+            const uint2 *src = reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(p.X) + row * p.ldx + g * D + CP * sub);
+#pragma unroll
+            for (int j = 0; j < CP / 4; j++) {
+                const uint2 v = src[j];
+                w[4 * j] = __uint_as_float(v.x << 16); w[4 * j + 1] = __uint_as_float(v.x & 0xFFFF0000u);
+                w[4 * j + 2] = __uint_as_float(v.y << 16); w[4 * j + 3] = __uint_as_float(v.y & 0xFFFF0000u);
+            }
+        }
+
+        // ---- the point (Sec. 2.5)
+        float a[CP], sq[CP], t[CP];
+#pragma unroll
+        for (int j = 0; j < CP; j++) { a[j] = fabsf(w[j]); sq[j] = w[j] * w[j]; }
+        const float l1 = row_sum_pairs(tree_sum<CP>(a)), ss = row_sum_pairs(tree_sum<CP>(sq));
+        const float gain = (float)K / l1;
+        const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(gain < INFINITY);
+        int m[CP];
+        int S = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            t[j] = a[j] * gain;
+            m[j] = degenerate ? 0 : (int)rintf(t[j]);
+            S += m[j];
+        }
+        S = row_sum_int(S);
+        if (degenerate) {
+            if (sub == 15) m[CP - 1] = K;   // the point (0, ..., 0, +K): index 0
+            S = K;
+        }
+        // one pulse per step and group, as in the wave-per-group form; the wave goes on while any of its
+        // four groups is off the pyramid (a valid group needs at most D/2 steps)
+        for (int step = 0; step < D; step++) {
+            const bool need = S != K;           // the same in the 16 lanes of a group
+            if (!__any(need)) break;
+            const bool down = S > K;
+            float be = -INFINITY;
+            int bi = 0x7FFFFFFF;
+#pragma unroll
+            for (int j = 0; j < CP; j++) {
+                const float e = down ? (float)m[j] - t[j] : t[j] - (float)m[j];
+                const bool can = !down || m[j] > 0;
+                if (can && (bi == 0x7FFFFFFF || e > be)) { be = e; bi = CP * sub + j; }
+            }
+#define PVQ_STEP(CTRL)                                                                                   \
+    {                                                                                                    \
+        const float oe = __uint_as_float(dpp_move<CTRL>(__float_as_uint(be), 0xFF800000u));              \
+        const int oi = (int)dpp_move<CTRL>((uint32_t)bi, 0x7FFFFFFFu);                                   \
+        const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));    \
+        if (take) { be = oe; bi = oi; }                                                                  \
+    }
+            PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+            if (need) {
+#pragma unroll
+                for (int j = 0; j < CP; j++)
+                    if (bi == CP * sub + j) m[j] += down ? -1 : 1;
+                S += down ? -1 : 1;
+            }
+        }
+
+        // ---- amplitude (Sec. 2.3, or Sec. 3.3 Step 4)
+        float amp;
+        if (p.ls) {
+            float pr[CP];
+            int n2 = 0;
+#pragma unroll
+            for (int j = 0; j < CP; j++) {
+                const int ys = w[j] < 0.0f ? -m[j] : m[j];
+                pr[j] = (float)ys * w[j];
+                n2 += m[j] * m[j];
+            }
+            amp = row_sum_pairs(tree_sum<CP>(pr)) / sqrtf((float)row_sum_int(n2));
+        } else {
+            amp = sqrtf(ss);
+        }
+        if (on && sub == 0) p.scale_out[row * p.groups + g] = amp;
+        if (on && p.pulses_out) {
+#pragma unroll
+            for (int j = 0; j < CP; j++)
+                p.pulses_out[row * p.cols + g * D + CP * sub + j] = (int8_t)(w[j] < 0.0f ? -m[j] : m[j]);
+        }
+
+        // ---- the index (App. B.2)
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) mine += m[j];
+        int incl = mine;   // inclusive prefix sum over the 16 lanes of the group
+        incl += (int)dpp_move<0x111>((uint32_t)incl);        // row_shr:1
+        incl += (int)dpp_move<0x112>((uint32_t)incl);        // row_shr:2
+        incl += (int)dpp_move<0x114>((uint32_t)incl);        // row_shr:4
+        incl += (int)dpp_move<0x118>((uint32_t)incl);        // row_shr:8
+        int k = K - (incl - mine);
+        const uint32_t last_neg = (m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 1u : 0u;
+        bool neg_before = dpp_move<0x111>(last_neg) != 0;    // the lane before in the row; none for sub = 0
+        wint<W> acc;
+#pragma unroll
+        for (int i = 0; i < W; i++) acc.w[i] = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            const int d = D - (CP * sub + j);
+            const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
+            const int times = (mm > 0 ? 1 : 0) + (neg_before ? 1 : 0);
+            if (times) {
+                const wint<W> n = load_entry<W>(p.tab_n, (int64_t)d * (K + 1) + kk);
+                add_to(acc, n);
+                if (times == 2) add_to(acc, n);
+            }
+            if (mm > 0) {
+                const wint<W> e = load_entry<W>(p.tab_e, (int64_t)(d - 1) * (K + 1) + (kk - mm));
+                uint32_t br;
+                acc = subtract(acc, e, &br);
+            }
+            neg_before = mm > 0 && w[j] < 0.0f;
+            k = kk - mm;
+        }
+        if (sub == 15 && neg_before) {   // N(0,0) = 1 after a negative last coordinate
+            wint<W> one;
+#pragma unroll
+            for (int i = 0; i < W; i++) one.w[i] = 0;
+            one.w[0] = 1;
+            add_to(acc, one);
+        }
+#define PVQ_STEP(CTRL)                                                                  \
+    {                                                                                   \
+        wint<W> other;                                                                  \
+        _Pragma("unroll") for (int i = 0; i < W; i++) other.w[i] = dpp_move<CTRL>(acc.w[i]); \
+        add_to(acc, other);                                                             \
+    }
+        PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+
+        // ---- into the tile's bit stream: lane sub = i of the group takes word i of the index
+        uint32_t word = 0;
+#pragma unroll
+        for (int i = 0; i < W; i++) word = sub == i ? acc.w[i] : word;
+        const int off = gl * p.bits, sh = off & 31, w0 = off >> 5;
+        const uint32_t prev = dpp_move<0x111>(word);         // word sub-1, zero for sub = 0
+        const uint32_t out = sh ? (word << sh) | (prev >> (32 - sh)) : word;
+        if (on && sub <= W && w0 + sub < tile_words && out) atomicOr(&stream[w0 + sub], out);
+    }
+    __syncthreads();
+    uint32_t *dst = p.index_out + row * p.index_row_words + first_word;
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) dst[i] = stream[i];
+}
+
 struct decode_wide_params {
     const uint32_t *index;
     const float *scale;
@@ -445,26 +660,36 @@ hipError_t pvq_wide_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, in
     encode_wide_params p;
     p.X = a.W; p.ldx = a.ldw; p.groups = a.groups; p.index_row_words = a.index_row_words;
     p.K = c->K; p.bits = c->index_bits; p.ls = a.ls_amplitude;
-    p.tile_groups = 32 / gcd_int(c->index_bits, 32);
-    p.tiles_per_row = (int)((a.groups + p.tile_groups - 1) / p.tile_groups);
     p.tab_n = c->tab_n; p.tab_e = c->tab_u;
     p.index_out = a.index_out; p.scale_out = reinterpret_cast<float *>(a.scale_out); p.pulses_out = a.pulses_out;
     p.cols = a.cols;
+    // 16 lanes per group, four groups per wave, when the index and the word it may spill into fit 16 lanes
+    // and there are enough groups to fill the waves; else a wave per group (shorter chain per group)
+    const bool rows16 = c->words <= 12 && a.rows * a.groups >= 16384;
+    p.tile_groups = 32 / gcd_int(c->index_bits, 32);
+    if (rows16 && p.tile_groups < 4) p.tile_groups = 4;
+    p.tiles_per_row = (int)((a.groups + p.tile_groups - 1) / p.tile_groups);
     if (a.rows * p.tiles_per_row > 0x7FFFFFFF) return hipErrorInvalidValue;
-    const int waves = p.tile_groups < 8 ? p.tile_groups : 8;
+    const int per_wave = rows16 ? 4 : 1;
+    const int waves = std::min(p.tile_groups / per_wave, 8);
     const size_t lds = (size_t)(p.tile_groups * c->index_bits / 32) * 4;
     const dim3 grid((unsigned)(a.rows * p.tiles_per_row)), blk(64u * waves);
 #define PVQ_WIDE_ENC(T, CP, W) hipLaunchKernelGGL((encode_wide_kernel<T, CP, W>), grid, blk, lds, s, p)
-#define PVQ_WIDE_ENC_W(T, CP)                                  \
-    switch (c->words) {                                        \
-    case 4: PVQ_WIDE_ENC(T, CP, 4); break;                     \
-    case 8: PVQ_WIDE_ENC(T, CP, 8); break;                     \
-    case 12: PVQ_WIDE_ENC(T, CP, 12); break;                   \
-    default: PVQ_WIDE_ENC(T, CP, 16); break;                   \
+#define PVQ_WIDE_ENC16(T, CP, W) hipLaunchKernelGGL((encode_wide16_kernel<T, CP, W>), grid, blk, lds, s, p)
+#define PVQ_WIDE_ENC_W(T, D64)                                                                                  \
+    switch (c->words) {                                                                                         \
+    case 4: if (rows16) { if (D64) PVQ_WIDE_ENC16(T, 4, 4); else PVQ_WIDE_ENC16(T, 8, 4); }                     \
+            else { if (D64) PVQ_WIDE_ENC(T, 1, 4); else PVQ_WIDE_ENC(T, 2, 4); } break;                         \
+    case 8: if (rows16) { if (D64) PVQ_WIDE_ENC16(T, 4, 8); else PVQ_WIDE_ENC16(T, 8, 8); }                     \
+            else { if (D64) PVQ_WIDE_ENC(T, 1, 8); else PVQ_WIDE_ENC(T, 2, 8); } break;                         \
+    case 12: if (rows16) { if (D64) PVQ_WIDE_ENC16(T, 4, 12); else PVQ_WIDE_ENC16(T, 8, 12); }                  \
+             else { if (D64) PVQ_WIDE_ENC(T, 1, 12); else PVQ_WIDE_ENC(T, 2, 12); } break;                      \
+    default: if (D64) PVQ_WIDE_ENC(T, 1, 16); else PVQ_WIDE_ENC(T, 2, 16); break;                               \
     }
-    if (dtype == PVQ_F32) { if (c->D == 128) { PVQ_WIDE_ENC_W(PVQ_F32, 2) } else { PVQ_WIDE_ENC_W(PVQ_F32, 1) } }
-    else { if (c->D == 128) { PVQ_WIDE_ENC_W(PVQ_BF16, 2) } else { PVQ_WIDE_ENC_W(PVQ_BF16, 1) } }
+    const bool d64 = c->D == 64;
+    if (dtype == PVQ_F32) { PVQ_WIDE_ENC_W(PVQ_F32, d64) } else { PVQ_WIDE_ENC_W(PVQ_BF16, d64) }
 #undef PVQ_WIDE_ENC_W
+#undef PVQ_WIDE_ENC16
 #undef PVQ_WIDE_ENC
     return hipGetLastError();
 }

@@ -182,6 +182,21 @@ def test_long_groups_bf16_activations(D, bits_per_value, tokens, hidden):
     run_long_groups(xf, D, K, src_bits=xb)
 
 
+@pytest.mark.parametrize("D,K,tokens,hidden,bf16", [(128, 187, 300, 8192, True), (128, 84, 260, 8192, False),
+                                                    (64, 40, 1300, 64 * 13, True), (64, 96, 520, 2048, False),
+                                                    (128, 1, 130, 128 * 130, True)])
+def test_long_groups_large_batches(D, K, tokens, hidden, bf16):
+    # from 16384 groups on the encoder works with 16 lanes per group, four groups per wave: 12-, 8- and
+    # 4-word integers, 13 groups per row (a last tile with one of four groups), widths of 123 bits
+    if bf16:
+        xf, xb = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + D + K, rotate=False)
+        run_long_groups(xf, D, K, src_bits=xb)
+        run_long_groups(xf, D, K, src_bits=xb, amplitude="ls")
+    else:
+        X = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + D + K, rotate=False, bf16=False)
+        run_long_groups(X, D, K, want_pulses=K <= 127)
+
+
 @pytest.mark.parametrize("D,K", [(128, 187), (64, 40), (64, 127), (128, 1), (64, 2), (128, 382)])
 def test_long_groups_float32_and_odd_widths(D, K):
     # float32 source without rotation (outlier channels stay: a few huge coordinates per group), index
@@ -194,10 +209,11 @@ def test_long_groups_float32_and_odd_widths(D, K):
 @pytest.mark.parametrize("D,K", [(128, 187), (64, 40)])
 def test_long_groups_adversarial(D, K):
     # rounding ties, repair ties, zeros (index 0, amplitude 0), one-hot groups, wide dynamic range
-    n = 1 << 11
-    X = si.adversarial_groups(n, D, seed=55 + D).reshape(n * D // 1024, 1024)
-    run_long_groups(X, D, K)
-    run_long_groups(X, D, K, amplitude="ls")
+    # 2048 groups (a wave per group) and 32768 groups (16 lanes per group)
+    for n in (1 << 11, 1 << 15):
+        X = si.adversarial_groups(n, D, seed=55 + D).reshape(n * D // 1024, 1024)
+        run_long_groups(X, D, K)
+        run_long_groups(X, D, K, amplitude="ls")
 
 
 def test_long_groups_argument_errors():

@@ -235,6 +235,35 @@ def test_long_groups_argument_errors():
     ctx.close()
 
 
+def _random_configurations():
+    rng = np.random.default_rng(si.BASE_SEED + 4242)
+    out = []
+    for i in range(36):
+        D = int(rng.choice([8, 8, 8, 16, 32]))
+        budget = int(rng.integers(D + 2, min(4 * D, 127) + 1))       # index bits per group
+        bits = int(rng.choice([0, 0, 1, 2, 4, 8]))
+        rows = int(rng.integers(1, 48))
+        G = int(rng.integers(1, 70)) * int(rng.choice([1, 1, 4, 8]))
+        if bits and G < 2:
+            G = 2
+        out.append((i, D, budget, bits, rows, G, bool(rng.integers(0, 2)), str(rng.choice(["l2", "ls"]))))
+    return out
+
+
+@pytest.mark.parametrize("i,D,budget,bits,rows,G,bf16,amplitude", _random_configurations())
+def test_random_configurations(i, D, budget, bits, rows, G, bf16, amplitude):
+    # seeded draws over group size, pulse count (through the index width), amplitude format, shape,
+    # source type and amplitude kind: whichever kernel family the dispatch picks must match the oracle
+    K = pvq.pvq_max_k(D, budget)
+    cols = G * D
+    if bf16:
+        wf, wb = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 5000 + i, rotate=False, bf16=True)
+        run_case(wf, D, K, bits, src_bits=wb, batches=(1, 3, 6), out_dtypes=("f32", "bf16"), amplitude=amplitude)
+    else:
+        W = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 5000 + i, rotate=False)
+        run_case(W, D, K, bits, batches=(2, 16), out_dtypes=("f32", "f16"), amplitude=amplitude)
+
+
 def test_leading_dimensions_and_views():
     D, K = 8, 16
     rows, cols, ld = 33, 512, 640

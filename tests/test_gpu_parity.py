@@ -343,13 +343,37 @@ def test_zero_matrix_and_nonfinite_inputs_are_safe():
 
 
 def test_corrupt_indices_do_not_fault():
+    # stored fields at or above N(D,K): unspecified values, but every kernel family stays inside its tables
+    # (D = 8: the index is clamped; generic kernels: the walk is bounded by the pulses left; long groups:
+    # such a group decodes to zeros, like the oracle's)
     D, K = 8, 16
     ctx = pvq.pvq_ctx_create(D, K)
-    idx = torch.full((16, 96), -1, dtype=torch.int32, device="cuda")     # every field = 2^24-1 >= N
-    p = pvq.Packed(16, 1024, idx, torch.ones((16, 128), device="cuda"), torch.ones(16, device="cuda"))
+    idx = torch.full((16, 768), -1, dtype=torch.int32, device="cuda")     # every field = 2^24-1 >= N
+    p = pvq.Packed(16, 8192, idx, torch.ones((16, 1024), device="cuda"), torch.ones(16, device="cuda"))
+    out = pvq.pvq_decode(ctx, p, torch.float32)
+    x = torch.ones((16, 8192), dtype=torch.bfloat16, device="cuda")
+    for b in (1, 4, 16):                     # the single-vector, four-vector and matrix-core passes
+        y = pvq.pvq_decode_gemv(ctx, p, x[:b])
+        assert bool(torch.isfinite(y).all())
+    torch.cuda.synchronize()
+    assert out.shape == (16, 8192) and bool(torch.isfinite(out).all())
+    ctx.close()
+
+    ctx = pvq.pvq_ctx_create(16, 33)         # 52-bit fields, all ones
+    idx = torch.full((8, 104), -1, dtype=torch.int32, device="cuda")
+    p = pvq.Packed(8, 1024, idx, torch.ones((8, 64), device="cuda"), torch.ones(8, device="cuda"))
+    out = pvq.pvq_decode(ctx, p, torch.float32)
+    y = pvq.pvq_decode_gemv(ctx, p, x[:2, :1024].contiguous())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(y).all())
+    ctx.close()
+
+    ctx = pvq.pvq_ctx_create(128, 187)       # 384-bit fields, all ones: not codewords, decoded as zeros
+    idx = torch.full((4, 24), -1, dtype=torch.int32, device="cuda")
+    p = pvq.Packed(4, 256, idx, torch.ones((4, 2), device="cuda"), torch.ones(4, device="cuda"))
     out = pvq.pvq_decode(ctx, p, torch.float32)
     torch.cuda.synchronize()
-    assert out.shape == (16, 1024)
+    assert float(out.abs().sum()) == 0.0
     ctx.close()
 
 

@@ -97,7 +97,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (rows would shard across "
-                 "GPUs without any exchange, see DESIGN.md)")
+                 "GPUs without any exchange; nothing here runs on a second GPU)")
 
     import numpy as np
     import torch

@@ -217,6 +217,9 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     if (bits < 1 || bits > (wide ? 512 : 128)) return PVQ_E_UNSUPPORTED;
     int words = bits <= 32 ? 1 : (bits <= 64 ? 2 : 4);
     if (wide) words = 4 * ((std::max(t.at(D, K).bit_length(), 1) + 127) / 128);   // N(D,K) itself is an entry
+    // the decoders form N(D,K) - 1 - index in `words` words: N(D,K) must fit them (it fails to only when it
+    // is exactly 2^(32 words), which no supported (D,K) gives)
+    if (t.at(D, K).bit_length() > 32 * words) return PVQ_E_UNSUPPORTED;
 
     int n = scale_bits ? (1 << scale_bits) : 0;
     std::vector<float> e32, sc32;

@@ -337,47 +337,58 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(tables_t tb, pvq_encod
 // decode
 // ---------------------------------------------------------------------------------------------
 
-// App. B.3 in residual form: r is the position inside the sub-pyramid still open.  At a
-// coordinate with d' dimensions after it and k pulses left, the block of x = 0 has N(d',k)
-// points, then come the blocks of +j and -j with N(d',k-j) points each, j = 1..k.
-// tab_n is the LDS copy of N(d',k), d' = 0..D-1.  Returns sum of squares of the point.
+// App. B.3 over the cumulative table alone.  With U(d,x) = N(d,0) + ... + N(d,x) (U(d,-1) = 0), the points
+// of P(d,k) whose first coordinate has magnitude below m >= 1 number  N(d,k) - 2 U(d-1,k-m)  (all points
+// minus those of magnitude m or more, two signs each), and N(d,k) = U(d-1,k) + U(d-1,k-1).  The lane keeps
+// q = N(d,k) - 1 - r for the residual r in the sub-pyramid still open.  The coordinate's magnitude is the
+// smallest m with 2 U(d-1,k-1-m) <= q, that is  m = k - #{x in [0,k-1] : U(d-1,x) <= q/2}: a binary search
+// in a row of the table (the same number of steps in every lane, whatever the magnitudes), instead of
+// one step per unit of magnitude.  For m = 0 the next q is q - 2 U(d-1,k-1); for m >= 1, with x = k-m and
+// N' = N(d-1,x) = U(d-1,x) - U(d-1,x-1):  v = q - 2 U(d-1,x) + N'  is the place inside the block of +-m counted
+// from the end of its first half: v >= 0 means +m and the next q is v, v < 0 means -m and the next q is
+// v + N'.  (|v| < N' <= N(D,K)/3, so the top bit of the W-word integer is a sign bit.)
+// tab_u is the LDS copy of the rows U(d', .), d' = 0..D-1, each shifted by one entry so that U(-1) is stored.
+// Every table read stays inside its row whatever the stored field holds.  Returns the sum of squares.
 template <int D, int W>
-__device__ inline int unrank_point(typename wide<W>::type r, int K,
-                                   const typename wide<W>::type *tab_n, int (&y)[D])
+__device__ inline int unrank_point(typename wide<W>::type c, int K,
+                                   const typename wide<W>::type *tab_u, int (&y)[D])
 {
     using T = typename wide<W>::type;
+    int top = 1;                                   // largest power of two <= K (K >= 1)
+    while (2 * top <= K) top *= 2;
+    const T *u0 = tab_u + (D - 1) * (K + 2) + 1;   // u0[x] = U(D-1, x)
+    T q = u0[K] + u0[K - 1] - 1 - c;               // N(D,K) - 1 - c
     int k = K;
     int n2 = 0;
 #pragma unroll
     for (int i = 0; i < D - 1; i++) {
-        const T *n = tab_n + (D - 1 - i) * (K + 1);
+        const T *u = tab_u + (D - 1 - i) * (K + 2) + 1;
         int v = 0;
         if (k > 0) {
-            const T n0 = n[k];
-            if (r >= n0) {
-                r -= n0;
-                int j = 1;
-                while (j < k) {
-                    T t = n[k - j];
-                    t += t;
-                    if (r < t) break;
-                    r -= t;
-                    j++;
-                }
-                const T nj = n[k - j];
-                if (r < nj) {
-                    v = j;
-                } else {
-                    v = -j;
-                    r -= nj;
-                }
-                k -= j;
+            const T h = q >> 1;
+            int count = 0;
+            for (int step = top; step > 0; step >>= 1) {
+                const int np = count + step;
+                const int at = np <= k ? np - 1 : k - 1;          // inside the row either way
+                if (np <= k && u[at] <= h) count = np;
+            }
+            const int m = k - count;
+            if (m == 0) {
+                q -= u[k - 1] + u[k - 1];
+            } else {
+                const T ux = u[count], np1 = ux - u[count - 1];   // U(d-1,x), N(d-1,x) with x = k - m
+                T vv = q - ux - ux + np1;
+                const bool negative = (vv >> (32 * W - 1)) != 0;
+                if (negative) vv += np1;
+                q = vv;
+                v = negative ? -m : m;
+                k = count;
             }
         }
         y[i] = v;
         n2 += v * v;
     }
-    y[D - 1] = (r == 0) ? k : -k;
+    y[D - 1] = (q == 0) ? -k : k;                  // the two points +k, -k of P(1,k): q = 1, 0
     n2 += k * k;
     return n2;
 }
@@ -399,9 +410,9 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(tables_t tb, pvq_decod
     using T = typename wide<W>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     const int K = tb.K;
-    T *tab_n = reinterpret_cast<T *>(smem);
-    float *sqrtc = reinterpret_cast<float *>(tab_n + D * (K + 1));
-    copy_to_lds(tab_n, reinterpret_cast<const T *>(tb.tab_n), D * (K + 1));
+    T *tab_u = reinterpret_cast<T *>(smem);
+    float *sqrtc = reinterpret_cast<float *>(tab_u + D * (K + 2));
+    copy_to_lds(tab_u, reinterpret_cast<const T *>(tb.tab_u), D * (K + 2));
     if (tb.scale_bits > 0) copy_to_lds(sqrtc, tb.sqrtc, 1 << tb.scale_bits);
     __syncthreads();
 
@@ -412,7 +423,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(tables_t tb, pvq_decod
         const uint32_t *irow = a.index + row * a.index_row_words;
         const T c = load_field<W>(irow, (uint32_t)g * (uint32_t)tb.index_bits, tb.index_bits);
         int y[D];
-        const int n2 = unrank_point<D, W>(c, K, tab_n, y);
+        const int n2 = unrank_point<D, W>(c, K, tab_u, y);
         const float srn = tb.scale_bits > 0 ? sqrtf(a.rownorm[row]) : 0.0f;
         const float amp = load_amplitude(tb, a, row, g, srn, sqrtc);
         // direction on the unit sphere times the amplitude (Sec. 2.4): w = amp * y / ||y||_2
@@ -455,9 +466,9 @@ __global__ __launch_bounds__(kThreads) void gemv_kernel(tables_t tb, pvq_decode_
     using T = typename wide<W>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     const int K = tb.K;
-    T *tab_n = reinterpret_cast<T *>(smem);
-    float *sqrtc = reinterpret_cast<float *>(tab_n + D * (K + 1));
-    copy_to_lds(tab_n, reinterpret_cast<const T *>(tb.tab_n), D * (K + 1));
+    T *tab_u = reinterpret_cast<T *>(smem);
+    float *sqrtc = reinterpret_cast<float *>(tab_u + D * (K + 2));
+    copy_to_lds(tab_u, reinterpret_cast<const T *>(tb.tab_u), D * (K + 2));
     if (tb.scale_bits > 0) copy_to_lds(sqrtc, tb.sqrtc, 1 << tb.scale_bits);
     __syncthreads();
 
@@ -474,7 +485,7 @@ __global__ __launch_bounds__(kThreads) void gemv_kernel(tables_t tb, pvq_decode_
         for (int g = lane; g < G; g += kWave) {
             const T c = load_field<W>(irow, (uint32_t)g * (uint32_t)tb.index_bits, tb.index_bits);
             int y[D];
-            const int n2 = unrank_point<D, W>(c, K, tab_n, y);
+            const int n2 = unrank_point<D, W>(c, K, tab_u, y);
             const float amp = load_amplitude(tb, a, row, g, srn, sqrtc);
             const float gain = amp / sqrtf((float)n2);
 #pragma unroll
@@ -536,7 +547,7 @@ hipError_t launch_encode_dw(const pvq_ctx *c, const pvq_encode_args &a, int dtyp
 template <int D, int W>
 hipError_t launch_decode_dw(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
 {
-    const size_t lds = (size_t)D * (c->K + 1) * W * 4 + 256 * 4;
+    const size_t lds = (size_t)D * (c->K + 2) * W * 4 + 256 * 4;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((a.groups + kThreads - 1) / kThreads), (unsigned)std::min<int64_t>(a.rows, 65535));
     const tables_t t = make_tables(c);
@@ -551,7 +562,7 @@ hipError_t launch_decode_dw(const pvq_ctx *c, const pvq_decode_args &a, int out_
 template <int D, int W>
 hipError_t launch_gemv_dw(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
 {
-    const size_t lds = (size_t)D * (c->K + 1) * W * 4 + 256 * 4;
+    const size_t lds = (size_t)D * (c->K + 2) * W * 4 + 256 * 4;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     const int rows_per_block = kThreads / kWave;
     const dim3 grid((unsigned)std::min<int64_t>((a.rows + rows_per_block - 1) / rows_per_block, 1 << 20));

@@ -237,7 +237,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     // tab_n[dp][k] = N(dp,k); tab_u[dp][k+1] = N(dp,0) + ... + N(dp,k), tab_u[dp][0] = 0.
     // Every entry is below N(D,K) (the pyramid of one more dimension contains all of them), so it
     // fits `words` words.
-    std::vector<uint32_t> hn, hu;
+    std::vector<uint32_t> hn, hu, hc;
     if (wide) {
         // tab_n[d][k] = N(d,k), d = 0..D;  tab_u[d][k] = 2 (N(d,0) + ... + N(d,k)) mod 2^(32 words), d = 0..D-1
         hn.resize((size_t)(D + 1) * (K + 1) * words);
@@ -255,6 +255,28 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
                 }
             }
         }
+        // The encoders' table: what a cell (d,k) of the walk adds to the index, in its four forms
+        //   N,  -E,  N - E,  2N - E   (modulo 2^(32 words); E = 0 in row D, whose cell only ever adds N),
+        // entry ((d (K+1) + k) 4 + form) of `words` words.
+        hc.resize((size_t)(D + 1) * (K + 1) * 4 * words);
+        for (int d = 0; d <= D; d++)
+            for (int k = 0; k <= K; k++) {
+                const uint32_t *n = &hn[((size_t)d * (K + 1) + k) * words];
+                const uint32_t *ev = d < D ? &hu[((size_t)d * (K + 1) + k) * words] : nullptr;
+                uint32_t *out = &hc[((size_t)d * (K + 1) + k) * 4 * words];
+                for (int form = 0; form < 4; form++) {
+                    const int times = form == 0 ? 1 : form - 1;          // how often N counts: 1, 0, 1, 2
+                    uint64_t carry = 0;
+                    int64_t borrow = 0;
+                    for (int w = 0; w < words; w++) {
+                        const uint64_t add = (uint64_t)n[w] * (uint64_t)times + carry;
+                        carry = add >> 32;
+                        const int64_t sub = (int64_t)(add & 0xFFFFFFFFu) - (form > 0 && ev ? (int64_t)ev[w] : 0) - borrow;
+                        borrow = sub < 0 ? 1 : 0;
+                        out[(size_t)form * words + w] = (uint32_t)sub;
+                    }
+                }
+            }
     } else {
         hn.resize((size_t)D * (K + 1) * words);
         hu.resize((size_t)D * (K + 2) * words);
@@ -275,7 +297,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits; c->wide = wide ? 1 : 0;
-    c->tab_n = c->tab_u = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
+    c->tab_n = c->tab_u = c->tab_c = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -283,6 +305,10 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     if (e == hipSuccess) e = hipMalloc((void **)&c->tab_u, c->tab_u_bytes);
     if (e == hipSuccess) e = hipMemcpy(c->tab_n, hn.data(), c->tab_n_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(c->tab_u, hu.data(), c->tab_u_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess && !hc.empty()) {
+        e = hipMalloc((void **)&c->tab_c, hc.size() * 4);
+        if (e == hipSuccess) e = hipMemcpy(c->tab_c, hc.data(), hc.size() * 4, hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess && scale_bits) {
         // the edge table is padded to 2^b entries with +inf so that kernels may read a full table
         e32.push_back(INFINITY);
@@ -333,7 +359,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[7] = {c->tab_n, c->tab_u, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->enc8_offs};
+    void *ptrs[8] = {c->tab_n, c->tab_u, c->tab_c, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->enc8_offs};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);

@@ -22,6 +22,7 @@ struct pvq_ctx {
     //                    App. C.2's V table, shifted so that the empty sum is an entry)
     uint32_t *tab_n;
     uint32_t *tab_u;
+    uint32_t *tab_c;   // wide only: [D+1][K+1][4][words], the four forms N, -E, N-E, 2N-E of a cell (encoders)
     float *edges;   // 2^scale_bits - 1 float32 edges (or nullptr)
     float *sqrtc;   // 2^scale_bits float32 sqrt(centers) (or nullptr)
     size_t tab_n_bytes, tab_u_bytes;

@@ -4,7 +4,7 @@
 // small groups).  The size table no longer fits LDS (1.2 MB for (128,187)); it is read from device
 // memory, where the L2 keeps it.
 //
-// Two tables of W-word integers (W = 4, 8, 12 or 16; arithmetic is modulo 2^(32W), every true result
+// Tables of W-word integers (W = 4, 8, 12 or 16; arithmetic is modulo 2^(32W), every true result
 // fits):  N(d,k), and E(d,k) = 2 (N(d,0) + ... + N(d,k)).  With them the number of points of P(d,k)
 // whose first coordinate has magnitude below m >= 1 is  A(m) = N(d,k) - E(d-1,k-m)  (all points minus
 // those of magnitude m or more, two signs each), so that, in the order 0, +1, -1, +2, -2, ... of
@@ -15,10 +15,11 @@
 // lane, then across lanes by data-parallel-primitive moves, no LDS traffic), the repair of the pulse
 // count picks one coordinate per step by a wave-wide argmax (lowest coordinate on ties).  The index is a sum of per-coordinate terms that depend
 // on the coordinate's magnitude, sign and the pulses left before it only; a prefix sum over the
-// magnitudes gives the latter, every lane adds up its coordinates' terms from two table entries each,
-// and six levels of multi-word additions across the lanes give the total.  Because the pulses left after coordinate i
-// are those before coordinate i+1, the N(d-1,k-m) of a negative coordinate is the N(d,k) of the next
-// one and is read once.
+// magnitudes gives the latter.  Because the pulses left after coordinate j-1 are those before
+// coordinate j, the terms regroup by the cells (d_j, k_j) that the walk visits: cell j adds
+// N(d_j,k_j) ([m_j > 0] + [coordinate j-1 negative]) - E(d_j,k_j) [m_{j-1} > 0].  A third table holds, per
+// cell, the four forms this can take (N, -E, N-E, 2N-E), so a coordinate costs one table entry and one
+// multi-word addition; six levels of multi-word additions across the lanes give the total.
 //
 // Decoding (App. B.3): one lane per group, coordinate by coordinate.  The lane keeps q = N(d,k) - 1 - r
 // for the residual r; the coordinate's magnitude is the smallest m with E(d-1,k-1-m) <= q (E(.,-1) = 0),
@@ -110,7 +111,7 @@ struct encode_wide_params {
     const void *X;
     int64_t ldx, groups, index_row_words;
     int K, bits, tile_groups, tiles_per_row, ls;
-    const uint32_t *tab_n, *tab_e;
+    const uint32_t *tab_c;   // per cell (d,k) the four forms N, -E, N-E, 2N-E
     uint32_t *index_out;
     float *scale_out;
     int8_t *pulses_out;
@@ -246,11 +247,15 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
         incl += (int)dpp_move<0x142, 0xA>((uint32_t)incl);   // lane 15 of rows 0, 2 into rows 1, 3
         incl += (int)dpp_move<0x143, 0xC>((uint32_t)incl);   // lane 31 into rows 2, 3
         int k = K - (incl - mine);   // pulses left before this lane's first coordinate
-        bool neg_before;             // the coordinate before is negative
+        // The walk visits the cells (d_j, k_j), j = 0..D, d_j = D - j, k_j = pulses left before coordinate
+        // j.  Cell j adds  N(d_j,k_j) ([m_j > 0] + [coordinate j-1 negative]) - E(d_j,k_j) [m_{j-1} > 0]
+        // (the -E(d-1,k-m) of coordinate j-1 and the N(d-1,k-m) of a negative one are values of the next
+        // cell): one table entry, in the form that the two coordinates around the cell call for.
+        int prev_state;              // of the coordinate before: bit 0 = magnitude > 0, bit 1 = negative
         {
-            const int last_neg = (m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 1 : 0;
-            const int up = __shfl_up(last_neg, 1, 64);
-            neg_before = lane > 0 && up;
+            const int last = (m[CP - 1] > 0 ? 1 : 0) | ((m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 2 : 0);
+            const int up = __shfl_up(last, 1, 64);
+            prev_state = lane > 0 ? up : 0;
         }
         wint<W> acc;
 #pragma unroll
@@ -259,26 +264,23 @@ __global__ __launch_bounds__(512) void encode_wide_kernel(encode_wide_params p)
         for (int j = 0; j < CP; j++) {
             const int d = D - (CP * lane + j);
             const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
-            const int times = (mm > 0 ? 1 : 0) + (neg_before ? 1 : 0);      // how often N(d,k) counts
-            if (times) {
-                const wint<W> n = load_entry<W>(p.tab_n, (int64_t)d * (K + 1) + kk);
-                add_to(acc, n);
-                if (times == 2) add_to(acc, n);
+            const int times = (mm > 0 ? 1 : 0) + (prev_state >> 1);         // how often N(d,k) counts
+            const bool prev_pos = prev_state & 1;
+            if (prev_pos || times) {
+                const int form = prev_pos ? 1 + times : 0;
+                add_to(acc, load_entry<W>(p.tab_c, ((int64_t)d * (K + 1) + kk) * 4 + form));
             }
-            if (mm > 0) {
-                const wint<W> e = load_entry<W>(p.tab_e, (int64_t)(d - 1) * (K + 1) + (kk - mm));
-                uint32_t br;
-                acc = subtract(acc, e, &br);
-            }
-            neg_before = mm > 0 && w[j] < 0.0f;
+            prev_state = (mm > 0 ? 1 : 0) | ((mm > 0 && w[j] < 0.0f) ? 2 : 0);
             k = kk - mm;
         }
-        if (lane == 63 && neg_before) {   // N(0,0) = 1 after a negative last coordinate
-            wint<W> one;
+        if (lane == 63) {
+            // the last cell is (0, 0): N = 1, E = 2
+            const int32_t last_cell = (prev_state >> 1) - 2 * (prev_state & 1);
+            wint<W> small;
 #pragma unroll
-            for (int i = 0; i < W; i++) one.w[i] = 0;
-            one.w[0] = 1;
-            add_to(acc, one);
+            for (int i = 0; i < W; i++) small.w[i] = last_cell < 0 ? 0xFFFFFFFFu : 0u;
+            small.w[0] = (uint32_t)last_cell;
+            add_to(acc, small);
         }
 #define PVQ_STEP(CTRL, ROWS)                                                           \
     {                                                                                  \
@@ -468,8 +470,10 @@ __global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p
         incl += (int)dpp_move<0x114>((uint32_t)incl);        // row_shr:4
         incl += (int)dpp_move<0x118>((uint32_t)incl);        // row_shr:8
         int k = K - (incl - mine);
-        const uint32_t last_neg = (m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 1u : 0u;
-        bool neg_before = dpp_move<0x111>(last_neg) != 0;    // the lane before in the row; none for sub = 0
+        // cell by cell as in the wave-per-group form: one table entry per cell, in the form that the two
+        // coordinates around it call for
+        const uint32_t last_state = (m[CP - 1] > 0 ? 1u : 0u) | ((m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 2u : 0u);
+        int prev_state = (int)dpp_move<0x111>(last_state);   // the lane before in the row; none for sub = 0
         wint<W> acc;
 #pragma unroll
         for (int i = 0; i < W; i++) acc.w[i] = 0;
@@ -477,26 +481,23 @@ __global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p
         for (int j = 0; j < CP; j++) {
             const int d = D - (CP * sub + j);
             const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
-            const int times = (mm > 0 ? 1 : 0) + (neg_before ? 1 : 0);
-            if (times) {
-                const wint<W> n = load_entry<W>(p.tab_n, (int64_t)d * (K + 1) + kk);
-                add_to(acc, n);
-                if (times == 2) add_to(acc, n);
+            const int times = (mm > 0 ? 1 : 0) + (prev_state >> 1);
+            const bool prev_pos = prev_state & 1;
+            if (prev_pos || times) {
+                const int form = prev_pos ? 1 + times : 0;
+                add_to(acc, load_entry<W>(p.tab_c, ((int64_t)d * (K + 1) + kk) * 4 + form));
             }
-            if (mm > 0) {
-                const wint<W> e = load_entry<W>(p.tab_e, (int64_t)(d - 1) * (K + 1) + (kk - mm));
-                uint32_t br;
-                acc = subtract(acc, e, &br);
-            }
-            neg_before = mm > 0 && w[j] < 0.0f;
+            prev_state = (mm > 0 ? 1 : 0) | ((mm > 0 && w[j] < 0.0f) ? 2 : 0);
             k = kk - mm;
         }
-        if (sub == 15 && neg_before) {   // N(0,0) = 1 after a negative last coordinate
-            wint<W> one;
+        if (sub == 15) {
+            // the last cell is (0, 0): N = 1, E = 2
+            const int32_t last_cell = (prev_state >> 1) - 2 * (prev_state & 1);
+            wint<W> small;
 #pragma unroll
-            for (int i = 0; i < W; i++) one.w[i] = 0;
-            one.w[0] = 1;
-            add_to(acc, one);
+            for (int i = 0; i < W; i++) small.w[i] = last_cell < 0 ? 0xFFFFFFFFu : 0u;
+            small.w[0] = (uint32_t)last_cell;
+            add_to(acc, small);
         }
 #define PVQ_STEP(CTRL)                                                                  \
     {                                                                                   \
@@ -660,7 +661,7 @@ hipError_t pvq_wide_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, in
     encode_wide_params p;
     p.X = a.W; p.ldx = a.ldw; p.groups = a.groups; p.index_row_words = a.index_row_words;
     p.K = c->K; p.bits = c->index_bits; p.ls = a.ls_amplitude;
-    p.tab_n = c->tab_n; p.tab_e = c->tab_u;
+    p.tab_c = c->tab_c;
     p.index_out = a.index_out; p.scale_out = reinterpret_cast<float *>(a.scale_out); p.pulses_out = a.pulses_out;
     p.cols = a.cols;
     // 16 lanes per group, four groups per wave, when the index and the word it may spill into fit 16 lanes

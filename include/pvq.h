@@ -202,6 +202,25 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
                int8_t *pulses_out, void *stream);
 
 /*
+ * Rotation and encoding of activations in one pass (Sec. 3.3 Step 1 in front of Sec. 2.5 / App. B.2): every
+ * row of X is rotated as by pvq_hadamard(X, ..., block, signs, inverse = 0, float32 result) and the rotated
+ * float32 values are encoded as by pvq_encode, without being written: index_out and scale_out receive
+ * exactly what those two calls in a row would give.  For contexts with D = 128 and N(D,K) < 2^384
+ * (float32 amplitudes; the context's amplitude kind applies).
+ *
+ *   X          device, [rows][ldx] of `dtype` (PVQ_F32 or PVQ_BF16), 16-byte aligned, ldx >= cols,
+ *              ldx*sizeof(element) a multiple of 16.
+ *   block      a power of two, 128 .. 8192, dividing cols.
+ *   signs      device, uint8 [cols] (non-zero = -1), 8-byte aligned, or NULL.
+ *   index_out, scale_out   device, the planes of pvq_encode for this context and shape (4-byte aligned).
+ *
+ * PVQ_E_UNSUPPORTED: another context, block outside the above, or an index width for which the groups of
+ * one workgroup (16, 32 or 64 of them, for blocks up to 2048, of 4096, of 8192) do not fill whole words.
+ */
+int pvq_rotate_encode(const pvq_ctx *ctx, const void *X, int dtype, int64_t rows, int64_t cols, int64_t ldx,
+                      int block, const uint8_t *signs, uint32_t *index_out, float *scale_out, void *stream);
+
+/*
  * Decode a matrix: App. B.3 (index -> point p), Sec. 2.4 (direction p/||p||_2 on the unit sphere),
  * times the amplitude (the stored float32, or sqrt(centers[q] * rownorm[row]) per Sec. 3.4).
  *

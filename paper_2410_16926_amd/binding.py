@@ -13,7 +13,7 @@ from . import build as _build
 PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
-    "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables",
+    "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables", "pvq_rotate_encode",
     "pvq_fast_tables_selftest", "pvq_size_table_device", "pvq_hadamard",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
@@ -60,6 +60,7 @@ def lib():
         L.pvq_ctx_set_amplitude.argtypes = [vp, i32]
         L.pvq_packed_sizes.argtypes = [vp, i64, i64, vp, vp, vp]
         L.pvq_encode.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
+        L.pvq_rotate_encode.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
         L.pvq_decode_gemv.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp]
         _lib = L
@@ -245,6 +246,18 @@ def pvq_encode(ctx: PvqContext, W, out: Packed = None, want_pulses: bool = False
     _check(lib().pvq_encode(ctx.handle, _ptr(W), _dtype_code(W), rows, cols, ld, _ptr(out.index),
                             _ptr(out.scale), _ptr(out.rownorm), _ptr(out.pulses), _stream_ptr()),
            "pvq_encode")
+    return out
+
+
+def pvq_rotate_encode(ctx: PvqContext, X, block: int, signs=None, out: Packed = None) -> Packed:
+    """Randomised Hadamard rotation of the rows of X (blocks of `block` columns) and encoding of the rotated
+    values, in one kernel.  X: 2-D float32 or bfloat16 device tensor; signs: uint8 device tensor [cols] or None."""
+    rows, cols = X.shape
+    if out is None:
+        out = alloc_packed(ctx, rows, cols, X.device)
+    ld = X.stride(0) if rows > 1 else max(cols, 1)
+    _check(lib().pvq_rotate_encode(ctx.handle, _ptr(X), _dtype_code(X), rows, cols, ld, block, _ptr(signs),
+                                   _ptr(out.index), _ptr(out.scale), _stream_ptr()), "pvq_rotate_encode")
     return out
 
 

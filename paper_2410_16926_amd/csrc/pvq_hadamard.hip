@@ -16,86 +16,15 @@
 #include <algorithm>
 #include <cmath>
 
+#include "pvq_hadamard_dev.h"
 #include "pvq_internal.h"
 
 namespace {
 
+using namespace pvq_hadamard_dev;
+
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-
-// one word of padding per 32: neighbouring groups of lanes that are 64 or 512 words apart fall into
-// different banks
-__device__ inline uint32_t pad(uint32_t a) { return a + (a >> 5); }
-
-// butterflies over register distance 1, 2, 4 for the first `bits` of them
-__device__ inline void stages_in_registers(float (&v)[8], int bits)
-{
-#pragma unroll
-    for (int t = 0; t < 3; t++) {
-        if (t < bits) {
-            const int h = 1 << t;
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                if ((j & h) == 0) {
-                    const float a = v[j], b = v[j + h];
-                    v[j] = a + b;
-                    v[j + h] = a - b;
-                }
-            }
-        }
-    }
-}
-
-// One butterfly stage between lanes `mask` apart: the lane whose bit is clear holds a and gets a + b, the
-// other holds b and gets a - b.
-template <int MASK>
-__device__ inline void stage_across_lanes(float (&v)[8], int lane)
-{
-    const bool upper = lane & MASK;
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-        float partner;
-        if constexpr (MASK == 1)
-            partner = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[j]), 0xB1, 0xF, 0xF, false));
-        else if constexpr (MASK == 2)
-            partner = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[j]), 0x4E, 0xF, 0xF, false));
-        else
-            partner = __shfl_xor(v[j], MASK, 64);
-        v[j] = upper ? partner - v[j] : v[j] + partner;
-    }
-}
-
-// Ownership (P, R): the lane holds the 8 values of its chunk whose index differs in bits 3P .. 3P+R-1 (the
-// R low bits of the register number) and, for R < 3, in bits 0 .. 2-R (the other bits of the register
-// number); the lane number fills the remaining index bits in order.  (0, 3) is 8 consecutive values.
-// The index of register q is own_base(lane) | own_offset(q): the two never share a bit, so the padded
-// address splits the same way and the register's part is a compile-time constant.
-template <int P, int R>
-__device__ inline uint32_t own_base(uint32_t lane)
-{
-    const uint32_t rest = lane << (3 - R);
-    return (rest & ((1u << (3 * P)) - 1u)) | ((rest >> (3 * P)) << (3 * P + R));
-}
-template <int P, int R>
-__device__ constexpr uint32_t own_offset(int q)
-{
-    return ((uint32_t)q >> R) + (((uint32_t)q & ((1u << R) - 1u)) << (3 * P));
-}
-
-// Through LDS from ownership (P0, R0) to (P1, R1); the caller alternates two buffers, so that one barrier
-// per exchange is enough (a buffer is written again only after a barrier that every wave reaches after
-// its reads of it).
-template <int P0, int R0, int P1, int R1>
-__device__ inline void exchange(float (&v)[8], float *buf, uint32_t lane)
-{
-    float *w = buf + pad(own_base<P0, R0>(lane));
-#pragma unroll
-    for (int q = 0; q < 8; q++) w[pad(own_offset<P0, R0>(q))] = v[q];
-    __syncthreads();
-    const float *r = buf + pad(own_base<P1, R1>(lane));
-#pragma unroll
-    for (int q = 0; q < 8; q++) v[q] = r[pad(own_offset<P1, R1>(q))];
-}
 
 // IN / OUT: 0 = float32, 2 = bf16 (pvq_dtype values).  LOG2N: 9 stands for every block of up to 512 values
 // (log2n says which), 10 .. 13 for that block size.
@@ -146,33 +75,12 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
         for (int j = 0; j < 8; j++) v[j] = __uint_as_float(__float_as_uint(v[j]) ^ flip[j]);
     }
 
-    // index bits 0..2 are the register number, bits 3..8 the lane number inside the wave
-    if constexpr (LOG2N > 9) log2n = LOG2N;
-    stages_in_registers(v, min(3, log2n));
-    if (log2n > 3) stage_across_lanes<1>(v, lane);
-    if (log2n > 4) stage_across_lanes<2>(v, lane);
-    if (log2n > 5) stage_across_lanes<4>(v, lane);
-    if (log2n > 6) stage_across_lanes<8>(v, lane);
-    if (log2n > 7) stage_across_lanes<16>(v, lane);
-    if (log2n > 8) stage_across_lanes<32>(v, lane);
-    // from bit 9 on the partners sit in other waves
     // Blocks of 1024 and 8192 values end with a single stage (index bit 9, or 12): its ownership (P, 1)
     // still has runs of four consecutive values per lane, so the results are stored from there, as two
     // runs 8^P apart, instead of going through LDS once more.
     constexpr bool kSplitStore = LOG2N == 10 || LOG2N == 13;
     constexpr int kSplitP = LOG2N == 13 ? 4 : 3;
-    if constexpr (LOG2N > 9) {
-        constexpr int R3 = LOG2N - 9 < 3 ? LOG2N - 9 : 3;
-        float *buf0 = smem, *buf1 = smem + pad(8u * (uint32_t)L) + 1u;
-        exchange<0, 3, 3, R3>(v, buf0, lane);
-        stages_in_registers(v, R3);
-        if constexpr (LOG2N > 12) {
-            exchange<3, R3, 4, LOG2N - 12>(v, buf1, lane);
-            stages_in_registers(v, LOG2N - 12);
-        } else if constexpr (!kSplitStore) {
-            exchange<3, R3, 0, 3>(v, buf1, lane);
-        }
-    }
+    hadamard_stages<LOG2N, true>(v, lane, log2n, smem, L);
 
     if constexpr (kSplitStore) {
         // register q holds column  own_base(lane) + (q >> 1) + (q & 1) * 8^P  of the chunk

@@ -101,6 +101,9 @@ hipError_t pvq_launch_hadamard(const void *X, int in_dtype, int64_t rows, int64_
 // groups of 64 / 128 values, indices of up to 512 bits (pvq_wide.hip); for contexts with wide == 1
 hipError_t pvq_wide_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
 hipError_t pvq_wide_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
+// rotation of rows (blocks of `block` values, optional signs) and encoding in one kernel; D = 128, words <= 12
+hipError_t pvq_wide_launch_rotate_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, int block,
+                                         const uint8_t *signs, hipStream_t s);
 
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);

@@ -30,7 +30,9 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <cmath>
 
+#include "pvq_hadamard_dev.h"
 #include "pvq_internal.h"
 
 namespace {
@@ -347,6 +349,147 @@ __device__ inline float tree_sum(const float (&x)[CP])
     return t[0];
 }
 
+// One group of 16 * CP values held by 16 lanes (lane `sub` of the group: coordinates CP*sub .. CP*sub+CP-1):
+// the point, the amplitude, the index, and the index's words into the tile's bit stream in LDS at group
+// position gl.  `on` = false: the lanes go through the motions (every cross-lane step needs them) and
+// write nothing.  K and D = 16 * CP as in the context.
+template <int CP, int W>
+__device__ inline void encode_group16(const float (&w)[CP], int sub, bool on, int gl, int64_t row, int64_t g,
+                                      const encode_wide_params &p, uint32_t *stream, int tile_words)
+{
+    constexpr int D = 16 * CP;
+    const int K = p.K;
+    // ---- the point (Sec. 2.5)
+    float a[CP], sq[CP], t[CP];
+#pragma unroll
+    for (int j = 0; j < CP; j++) { a[j] = fabsf(w[j]); sq[j] = w[j] * w[j]; }
+    const float l1 = row_sum_pairs(tree_sum<CP>(a)), ss = row_sum_pairs(tree_sum<CP>(sq));
+    const float gain = (float)K / l1;
+    const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(gain < INFINITY);
+    int m[CP];
+    int S = 0;
+#pragma unroll
+    for (int j = 0; j < CP; j++) {
+        t[j] = a[j] * gain;
+        m[j] = degenerate ? 0 : (int)rintf(t[j]);
+        S += m[j];
+    }
+    S = row_sum_int(S);
+    if (degenerate) {
+        if (sub == 15) m[CP - 1] = K;   // the point (0, ..., 0, +K): index 0
+        S = K;
+    }
+    // one pulse per step and group, as in the wave-per-group form; the wave goes on while any of its
+    // four groups is off the pyramid (a valid group needs at most D/2 steps)
+    for (int step = 0; step < D; step++) {
+        const bool need = S != K;           // the same in the 16 lanes of a group
+        if (!__any(need)) break;
+        const bool down = S > K;
+        float be = -INFINITY;
+        int bi = 0x7FFFFFFF;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            const float e = down ? (float)m[j] - t[j] : t[j] - (float)m[j];
+            const bool can = !down || m[j] > 0;
+            if (can && (bi == 0x7FFFFFFF || e > be)) { be = e; bi = CP * sub + j; }
+        }
+#define PVQ_STEP(CTRL)                                                                                   \
+{                                                                                                    \
+    const float oe = __uint_as_float(dpp_move<CTRL>(__float_as_uint(be), 0xFF800000u));              \
+    const int oi = (int)dpp_move<CTRL>((uint32_t)bi, 0x7FFFFFFFu);                                   \
+    const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));    \
+    if (take) { be = oe; bi = oi; }                                                                  \
+}
+        PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+        if (need) {
+#pragma unroll
+            for (int j = 0; j < CP; j++)
+                if (bi == CP * sub + j) m[j] += down ? -1 : 1;
+            S += down ? -1 : 1;
+        }
+    }
+
+    // ---- amplitude (Sec. 2.3, or Sec. 3.3 Step 4)
+    float amp;
+    if (p.ls) {
+        float pr[CP];
+        int n2 = 0;
+#pragma unroll
+        for (int j = 0; j < CP; j++) {
+            const int ys = w[j] < 0.0f ? -m[j] : m[j];
+            pr[j] = (float)ys * w[j];
+            n2 += m[j] * m[j];
+        }
+        amp = row_sum_pairs(tree_sum<CP>(pr)) / sqrtf((float)row_sum_int(n2));
+    } else {
+        amp = sqrtf(ss);
+    }
+    if (on && sub == 0) p.scale_out[row * p.groups + g] = amp;
+    if (on && p.pulses_out) {
+#pragma unroll
+        for (int j = 0; j < CP; j++)
+            p.pulses_out[row * p.cols + g * D + CP * sub + j] = (int8_t)(w[j] < 0.0f ? -m[j] : m[j]);
+    }
+
+    // ---- the index (App. B.2)
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < CP; j++) mine += m[j];
+    int incl = mine;   // inclusive prefix sum over the 16 lanes of the group
+    incl += (int)dpp_move<0x111>((uint32_t)incl);        // row_shr:1
+    incl += (int)dpp_move<0x112>((uint32_t)incl);        // row_shr:2
+    incl += (int)dpp_move<0x114>((uint32_t)incl);        // row_shr:4
+    incl += (int)dpp_move<0x118>((uint32_t)incl);        // row_shr:8
+    int k = K - (incl - mine);
+    // cell by cell as in the wave-per-group form: one table entry per cell, in the form that the two
+    // coordinates around it call for
+    const uint32_t last_state = (m[CP - 1] > 0 ? 1u : 0u) | ((m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 2u : 0u);
+    int prev_state = (int)dpp_move<0x111>(last_state);   // the lane before in the row; none for sub = 0
+    wint<W> acc;
+#pragma unroll
+    for (int i = 0; i < W; i++) acc.w[i] = 0;
+#pragma unroll
+    for (int j = 0; j < CP; j++) {
+        const int d = D - (CP * sub + j);
+        const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
+        const int times = (mm > 0 ? 1 : 0) + (prev_state >> 1);
+        const bool prev_pos = prev_state & 1;
+        if (prev_pos || times) {
+            const int form = prev_pos ? 1 + times : 0;
+            add_to(acc, load_entry<W>(p.tab_c, ((int64_t)d * (K + 1) + kk) * 4 + form));
+        }
+        prev_state = (mm > 0 ? 1 : 0) | ((mm > 0 && w[j] < 0.0f) ? 2 : 0);
+        k = kk - mm;
+    }
+    if (sub == 15) {
+        // the last cell is (0, 0): N = 1, E = 2
+        const int32_t last_cell = (prev_state >> 1) - 2 * (prev_state & 1);
+        wint<W> small;
+#pragma unroll
+        for (int i = 0; i < W; i++) small.w[i] = last_cell < 0 ? 0xFFFFFFFFu : 0u;
+        small.w[0] = (uint32_t)last_cell;
+        add_to(acc, small);
+    }
+#define PVQ_STEP(CTRL)                                                                  \
+{                                                                                   \
+    wint<W> other;                                                                  \
+    _Pragma("unroll") for (int i = 0; i < W; i++) other.w[i] = dpp_move<CTRL>(acc.w[i]); \
+    add_to(acc, other);                                                             \
+}
+    PVQ_ROW_STEPS(PVQ_STEP)
+#undef PVQ_STEP
+
+    // ---- into the tile's bit stream: lane sub = i of the group takes word i of the index
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < W; i++) word = sub == i ? acc.w[i] : word;
+    const int off = gl * p.bits, sh = off & 31, w0 = off >> 5;
+    const uint32_t prev = dpp_move<0x111>(word);         // word sub-1, zero for sub = 0
+    const uint32_t out = sh ? (word << sh) | (prev >> (32 - sh)) : word;
+    if (on && sub <= W && w0 + sub < tile_words && out) atomicOr(&stream[w0 + sub], out);
+}
+
 template <int TIN, int CP, int W>
 __global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p)
 {
@@ -387,138 +530,82 @@ __global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p
             }
         }
 
-        // ---- the point (Sec. 2.5)
-        float a[CP], sq[CP], t[CP];
-#pragma unroll
-        for (int j = 0; j < CP; j++) { a[j] = fabsf(w[j]); sq[j] = w[j] * w[j]; }
-        const float l1 = row_sum_pairs(tree_sum<CP>(a)), ss = row_sum_pairs(tree_sum<CP>(sq));
-        const float gain = (float)K / l1;
-        const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(gain < INFINITY);
-        int m[CP];
-        int S = 0;
-#pragma unroll
-        for (int j = 0; j < CP; j++) {
-            t[j] = a[j] * gain;
-            m[j] = degenerate ? 0 : (int)rintf(t[j]);
-            S += m[j];
-        }
-        S = row_sum_int(S);
-        if (degenerate) {
-            if (sub == 15) m[CP - 1] = K;   // the point (0, ..., 0, +K): index 0
-            S = K;
-        }
-        // one pulse per step and group, as in the wave-per-group form; the wave goes on while any of its
-        // four groups is off the pyramid (a valid group needs at most D/2 steps)
-        for (int step = 0; step < D; step++) {
-            const bool need = S != K;           // the same in the 16 lanes of a group
-            if (!__any(need)) break;
-            const bool down = S > K;
-            float be = -INFINITY;
-            int bi = 0x7FFFFFFF;
-#pragma unroll
-            for (int j = 0; j < CP; j++) {
-                const float e = down ? (float)m[j] - t[j] : t[j] - (float)m[j];
-                const bool can = !down || m[j] > 0;
-                if (can && (bi == 0x7FFFFFFF || e > be)) { be = e; bi = CP * sub + j; }
-            }
-#define PVQ_STEP(CTRL)                                                                                   \
-    {                                                                                                    \
-        const float oe = __uint_as_float(dpp_move<CTRL>(__float_as_uint(be), 0xFF800000u));              \
-        const int oi = (int)dpp_move<CTRL>((uint32_t)bi, 0x7FFFFFFFu);                                   \
-        const bool take = oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || oe > be || (oe == be && oi < bi));    \
-        if (take) { be = oe; bi = oi; }                                                                  \
-    }
-            PVQ_ROW_STEPS(PVQ_STEP)
-#undef PVQ_STEP
-            if (need) {
-#pragma unroll
-                for (int j = 0; j < CP; j++)
-                    if (bi == CP * sub + j) m[j] += down ? -1 : 1;
-                S += down ? -1 : 1;
-            }
-        }
-
-        // ---- amplitude (Sec. 2.3, or Sec. 3.3 Step 4)
-        float amp;
-        if (p.ls) {
-            float pr[CP];
-            int n2 = 0;
-#pragma unroll
-            for (int j = 0; j < CP; j++) {
-                const int ys = w[j] < 0.0f ? -m[j] : m[j];
-                pr[j] = (float)ys * w[j];
-                n2 += m[j] * m[j];
-            }
-            amp = row_sum_pairs(tree_sum<CP>(pr)) / sqrtf((float)row_sum_int(n2));
-        } else {
-            amp = sqrtf(ss);
-        }
-        if (on && sub == 0) p.scale_out[row * p.groups + g] = amp;
-        if (on && p.pulses_out) {
-#pragma unroll
-            for (int j = 0; j < CP; j++)
-                p.pulses_out[row * p.cols + g * D + CP * sub + j] = (int8_t)(w[j] < 0.0f ? -m[j] : m[j]);
-        }
-
-        // ---- the index (App. B.2)
-        int mine = 0;
-#pragma unroll
-        for (int j = 0; j < CP; j++) mine += m[j];
-        int incl = mine;   // inclusive prefix sum over the 16 lanes of the group
-        incl += (int)dpp_move<0x111>((uint32_t)incl);        // row_shr:1
-        incl += (int)dpp_move<0x112>((uint32_t)incl);        // row_shr:2
-        incl += (int)dpp_move<0x114>((uint32_t)incl);        // row_shr:4
-        incl += (int)dpp_move<0x118>((uint32_t)incl);        // row_shr:8
-        int k = K - (incl - mine);
-        // cell by cell as in the wave-per-group form: one table entry per cell, in the form that the two
-        // coordinates around it call for
-        const uint32_t last_state = (m[CP - 1] > 0 ? 1u : 0u) | ((m[CP - 1] > 0 && w[CP - 1] < 0.0f) ? 2u : 0u);
-        int prev_state = (int)dpp_move<0x111>(last_state);   // the lane before in the row; none for sub = 0
-        wint<W> acc;
-#pragma unroll
-        for (int i = 0; i < W; i++) acc.w[i] = 0;
-#pragma unroll
-        for (int j = 0; j < CP; j++) {
-            const int d = D - (CP * sub + j);
-            const int kk = min(max(k, 0), K), mm = min(max(m[j], 0), kk);   // in range whatever the input
-            const int times = (mm > 0 ? 1 : 0) + (prev_state >> 1);
-            const bool prev_pos = prev_state & 1;
-            if (prev_pos || times) {
-                const int form = prev_pos ? 1 + times : 0;
-                add_to(acc, load_entry<W>(p.tab_c, ((int64_t)d * (K + 1) + kk) * 4 + form));
-            }
-            prev_state = (mm > 0 ? 1 : 0) | ((mm > 0 && w[j] < 0.0f) ? 2 : 0);
-            k = kk - mm;
-        }
-        if (sub == 15) {
-            // the last cell is (0, 0): N = 1, E = 2
-            const int32_t last_cell = (prev_state >> 1) - 2 * (prev_state & 1);
-            wint<W> small;
-#pragma unroll
-            for (int i = 0; i < W; i++) small.w[i] = last_cell < 0 ? 0xFFFFFFFFu : 0u;
-            small.w[0] = (uint32_t)last_cell;
-            add_to(acc, small);
-        }
-#define PVQ_STEP(CTRL)                                                                  \
-    {                                                                                   \
-        wint<W> other;                                                                  \
-        _Pragma("unroll") for (int i = 0; i < W; i++) other.w[i] = dpp_move<CTRL>(acc.w[i]); \
-        add_to(acc, other);                                                             \
-    }
-        PVQ_ROW_STEPS(PVQ_STEP)
-#undef PVQ_STEP
-
-        // ---- into the tile's bit stream: lane sub = i of the group takes word i of the index
-        uint32_t word = 0;
-#pragma unroll
-        for (int i = 0; i < W; i++) word = sub == i ? acc.w[i] : word;
-        const int off = gl * p.bits, sh = off & 31, w0 = off >> 5;
-        const uint32_t prev = dpp_move<0x111>(word);         // word sub-1, zero for sub = 0
-        const uint32_t out = sh ? (word << sh) | (prev >> (32 - sh)) : word;
-        if (on && sub <= W && w0 + sub < tile_words && out) atomicOr(&stream[w0 + sub], out);
+        encode_group16<CP, W>(w, sub, on, gl, row, g, p, stream, tile_words);
     }
     __syncthreads();
     uint32_t *dst = p.index_out + row * p.index_row_words + first_word;
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) dst[i] = stream[i];
+}
+
+// Rotation and quantisation of activations in one kernel (Sec. 3.3 Step 1 in front of the encoder): a
+// workgroup of L lanes takes 8L consecutive values of a row, 8 per lane, runs the block Walsh-Hadamard
+// transform of the rotation kernel on them (same stages, same order, float32), and, since a lane ends with
+// 8 consecutive rotated values, 16 neighbouring lanes hold one group of 128: the group encoder above
+// takes them from the registers.  The rotated values are never written.
+struct rotate_encode_params {
+    const void *X;
+    int64_t ldx, cols;
+    int log2n, chunks_per_row;
+    const uint8_t *signs;
+    float scale;
+    encode_wide_params e;
+};
+
+template <int TIN, int W, int LOG2N>
+__global__ __launch_bounds__(1024) void rotate_encode16_kernel(rotate_encode_params p)
+{
+    extern __shared__ __align__(16) float smem[];
+    const int L = blockDim.x;
+    const int lane = threadIdx.x;
+    const int64_t row = blockIdx.x / p.chunks_per_row;
+    const int chunk = blockIdx.x - (int)(row * p.chunks_per_row);
+    const int64_t col0 = (int64_t)chunk * 8 * L + 8 * lane;   // first of this lane's 8 columns
+    const bool live = col0 < p.cols;                           // whole blocks and groups: a lane is in or out
+
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = 0.0f;
+    if (live) {
+        if constexpr (TIN == PVQ_F32) {
+            const float *src = reinterpret_cast<const float *>(p.X) + row * p.ldx + col0;
+            const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        } else {
+            const uint4 q = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(p.X) + row * p.ldx + col0);
+            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                v[2 * j] = __uint_as_float(u[j] << 16);
+                v[2 * j + 1] = __uint_as_float(u[j] & 0xFFFF0000u);
+            }
+        }
+        if (p.signs) {
+            const uint2 s8 = *reinterpret_cast<const uint2 *>(p.signs + col0);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t byte = ((j < 4 ? s8.x : s8.y) >> (8 * (j & 3))) & 0xFFu;
+                if (byte) v[j] = -v[j];
+            }
+        }
+    }
+    pvq_hadamard_dev::hadamard_stages<LOG2N, false>(v, lane, p.log2n, smem, L);
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = v[j] * p.scale;
+
+    // the chunk's groups are a tile of the index plane (whole words: the host checks it)
+    uint32_t *stream = reinterpret_cast<uint32_t *>(smem) + (LOG2N > 9 ? 2 * (pvq_hadamard_dev::pad(8u * (uint32_t)L) + 1u) : 0u);
+    const int per_chunk = L / 16;
+    const int64_t g0 = (int64_t)chunk * per_chunk;
+    const int ng = (int)min((int64_t)per_chunk, p.e.groups - g0);
+    const int tile_words = ng > 0 ? (int)(((int64_t)ng * p.e.bits + 31) / 32) : 0;
+    const int64_t first_word = g0 * p.e.bits / 32;
+    for (int i = threadIdx.x; i < tile_words; i += blockDim.x) stream[i] = 0;
+    __syncthreads();
+    const int sub = lane & 15, gl = lane >> 4;
+    const bool on = gl < ng;
+    encode_group16<8, W>(v, sub, on, gl, row, g0 + (on ? gl : 0), p.e, stream, tile_words);
+    __syncthreads();
+    uint32_t *dst = p.e.index_out + row * p.e.index_row_words + first_word;
     for (int i = threadIdx.x; i < tile_words; i += blockDim.x) dst[i] = stream[i];
 }
 
@@ -692,6 +779,48 @@ hipError_t pvq_wide_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, in
 #undef PVQ_WIDE_ENC_W
 #undef PVQ_WIDE_ENC16
 #undef PVQ_WIDE_ENC
+    return hipGetLastError();
+}
+
+hipError_t pvq_wide_launch_rotate_encode(const pvq_ctx *c, const pvq_encode_args &a, int dtype, int block,
+                                         const uint8_t *signs, hipStream_t s)
+{
+    rotate_encode_params p;
+    int log2n = 0;
+    while ((1 << log2n) < block) log2n++;
+    const int L = std::min(1024, std::max(256, block / 8));
+    const int chunk = 8 * L;
+    p.X = a.W; p.ldx = a.ldw; p.cols = a.cols; p.log2n = log2n; p.signs = signs;
+    p.chunks_per_row = (int)((a.cols + chunk - 1) / chunk);
+    p.scale = (float)(1.0 / std::sqrt((double)block));
+    p.e.X = nullptr; p.e.ldx = 0; p.e.groups = a.groups; p.e.index_row_words = a.index_row_words;
+    p.e.K = c->K; p.e.bits = c->index_bits; p.e.ls = a.ls_amplitude;
+    p.e.tile_groups = L / 16; p.e.tiles_per_row = p.chunks_per_row;
+    p.e.tab_c = c->tab_c; p.e.index_out = a.index_out; p.e.scale_out = reinterpret_cast<float *>(a.scale_out);
+    p.e.pulses_out = nullptr; p.e.cols = a.cols;
+    if (a.rows * p.chunks_per_row > 0x7FFFFFFF) return hipErrorInvalidValue;
+    size_t lds = (size_t)(L / 16) * c->index_bits / 8 + 16;
+    if (log2n > 9) lds += 2 * (size_t)(chunk + chunk / 32 + 1) * sizeof(float);
+    const dim3 grid((unsigned)(a.rows * p.chunks_per_row)), blk((unsigned)L);
+#define PVQ_RE(T, W, N) hipLaunchKernelGGL((rotate_encode16_kernel<T, W, N>), grid, blk, lds, s, p)
+#define PVQ_RE_N(T, W)                             \
+    switch (log2n) {                               \
+    case 13: PVQ_RE(T, W, 13); break;              \
+    case 12: PVQ_RE(T, W, 12); break;              \
+    case 11: PVQ_RE(T, W, 11); break;              \
+    case 10: PVQ_RE(T, W, 10); break;              \
+    default: PVQ_RE(T, W, 9); break;               \
+    }
+#define PVQ_RE_W(T)                                \
+    switch (c->words) {                            \
+    case 4: PVQ_RE_N(T, 4) break;                  \
+    case 8: PVQ_RE_N(T, 8) break;                  \
+    default: PVQ_RE_N(T, 12) break;                \
+    }
+    if (dtype == PVQ_F32) { PVQ_RE_W(PVQ_F32) } else { PVQ_RE_W(PVQ_BF16) }
+#undef PVQ_RE_W
+#undef PVQ_RE_N
+#undef PVQ_RE
     return hipGetLastError();
 }
 

@@ -216,6 +216,63 @@ def test_long_groups_adversarial(D, K):
         run_long_groups(X, D, K, amplitude="ls")
 
 
+@pytest.mark.parametrize("tokens,hidden,block,bits_per_value,bf16", [(5, 8192, 8192, 3, True), (3, 16384, 8192, 3, False),
+                                                                     (9, 4096, 4096, 3, True), (4, 12288, 4096, 2, False),
+                                                                     (7, 2048, 512, 3, True), (6, 6144, 2048, 3, True),
+                                                                     (2, 3072, 1024, 2, False), (300, 8192, 8192, 3, True)])
+def test_rotation_and_encoding_in_one_kernel(tokens, hidden, block, bits_per_value, bf16):
+    # pvq_rotate_encode must give exactly what the oracle's rotation (float32) followed by the oracle's
+    # encoder gives: the rotated values stay in registers in the same float32 bits
+    D = 128
+    K = pvq.pvq_max_k(D, bits_per_value * D)
+    rng = np.random.default_rng(tokens + hidden + block)
+    sg = rng.integers(0, 2, size=hidden).astype(np.uint8)
+    if bf16:
+        xf, xb = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + block, rotate=False)
+        Xd = gu.to_dev_bf16(xb)
+    else:
+        xf = si.activation_matrix(tokens, hidden, seed=si.BASE_SEED + block, rotate=False, bf16=False)
+        Xd = gu.to_dev_f32(xf)
+    rotated = oracle.hadamard_rows(xf, block, sg)
+    for amplitude in ("l2", "ls"):
+        ctx = pvq.pvq_ctx_create(D, K)
+        ctx.set_amplitude({"l2": "norm", "ls": "ls"}[amplitude])
+        packed = pvq.pvq_rotate_encode(ctx, Xd, block, torch.from_numpy(sg).cuda())
+        torch.cuda.synchronize()
+        enc = oracle.encode(rotated, D, K, 0, None, nthreads=8, amplitude=amplitude)
+        gu.assert_encode_equal(packed, enc, check_pulses=False)
+        # and the two separate calls agree with it as well
+        two = pvq.pvq_encode(ctx, pvq.pvq_hadamard(Xd, block, torch.from_numpy(sg).cuda(), out_dtype=torch.float32))
+        assert torch.equal(two.index, packed.index) and torch.equal(two.scale, packed.scale)
+        ctx.close()
+    # without signs
+    ctx = pvq.pvq_ctx_create(D, K)
+    packed = pvq.pvq_rotate_encode(ctx, Xd, block)
+    enc = oracle.encode(oracle.hadamard_rows(xf, block), D, K, 0, None, nthreads=8)
+    gu.assert_encode_equal(packed, enc, check_pulses=False)
+    ctx.close()
+
+
+def test_rotation_and_encoding_argument_errors():
+    X = torch.zeros((2, 1024), dtype=torch.float32, device="cuda")
+    ctx8 = pvq.pvq_ctx_create(8, 16)
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_rotate_encode(ctx8, X, 1024)                 # groups of 128 only
+    assert e.value.status == -2
+    ctx8.close()
+    ctx = pvq.pvq_ctx_create(128, 187)
+    for block in (64, 96, 2048, 16384):                      # too small, no power of two, not dividing, too large
+        with pytest.raises(pvq.PvqError) as e:
+            pvq.pvq_rotate_encode(ctx, X, block)
+        assert e.value.status == -2
+    ctx.close()
+    ctx = pvq.pvq_ctx_create(128, 186)                       # 383-bit indices: 16 groups do not fill whole words
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_rotate_encode(ctx, X, 1024)
+    assert e.value.status == -2
+    ctx.close()
+
+
 def test_long_groups_argument_errors():
     with pytest.raises(pvq.PvqError) as e:
         pvq.pvq_ctx_create(128, 400)              # N(128,400) needs more than 512 bits

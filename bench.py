@@ -307,8 +307,11 @@ def main():
             Xo = torch.empty_like(X)
             te = timed(lambda: pvq.pvq_encode(ctxa, X, out=pa), reps=10)
             td = timed(lambda: pvq.pvq_decode(ctxa, pa, out=Xo), reps=10)
+            sga = torch.randint(0, 2, (8192,), dtype=torch.uint8, device=dev)
+            tf = timed(lambda: pvq.pvq_rotate_encode(ctxa, X, 8192, sga, out=pa), reps=10)
             act[f"tokens_{tokens}"] = {"encode_ms": round(te, 4), "decode_ms": round(td, 4),
-                                       "encode_Gvalues_per_s": round(tokens * 8192 / te / 1e6, 2)}
+                                       "encode_Gvalues_per_s": round(tokens * 8192 / te / 1e6, 2),
+                                       "rotate_encode_ms": round(tf, 4)}
             if tokens == 16:
                 xf = si.bf16_bits_to_f32(xb)
                 t0 = time.perf_counter(); oracle.encode(xf, 128, K128, nthreads=1); t_cpu = time.perf_counter() - t0

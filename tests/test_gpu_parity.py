@@ -321,6 +321,56 @@ def test_random_configurations(i, D, budget, bits, rows, G, bf16, amplitude):
         run_case(W, D, K, bits, batches=(2, 16), out_dtypes=("f32", "f16"), amplitude=amplitude)
 
 
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # encode, decode, the fused product (single-vector and matrix-core passes), the rotation and the size
+    # table enqueue kernels only (no memset, no allocation), so a caller may capture them; every replay
+    # must reproduce the eager results for the inputs then in the buffers
+    D, K, bits, rows, cols = 8, 16, 2, 64, 2048
+    ctx, _, _ = gu.make_ctx(D, K, bits, cols // D)
+    W = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    x = torch.empty((16, cols), dtype=torch.bfloat16, device="cuda")
+    packed = pvq.alloc_packed(ctx, rows, cols, W.device)
+    What = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    y1 = torch.empty((1, rows), dtype=torch.float32, device="cuda")
+    y16 = torch.empty((16, rows), dtype=torch.float32, device="cuda")
+    R = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+
+    def fill(seed):
+        _, wb = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + seed, rotate=False, bf16=True)
+        _, xb = si.activations(16, cols, seed=si.BASE_SEED + seed)
+        W.copy_(gu.to_dev_bf16(wb)); x.copy_(gu.to_dev_bf16(xb))
+
+    def run():
+        pvq.pvq_encode(ctx, W, out=packed)
+        pvq.pvq_decode(ctx, packed, out=What)
+        pvq.pvq_decode_gemv(ctx, packed, x[:1], out=y1)
+        pvq.pvq_decode_gemv(ctx, packed, x, out=y16)
+        pvq.pvq_hadamard(W, 2048, out=R)
+
+    fill(1)
+    run()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for seed in (2, 3, 4):
+        fill(seed)
+        run()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (packed.index, packed.scale, packed.rownorm, What, y1, y16, R)]
+        for t in (packed.index, packed.scale, packed.rownorm, What, y1, y16, R):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (packed.index, packed.scale, packed.rownorm, What, y1, y16, R)):
+            assert torch.equal(a, b)
+    ctx.close()
+
+
 def test_leading_dimensions_and_views():
     D, K = 8, 16
     rows, cols, ld = 33, 512, 640

@@ -395,6 +395,25 @@ def test_leading_dimensions_and_views():
     ctx.close()
 
 
+def test_leading_dimensions_in_the_many_vector_pass():
+    # rows of 256 groups with 24-bit indices go to the matrix-core pass for 5..16 vectors: activations
+    # and results as views with larger leading dimensions, results beyond the rows untouched
+    D, K, rows, cols, ld = 8, 16, 21, 2048, 2048 + 64
+    wf, wb = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 51, bf16=True)
+    ctx = pvq.pvq_ctx_create(D, K)
+    packed = pvq.pvq_encode(ctx, gu.to_dev_bf16(wb))
+    ref, _, _ = oracle.decode(oracle.encode(wf, D, K))
+    for batch in (5, 16):
+        xf, xb = si.activations(batch, ld, seed=7 + batch)
+        xv = gu.to_dev_bf16(xb)[:, :cols]
+        y_big = torch.full((batch, rows + 11), -3.0, dtype=torch.float32, device="cuda")
+        pvq.pvq_decode_gemv(ctx, packed, xv, out=y_big[:, :rows])
+        gu.assert_gemv_close(y_big[:, :rows].cpu().numpy(), xf[:, :cols].astype(np.float64) @ ref.T,
+                             gu.product_scale(xf[:, :cols], ref))
+        assert torch.all(y_big[:, rows:] == -3.0)
+    ctx.close()
+
+
 def test_empty_inputs_and_argument_errors():
     ctx = pvq.pvq_ctx_create(8, 16)
     L = pvq.lib()

@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
     ap.add_argument("--only", default="", help="comma-separated subset of encode,decode,gemv_b1,gemv_b4,"
                     "gemv_b16 to run in the timed steps (profiling aid; the JSON line is then partial)")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="leave out the back-to-back and cache-warm loops of the batch-1 kernel, so that a kernel "
+                         "trace of the run holds the launches of the timed steps and the warm-up only")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed steps also time, on the same matrix: pvq_encode with least-squares "
                     "amplitudes, and the D=16 / 52-bit index / 4-bit amplitude setting (generic kernels)")
@@ -191,7 +194,9 @@ def main():
     # kernels, a few us per kernel, and every launch there follows a kernel that has just swept the
     # caches; back to back the tables stay cached and launches overlap their ends.
     b2b = ms["gemv_b1"]
-    if not only or "gemv_b1" in only:
+    if args.steps_only:
+        b2b = warm = float("nan")
+    elif not only or "gemv_b1" in only:
         n = max(args.steps, 10)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()

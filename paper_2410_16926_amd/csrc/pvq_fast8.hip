@@ -977,7 +977,9 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
         hipError_t e;
         // from eight vectors on, one 16-vector pass (about 215 us on the benchmark shape whatever the
         // count) beats two or more 4-vector passes (111 us each)
-        if (left >= 5 && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
+        // (measured on the benchmark shape: 2 vectors 91 us and 4 vectors 114 us on the vector-ALU kernels,
+        // 3 vectors 169 us as 2 + 1; the matrix-core pass takes 120..130 us whatever the count)
+        if ((left >= 5 || left == 3) && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
         else if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
         else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }

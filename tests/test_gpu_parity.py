@@ -130,10 +130,10 @@ def test_many_vectors_on_ragged_shapes(rows, cols, bits):
 @pytest.mark.parametrize("rows,cols,bits", [(1, 8 * 256, 0), (37, 8 * 256, 2), (130, 8 * 768, 8), (19, 8 * 1024, 2),
                                             (300, 8 * 512, 1), (16, 8 * 1024, 4), (33, 8 * 1024, 0)])
 def test_many_vectors_on_the_matrix_cores(rows, cols, bits):
-    # 5..16 vectors with rows of 4, 8, 12, 16 slabs of 64 groups: the pass whose dot products run as
+    # 3 or 5..16 vectors with rows of 4, 8, 12, 16 slabs of 64 groups: the pass whose dot products run as
     # 16x16x32 matrix instructions; row counts that leave partial tiles of 16 rows, every amplitude format
     wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 90 + rows, rotate=False, bf16=True)
-    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 9, 13), out_dtypes=())
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 9, 13, 3), out_dtypes=())
 
 
 @pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])

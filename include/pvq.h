@@ -244,8 +244,8 @@ int pvq_decode(const pvq_ctx *ctx, const uint32_t *index, const void *scale, con
  *   x   device, bf16 [batch][ldx], 16-byte aligned, ldx >= cols, ldx a multiple of 8; 1 <= batch <= 16.
  *   y   device, float32 [batch][ldy], ldy >= rows.  Float32 accumulation in a fixed order
  *       (deterministic for a given shape and batch).  Weights are the float32 values gain * y, except in
- *       the pass that takes 3 or 5..16 vectors at once on the matrix cores (D = 8 with 24-bit indices and
- *       256, 512, 768 or 1024 groups per row), where each weight enters as the sum of two bf16 terms
+ *       the pass that takes 3..16 vectors at once on the matrix cores (D = 8 with 24-bit indices and
+ *       rows of 256 or more groups, a multiple of 64), where each weight enters as the sum of two bf16 terms
  *       (relative error below 2^-14; products with the bf16 activations exact in float32).
  */
 int pvq_decode_gemv(const pvq_ctx *ctx, const uint32_t *index, const void *scale,

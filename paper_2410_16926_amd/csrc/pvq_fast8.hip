@@ -585,39 +585,40 @@ constexpr int kMfmaSlab = 64;                 // groups of a row that one wave t
 constexpr int kMfmaSlots = 4;                 // waves whose results meet in LDS at a time
 constexpr size_t kMfmaPartBytes = kMfmaSlots * 256 * sizeof(float);
 
-// AMP: 0 = float32 amplitudes, 1 = amplitude codes.  24-bit indices.  nsl = slabs per row (a multiple
-// of 4, at most 16), rl = row tiles that the workgroup's waves work on at a time.
+// AMP: 0 = float32 amplitudes, 1 = amplitude codes.  24-bit indices.  nslabs = slabs per row.  A workgroup
+// owns tiles_per_block consecutive row tiles and takes them in rounds: four tiles at a time while four are
+// left (four waves per tile, every wave the slabs slice, slice + 4, ...), then two (eight waves each), then
+// one (sixteen waves, or as many as the row has slabs, rounded up to four).  Few, long rounds keep the
+// barriers of the reduction and the unhidden first loads of a tile rare.
 template <int AMP>
 __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f, pvq_decode_args a, int b0,
-                                                                  int nvec, int nsl, int rl, int rows_per_block)
+                                                                  int nvec, int tiles_per_block, int nslabs)
 {
     constexpr bool CODES = AMP != 0;
+    constexpr int kWaves = kGemvThreads / kWave;
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
     float *sqrtc_l = reinterpret_cast<float *>(lds + f.p.tab_bytes);
     float *part = sqrtc_l + 256;
 
-    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
+    const int64_t r_begin = (int64_t)blockIdx.x * tiles_per_block * kMfmaRows;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + (int64_t)tiles_per_block * kMfmaRows);
     const int64_t r_last = r_end - 1;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int nwaves = nsl * rl;
-    const int slice = wave % nsl, rowlane = wave / nsl;
     const int m = lane & 15, kb = lane >> 4;
-    const uint32_t gl0 = (uint32_t)(slice * kMfmaSlab + 4 * kb);   // the lane's first group: quad q starts 16 q further
     const uint32_t sb = (uint32_t)f.scale_bits;
+    const int nsl_cap = std::min(kWaves, (nslabs + kMfmaSlots - 1) / kMfmaSlots * kMfmaSlots);
 
     load_tables<false>(lds, f, sqrtc_l);
     if (r_begin >= r_end) return;
 
     // the other operand: vector m, the 8 columns of the lane's group.  Lanes beyond the vectors given read
     // the last vector again (no condition around the loads); their columns of the result are not stored.
-    const uint16_t *xrow = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + std::min(m, nvec - 1)) * a.ldx + (int64_t)gl0 * 8;
+    const uint16_t *xvec = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)(b0 + std::min(m, nvec - 1)) * a.ldx;
 
     // what a lane reads per four groups: three index words, and the word with the four codes or four floats
     struct quad_t { uint32_t w[3]; uint32_t s[CODES ? 1 : 4]; };
-    auto fetch = [&](int64_t row, int q, quad_t &it) {
-        const uint32_t g = gl0 + 16u * (uint32_t)q;
+    auto fetch = [&](int64_t row, uint32_t g, quad_t &it) {
         const uint3 iw = *reinterpret_cast<const uint3 *>(a.index + row * a.index_row_words + (g >> 2) * 3u);   // one 12-byte load
         it.w[0] = iw.x; it.w[1] = iw.y; it.w[2] = iw.z;
         if constexpr (CODES) {
@@ -629,28 +630,51 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
         }
     };
 
-    const int64_t tiles = (r_end - r_begin + kMfmaRows - 1) / kMfmaRows;
-    for (int64_t t0 = 0; t0 < tiles; t0 += rl) {
-        const int64_t tile = t0 + rowlane;                           // uniform in the wave
-        const bool live = wave < nwaves && tile < tiles;
+    const int tiles = (int)((r_end - r_begin + kMfmaRows - 1) / kMfmaRows);
+    // a round: rl tiles from t0 on, nsl waves each (uniform in the workgroup); this wave's part of it
+    struct round_t { int rl, nsl, nwaves, nq; uint32_t gl0; int64_t row; bool live; };
+    auto make_round = [&](int t0) {
+        round_t R;
+        const int left = tiles - t0;
+        R.rl = left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        R.nsl = std::min(kWaves / R.rl, nsl_cap);
+        R.nwaves = R.nsl * R.rl;
+        const int slice = wave % R.nsl, tile = t0 + wave / R.nsl;     // uniform in the wave
+        // the lane's groups: slab slice + nsl * pass, there 4 * kb + 16 * q + j; quad number qq = 4 * pass + q
+        R.gl0 = (uint32_t)(slice * kMfmaSlab + 4 * kb);
+        R.nq = slice < nslabs ? 4 * ((nslabs - slice + R.nsl - 1) / R.nsl) : 0;
+        R.live = left > 0 && wave < R.nwaves && tile < tiles && R.nq > 0;
+        R.row = std::min<int64_t>(r_begin + (int64_t)tile * kMfmaRows + m, r_last);
+        return R;
+    };
+    round_t R = make_round(0);
+    quad_t cur, nxt;
+    if (R.live) fetch(R.row, R.gl0, cur);
+    for (int t0 = 0; t0 < tiles;) {
+        // the first quad of the next round is fetched during the last quad of this one, so that the
+        // reduction's barriers do not stand between a wave and its next indices
+        const round_t N = make_round(t0 + R.rl);
+        const int nsl = R.nsl, nwaves = R.nwaves, nq = R.nq;
+        const bool live = R.live;
+        auto quad_group = [&](int qq) { return R.gl0 + (uint32_t)((qq >> 2) * nsl * kMfmaSlab + 16 * (qq & 3)); };
         f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (!live && N.live) fetch(N.row, N.gl0, cur);
         if (live) {
-            const int64_t row = std::min<int64_t>(r_begin + tile * kMfmaRows + m, r_last);
-            quad_t cur, nxt;
-            fetch(row, 0, cur);
 #pragma unroll 1
-            for (int q = 0; q < 4; q++) {
-                fetch(row, q < 3 ? q + 1 : 3, nxt);
+            for (int q = 0; q < nq; q++) {
+                const uint32_t gq = quad_group(q);
+                const bool last = q + 1 == nq;
+                fetch(last && N.live ? N.row : R.row, last ? (N.live ? N.gl0 : gq) : quad_group(q + 1), nxt);
                 uint4 bx[4];
 #pragma unroll
-                for (int j = 0; j < 4; j++) bx[j] = *reinterpret_cast<const uint4 *>(xrow + (16 * q + j) * 8);
+                for (int j = 0; j < 4; j++) bx[j] = *reinterpret_cast<const uint4 *>(xvec + (int64_t)(gq + j) * 8);
                 uint32_t c[4], pr[4][4], n2x4[4];
                 c[0] = cur.w[0] & 0xFFFFFFu;
                 c[1] = __builtin_amdgcn_alignbit(cur.w[1], cur.w[0], 24) & 0xFFFFFFu;
                 c[2] = __builtin_amdgcn_alignbit(cur.w[2], cur.w[1], 16) & 0xFFFFFFu;
                 c[3] = cur.w[2] >> 8;
                 pvq_fast8_decode<4, false>(lds, f.blob, f.p, c, pr, n2x4);
-                const uint32_t codes = CODES ? cur.s[0] >> (((gl0 + 16u * (uint32_t)q) * sb) & 31u) : 0u;
+                const uint32_t codes = CODES ? cur.s[0] >> ((gq * sb) & 31u) : 0u;
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
                     float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]);
@@ -675,12 +699,13 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
                 cur = nxt;
             }
         }
-        // acc[r] = partial sum for row 4*kb + r of the tile and vector m.  Phases of four waves: slices
-        // 4p..4p+3 of one row tile each; thread (tile row, vector) of the first 256 adds them in order.
+        // acc[r] = partial sum for row 4*kb + r of the tile and vector m.  Phases of four waves (nsl is a
+        // multiple of four, so a phase lies within one row tile); thread (tile row, vector) of the first
+        // 256 adds them in wave order.
         float sum = 0.0f;
-        const int phases = (nwaves + kMfmaSlots - 1) / kMfmaSlots;
+        const int phases = nwaves / kMfmaSlots;
         for (int ph = 0; ph < phases; ph++) {
-            if (wave / kMfmaSlots == ph && wave < nwaves) {
+            if (wave / kMfmaSlots == ph) {
                 float *slot = part + (wave % kMfmaSlots) * 256;
 #pragma unroll
                 for (int r = 0; r < 4; r++) slot[(4 * kb + r) * 16 + m] = live ? acc[r] : 0.0f;
@@ -688,12 +713,11 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
             __syncthreads();
             if (threadIdx.x < 256) {
 #pragma unroll
-                for (int sidx = 0; sidx < kMfmaSlots; sidx++)
-                    if (ph * kMfmaSlots + sidx < nwaves) sum += part[sidx * 256 + threadIdx.x];
+                for (int sidx = 0; sidx < kMfmaSlots; sidx++) sum += part[sidx * 256 + threadIdx.x];
                 // the last slices of a row tile: its sums are complete
                 if (((ph + 1) * kMfmaSlots) % nsl == 0) {
-                    const int64_t otile = t0 + (ph * kMfmaSlots) / nsl;
-                    const int64_t orow = r_begin + otile * kMfmaRows + (threadIdx.x >> 4);
+                    const int otile = t0 + (ph * kMfmaSlots) / nsl;
+                    const int64_t orow = r_begin + (int64_t)otile * kMfmaRows + (threadIdx.x >> 4);
                     const int n = threadIdx.x & 15;
                     if (otile < tiles && orow < r_end && n < nvec) {
                         float v = sum;
@@ -705,6 +729,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
             }
             __syncthreads();
         }
+        t0 += R.rl;
+        R = N;
     }
 }
 
@@ -935,24 +961,22 @@ hipError_t launch_gemv_wide(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
 hipError_t launch_gemv_mfma(const pvq_ctx *c, const pvq_decode_args &a, int b0, int nvec, hipStream_t s)
 {
     const fast8_launch f = make_launch(c, false);
-    const int nsl = (int)(a.groups / kMfmaSlab);
-    const int rl = std::max(1, (kGemvThreads / kWave) / nsl);
-    const int RB = kMfmaRows * rl;
-    const int64_t batches = (a.rows + RB - 1) / RB;
-    const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, batches));
-    const int rows_per_block = (int)(((batches + nblocks - 1) / nblocks) * RB);
-    const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)kGemvThreads);
-    if (f.scale_bits > 0) hipLaunchKernelGGL((gemv8_mfma_kernel<1>), grid, block, 0, s, f, a, b0, nvec, nsl, rl, rows_per_block);
-    else hipLaunchKernelGGL((gemv8_mfma_kernel<0>), grid, block, 0, s, f, a, b0, nvec, nsl, rl, rows_per_block);
+    const int nslabs = (int)(a.groups / kMfmaSlab);
+    const int64_t tiles = (a.rows + kMfmaRows - 1) / kMfmaRows;
+    const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, tiles));
+    const int tiles_per_block = (int)((tiles + nblocks - 1) / nblocks);
+    const dim3 grid((unsigned)((tiles + tiles_per_block - 1) / tiles_per_block)), block((unsigned)kGemvThreads);
+    if (f.scale_bits > 0) hipLaunchKernelGGL((gemv8_mfma_kernel<1>), grid, block, 0, s, f, a, b0, nvec, tiles_per_block, nslabs);
+    else hipLaunchKernelGGL((gemv8_mfma_kernel<0>), grid, block, 0, s, f, a, b0, nvec, tiles_per_block, nslabs);
     return hipGetLastError();
 }
 
-// the matrix-core kernel takes 24-bit indices and rows of 4, 8, 12 or 16 slabs of 64 groups, and needs
+// the matrix-core kernel takes 24-bit indices and rows of four or more whole slabs of 64 groups, and needs
 // room in LDS for the tables, the amplitude table and four waves' results
 bool mfma_usable(const pvq_ctx *c, const pvq_decode_args &a)
 {
-    const int64_t nsl = a.groups / kMfmaSlab;
-    return c->index_bits == 24 && a.groups % (4 * kMfmaSlab) == 0 && nsl <= kGemvThreads / kWave &&
+    return c->index_bits == 24 && a.groups % kMfmaSlab == 0 && a.groups >= 4 * kMfmaSlab && a.groups <= (1 << 20) &&
+           a.rows <= ((int64_t)1 << 30) &&
            (size_t)c->fast8.tab_bytes + 256 * sizeof(float) + kMfmaPartBytes <= (size_t)kLdsBytes;
 }
 
@@ -975,11 +999,11 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
     while (b0 < a.batch) {
         const int left = a.batch - b0;
         hipError_t e;
-        // from eight vectors on, one 16-vector pass (about 215 us on the benchmark shape whatever the
-        // count) beats two or more 4-vector passes (111 us each)
-        // (measured on the benchmark shape: 2 vectors 91 us and 4 vectors 114 us on the vector-ALU kernels,
-        // 3 vectors 169 us as 2 + 1; the matrix-core pass takes 120..130 us whatever the count)
-        if ((left >= 5 || left == 3) && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
+        // measured on the benchmark shape: 1 vector 84 us, 2 vectors 91 us and 4 vectors 111..125 us on the
+        // vector-ALU kernels; the matrix-core pass takes 105..117 us whatever the count, so it takes three
+        // vectors and more.  Where it cannot run, one 16-vector pass (about 215 us) beats two or more
+        // 4-vector passes from eight vectors on.
+        if (left >= 3 && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
         else if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
         else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }

@@ -128,12 +128,23 @@ def test_many_vectors_on_ragged_shapes(rows, cols, bits):
 
 
 @pytest.mark.parametrize("rows,cols,bits", [(1, 8 * 256, 0), (37, 8 * 256, 2), (130, 8 * 768, 8), (19, 8 * 1024, 2),
-                                            (300, 8 * 512, 1), (16, 8 * 1024, 4), (33, 8 * 1024, 0)])
+                                            (300, 8 * 512, 1), (16, 8 * 1024, 4), (33, 8 * 1024, 0),
+                                            (120, 8 * 320, 2), (49, 8 * 448, 0), (97, 8 * 832, 2)])
 def test_many_vectors_on_the_matrix_cores(rows, cols, bits):
-    # 3 or 5..16 vectors with rows of 4, 8, 12, 16 slabs of 64 groups: the pass whose dot products run as
-    # 16x16x32 matrix instructions; row counts that leave partial tiles of 16 rows, every amplitude format
+    # 3..16 vectors with rows of 4, 5, 7, 8, 12, 13, 16 slabs of 64 groups: the pass whose dot products
+    # run as 16x16x32 matrix instructions; row counts that leave partial tiles of 16 rows and rounds of
+    # four, two and one tile, every amplitude format
     wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 90 + rows, rotate=False, bf16=True)
     run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 9, 13, 3), out_dtypes=())
+
+
+@pytest.mark.parametrize("rows,cols,bits", [(21, 8 * 1088, 2), (40, 8 * 1792, 2), (17, 8 * 3584, 0), (3, 8 * 2048, 8),
+                                            (70, 8 * 1984, 1)])
+def test_many_vectors_on_the_matrix_cores_long_rows(rows, cols, bits):
+    # rows of more than 16 slabs (17, 28, 56, 32, 31): the sixteen waves of a row tile take several slabs
+    # each, some one more than others
+    wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 95 + rows, rotate=False, bf16=True)
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 3), out_dtypes=())
 
 
 @pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])
@@ -396,7 +407,7 @@ def test_leading_dimensions_and_views():
 
 
 def test_leading_dimensions_in_the_many_vector_pass():
-    # rows of 256 groups with 24-bit indices go to the matrix-core pass for 5..16 vectors: activations
+    # rows of 256 groups with 24-bit indices go to the matrix-core pass for 3..16 vectors: activations
     # and results as views with larger leading dimensions, results beyond the rows untouched
     D, K, rows, cols, ld = 8, 16, 21, 2048, 2048 + 64
     wf, wb = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 51, bf16=True)

@@ -17,6 +17,7 @@
  *   - amplitude codes against Beta quantile edges               (Sec. 3.3 Step 5, Sec. 3.4)
  *   - dequantisation: point -> unit sphere -> times amplitude   (Sec. 2.4 eq. for S(D,K), Sec. 3.4)
  *   - the randomised Hadamard rotation along the rows           (Sec. 2.3, Sec. 3.3 Step 1)
+ *   - the group-by-group correction of the quantisation error   (Sec. 3.3 Step 6)
  *   - the reference product  out = W_hat x                       (float64 textbook matmul)
  *
  * Arithmetic.  Index arithmetic uses the fixed-width multi-word integers below (NW 32-bit
@@ -598,6 +599,102 @@ int pvqo_encode(const float *W, int64_t rows, int64_t cols, int D, int K, int sc
         for (int i = 0; i < nthreads; i++) pthread_join(th[i], NULL);
     free(th); free(jobs);
     tab_free(t);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* correcting the quantisation error, group after group   (Sec. 3.3 Step 6) */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Every row w of W (float32 [rows][cols], in place) goes through the groups g = 0 .. G-1 in
+ * order.  At group g (columns gD .. gD+D-1):
+ *   1. the group's current values are quantised as in Steps 3 and 4: point y on P(D,K),
+ *      amplitude s (norm, or amp_mode 1: least squares), and its quantised value
+ *          q_i = (s / sqrtf((float) sum y_i^2)) * (float) y_i            (float32, as written);
+ *   2. e = w_g - q (float32) is the error that the columns not yet quantised take up:
+ *          w_rest <- w_rest - e (A_gg)^-1 A_g,rest,
+ *      A the inverse of the Hessian restricted to the columns from g on.  (Reading: the section
+ *      prints the two sub-matrices with their indices mixed up; this is the update that
+ *      minimises the proxy loss of Sec. 2.1 over the remaining columns with the columns up to
+ *      g held at their quantised values, the block form of the update of the work it cites.)
+ *      With H^-1 = U^T U, U upper triangular (the Cholesky factor that the section points to),
+ *      A = U_{g:,g:}^T U_{g:,g:}, so (A_gg)^-1 A_g,rest = U_gg^-1 U_g,rest:
+ *          t U_gg = e          by substitution, j = 0 .. D-1:
+ *                              t_j = (e_j - t_0 U[gD+0][gD+j] - ... - t_{j-1} U[gD+j-1][gD+j]) / U[gD+j][gD+j]
+ *          w_c <- w_c - t_0 U[gD][c] - ... - t_{D-1} U[gD+D-1][c]     for every column c >= (g+1) D.
+ *      float32; each "- t_i U" is one fused multiply-add fmaf(-t_i, U, .), applied in the
+ *      order i = 0, 1, ... to the running value (a fixed order, so that two implementations
+ *      that decide roundings from these values can agree bit for bit).
+ * The columns of group g are not written again after step g: on return W holds, for every
+ * group, the values that were quantised, so that encoding W reproduces y and s.
+ * Reading: the amplitude in the error is the float32 amplitude of Step 4 also when amplitude
+ * codes (Step 5) are stored afterwards: their row normaliser needs the amplitudes of the whole
+ * row, which exist only after the last group.
+ * U: float32 [cols][cols], row-major; only its upper triangle is read.  Q_out (optional,
+ * float32 [rows][cols]) receives the quantised values q.
+ */
+typedef struct {
+    float *W; float *Q_out; const float *U;
+    int64_t cols, r0, r1;
+    int D, K, amp_mode;
+} corr_job_t;
+
+static void *correct_rows(void *arg)
+{
+    corr_job_t *J = arg;
+    int D = J->D;
+    int64_t C = J->cols, G = C / D;
+    int32_t *y = malloc(sizeof(int32_t) * D);
+    float *t = malloc(sizeof(float) * D);
+    for (int64_t r = J->r0; r < J->r1; r++) {
+        float *w = J->W + r * C;
+        for (int64_t g = 0; g < G; g++) {
+            float *wg = w + g * D;
+            const float *Ug = J->U + (g * D) * C;   /* row gD of U */
+            float ss, s;
+            pvqo_quantize_group(wg, D, J->K, y, &ss);
+            s = J->amp_mode == 1 ? pvqo_ls_amplitude(wg, y, D) : sqrtf(ss);
+            int32_t n2 = 0;
+            for (int i = 0; i < D; i++) n2 += y[i] * y[i];
+            float gain = s / sqrtf((float)n2);
+            for (int j = 0; j < D; j++) {
+                float q = gain * (float)y[j];
+                if (J->Q_out) J->Q_out[r * C + g * D + j] = q;
+                float acc = wg[j] - q;
+                for (int i = 0; i < j; i++) acc = fmaf(-t[i], Ug[i * C + g * D + j], acc);
+                t[j] = acc / Ug[j * C + g * D + j];
+            }
+            for (int64_t c = (g + 1) * D; c < C; c++) {
+                float acc = w[c];
+                for (int i = 0; i < D; i++) acc = fmaf(-t[i], Ug[i * C + c], acc);
+                w[c] = acc;
+            }
+        }
+    }
+    free(y); free(t);
+    return NULL;
+}
+
+int pvqo_correct(float *W, int64_t rows, int64_t cols, int D, int K, int amp_mode,
+                 const float *U, float *Q_out, int nthreads)
+{
+    if (D < 1 || K < 1 || K > 1023 || cols % D || !W || !U) return -1;
+    if (amp_mode != 0 && amp_mode != 1) return -1;
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > rows) nthreads = rows > 0 ? (int)rows : 1;
+    pthread_t *th = malloc(sizeof(pthread_t) * nthreads);
+    corr_job_t *jobs = malloc(sizeof(corr_job_t) * nthreads);
+    for (int i = 0; i < nthreads; i++) {
+        corr_job_t j = { W, Q_out, U, cols, rows * i / nthreads, rows * (i + 1) / nthreads,
+                         D, K, amp_mode };
+        jobs[i] = j;
+        if (nthreads == 1) correct_rows(&jobs[i]);
+        else pthread_create(&th[i], NULL, correct_rows, &jobs[i]);
+    }
+    if (nthreads > 1)
+        for (int i = 0; i < nthreads; i++) pthread_join(th[i], NULL);
+    free(th); free(jobs);
     return 0;
 }
 

@@ -53,6 +53,7 @@ def lib():
         L.pvqo_unrank_many.argtypes = [i32, i32, i64, vp, vp, i32]
         L.pvqo_encode.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         L.pvqo_hadamard_rows.argtypes = [vp, i64, i64, i64, vp, i32, vp]
+        L.pvqo_correct.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, i32]
         L.pvqo_ls_amplitude.argtypes = [vp, vp, i32]
         L.pvqo_ls_amplitude.restype = C.c_float
         L.pvqo_decode.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, i32,
@@ -254,6 +255,22 @@ def hadamard_rows(X, block: int, signs=None, signs_after: bool = False) -> np.nd
     if lib().pvqo_hadamard_rows(_p(X), rows, cols, int(block), _p(sg), 1 if signs_after else 0, _p(Y)) != 0:
         raise ValueError("pvqo_hadamard_rows rejected its arguments")
     return Y
+
+
+def correct(W, U, D: int, K: int, amplitude: str = "l2", nthreads: int = 1):
+    """Sec. 3.3 Step 6: the rows of W (float32) taken through the groups in order, every group's
+    quantisation error handed on to the columns behind it through U (float32 [cols][cols], upper
+    triangular, U^T U = inverse Hessian).  Returns (the values that were quantised, their quantised
+    values), both float32 [rows][cols]."""
+    Wc = np.array(W, dtype=np.float32, order="C", copy=True)
+    U32 = np.ascontiguousarray(U, dtype=np.float32)
+    rows, cols = Wc.shape
+    assert U32.shape == (cols, cols)
+    Q = np.zeros_like(Wc)
+    rc = lib().pvqo_correct(_p(Wc), rows, cols, D, K, {"l2": 0, "ls": 1}[amplitude], _p(U32), _p(Q), nthreads)
+    if rc != 0:
+        raise ValueError("pvqo_correct rejected its arguments")
+    return Wc, Q
 
 
 def unpack_fields(words, groups: int, bits: int):

@@ -107,6 +107,27 @@ def activation_matrix(tokens: int, hidden: int, seed: int, rotate: bool = True, 
     return x
 
 
+def calibration_hessian(cols: int, samples: int, seed: int, damp: float = 0.01):
+    """A layer-wise Hessian H = X^T X / samples of synthetic calibration activations (Sec. 2.1: the
+    expectation of x x^T over a calibration set, which is not available here), float64 [cols][cols], and
+    the factor that the error correction of Sec. 3.3 Step 6 takes as its input: U upper triangular with
+    U^T U = H^-1, rounded once to float32.  The activations are Gaussian with correlated neighbouring
+    channels (a first-order autoregression along the channel axis, coefficient 0.9) and a few channels of
+    ten times the scale, a rough picture of the feature statistics of a transformer layer; `damp` times the
+    mean diagonal is added to the diagonal, as is usual before factorising.  The factor comes from LAPACK
+    routines (inverse, then Cholesky), as a caller of the library would make it."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((samples, cols))
+    for c in range(1, cols):
+        X[:, c] = 0.9 * X[:, c - 1] + np.sqrt(1.0 - 0.81) * X[:, c]
+    loud = rng.choice(cols, size=max(1, cols // 64), replace=False)
+    X[:, loud] *= 10.0
+    H = X.T @ X / samples
+    H[np.diag_indices(cols)] += damp * np.mean(np.diag(H))
+    U = np.linalg.cholesky(np.linalg.inv(H)).T          # inv(H) = L L^T = U^T U with U = L^T
+    return H, np.ascontiguousarray(U, dtype=np.float32)
+
+
 def adversarial_groups(n_groups: int, D: int, seed: int) -> np.ndarray:
     """Groups built to sit on rounding ties and fix-up ties: small-integer and half-integer
     multiples of a power of two, repeated magnitudes, zeros, mixed signs, one-hot and all-zero

@@ -202,6 +202,33 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
                int8_t *pulses_out, void *stream);
 
 /*
+ * Correcting the quantisation error (Sec. 3.3 Step 6, with the proxy loss of Sec. 2.1): the rows of W are
+ * taken through their groups in order; every group is quantised as pvq_encode would quantise it (point
+ * and amplitude of the context's kind, Steps 3 and 4), and its error e = w_g - q_g is handed on to the
+ * columns behind it,
+ *     w_rest <- w_rest - e (A_gg)^-1 A_g,rest,   A = inverse of the Hessian restricted to the columns from g on,
+ * which minimises the loss over those columns.  The caller gives the upper triangular U with
+ * U^T U = H^-1 (from any LAPACK: inverse, then Cholesky), for which (A_gg)^-1 A_g,rest = U_gg^-1 U_g,rest.
+ * On return W holds, for every group, the values that were quantised at its step: pvq_encode of W gives
+ * the corrected code (amplitude codes, Step 5, are formed there, after the last group).
+ *
+ *   W      device, float32 [rows][ldw], 16-byte aligned, ldw >= cols, ldw a multiple of 4; overwritten.
+ *   U      device, float32 [cols][ldu], 16-byte aligned, ldu >= cols, ldu a multiple of 4; the upper
+ *          triangle is read (and the 64 x 64 blocks on the diagonal whole).  Not modified.
+ *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (64 floats per
+ *          row), owned by the caller, contents undefined afterwards.
+ *
+ * float32 throughout; q = (s / sqrt(sum y^2)) * y; the substitution and the updates are fused multiply-adds
+ * applied one at a time in the order of the rows of U, so the result does not depend on the launch shape.
+ * Contexts with D = 8, 16 or 32 and cols a multiple of 64, else PVQ_E_UNSUPPORTED.  A zero on the
+ * diagonal of U gives non-finite weights (then encoded as pvq_encode encodes them), never a fault.
+ * Launches 2 cols/64 kernels on `stream`; asynchronous.
+ */
+int pvq_correct_work_bytes(int64_t rows, size_t *bytes);
+int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                int64_t ldu, void *work, size_t work_bytes, void *stream);
+
+/*
  * Rotation and encoding of activations in one pass (Sec. 3.3 Step 1 in front of Sec. 2.5 / App. B.2): every
  * row of X is rotated as by pvq_hadamard(X, ..., block, signs, inverse = 0, float32 result) and the rotated
  * float32 values are encoded as by pvq_encode, without being written: index_out and scale_out receive

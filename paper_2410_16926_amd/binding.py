@@ -13,7 +13,7 @@ from . import build as _build
 PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
-    "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables", "pvq_rotate_encode",
+    "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables", "pvq_rotate_encode", "pvq_correct", "pvq_correct_work_bytes",
     "pvq_fast_tables_selftest", "pvq_size_table_device", "pvq_hadamard",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
@@ -61,6 +61,8 @@ def lib():
         L.pvq_packed_sizes.argtypes = [vp, i64, i64, vp, vp, vp]
         L.pvq_encode.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
         L.pvq_rotate_encode.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
+        L.pvq_correct_work_bytes.argtypes = [i64, vp]
+        L.pvq_correct.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, C.c_size_t, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
         L.pvq_decode_gemv.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp]
         _lib = L
@@ -259,6 +261,24 @@ def pvq_rotate_encode(ctx: PvqContext, X, block: int, signs=None, out: Packed = 
     _check(lib().pvq_rotate_encode(ctx.handle, _ptr(X), _dtype_code(X), rows, cols, ld, block, _ptr(signs),
                                    _ptr(out.index), _ptr(out.scale), _stream_ptr()), "pvq_rotate_encode")
     return out
+
+
+def pvq_correct(ctx: PvqContext, W, U, work=None):
+    """Error correction group after group, in place.  W: float32 [rows][cols] device tensor (overwritten
+    with the values to encode), U: float32 [cols][cols] upper triangular device tensor, U^T U = inverse
+    Hessian; work: optional uint8 device tensor of pvq_correct_work_bytes(rows) bytes.  Returns W."""
+    import torch
+    rows, cols = W.shape
+    assert W.dtype == torch.float32 and U.dtype == torch.float32 and tuple(U.shape) == (cols, cols)
+    if work is None:
+        nbytes = C.c_size_t(0)
+        _check(lib().pvq_correct_work_bytes(rows, C.byref(nbytes)), "pvq_correct_work_bytes")
+        work = torch.empty((max(int(nbytes.value), 16),), dtype=torch.uint8, device=W.device)
+    ldw = W.stride(0) if rows > 1 else max(cols, 1)
+    ldu = U.stride(0) if cols > 1 else 1
+    _check(lib().pvq_correct(ctx.handle, _ptr(W), rows, cols, ldw, _ptr(U), ldu, _ptr(work), work.numel(),
+                             _stream_ptr()), "pvq_correct")
+    return W
 
 
 def pvq_decode(ctx: PvqContext, packed: Packed, out_dtype=None, out=None):

@@ -1,0 +1,178 @@
+// Correcting the quantisation error group after group (Sec. 3.3 Step 6), rows of W in place.
+//
+// For every row, groups g = 0 .. G-1 in order: the group's current values w_g are quantised as in Steps 3
+// and 4 (point y, amplitude s), q = (s / sqrt(sum y^2)) y, e = w_g - q, and the columns behind the group
+// take up the error:  t U_gg = e by substitution, then w_c <- w_c - t_0 U[gD][c] - ... - t_{D-1} U[gD+D-1][c],
+// with U the upper triangular factor of the inverse Hessian (U^T U = H^-1).  float32; every "- t_i U" is
+// one fused multiply-add applied in the order i = 0, 1, ... to the running value, group after group: the
+// order is part of the definition, because later roundings are decided from these values.  On return W
+// holds, for every group, the values that were quantised: encoding it gives the corrected code.
+//
+// Rows are independent, groups of a row strictly sequential, and U is the same for every row.  Columns are
+// taken in blocks of 64:
+//   correct_block_kernel   one lane per row holds the block's 64 values in registers, goes through the
+//                          block's groups (quantise, substitution, update of the later columns of the
+//                          block) and leaves the block's t values (rows x 64) in a work buffer.  U is
+//                          the same in every lane: its entries are read through the scalar unit and
+//                          enter the multiply-adds as scalar operands.
+//   correct_trailing_kernel  applies the block's 64 multiply-adds per element, in the same order, to all
+//                          columns behind the block: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS.
+//                          Bound: float32 vector ALU (64 multiply-adds per 8 bytes moved) and HBM alike.
+// Not on the matrix cores: their accumulation order inside an instruction is not the one defined above.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "pvq_internal.h"
+#include "pvq_quantize_dev.h"
+
+namespace {
+
+using namespace pvq_quantize_dev;
+
+constexpr int kBlockCols = 64;    // columns per block
+constexpr int kTile = 128;        // rows and columns of a tile of the trailing update
+constexpr int kTrailThreads = 256;
+
+struct correct_args {
+    float *W; int64_t ldw, rows, cols;
+    const float *U; int64_t ldu;
+    float *T;            // [rows][64]
+    int K, ls;
+};
+
+template <int D>
+__global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64_t c0)
+{
+    const int64_t r = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (r >= a.rows) return;
+    float *wrow = a.W + r * a.ldw + c0;
+    const float *__restrict__ U = a.U + c0 * a.ldu + c0;   // U[i][c] below: row c0 + i, column c0 + c
+    float w[kBlockCols], t[kBlockCols];
+#pragma unroll
+    for (int c = 0; c < kBlockCols; c += 4) {
+        const float4 v = *reinterpret_cast<const float4 *>(wrow + c);
+        w[c] = v.x; w[c + 1] = v.y; w[c + 2] = v.z; w[c + 3] = v.w;
+    }
+#pragma unroll
+    for (int g = 0; g < kBlockCols / D; g++) {
+        float wg[D];
+        int y[D];
+#pragma unroll
+        for (int i = 0; i < D; i++) wg[i] = w[g * D + i];
+        const float ss = quantize_group<D>(wg, a.K, y);
+        const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
+        int n2 = 0;
+#pragma unroll
+        for (int i = 0; i < D; i++) n2 += y[i] * y[i];
+        const float gain = s / sqrtf((float)n2);
+#pragma unroll
+        for (int j = 0; j < D; j++) {
+            float acc = wg[j] - gain * (float)y[j];
+#pragma unroll
+            for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[g * D + i], U[(int64_t)(g * D + i) * a.ldu + g * D + j], acc);
+            t[g * D + j] = acc / U[(int64_t)(g * D + j) * a.ldu + g * D + j];
+        }
+#pragma unroll
+        for (int c = (g + 1) * D; c < kBlockCols; c++) {
+            float acc = w[c];
+#pragma unroll
+            for (int i = 0; i < D; i++) acc = __builtin_fmaf(-t[g * D + i], U[(int64_t)(g * D + i) * a.ldu + c], acc);
+            w[c] = acc;
+        }
+    }
+    float *trow = a.T + r * kBlockCols;
+#pragma unroll
+    for (int c = 0; c < kBlockCols; c += 4) {
+        *reinterpret_cast<float4 *>(wrow + c) = make_float4(w[c], w[c + 1], w[c + 2], w[c + 3]);
+        *reinterpret_cast<float4 *>(trow + c) = make_float4(t[c], t[c + 1], t[c + 2], t[c + 3]);
+    }
+}
+
+// Columns [c1, cols): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][63] U[c0+63][c], one multiply-add
+// after the other.  blockIdx.x = column tile, blockIdx.y = row tile.
+__global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int64_t c1)
+{
+    __shared__ __align__(16) float Ts[kBlockCols][kTile + 4];   // [k][row of the tile]
+    __shared__ __align__(16) float Us[kBlockCols][kTile];       // [k][column of the tile]
+    const int64_t row0 = (int64_t)blockIdx.y * kTile, col0 = c1 + (int64_t)blockIdx.x * kTile;
+    const int tid = threadIdx.x;
+
+    // t tile: 128 rows x 64 values, a float4 per lane and pass, stored transposed
+    for (int e = tid; e < kTile * (kBlockCols / 4); e += kTrailThreads) {
+        const int rr = e / (kBlockCols / 4), k4 = (e % (kBlockCols / 4)) * 4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kBlockCols + k4);
+        Ts[k4][rr] = v.x; Ts[k4 + 1][rr] = v.y; Ts[k4 + 2][rr] = v.z; Ts[k4 + 3][rr] = v.w;
+    }
+    // U tile: 64 rows x 128 columns (columns in whole fours: cols is a multiple of 64)
+    for (int e = tid; e < kBlockCols * (kTile / 4); e += kTrailThreads) {
+        const int k = e / (kTile / 4), cc = (e % (kTile / 4)) * 4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (col0 + cc < a.cols) v = *reinterpret_cast<const float4 *>(a.U + (c0 + k) * a.ldu + col0 + cc);
+        *reinterpret_cast<float4 *>(&Us[k][cc]) = v;
+    }
+    __syncthreads();
+
+    const int ty = tid >> 4, tx = tid & 15;       // rows 8 ty .. 8 ty + 7, columns 8 tx .. 8 tx + 7 of the tile
+    const bool cols_in = col0 + 8 * tx < a.cols;  // eight columns are in or out together
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int64_t r = row0 + 8 * ty + i;
+        float4 v0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), v1 = v0;
+        if (r < a.rows && cols_in) {
+            const float *p = a.W + r * a.ldw + col0 + 8 * tx;
+            v0 = *reinterpret_cast<const float4 *>(p); v1 = *reinterpret_cast<const float4 *>(p + 4);
+        }
+        acc[i][0] = v0.x; acc[i][1] = v0.y; acc[i][2] = v0.z; acc[i][3] = v0.w;
+        acc[i][4] = v1.x; acc[i][5] = v1.y; acc[i][6] = v1.z; acc[i][7] = v1.w;
+    }
+#pragma unroll 4
+    for (int k = 0; k < kBlockCols; k++) {
+        const float4 a0 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty]), a1 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty + 4]);
+        const float4 b0 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx]), b1 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx + 4]);
+        const float tv[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const float uv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[i][j] = __builtin_fmaf(-tv[i], uv[j], acc[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int64_t r = row0 + 8 * ty + i;
+        if (r < a.rows && cols_in) {
+            float *p = a.W + r * a.ldw + col0 + 8 * tx;
+            *reinterpret_cast<float4 *>(p) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+            *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+        }
+    }
+}
+
+}  // namespace
+
+// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 64 floats
+hipError_t pvq_launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                              int64_t ldu, float *work, hipStream_t s)
+{
+    correct_args a;
+    a.W = W; a.ldw = ldw; a.rows = rows; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work;
+    a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
+    const dim3 bgrid((unsigned)((rows + 63) / 64)), bblock(64);
+    for (int64_t c0 = 0; c0 < cols; c0 += kBlockCols) {
+        switch (c->D) {
+        case 8: hipLaunchKernelGGL((correct_block_kernel<8>), bgrid, bblock, 0, s, a, c0); break;
+        case 16: hipLaunchKernelGGL((correct_block_kernel<16>), bgrid, bblock, 0, s, a, c0); break;
+        default: hipLaunchKernelGGL((correct_block_kernel<32>), bgrid, bblock, 0, s, a, c0); break;
+        }
+        const int64_t c1 = c0 + kBlockCols;
+        if (c1 < cols) {
+            const dim3 tgrid((unsigned)((cols - c1 + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
+            hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, s, a, c0, c1);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}

@@ -1,0 +1,92 @@
+// Device code shared by the kernels that quantise a group onto the pyramid (Sec. 2.5): the generic
+// encoder and the error correction of Sec. 3.3 Step 6.  float32, fixed evaluation order: the results
+// are part of the format.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace pvq_quantize_dev {
+
+// Sum over adjacent pairs, level by level: ((v0+v1)+(v2+v3))+...  (fixed order, float32).
+template <int D>
+__device__ inline float tree_sum(float (&v)[D])
+{
+#pragma unroll
+    for (int s = 1; s < D; s *= 2)
+#pragma unroll
+        for (int i = 0; i < D; i += 2 * s) v[i] = v[i] + v[i + s];
+    return v[0];
+}
+
+// Sec. 2.5: project onto the l1 ball of radius K, round to nearest even, then move single pulses
+// on the coordinates of largest deviation (lowest coordinate on ties) until the count is K.
+// Returns the sum of squares; y gets the signed point.
+template <int D>
+__device__ inline float quantize_group(const float (&w)[D], int K, int (&y)[D])
+{
+    float a[D], t[D], tmp[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) { a[i] = fabsf(w[i]); tmp[i] = a[i]; }
+    const float l1 = tree_sum<D>(tmp);
+#pragma unroll
+    for (int i = 0; i < D; i++) tmp[i] = w[i] * w[i];
+    const float ss = tree_sum<D>(tmp);
+
+    const float g = (float)K / l1;
+    if (!(l1 > 0.0f) || !(fabsf(g) < INFINITY)) {
+#pragma unroll
+        for (int i = 0; i < D; i++) y[i] = 0;
+        y[D - 1] = K;
+        return ss;
+    }
+    int S = 0;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        t[i] = a[i] * g;
+        // a non-finite weight must not turn into an out-of-range pulse count
+        float r = fminf(rintf(t[i]), (float)K);
+        y[i] = r >= 0.0f ? (int)r : 0;
+        S += y[i];
+    }
+    // At most D adjustments ever make sense (each coordinate moves at most once for finite
+    // input); the bound also ends the loops for non-finite input.
+    for (int it = 0; it < D && S > K; it++) {
+        int best = -1;
+        float dev = 0.0f;
+#pragma unroll
+        for (int i = 0; i < D; i++) {
+            const float e = (float)y[i] - t[i];
+            const bool take = y[i] > 0 && (best < 0 || e > dev);
+            best = take ? i : best;
+            dev = take ? e : dev;
+        }
+#pragma unroll
+        for (int i = 0; i < D; i++) y[i] -= (i == best);
+        S -= best >= 0;
+    }
+    for (int it = 0; it < D && S < K; it++) {
+        int best = -1;
+        float dev = 0.0f;
+#pragma unroll
+        for (int i = 0; i < D; i++) {
+            const float e = t[i] - (float)y[i];
+            const bool take = best < 0 || e > dev;
+            best = take ? i : best;
+            dev = take ? e : dev;
+        }
+#pragma unroll
+        for (int i = 0; i < D; i++) y[i] += (i == best);
+        S += 1;
+    }
+    if (S != K) {  // only reachable with non-finite input: fall back to a valid point
+#pragma unroll
+        for (int i = 0; i < D; i++) y[i] = 0;
+        y[D - 1] = K;
+        return ss;
+    }
+#pragma unroll
+    for (int i = 0; i < D; i++) y[i] = w[i] < 0.0f ? -y[i] : y[i];
+    return ss;
+}
+
+}  // namespace pvq_quantize_dev

@@ -1,0 +1,89 @@
+"""GPU parity of the error correction (Sec. 3.3 Step 6): the corrected weight matrix must equal the
+oracle's bit for bit (every later rounding is decided from these values), and so must its code."""
+import numpy as np
+import pytest
+
+import paper_2410_16926_amd as pvq
+import synth_inputs as si
+from oracle import pvq_oracle as oracle
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def run_correct(D, K, rows, cols, seed, amplitude="l2", scale_bits=0, ld_extra=0):
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=seed, rotate=False, bf16=False), dtype=np.float32)
+    _, U = si.calibration_hessian(cols, 2 * cols, seed + 1)
+    ctx, oe, oc = gu.make_ctx(D, K, scale_bits, cols // D)
+    if amplitude == "ls":
+        ctx.set_amplitude("ls")
+    Wd = torch.zeros((rows, cols + ld_extra), dtype=torch.float32, device="cuda")
+    Wd[:, :cols] = gu.to_dev_f32(W0)
+    Ud = torch.zeros((cols, cols + ld_extra), dtype=torch.float32, device="cuda")
+    Ud[:, :cols] = gu.to_dev_f32(U)
+    Wv, Uv = Wd[:, :cols], Ud[:, :cols]
+    pvq.pvq_correct(ctx, Wv, Uv)
+    torch.cuda.synchronize()
+    got = Wv.cpu().numpy()
+    ref, _ = oracle.correct(W0, U, D, K, amplitude=amplitude, nthreads=8)
+    bad = np.argwhere(got.view(np.uint32) != ref.view(np.uint32))
+    assert bad.size == 0, f"{bad.shape[0]} corrected weights differ, first at {bad[0]}: {got[tuple(bad[0])]} vs {ref[tuple(bad[0])]}"
+    if ld_extra:
+        assert torch.all(Wd[:, cols:] == 0)
+    # and the code of the corrected matrix is the oracle's code of its corrected matrix
+    packed = pvq.pvq_encode(ctx, Wv.contiguous(), want_pulses=True)
+    enc = oracle.encode(ref, D, K, scale_bits, oe, nthreads=8, amplitude=amplitude)
+    gu.assert_encode_equal(packed, enc)
+    ctx.close()
+    return W0, ref
+
+
+@pytest.mark.parametrize("D,K,rows,cols,amplitude", [
+    (8, 16, 200, 256, "l2"), (8, 16, 70, 512, "ls"), (8, 16, 1, 64, "l2"), (8, 16, 129, 192, "l2"),
+    (16, 33, 130, 256, "l2"), (16, 33, 65, 128, "ls"), (32, 60, 64, 128, "l2"), (32, 60, 131, 320, "ls"),
+    (8, 5, 300, 128, "l2")])
+def test_corrected_weights_equal_the_oracles(D, K, rows, cols, amplitude):
+    run_correct(D, K, rows, cols, seed=si.BASE_SEED + 500 + rows + cols, amplitude=amplitude)
+
+
+def test_corrected_weights_with_amplitude_codes_and_leading_dimensions():
+    # amplitude codes (Sec. 3.3 Step 5) are formed when the corrected matrix is encoded; W and U as views
+    run_correct(8, 16, 96, 1024, seed=si.BASE_SEED + 541, scale_bits=2, ld_extra=12)
+
+
+def test_a_wider_matrix():
+    # 24 blocks of 64 columns, row tiles with a ragged end: the order of the updates across blocks
+    run_correct(8, 16, 700, 1536, seed=si.BASE_SEED + 542)
+
+
+def test_uncorrelated_inputs_leave_the_weights_alone():
+    D, K, rows, cols = 8, 16, 50, 256
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=77, rotate=False, bf16=False), dtype=np.float32)
+    ctx = pvq.pvq_ctx_create(D, K)
+    Wd = gu.to_dev_f32(W0)
+    Ud = torch.diag(torch.linspace(0.5, 2.0, cols, device="cuda"))
+    pvq.pvq_correct(ctx, Wd, Ud)
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint32), W0.view(np.uint32))
+    ctx.close()
+
+
+def test_argument_errors():
+    ctx = pvq.pvq_ctx_create(8, 16)
+    W = torch.zeros((4, 96), dtype=torch.float32, device="cuda")
+    U = torch.eye(96, device="cuda")
+    with pytest.raises(pvq.PvqError) as e:          # columns not in whole blocks of 64
+        pvq.pvq_correct(ctx, W, U)
+    assert e.value.status == -2
+    W = torch.zeros((4, 128), dtype=torch.float32, device="cuda")
+    U = torch.eye(128, device="cuda")
+    with pytest.raises(pvq.PvqError) as e:          # work buffer too small
+        pvq.pvq_correct(ctx, W, U, work=torch.empty((512,), dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -1
+    pvq.pvq_correct(ctx, W[:0], U)                  # no rows: nothing to do
+    ctx.close()
+    wide = pvq.pvq_ctx_create(128, 187)
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_correct(wide, W, U)
+    assert e.value.status == -2
+    wide.close()

@@ -11,8 +11,8 @@
 // Rows are independent, groups of a row strictly sequential, and U is the same for every row.  Columns are
 // taken in blocks of 64:
 //   correct_block_kernel   one lane per row holds the block's 64 values in registers, goes through the
-//                          block's groups (quantise, substitution, update of the later columns of the
-//                          block) and leaves the block's t values (rows x 64) in a work buffer.  U is
+//                          block's groups (pending updates from the block's earlier groups, quantise,
+//                          substitution) and leaves the block's t values (rows x 64) in a work buffer.  U is
 //                          the same in every lane: its entries are read through the scalar unit and
 //                          enter the multiply-adds as scalar operands.
 //   correct_trailing_kernel  applies the block's 64 multiply-adds per element, in the same order, to all
@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <utility>
 
 #include "pvq_internal.h"
 #include "pvq_quantize_dev.h"
@@ -41,46 +42,68 @@ struct correct_args {
     int K, ls;
 };
 
+// Group G of the block (a template parameter, so that every register index below is a constant).  First the
+// group's columns take the updates of the block's earlier groups, which are still pending (rows 0 .. G D - 1
+// of the block's part of U, in that order: per element the same multiply-adds in the same order as if every
+// group had updated all later columns at once, with the entries of U read right where they are used);
+// then quantise and substitution.  U points at the block's first diagonal entry; its entries are the same in
+// every lane and are read through the scalar unit.  The fences keep the compiler from fetching many rows
+// ahead, which the scalar registers do not hold.
+template <int D, int G>
+__device__ inline void block_step(float (&w)[kBlockCols], float (&t)[kBlockCols], const float *__restrict__ U, int64_t ldu,
+                                  int K, int ls)
+{
+    float wg[D];
+    int y[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) wg[i] = w[G * D + i];
+#pragma unroll
+    for (int k = 0; k < G * D; k++) {
+        if (k % (D >= 16 ? 2 : 4) == 0) __builtin_amdgcn_sched_barrier(0);
+        const float *__restrict__ Uk = U + (int64_t)k * ldu + G * D;
+#pragma unroll
+        for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-t[k], Uk[j], wg[j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < D; i++) w[G * D + i] = wg[i];   // what is quantised, and stays in W
+    const float ss = quantize_group<D>(wg, K, y);
+    const float s = ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
+    int n2 = 0;
+#pragma unroll
+    for (int i = 0; i < D; i++) n2 += y[i] * y[i];
+    const float gain = s / sqrtf((float)n2);
+    const float *__restrict__ Ug = U + (int64_t)(G * D) * ldu + G * D;   // the group's D x D part
+#pragma unroll
+    for (int j = 0; j < D; j++) {
+        float acc = wg[j] - gain * (float)y[j];
+#pragma unroll
+        for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[G * D + i], Ug[(int64_t)i * ldu + j], acc);
+        t[G * D + j] = acc / Ug[(int64_t)j * ldu + j];
+    }
+}
+
+template <int D, int... Gs>
+__device__ inline void block_steps(float (&w)[kBlockCols], float (&t)[kBlockCols], const float *__restrict__ U, int64_t ldu,
+                                   int K, int ls, std::integer_sequence<int, Gs...>)
+{
+    (block_step<D, Gs>(w, t, U, ldu, K, ls), ...);
+}
+
 template <int D>
 __global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64_t c0)
 {
     const int64_t r = (int64_t)blockIdx.x * 64 + threadIdx.x;
     if (r >= a.rows) return;
     float *wrow = a.W + r * a.ldw + c0;
-    const float *__restrict__ U = a.U + c0 * a.ldu + c0;   // U[i][c] below: row c0 + i, column c0 + c
+    const float *__restrict__ U = a.U + c0 * a.ldu + c0;   // row c0 + i, column c0 + c of the factor
     float w[kBlockCols], t[kBlockCols];
 #pragma unroll
     for (int c = 0; c < kBlockCols; c += 4) {
         const float4 v = *reinterpret_cast<const float4 *>(wrow + c);
         w[c] = v.x; w[c + 1] = v.y; w[c + 2] = v.z; w[c + 3] = v.w;
     }
-#pragma unroll
-    for (int g = 0; g < kBlockCols / D; g++) {
-        float wg[D];
-        int y[D];
-#pragma unroll
-        for (int i = 0; i < D; i++) wg[i] = w[g * D + i];
-        const float ss = quantize_group<D>(wg, a.K, y);
-        const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
-        int n2 = 0;
-#pragma unroll
-        for (int i = 0; i < D; i++) n2 += y[i] * y[i];
-        const float gain = s / sqrtf((float)n2);
-#pragma unroll
-        for (int j = 0; j < D; j++) {
-            float acc = wg[j] - gain * (float)y[j];
-#pragma unroll
-            for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[g * D + i], U[(int64_t)(g * D + i) * a.ldu + g * D + j], acc);
-            t[g * D + j] = acc / U[(int64_t)(g * D + j) * a.ldu + g * D + j];
-        }
-#pragma unroll
-        for (int c = (g + 1) * D; c < kBlockCols; c++) {
-            float acc = w[c];
-#pragma unroll
-            for (int i = 0; i < D; i++) acc = __builtin_fmaf(-t[g * D + i], U[(int64_t)(g * D + i) * a.ldu + c], acc);
-            w[c] = acc;
-        }
-    }
+    block_steps<D>(w, t, U, a.ldu, a.K, a.ls, std::make_integer_sequence<int, kBlockCols / D>{});
     float *trow = a.T + r * kBlockCols;
 #pragma unroll
     for (int c = 0; c < kBlockCols; c += 4) {
@@ -150,29 +173,67 @@ __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct
     }
 }
 
+hipError_t make_side_streams(pvq_ctx *c)
+{
+    if (c->side_ready) return hipSuccess;
+    hipError_t e = hipEventCreateWithFlags(&c->side_fork, hipEventDisableTiming);
+    for (int i = 0; i < pvq_ctx::kSideStreams && e == hipSuccess; i++) {
+        e = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->side_join[i], hipEventDisableTiming);
+    }
+    c->side_ready = true;   // whatever was made is released with the context
+    return e;
+}
+
 }  // namespace
 
-// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 64 floats
-hipError_t pvq_launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 64 floats.
+// Rows are independent, and within a chunk of rows the launches form a chain in which every second one (the
+// block kernel) is a single wave per 64 rows bound by its own latency: up to four chunks of rows run side by
+// side, the first on the caller's stream and the others on streams of the context that fork from and
+// join the caller's stream through events, so that one chunk's block kernel runs beside another
+// chunk's trailing update.
+hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
                               int64_t ldu, float *work, hipStream_t s)
 {
-    correct_args a;
-    a.W = W; a.ldw = ldw; a.rows = rows; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work;
-    a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
-    const dim3 bgrid((unsigned)((rows + 63) / 64)), bblock(64);
-    for (int64_t c0 = 0; c0 < cols; c0 += kBlockCols) {
-        switch (c->D) {
-        case 8: hipLaunchKernelGGL((correct_block_kernel<8>), bgrid, bblock, 0, s, a, c0); break;
-        case 16: hipLaunchKernelGGL((correct_block_kernel<16>), bgrid, bblock, 0, s, a, c0); break;
-        default: hipLaunchKernelGGL((correct_block_kernel<32>), bgrid, bblock, 0, s, a, c0); break;
-        }
-        const int64_t c1 = c0 + kBlockCols;
-        if (c1 < cols) {
-            const dim3 tgrid((unsigned)((cols - c1 + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
-            hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, s, a, c0, c1);
-        }
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    pvq_ctx *c = const_cast<pvq_ctx *>(cc);
+    const int64_t nch = std::max<int64_t>(1, std::min<int64_t>(1 + pvq_ctx::kSideStreams, rows / 512));
+    const int64_t chunk_rows = ((rows + nch - 1) / nch + kTile - 1) / kTile * kTile;
+    std::lock_guard<std::mutex> hold(c->side_lock);   // the events below belong to one call at a time
+    hipError_t e = hipSuccess;
+    if (nch > 1) {
+        if ((e = make_side_streams(c)) != hipSuccess) return e;
+        if ((e = hipEventRecord(c->side_fork, s)) != hipSuccess) return e;
+        for (int i = 0; i + 1 < nch; i++)
+            if ((e = hipStreamWaitEvent(c->side[i], c->side_fork, 0)) != hipSuccess) return e;
     }
-    return hipSuccess;
+    for (int64_t c0 = 0; c0 < cols && e == hipSuccess; c0 += kBlockCols) {
+        for (int64_t ch = 0; ch < nch; ch++) {
+            const int64_t r0 = ch * chunk_rows, nr = std::min(chunk_rows, rows - r0);
+            if (nr <= 0) continue;
+            hipStream_t st = ch == 0 ? s : c->side[ch - 1];
+            correct_args a;
+            a.W = W + r0 * ldw; a.ldw = ldw; a.rows = nr; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work + r0 * kBlockCols;
+            a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
+            const dim3 bgrid((unsigned)((nr + 63) / 64)), bblock(64);
+            switch (c->D) {
+            case 8: hipLaunchKernelGGL((correct_block_kernel<8>), bgrid, bblock, 0, st, a, c0); break;
+            case 16: hipLaunchKernelGGL((correct_block_kernel<16>), bgrid, bblock, 0, st, a, c0); break;
+            default: hipLaunchKernelGGL((correct_block_kernel<32>), bgrid, bblock, 0, st, a, c0); break;
+            }
+            const int64_t c1 = c0 + kBlockCols;
+            if (c1 < cols) {
+                const dim3 tgrid((unsigned)((cols - c1 + kTile - 1) / kTile), (unsigned)((nr + kTile - 1) / kTile));
+                hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, c1);
+            }
+        }
+        e = hipGetLastError();
+    }
+    // join also after a failed launch, so that the caller's stream never runs ahead of the side streams
+    for (int i = 0; i + 1 < nch; i++) {
+        hipError_t j = hipEventRecord(c->side_join[i], c->side[i]);
+        if (j == hipSuccess) j = hipStreamWaitEvent(s, c->side_join[i], 0);
+        if (e == hipSuccess) e = j;
+    }
+    return e;
 }

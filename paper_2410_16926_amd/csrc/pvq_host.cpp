@@ -365,6 +365,13 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
         hipError_t e = hipFree(p);
         if (first == hipSuccess) first = e;
     }
+    if (c->side_ready) {
+        for (int i = 0; i < pvq_ctx::kSideStreams; i++) {
+            if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+            if (c->side_join[i]) (void)hipEventDestroy(c->side_join[i]);
+        }
+        if (c->side_fork) (void)hipEventDestroy(c->side_fork);
+    }
     delete c;
     return first == hipSuccess ? PVQ_OK : hip_fail(first);
 }

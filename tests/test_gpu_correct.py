@@ -57,6 +57,23 @@ def test_a_wider_matrix():
     run_correct(8, 16, 700, 1536, seed=si.BASE_SEED + 542)
 
 
+@pytest.mark.parametrize("rows", [1100, 2100])
+def test_row_chunks_side_by_side(rows):
+    # from 1024 rows on the rows go in two to four chunks on streams of the context that fork from and
+    # join the caller's stream; the last chunk is shorter; the call is repeated on the same context
+    W0, ref = run_correct(8, 16, rows, 192, seed=si.BASE_SEED + 543 + rows)
+    ctx = pvq.pvq_ctx_create(8, 16)
+    _, U = si.calibration_hessian(192, 2 * 192, si.BASE_SEED + 543 + rows + 1)
+    Ud = gu.to_dev_f32(U)
+    for _ in range(2):
+        Wd = gu.to_dev_f32(W0)
+        pvq.pvq_correct(ctx, Wd, Ud)
+        # work queued behind the call on the caller's stream sees the finished matrix
+        got = (Wd + 0.0).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    ctx.close()
+
+
 def test_uncorrelated_inputs_leave_the_weights_alone():
     D, K, rows, cols = 8, 16, 50, 256
     W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=77, rotate=False, bf16=False), dtype=np.float32)

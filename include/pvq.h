@@ -215,14 +215,16 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
  *   W      device, float32 [rows][ldw], 16-byte aligned, ldw >= cols, ldw a multiple of 4; overwritten.
  *   U      device, float32 [cols][ldu], 16-byte aligned, ldu >= cols, ldu a multiple of 4; the upper
  *          triangle is read (and the 64 x 64 blocks on the diagonal whole).  Not modified.
- *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (64 floats per
+ *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (128 floats per
  *          row), owned by the caller, contents undefined afterwards.
  *
  * float32 throughout; q = (s / sqrt(sum y^2)) * y; the substitution and the updates are fused multiply-adds
  * applied one at a time in the order of the rows of U, so the result does not depend on the launch shape.
  * Contexts with D = 8, 16 or 32 and cols a multiple of 64, else PVQ_E_UNSUPPORTED.  A zero on the
  * diagonal of U gives non-finite weights (then encoded as pvq_encode encodes them), never a fault.
- * Launches 2 cols/64 kernels on `stream`; asynchronous.
+ * Launches about 2 cols/64 kernels; asynchronous.  From 1024 rows on, chunks of rows run side by side on
+ * streams that the context owns (default priority); they fork from `stream` and join it again through events,
+ * so work queued on `stream` after the call sees the finished matrix.
  */
 int pvq_correct_work_bytes(int64_t rows, size_t *bytes);
 int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,

@@ -15,9 +15,13 @@
 //                          substitution) and leaves the block's t values (rows x 64) in a work buffer.  U is
 //                          the same in every lane: its entries are read through the scalar unit and
 //                          enter the multiply-adds as scalar operands.
-//   correct_trailing_kernel  applies the block's 64 multiply-adds per element, in the same order, to all
-//                          columns behind the block: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS.
-//                          Bound: float32 vector ALU (64 multiply-adds per 8 bytes moved) and HBM alike.
+//   correct_trailing_kernel  applies a block's 64 multiply-adds per element, in the same order, to columns
+//                          behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS.  Two blocks
+//                          make a panel: the first block's update goes to the second block's columns
+//                          only, and after the second block one launch applies both blocks' 128
+//                          multiply-adds to everything behind the panel, reading and writing W once
+//                          (with 64 per pass the kernel was bound by HBM as much as by the vector ALU).
+//                          Bound: float32 vector ALU.
 // Not on the matrix cores: their accumulation order inside an instruction is not the one defined above.
 #include <hip/hip_runtime.h>
 
@@ -32,13 +36,14 @@ namespace {
 using namespace pvq_quantize_dev;
 
 constexpr int kBlockCols = 64;    // columns per block
+constexpr int kPanelCols = 128;   // columns per panel: two blocks, whose updates of the columns behind the panel go together
 constexpr int kTile = 128;        // rows and columns of a tile of the trailing update
 constexpr int kTrailThreads = 256;
 
 struct correct_args {
     float *W; int64_t ldw, rows, cols;
     const float *U; int64_t ldu;
-    float *T;            // [rows][64]
+    float *T;            // [rows][128]: the t values of the two blocks of a panel
     int K, ls;
 };
 
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64
         w[c] = v.x; w[c + 1] = v.y; w[c + 2] = v.z; w[c + 3] = v.w;
     }
     block_steps<D>(w, t, U, a.ldu, a.K, a.ls, std::make_integer_sequence<int, kBlockCols / D>{});
-    float *trow = a.T + r * kBlockCols;
+    float *trow = a.T + r * kPanelCols + (c0 % kPanelCols);
 #pragma unroll
     for (int c = 0; c < kBlockCols; c += 4) {
         *reinterpret_cast<float4 *>(wrow + c) = make_float4(w[c], w[c + 1], w[c + 2], w[c + 3]);
@@ -112,33 +117,19 @@ __global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64
     }
 }
 
-// Columns [c1, cols): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][63] U[c0+63][c], one multiply-add
-// after the other.  blockIdx.x = column tile, blockIdx.y = row tile.
-__global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int64_t c1)
+// Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][64 stages - 1] U[c0 + 64 stages - 1][c],
+// one multiply-add after the other; t[r][k] = T[r][t0 + k].  stages = 1: one block's update (of the second
+// block of its panel), 2: a panel's update of everything behind it, with the tile of W read and written once
+// for 128 multiply-adds per element.  blockIdx.x = column tile, blockIdx.y = row tile.
+__global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int t0, int stages,
+                                                                          int64_t c1, int64_t cend)
 {
     __shared__ __align__(16) float Ts[kBlockCols][kTile + 4];   // [k][row of the tile]
     __shared__ __align__(16) float Us[kBlockCols][kTile];       // [k][column of the tile]
     const int64_t row0 = (int64_t)blockIdx.y * kTile, col0 = c1 + (int64_t)blockIdx.x * kTile;
     const int tid = threadIdx.x;
-
-    // t tile: 128 rows x 64 values, a float4 per lane and pass, stored transposed
-    for (int e = tid; e < kTile * (kBlockCols / 4); e += kTrailThreads) {
-        const int rr = e / (kBlockCols / 4), k4 = (e % (kBlockCols / 4)) * 4;
-        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kBlockCols + k4);
-        Ts[k4][rr] = v.x; Ts[k4 + 1][rr] = v.y; Ts[k4 + 2][rr] = v.z; Ts[k4 + 3][rr] = v.w;
-    }
-    // U tile: 64 rows x 128 columns (columns in whole fours: cols is a multiple of 64)
-    for (int e = tid; e < kBlockCols * (kTile / 4); e += kTrailThreads) {
-        const int k = e / (kTile / 4), cc = (e % (kTile / 4)) * 4;
-        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (col0 + cc < a.cols) v = *reinterpret_cast<const float4 *>(a.U + (c0 + k) * a.ldu + col0 + cc);
-        *reinterpret_cast<float4 *>(&Us[k][cc]) = v;
-    }
-    __syncthreads();
-
     const int ty = tid >> 4, tx = tid & 15;       // rows 8 ty .. 8 ty + 7, columns 8 tx .. 8 tx + 7 of the tile
-    const bool cols_in = col0 + 8 * tx < a.cols;  // eight columns are in or out together
+    const bool cols_in = col0 + 8 * tx < cend;    // eight columns are in or out together
     float acc[8][8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -151,16 +142,34 @@ __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct
         acc[i][0] = v0.x; acc[i][1] = v0.y; acc[i][2] = v0.z; acc[i][3] = v0.w;
         acc[i][4] = v1.x; acc[i][5] = v1.y; acc[i][6] = v1.z; acc[i][7] = v1.w;
     }
+    for (int st = 0; st < stages; st++) {
+        if (st) __syncthreads();                  // the tiles of the stage before are no longer read
+        // t tile: 128 rows x 64 values, a float4 per lane and pass, stored transposed
+        for (int e = tid; e < kTile * (kBlockCols / 4); e += kTrailThreads) {
+            const int rr = e / (kBlockCols / 4), k4 = (e % (kBlockCols / 4)) * 4;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kPanelCols + t0 + st * kBlockCols + k4);
+            Ts[k4][rr] = v.x; Ts[k4 + 1][rr] = v.y; Ts[k4 + 2][rr] = v.z; Ts[k4 + 3][rr] = v.w;
+        }
+        // U tile: 64 rows x 128 columns (columns in whole fours: cend is a multiple of 64)
+        for (int e = tid; e < kBlockCols * (kTile / 4); e += kTrailThreads) {
+            const int k = e / (kTile / 4), cc = (e % (kTile / 4)) * 4;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (col0 + cc < cend) v = *reinterpret_cast<const float4 *>(a.U + (c0 + st * kBlockCols + k) * a.ldu + col0 + cc);
+            *reinterpret_cast<float4 *>(&Us[k][cc]) = v;
+        }
+        __syncthreads();
 #pragma unroll 4
-    for (int k = 0; k < kBlockCols; k++) {
-        const float4 a0 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty]), a1 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty + 4]);
-        const float4 b0 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx]), b1 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx + 4]);
-        const float tv[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-        const float uv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+        for (int k = 0; k < kBlockCols; k++) {
+            const float4 a0 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty]), a1 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty + 4]);
+            const float4 b0 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx]), b1 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx + 4]);
+            const float tv[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const float uv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-        for (int i = 0; i < 8; i++)
+            for (int i = 0; i < 8; i++)
 #pragma unroll
-            for (int j = 0; j < 8; j++) acc[i][j] = __builtin_fmaf(-tv[i], uv[j], acc[i][j]);
+                for (int j = 0; j < 8; j++) acc[i][j] = __builtin_fmaf(-tv[i], uv[j], acc[i][j]);
+        }
     }
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -187,7 +196,7 @@ hipError_t make_side_streams(pvq_ctx *c)
 
 }  // namespace
 
-// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 64 floats.
+// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 128 floats.
 // Rows are independent, and within a chunk of rows the launches form a chain in which every second one (the
 // block kernel) is a single wave per 64 rows bound by its own latency: up to four chunks of rows run side by
 // side, the first on the caller's stream and the others on streams of the context that fork from and
@@ -213,7 +222,7 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
             if (nr <= 0) continue;
             hipStream_t st = ch == 0 ? s : c->side[ch - 1];
             correct_args a;
-            a.W = W + r0 * ldw; a.ldw = ldw; a.rows = nr; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work + r0 * kBlockCols;
+            a.W = W + r0 * ldw; a.ldw = ldw; a.rows = nr; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work + r0 * kPanelCols;
             a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
             const dim3 bgrid((unsigned)((nr + 63) / 64)), bblock(64);
             switch (c->D) {
@@ -221,10 +230,15 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
             case 16: hipLaunchKernelGGL((correct_block_kernel<16>), bgrid, bblock, 0, st, a, c0); break;
             default: hipLaunchKernelGGL((correct_block_kernel<32>), bgrid, bblock, 0, st, a, c0); break;
             }
+            // behind the first block of a panel: the panel's second block only; behind the second: everything
+            // behind the panel, for both blocks at once
             const int64_t c1 = c0 + kBlockCols;
-            if (c1 < cols) {
-                const dim3 tgrid((unsigned)((cols - c1 + kTile - 1) / kTile), (unsigned)((nr + kTile - 1) / kTile));
-                hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, c1);
+            const bool first = c0 % kPanelCols == 0;
+            const int64_t cend = first ? std::min(c1 + kBlockCols, cols) : cols;
+            if (c1 < cend) {
+                const dim3 tgrid((unsigned)((cend - c1 + kTile - 1) / kTile), (unsigned)((nr + kTile - 1) / kTile));
+                if (first) hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, 0, 1, c1, cend);
+                else hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0 - kBlockCols, 0, 2, c1, cend);
             }
         }
         e = hipGetLastError();

@@ -518,7 +518,7 @@ extern "C" int pvq_rotate_encode(const pvq_ctx *c, const void *X, int dtype, int
 extern "C" int pvq_correct_work_bytes(int64_t rows, size_t *bytes)
 {
     if (rows < 0 || rows > (int64_t)1 << 30 || !bytes) return PVQ_E_INVALID_ARG;
-    *bytes = (size_t)rows * 64 * sizeof(float);
+    *bytes = (size_t)rows * 128 * sizeof(float);
     return PVQ_OK;
 }
 
@@ -530,7 +530,7 @@ extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t col
     if (c->wide || (c->D != 8 && c->D != 16 && c->D != 32) || cols % 64) return PVQ_E_UNSUPPORTED;
     if (rows == 0 || cols == 0) return PVQ_OK;
     if (!W || !U || !work || ldw < cols || ldu < cols) return PVQ_E_INVALID_ARG;
-    if (work_bytes < (size_t)rows * 64 * sizeof(float)) return PVQ_E_INVALID_ARG;
+    if (work_bytes < (size_t)rows * 128 * sizeof(float)) return PVQ_E_INVALID_ARG;
     if (!aligned(W, 16) || ldw % 4 || !aligned(U, 16) || ldu % 4 || !aligned(work, 16)) return PVQ_E_ALIGNMENT;
     if ((rc = check_device(c))) return rc;
     const hipError_t e = pvq_launch_correct(c, W, rows, cols, ldw, U, ldu, (float *)work, (hipStream_t)stream);

@@ -100,7 +100,7 @@ hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, 
 hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s);
 
 // error correction of Sec. 3.3 Step 6 (pvq_correct.hip): W rows x cols float32 in place, cols a multiple
-// of 64, U cols x cols upper triangular, work rows x 64 floats
+// of 64, U cols x cols upper triangular, work rows x 128 floats
 hipError_t pvq_launch_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
                               int64_t ldu, float *work, hipStream_t s);   // p[0..n) = 0 by a kernel
 

@@ -224,7 +224,8 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
  * diagonal of U gives non-finite weights (then encoded as pvq_encode encodes them), never a fault.
  * Launches about 2 cols/64 kernels; asynchronous.  From 1024 rows on, chunks of rows run side by side on
  * streams that the context owns (default priority); they fork from `stream` and join it again through events,
- * so work queued on `stream` after the call sees the finished matrix.
+ * so work queued on `stream` after the call sees the finished matrix.  The call enqueues kernels, event records
+ * and waits only, so it can be captured in a graph once the context has made its streams (at its first call).
  */
 int pvq_correct_work_bytes(int64_t rows, size_t *bytes);
 int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,

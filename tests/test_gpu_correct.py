@@ -74,6 +74,45 @@ def test_row_chunks_side_by_side(rows):
     ctx.close()
 
 
+@pytest.mark.parametrize("rows", [200, 1100])
+def test_the_call_can_be_captured_in_a_graph_and_replayed(rows):
+    # kernels, event records and waits only (the context's streams exist after the first, eager call): one
+    # chunk on the capturing stream, or two chunks that fork from it and join it again; every replay must
+    # reproduce the eager result for the weights then in the buffer
+    D, K, cols = 8, 16, 256
+    ctx = pvq.pvq_ctx_create(D, K)
+    _, U = si.calibration_hessian(cols, 2 * cols, si.BASE_SEED + 561)
+    Ud = gu.to_dev_f32(U)
+    W = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    work = torch.empty((rows * 512,), dtype=torch.uint8, device="cuda")
+
+    def fill(seed):
+        W.copy_(gu.to_dev_f32(si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + seed, rotate=False, bf16=False)))
+
+    fill(1)
+    pvq.pvq_correct(ctx, W, Ud, work=work)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    fill(1)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pvq.pvq_correct(ctx, W, Ud, work=work)
+    torch.cuda.synchronize()
+    for seed in (2, 3, 4):
+        fill(seed)
+        pvq.pvq_correct(ctx, W, Ud, work=work)
+        torch.cuda.synchronize()
+        want = W.clone()
+        fill(seed)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(want, W)
+    ctx.close()
+
+
 def test_uncorrelated_inputs_leave_the_weights_alone():
     D, K, rows, cols = 8, 16, 50, 256
     W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=77, rotate=False, bf16=False), dtype=np.float32)

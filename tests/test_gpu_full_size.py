@@ -83,3 +83,28 @@ def test_prefill_batch_of_activations_long_groups():
     got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
     assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
     ctx.close()
+
+
+def test_error_correction_of_a_square_projection():
+    # Sec. 3.3 Step 6 on 8192 x 8192 (the attention projections' shape), in the configuration that the
+    # benchmark's extras time: four chunks of rows side by side, 64 panels.  Rows are independent, so the
+    # oracle corrects a sample of rows (first and last rows of tiles and of chunks) and those must match bit
+    # for bit.  The factor is a seeded well-conditioned upper triangular matrix (any such matrix is the
+    # factor of some inverse Hessian); the arithmetic, not the statistics, is what is compared here.
+    rows = cols = 8192
+    D, K = 8, 16
+    rng = np.random.default_rng(si.BASE_SEED + 900)
+    U = np.triu(rng.standard_normal((cols, cols), dtype=np.float32) * np.float32(0.3 / cols ** 0.5))
+    U[np.diag_indices(cols)] += np.float32(1.0)
+    W0 = device_matrix(rows, cols, si.BASE_SEED + 901)[0].to(torch.float32)
+    ctx = pvq.pvq_ctx_create(D, K)
+    Wd = W0.clone()
+    pvq.pvq_correct(ctx, Wd, gu.to_dev_f32(U))
+    torch.cuda.synchronize()
+    sample = np.array([0, 1, 63, 64, 127, 128, 2047, 2048, 4095, 4096, 5000, 6143, 6144, 8190, 8191])
+    got = Wd[torch.from_numpy(sample).cuda()].cpu().numpy()
+    ref, _ = oracle.correct(W0[torch.from_numpy(sample).cuda()].cpu().numpy(), U, D, K, nthreads=8)
+    bad = np.argwhere(got.view(np.uint32) != ref.view(np.uint32))
+    assert bad.size == 0, f"{bad.shape[0]} corrected weights differ, first at row {sample[bad[0][0]]}, column {bad[0][1]}"
+    assert not np.array_equal(got, W0[torch.from_numpy(sample).cuda()].cpu().numpy())
+    ctx.close()

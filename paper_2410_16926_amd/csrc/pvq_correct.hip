@@ -62,12 +62,33 @@ __device__ inline void block_step(float (&w)[kBlockCols], float (&t)[kBlockCols]
     int y[D];
 #pragma unroll
     for (int i = 0; i < D; i++) wg[i] = w[G * D + i];
+    // rows in batches of R, the next batch's entries of U requested before the current batch's
+    // multiply-adds (a fence per batch: no more than two batches are ever in the scalar registers)
+    constexpr int R = D >= 16 ? 2 : 4;
+    float cur[R][D], nxt[R][D];
+    if constexpr (G > 0) {
 #pragma unroll
-    for (int k = 0; k < G * D; k++) {
-        if (k % (D >= 16 ? 2 : 4) == 0) __builtin_amdgcn_sched_barrier(0);
-        const float *__restrict__ Uk = U + (int64_t)k * ldu + G * D;
+        for (int r = 0; r < R; r++)
 #pragma unroll
-        for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-t[k], Uk[j], wg[j]);
+            for (int j = 0; j < D; j++) cur[r][j] = U[(int64_t)r * ldu + G * D + j];
+    }
+#pragma unroll
+    for (int k0 = 0; k0 < G * D; k0 += R) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (k0 + R < G * D) {
+#pragma unroll
+            for (int r = 0; r < R; r++)
+#pragma unroll
+                for (int j = 0; j < D; j++) nxt[r][j] = U[(int64_t)(k0 + R + r) * ldu + G * D + j];
+        }
+#pragma unroll
+        for (int r = 0; r < R; r++)
+#pragma unroll
+            for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-t[k0 + r], cur[r][j], wg[j]);
+#pragma unroll
+        for (int r = 0; r < R; r++)
+#pragma unroll
+            for (int j = 0; j < D; j++) cur[r][j] = nxt[r][j];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -120,13 +141,14 @@ __global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64
 // Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][64 stages - 1] U[c0 + 64 stages - 1][c],
 // one multiply-add after the other; t[r][k] = T[r][t0 + k].  stages = 1: one block's update (of the second
 // block of its panel), 2: a panel's update of everything behind it, with the tile of W read and written once
-// for 128 multiply-adds per element.  blockIdx.x = column tile, blockIdx.y = row tile.
+// for 128 multiply-adds per element.  blockIdx.x = row tile (neighbouring workgroups share the tile of U),
+// blockIdx.y = column tile.
 __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int t0, int stages,
                                                                           int64_t c1, int64_t cend)
 {
     __shared__ __align__(16) float Ts[kBlockCols][kTile + 4];   // [k][row of the tile]
     __shared__ __align__(16) float Us[kBlockCols][kTile];       // [k][column of the tile]
-    const int64_t row0 = (int64_t)blockIdx.y * kTile, col0 = c1 + (int64_t)blockIdx.x * kTile;
+    const int64_t row0 = (int64_t)blockIdx.x * kTile, col0 = c1 + (int64_t)blockIdx.y * kTile;
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;       // rows 8 ty .. 8 ty + 7, columns 8 tx .. 8 tx + 7 of the tile
     const bool cols_in = col0 + 8 * tx < cend;    // eight columns are in or out together
@@ -236,7 +258,7 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
             const bool first = c0 % kPanelCols == 0;
             const int64_t cend = first ? std::min(c1 + kBlockCols, cols) : cols;
             if (c1 < cend) {
-                const dim3 tgrid((unsigned)((cend - c1 + kTile - 1) / kTile), (unsigned)((nr + kTile - 1) / kTile));
+                const dim3 tgrid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((cend - c1 + kTile - 1) / kTile));
                 if (first) hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, 0, 1, c1, cend);
                 else hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0 - kBlockCols, 0, 2, c1, cend);
             }

@@ -527,7 +527,8 @@ extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t col
 {
     int rc = check_shape(c, rows, cols);
     if (rc) return rc;
-    if (c->wide || (c->D != 8 && c->D != 16 && c->D != 32) || cols % 64) return PVQ_E_UNSUPPORTED;
+    // (column tiles of 128 are the second grid dimension of the update kernel: at most 65535 of them)
+    if (c->wide || (c->D != 8 && c->D != 16 && c->D != 32) || cols % 64 || cols > (int64_t)1 << 22) return PVQ_E_UNSUPPORTED;
     if (rows == 0 || cols == 0) return PVQ_OK;
     if (!W || !U || !work || ldw < cols || ldu < cols) return PVQ_E_INVALID_ARG;
     if (work_bytes < (size_t)rows * 128 * sizeof(float)) return PVQ_E_INVALID_ARG;

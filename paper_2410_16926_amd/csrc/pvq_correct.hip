@@ -16,7 +16,8 @@
 //                          the same in every lane: its entries are read through the scalar unit and
 //                          enter the multiply-adds as scalar operands.
 //   correct_trailing_kernel  applies a block's 64 multiply-adds per element, in the same order, to columns
-//                          behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS.  Two blocks
+//                          behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS (32 rows of U at a
+//                          time).  Two blocks
 //                          make a panel: the first block's update goes to the second block's columns
 //                          only, and after the second block one launch applies both blocks' 128
 //                          multiply-adds to everything behind the panel, reading and writing W once
@@ -39,6 +40,7 @@ constexpr int kBlockCols = 64;    // columns per block
 constexpr int kPanelCols = 128;   // columns per panel: two blocks, whose updates of the columns behind the panel go together
 constexpr int kTile = 128;        // rows and columns of a tile of the trailing update
 constexpr int kTrailThreads = 256;
+constexpr int kStage = 32;        // rows of U (and t values per row) that the trailing update holds in LDS at a time
 
 struct correct_args {
     float *W; int64_t ldw, rows, cols;
@@ -138,16 +140,17 @@ __global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64
     }
 }
 
-// Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][64 stages - 1] U[c0 + 64 stages - 1][c],
-// one multiply-add after the other; t[r][k] = T[r][t0 + k].  stages = 1: one block's update (of the second
-// block of its panel), 2: a panel's update of everything behind it, with the tile of W read and written once
-// for 128 multiply-adds per element.  blockIdx.x = row tile (neighbouring workgroups share the tile of U),
-// blockIdx.y = column tile.
+// Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][n - 1] U[c0 + n - 1][c], n = 32 stages,
+// one multiply-add after the other; t[r][k] = T[r][t0 + k].  n = 64: one block's update (of the second block
+// of its panel); n = 128: a panel's update of everything behind it, with the tile of W read and written once
+// for 128 multiply-adds per element.  A stage = 32 rows of U and 32 t values per row in LDS (33 KB, four
+// workgroups per compute unit; with 64 per stage, two workgroups, the update ran at 57 instead of 66 TFLOP/s).
+// blockIdx.x = row tile (neighbouring workgroups share the tile of U), blockIdx.y = column tile.
 __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int t0, int stages,
                                                                           int64_t c1, int64_t cend)
 {
-    __shared__ __align__(16) float Ts[kBlockCols][kTile + 4];   // [k][row of the tile]
-    __shared__ __align__(16) float Us[kBlockCols][kTile];       // [k][column of the tile]
+    __shared__ __align__(16) float Ts[kStage][kTile + 4];   // [k][row of the tile]
+    __shared__ __align__(16) float Us[kStage][kTile];       // [k][column of the tile]
     const int64_t row0 = (int64_t)blockIdx.x * kTile, col0 = c1 + (int64_t)blockIdx.y * kTile;
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;       // rows 8 ty .. 8 ty + 7, columns 8 tx .. 8 tx + 7 of the tile
@@ -166,23 +169,23 @@ __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct
     }
     for (int st = 0; st < stages; st++) {
         if (st) __syncthreads();                  // the tiles of the stage before are no longer read
-        // t tile: 128 rows x 64 values, a float4 per lane and pass, stored transposed
-        for (int e = tid; e < kTile * (kBlockCols / 4); e += kTrailThreads) {
-            const int rr = e / (kBlockCols / 4), k4 = (e % (kBlockCols / 4)) * 4;
+        // t tile: 128 rows x 32 values, a float4 per lane and pass, stored transposed
+        for (int e = tid; e < kTile * (kStage / 4); e += kTrailThreads) {
+            const int rr = e / (kStage / 4), k4 = (e % (kStage / 4)) * 4;
             float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kPanelCols + t0 + st * kBlockCols + k4);
+            if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kPanelCols + t0 + st * kStage + k4);
             Ts[k4][rr] = v.x; Ts[k4 + 1][rr] = v.y; Ts[k4 + 2][rr] = v.z; Ts[k4 + 3][rr] = v.w;
         }
-        // U tile: 64 rows x 128 columns (columns in whole fours: cend is a multiple of 64)
-        for (int e = tid; e < kBlockCols * (kTile / 4); e += kTrailThreads) {
+        // U tile: 32 rows x 128 columns (columns in whole fours: cend is a multiple of 64)
+        for (int e = tid; e < kStage * (kTile / 4); e += kTrailThreads) {
             const int k = e / (kTile / 4), cc = (e % (kTile / 4)) * 4;
             float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (col0 + cc < cend) v = *reinterpret_cast<const float4 *>(a.U + (c0 + st * kBlockCols + k) * a.ldu + col0 + cc);
+            if (col0 + cc < cend) v = *reinterpret_cast<const float4 *>(a.U + (c0 + st * kStage + k) * a.ldu + col0 + cc);
             *reinterpret_cast<float4 *>(&Us[k][cc]) = v;
         }
         __syncthreads();
 #pragma unroll 4
-        for (int k = 0; k < kBlockCols; k++) {
+        for (int k = 0; k < kStage; k++) {
             const float4 a0 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty]), a1 = *reinterpret_cast<const float4 *>(&Ts[k][8 * ty + 4]);
             const float4 b0 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx]), b1 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx + 4]);
             const float tv[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
@@ -259,8 +262,8 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
             const int64_t cend = first ? std::min(c1 + kBlockCols, cols) : cols;
             if (c1 < cend) {
                 const dim3 tgrid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((cend - c1 + kTile - 1) / kTile));
-                if (first) hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, 0, 1, c1, cend);
-                else hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0 - kBlockCols, 0, 2, c1, cend);
+                if (first) hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, 0, kBlockCols / kStage, c1, cend);
+                else hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0 - kBlockCols, 0, kPanelCols / kStage, c1, cend);
             }
         }
         e = hipGetLastError();

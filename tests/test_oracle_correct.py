@@ -96,3 +96,15 @@ def test_threads_do_not_change_the_result():
     a, qa = oracle.correct(W0, U, D, K, nthreads=1)
     b, qb = oracle.correct(W0, U, D, K, nthreads=4)
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32)) and np.array_equal(qa.view(np.uint32), qb.view(np.uint32))
+
+
+def test_the_synthetic_hessian_and_its_factor():
+    # the input recipe: H symmetric positive definite with strongly coupled neighbouring channels, U upper
+    # triangular with a positive diagonal and U^T U = H^-1 (up to its rounding to float32)
+    H, U = si.calibration_hessian(96, 400, 916)
+    assert np.allclose(H, H.T) and np.linalg.eigvalsh(H).min() > 0
+    corr = H[np.arange(95), np.arange(1, 96)] / np.sqrt(np.diag(H)[:-1] * np.diag(H)[1:])
+    assert np.median(corr) > 0.7
+    assert U.dtype == np.float32 and np.array_equal(U, np.triu(U)) and np.diag(U).min() > 0
+    U64 = U.astype(np.float64)
+    assert np.abs(U64.T @ U64 @ H - np.eye(96)).max() < 1e-4

@@ -213,8 +213,8 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
  * the corrected code (amplitude codes, Step 5, are formed there, after the last group).
  *
  *   W      device, float32 [rows][ldw], 16-byte aligned, ldw >= cols, ldw a multiple of 4; overwritten.
- *   U      device, float32 [cols][ldu], 16-byte aligned, ldu >= cols, ldu a multiple of 4; the upper
- *          triangle is read (and the 64 x 64 blocks on the diagonal whole).  Not modified.
+ *   U      device, float32 [cols][ldu], 16-byte aligned, ldu >= cols, ldu a multiple of 4; only the upper
+ *          triangle is used (what lies below the diagonal may be anything).  Not modified.
  *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (128 floats per
  *          row), owned by the caller, contents undefined afterwards.
  *

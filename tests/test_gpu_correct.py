@@ -113,6 +113,19 @@ def test_the_call_can_be_captured_in_a_graph_and_replayed(rows):
     ctx.close()
 
 
+def test_entries_below_the_diagonal_are_not_used():
+    D, K, rows, cols = 8, 16, 90, 192
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=91, rotate=False, bf16=False), dtype=np.float32)
+    _, U = si.calibration_hessian(cols, 2 * cols, 92)
+    ref, _ = oracle.correct(W0, U, D, K)
+    ctx = pvq.pvq_ctx_create(D, K)
+    Wd = gu.to_dev_f32(W0)
+    Ud = gu.to_dev_f32(U + np.tril(np.full((cols, cols), np.nan, dtype=np.float32), -1))
+    pvq.pvq_correct(ctx, Wd, Ud)
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    ctx.close()
+
+
 def test_uncorrelated_inputs_leave_the_weights_alone():
     D, K, rows, cols = 8, 16, 50, 256
     W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=77, rotate=False, bf16=False), dtype=np.float32)

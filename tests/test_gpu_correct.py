@@ -113,6 +113,26 @@ def test_the_call_can_be_captured_in_a_graph_and_replayed(rows):
     ctx.close()
 
 
+def test_corrected_code_has_the_lower_proxy_loss():
+    # the point of the step (Sec. 2.1, Sec. 3.3 Step 6), end to end through the library: rotate-free synthetic
+    # weights, correct, encode, decode; Tr((W - W_hat) H (W - W_hat)^T) against the plain code of the same matrix
+    D, K, rows, cols = 8, 16, 48, 512
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=93, rotate=False, bf16=False), dtype=np.float32)
+    H, U = si.calibration_hessian(cols, 2 * cols, 94)
+    ctx, _, _ = gu.make_ctx(D, K, 2, cols // D)
+
+    def loss(What):
+        d = W0.astype(np.float64) - What.astype(np.float64)
+        return np.einsum("ri,ij,rj->", d, H, d)
+
+    plain = pvq.pvq_decode(ctx, pvq.pvq_encode(ctx, gu.to_dev_f32(W0)), torch.float32).cpu().numpy()
+    Wd = gu.to_dev_f32(W0)
+    pvq.pvq_correct(ctx, Wd, gu.to_dev_f32(U))
+    corrected = pvq.pvq_decode(ctx, pvq.pvq_encode(ctx, Wd), torch.float32).cpu().numpy()
+    assert loss(corrected) < 0.7 * loss(plain)
+    ctx.close()
+
+
 def test_entries_below_the_diagonal_are_not_used():
     D, K, rows, cols = 8, 16, 90, 192
     W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=91, rotate=False, bf16=False), dtype=np.float32)

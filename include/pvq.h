@@ -222,7 +222,7 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
  * applied one at a time in the order of the rows of U, so the result does not depend on the launch shape.
  * Contexts with D = 8, 16 or 32 and cols a multiple of 64, else PVQ_E_UNSUPPORTED.  A zero on the
  * diagonal of U gives non-finite weights (then encoded as pvq_encode encodes them), never a fault.
- * Launches about 2 cols/64 kernels; asynchronous.  From 1024 rows on, chunks of rows run side by side on
+ * Launches cols/64 kernels; asynchronous.  From 1024 rows on, chunks of rows run side by side on
  * streams that the context owns (default priority); they fork from `stream` and join it again through events,
  * so work queued on `stream` after the call sees the finished matrix.  The call enqueues kernels, event records
  * and waits only, so it can be captured in a graph once the context has made its streams (at its first call).

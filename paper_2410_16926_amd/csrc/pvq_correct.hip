@@ -9,25 +9,17 @@
 // holds, for every group, the values that were quantised: encoding it gives the corrected code.
 //
 // Rows are independent, groups of a row strictly sequential, and U is the same for every row.  Columns are
-// taken in blocks of 64:
-//   correct_block_kernel   one lane per row holds the block's 64 values in registers, goes through the
-//                          block's groups (pending updates from the block's earlier groups, quantise,
-//                          substitution) and leaves the block's t values (rows x 64) in a work buffer.  U is
-//                          the same in every lane: its entries are read through the scalar unit and
-//                          enter the multiply-adds as scalar operands.
-//   correct_trailing_kernel  applies a block's 64 multiply-adds per element, in the same order, to columns
-//                          behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS (32 rows of U at a
-//                          time).  Two blocks
-//                          make a panel: the first block's update goes to the second block's columns
-//                          only, and after the second block one launch applies both blocks' 128
-//                          multiply-adds to everything behind the panel, reading and writing W once
-//                          (with 64 per pass the kernel was bound by HBM as much as by the vector ALU).
-//                          Bound: float32 vector ALU.
+// taken in panels of 128:
+//   correct_panel_kernel   one lane per row goes through the panel's groups (pending updates from the
+//                          panel's earlier groups, quantise, substitution) and leaves the panel's t values
+//                          (rows x 128) in a work buffer.  Bound by its own latency: one wave per 64 rows.
+//   correct_trailing_kernel  applies the panel's 128 multiply-adds per element, in the same order, to all
+//                          columns behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS (32 rows
+//                          of U at a time), W read and written once per panel.  Bound: float32 vector ALU.
 // Not on the matrix cores: their accumulation order inside an instruction is not the one defined above.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <utility>
 
 #include "pvq_internal.h"
 #include "pvq_quantize_dev.h"
@@ -36,7 +28,6 @@ namespace {
 
 using namespace pvq_quantize_dev;
 
-constexpr int kBlockCols = 64;    // columns per block
 constexpr int kPanelCols = 128;   // columns per panel: two blocks, whose updates of the columns behind the panel go together
 constexpr int kTile = 128;        // rows and columns of a tile of the trailing update
 constexpr int kTrailThreads = 256;
@@ -49,101 +40,120 @@ struct correct_args {
     int K, ls;
 };
 
-// Group G of the block (a template parameter, so that every register index below is a constant).  First the
-// group's columns take the updates of the block's earlier groups, which are still pending (rows 0 .. G D - 1
-// of the block's part of U, in that order: per element the same multiply-adds in the same order as if every
-// group had updated all later columns at once, with the entries of U read right where they are used);
-// then quantise and substitution.  U points at the block's first diagonal entry; its entries are the same in
-// every lane and are read through the scalar unit.  The fences keep the compiler from fetching many rows
-// ahead, which the scalar registers do not hold.
-template <int D, int G>
-__device__ inline void block_step(float (&w)[kBlockCols], float (&t)[kBlockCols], const float *__restrict__ U, int64_t ldu,
-                                  int K, int ls)
+// A panel of `width` columns (128, or 64 at the end of a matrix with an odd number of blocks) from column p0
+// on, one lane per row.  Group after group: the group's D values come from W (requested while the group
+// before is worked on); they take the updates of the panel's earlier groups, which are still pending (rows
+// 0 .. G D - 1 of the panel's part of U, in that order: per element the same multiply-adds in the same order
+// as if every group had updated all later columns at once); then quantiser, amplitude, error and
+// substitution; the values go back to W, the group's t values to the work buffer and to LDS (a column per
+// lane: the pending updates of the later groups read them there, so that nothing is indexed by the group
+// number in registers and the groups are a real loop: the code stays small).  U is the same in every lane:
+// the rows that a group needs (its D columns of the panel's rows above it, and its own D x D part) are
+// fetched a group ahead, one or two rows per lane, parked in registers while the current group is worked
+// on, and then laid out in LDS, where every lane reads the same address (a broadcast).
+template <int D>
+__global__ __launch_bounds__(64) void correct_panel_kernel(correct_args a, int64_t p0, int width)
 {
-    float wg[D];
-    int y[D];
+    __shared__ float ts[kPanelCols][64];                        // t values of the panel so far, [column][lane]
+    __shared__ __align__(16) float us[2][kPanelCols][D];        // the U rows of the current and the next group
+    const int lane = threadIdx.x;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const bool in = r < a.rows;
+    // lanes beyond the rows work on the last row again (no lane waits for another); they store nothing
+    float *wrow = a.W + (in ? r : a.rows - 1) * a.ldw + p0;
+    float *trow = a.T + (in ? r : a.rows - 1) * kPanelCols;
+    const float *U = a.U + p0 * a.ldu + p0;                     // row p0 + i, column p0 + c of the factor
+    const int ngroups = width / D;
+
+    auto load_group_values = [&](int G, float (&v)[D]) {
 #pragma unroll
-    for (int i = 0; i < D; i++) wg[i] = w[G * D + i];
-    // rows in batches of R, the next batch's entries of U requested before the current batch's
-    // multiply-adds (a fence per batch: no more than two batches are ever in the scalar registers)
-    constexpr int R = D >= 16 ? 2 : 4;
-    float cur[R][D], nxt[R][D];
-    if constexpr (G > 0) {
+        for (int i = 0; i < D; i += 4) {
+            const float4 q = *reinterpret_cast<const float4 *>(wrow + G * D + i);
+            v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+        }
+    };
+    // rows lane and lane + 64 of the panel, the D columns of group G (rows up to the group's last one are
+    // needed: (G + 1) D of them; the others are fetched from a row that exists and not used)
+    auto fetch_u = [&](int G, float (&v)[2][D]) {
 #pragma unroll
-        for (int r = 0; r < R; r++)
+        for (int h = 0; h < 2; h++) {
+            const int k = lane + 64 * h;
+            const float *src = U + (int64_t)(k < (G + 1) * D ? k : 0) * a.ldu + G * D;
 #pragma unroll
-            for (int j = 0; j < D; j++) cur[r][j] = U[(int64_t)r * ldu + G * D + j];
-    }
+            for (int i = 0; i < D; i += 4) {
+                const float4 q = *reinterpret_cast<const float4 *>(src + i);
+                v[h][i] = q.x; v[h][i + 1] = q.y; v[h][i + 2] = q.z; v[h][i + 3] = q.w;
+            }
+        }
+    };
+    auto park_u = [&](int buf, const float (&v)[2][D]) {
 #pragma unroll
-    for (int k0 = 0; k0 < G * D; k0 += R) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (k0 + R < G * D) {
+        for (int h = 0; h < 2; h++)
 #pragma unroll
-            for (int r = 0; r < R; r++)
+            for (int i = 0; i < D; i += 4)
+                *reinterpret_cast<float4 *>(&us[buf][lane + 64 * h][i]) = make_float4(v[h][i], v[h][i + 1], v[h][i + 2], v[h][i + 3]);
+    };
+    float wg[D], wn[D], un[2][D];
+    load_group_values(0, wg);
+    fetch_u(0, un);
+    park_u(0, un);
+    __syncthreads();
+    for (int G = 0; G < ngroups; G++) {
+        const int Gn = G + 1 < ngroups ? G + 1 : G;
+        load_group_values(Gn, wn);
+        fetch_u(Gn, un);
+        const float (*ug)[D] = us[G & 1];
+        // pending updates: rows k = 0 .. G D - 1 of the panel, this group's columns
+        const int pending = G * D;
+#pragma unroll 8
+        for (int k = 0; k < pending; k++) {
+            const float tk = ts[k][lane];
+            float u[D];
 #pragma unroll
-                for (int j = 0; j < D; j++) nxt[r][j] = U[(int64_t)(k0 + R + r) * ldu + G * D + j];
+            for (int j = 0; j < D; j += 4) {
+                const float4 q = *reinterpret_cast<const float4 *>(&ug[k][j]);
+                u[j] = q.x; u[j + 1] = q.y; u[j + 2] = q.z; u[j + 3] = q.w;
+            }
+#pragma unroll
+            for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-tk, u[j], wg[j]);
+        }
+        // what is quantised, and stays in W
+        if (in) {
+#pragma unroll
+            for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(wrow + G * D + i) = make_float4(wg[i], wg[i + 1], wg[i + 2], wg[i + 3]);
+        }
+        int y[D];
+        const float ss = quantize_group<D>(wg, a.K, y);
+        const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
+        int n2 = 0;
+#pragma unroll
+        for (int i = 0; i < D; i++) n2 += y[i] * y[i];
+        const float gain = s / sqrtf((float)n2);
+        float t[D];
+#pragma unroll
+        for (int j = 0; j < D; j++) {
+            float acc = wg[j] - gain * (float)y[j];
+#pragma unroll
+            for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[i], ug[pending + i][j], acc);
+            t[j] = acc / ug[pending + j][j];
         }
 #pragma unroll
-        for (int r = 0; r < R; r++)
+        for (int j = 0; j < D; j++) ts[pending + j][lane] = t[j];
+        if (in) {
 #pragma unroll
-            for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-t[k0 + r], cur[r][j], wg[j]);
+            for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(trow + G * D + i) = make_float4(t[i], t[i + 1], t[i + 2], t[i + 3]);
+        }
+        park_u((G + 1) & 1, un);
+        __syncthreads();      // one wave: orders the LDS writes above before the next group's reads
 #pragma unroll
-        for (int r = 0; r < R; r++)
-#pragma unroll
-            for (int j = 0; j < D; j++) cur[r][j] = nxt[r][j];
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < D; i++) w[G * D + i] = wg[i];   // what is quantised, and stays in W
-    const float ss = quantize_group<D>(wg, K, y);
-    const float s = ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
-    int n2 = 0;
-#pragma unroll
-    for (int i = 0; i < D; i++) n2 += y[i] * y[i];
-    const float gain = s / sqrtf((float)n2);
-    const float *__restrict__ Ug = U + (int64_t)(G * D) * ldu + G * D;   // the group's D x D part
-#pragma unroll
-    for (int j = 0; j < D; j++) {
-        float acc = wg[j] - gain * (float)y[j];
-#pragma unroll
-        for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[G * D + i], Ug[(int64_t)i * ldu + j], acc);
-        t[G * D + j] = acc / Ug[(int64_t)j * ldu + j];
-    }
-}
-
-template <int D, int... Gs>
-__device__ inline void block_steps(float (&w)[kBlockCols], float (&t)[kBlockCols], const float *__restrict__ U, int64_t ldu,
-                                   int K, int ls, std::integer_sequence<int, Gs...>)
-{
-    (block_step<D, Gs>(w, t, U, ldu, K, ls), ...);
-}
-
-template <int D>
-__global__ __launch_bounds__(64) void correct_block_kernel(correct_args a, int64_t c0)
-{
-    const int64_t r = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (r >= a.rows) return;
-    float *wrow = a.W + r * a.ldw + c0;
-    const float *__restrict__ U = a.U + c0 * a.ldu + c0;   // row c0 + i, column c0 + c of the factor
-    float w[kBlockCols], t[kBlockCols];
-#pragma unroll
-    for (int c = 0; c < kBlockCols; c += 4) {
-        const float4 v = *reinterpret_cast<const float4 *>(wrow + c);
-        w[c] = v.x; w[c + 1] = v.y; w[c + 2] = v.z; w[c + 3] = v.w;
-    }
-    block_steps<D>(w, t, U, a.ldu, a.K, a.ls, std::make_integer_sequence<int, kBlockCols / D>{});
-    float *trow = a.T + r * kPanelCols + (c0 % kPanelCols);
-#pragma unroll
-    for (int c = 0; c < kBlockCols; c += 4) {
-        *reinterpret_cast<float4 *>(wrow + c) = make_float4(w[c], w[c + 1], w[c + 2], w[c + 3]);
-        *reinterpret_cast<float4 *>(trow + c) = make_float4(t[c], t[c + 1], t[c + 2], t[c + 3]);
+        for (int i = 0; i < D; i++) wg[i] = wn[i];
     }
 }
 
 // Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][n - 1] U[c0 + n - 1][c], n = 32 stages,
-// one multiply-add after the other; t[r][k] = T[r][t0 + k].  n = 64: one block's update (of the second block
-// of its panel); n = 128: a panel's update of everything behind it, with the tile of W read and written once
-// for 128 multiply-adds per element.  A stage = 32 rows of U and 32 t values per row in LDS (33 KB, four
+// one multiply-add after the other; t[r][k] = T[r][t0 + k].  n = 128: a panel's update of everything behind it,
+// with the tile of W read and written once for 128 multiply-adds per element (with 64 per pass the kernel was
+// bound by HBM as much as by the vector ALU).  A stage = 32 rows of U and 32 t values per row in LDS (33 KB, four
 // workgroups per compute unit; with 64 per stage, two workgroups, the update ran at 57 instead of 66 TFLOP/s).
 // blockIdx.x = row tile (neighbouring workgroups share the tile of U), blockIdx.y = column tile.
 __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int t0, int stages,
@@ -223,9 +233,9 @@ hipError_t make_side_streams(pvq_ctx *c)
 
 // W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 128 floats.
 // Rows are independent, and within a chunk of rows the launches form a chain in which every second one (the
-// block kernel) is a single wave per 64 rows bound by its own latency: up to four chunks of rows run side by
+// panel kernel) is a single wave per 64 rows bound by its own latency: up to four chunks of rows run side by
 // side, the first on the caller's stream and the others on streams of the context that fork from and
-// join the caller's stream through events, so that one chunk's block kernel runs beside another
+// join the caller's stream through events, so that one chunk's panel kernel runs beside another
 // chunk's trailing update.
 hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
                               int64_t ldu, float *work, hipStream_t s)
@@ -241,7 +251,8 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
         for (int i = 0; i + 1 < nch; i++)
             if ((e = hipStreamWaitEvent(c->side[i], c->side_fork, 0)) != hipSuccess) return e;
     }
-    for (int64_t c0 = 0; c0 < cols && e == hipSuccess; c0 += kBlockCols) {
+    for (int64_t p0 = 0; p0 < cols && e == hipSuccess; p0 += kPanelCols) {
+        const int width = (int)std::min<int64_t>(kPanelCols, cols - p0);   // 128, or 64 at the end
         for (int64_t ch = 0; ch < nch; ch++) {
             const int64_t r0 = ch * chunk_rows, nr = std::min(chunk_rows, rows - r0);
             if (nr <= 0) continue;
@@ -249,21 +260,17 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
             correct_args a;
             a.W = W + r0 * ldw; a.ldw = ldw; a.rows = nr; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work + r0 * kPanelCols;
             a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
-            const dim3 bgrid((unsigned)((nr + 63) / 64)), bblock(64);
+            const dim3 pgrid((unsigned)((nr + 63) / 64)), pblock(64);
             switch (c->D) {
-            case 8: hipLaunchKernelGGL((correct_block_kernel<8>), bgrid, bblock, 0, st, a, c0); break;
-            case 16: hipLaunchKernelGGL((correct_block_kernel<16>), bgrid, bblock, 0, st, a, c0); break;
-            default: hipLaunchKernelGGL((correct_block_kernel<32>), bgrid, bblock, 0, st, a, c0); break;
+            case 8: hipLaunchKernelGGL((correct_panel_kernel<8>), pgrid, pblock, 0, st, a, p0, width); break;
+            case 16: hipLaunchKernelGGL((correct_panel_kernel<16>), pgrid, pblock, 0, st, a, p0, width); break;
+            default: hipLaunchKernelGGL((correct_panel_kernel<32>), pgrid, pblock, 0, st, a, p0, width); break;
             }
-            // behind the first block of a panel: the panel's second block only; behind the second: everything
-            // behind the panel, for both blocks at once
-            const int64_t c1 = c0 + kBlockCols;
-            const bool first = c0 % kPanelCols == 0;
-            const int64_t cend = first ? std::min(c1 + kBlockCols, cols) : cols;
-            if (c1 < cend) {
-                const dim3 tgrid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((cend - c1 + kTile - 1) / kTile));
-                if (first) hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0, 0, kBlockCols / kStage, c1, cend);
-                else hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, c0 - kBlockCols, 0, kPanelCols / kStage, c1, cend);
+            // everything behind the panel takes the panel's 128 multiply-adds per element in one launch
+            const int64_t c1 = p0 + kPanelCols;
+            if (c1 < cols) {
+                const dim3 tgrid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((cols - c1 + kTile - 1) / kTile));
+                hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, p0, 0, kPanelCols / kStage, c1, cols);
             }
         }
         e = hipGetLastError();

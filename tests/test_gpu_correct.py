@@ -133,6 +133,29 @@ def test_corrected_code_has_the_lower_proxy_loss():
     ctx.close()
 
 
+def test_rows_that_are_not_finite_do_not_disturb_the_others():
+    # rows are independent: rows of zeros, with infinities or not-a-numbers give unspecified values in those
+    # rows only (and no fault); every other row still equals the oracle's
+    D, K, rows, cols = 8, 16, 70, 256
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=95, rotate=False, bf16=False), dtype=np.float32)
+    W0[3] = 0.0
+    W0[10, 17] = np.inf
+    W0[20, 100] = np.nan
+    W0[33, :8] = 3.0e38
+    W0[47, 64:72] = 1.0e-44
+    _, U = si.calibration_hessian(cols, 2 * cols, 96)
+    ctx = pvq.pvq_ctx_create(D, K)
+    Wd = gu.to_dev_f32(W0)
+    pvq.pvq_correct(ctx, Wd, gu.to_dev_f32(U))
+    torch.cuda.synchronize()
+    got = Wd.cpu().numpy()
+    ref, _ = oracle.correct(W0, U, D, K)
+    clean = np.array([r for r in range(rows) if r not in (10, 20, 33)])
+    assert np.array_equal(got[clean].view(np.uint32), ref[clean].view(np.uint32))
+    assert np.all(got[3] == 0.0)
+    ctx.close()
+
+
 def test_entries_below_the_diagonal_are_not_used():
     D, K, rows, cols = 8, 16, 90, 192
     W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=91, rotate=False, bf16=False), dtype=np.float32)

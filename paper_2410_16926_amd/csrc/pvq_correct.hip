@@ -123,7 +123,9 @@ __global__ __launch_bounds__(64) void correct_panel_kernel(correct_args a, int64
             for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(wrow + G * D + i) = make_float4(wg[i], wg[i + 1], wg[i + 2], wg[i + 3]);
         }
         int y[D];
-        const float ss = quantize_group<D>(wg, a.K, y);
+        float ss;
+        if constexpr (D == 8) ss = quantize_group8(wg, a.K, y);
+        else ss = quantize_group<D>(wg, a.K, y);
         const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
         int n2 = 0;
 #pragma unroll

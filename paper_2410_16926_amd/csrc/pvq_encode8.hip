@@ -22,8 +22,11 @@
 #include <algorithm>
 
 #include "pvq_internal.h"
+#include "pvq_quantize_dev.h"
 
 namespace {
+
+using pvq_quantize_dev::count_wins;
 
 constexpr int kWave = 64;
 constexpr int D = 8;
@@ -33,26 +36,6 @@ struct enc8_launch {
     const float *edges;     // 2^scale_bits entries, last = +inf (or nullptr)
     int K, scale_bits;
 };
-
-// Position of every coordinate in the order of keys (largest first, lower coordinate first on
-// ties): wins[i] = number of coordinates that i comes before.  One comparison per pair feeds two
-// counters through its carry: i's wins over later coordinates and j's losses against earlier ones.
-__device__ inline void count_wins(const float (&key)[D], int (&wins)[D])
-{
-    int lose[D];
-#pragma unroll
-    for (int i = 0; i < D; i++) { wins[i] = 0; lose[i] = 0; }
-#pragma unroll
-    for (int i = 0; i < D; i++)
-#pragma unroll
-        for (int j = i + 1; j < D; j++) {
-            const int first = key[i] >= key[j] ? 1 : 0;
-            wins[i] += first;
-            lose[j] += first;
-        }
-#pragma unroll
-    for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
-}
 
 // v + (v moved across lanes by one data-parallel-primitive pattern); lanes outside ROWS add zero
 template <int CTRL, int ROWS = 0xF>

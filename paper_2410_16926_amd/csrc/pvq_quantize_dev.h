@@ -89,4 +89,74 @@ __device__ inline float quantize_group(const float (&w)[D], int K, int (&y)[D])
     return ss;
 }
 
+// Position of every coordinate in the order of keys (largest first, lower coordinate first on
+// ties): wins[i] = number of coordinates that i comes before.  One comparison per pair feeds two
+// counters through its carry: i's wins over later coordinates and j's losses against earlier ones.
+__device__ inline void count_wins(const float (&key)[8], int (&wins)[8])
+{
+    constexpr int D = 8;
+    int lose[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) { wins[i] = 0; lose[i] = 0; }
+#pragma unroll
+    for (int i = 0; i < D; i++)
+#pragma unroll
+        for (int j = i + 1; j < D; j++) {
+            const int first = key[i] >= key[j] ? 1 : 0;
+            wins[i] += first;
+            lose[j] += first;
+        }
+#pragma unroll
+    for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
+}
+
+// The quantiser above for groups of 8 without branches: the coordinates' places in the order of deviations
+// are counted with 28 comparisons and the |sum - K| first places are adjusted, which equals the one-at-a-time
+// repair because no coordinate is ever adjusted twice (for finite input the |sum - K| largest deviations are
+// all positive, and an adjusted coordinate drops below -1/2).  Same results as quantize_group<8> for finite
+// input; weights that are not finite give unspecified points.
+__device__ inline float quantize_group8(const float (&w)[8], int K, int (&y)[8])
+{
+    constexpr int D = 8;
+    float a[D], tmp[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) { a[i] = fabsf(w[i]); tmp[i] = a[i]; }
+    const float l1 = tree_sum<D>(tmp);
+#pragma unroll
+    for (int i = 0; i < D; i++) tmp[i] = w[i] * w[i];
+    const float ss = tree_sum<D>(tmp);
+    const float g = (float)K / l1;
+    const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(g < INFINITY);
+    float t[D], yf[D];
+    float S = 0.0f;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        t[i] = a[i] * g;
+        yf[i] = rintf(t[i]);
+        S += yf[i];                       // small integers: exact in any order
+    }
+    const float m = (float)K - S;         // > 0: pulses to add, < 0: pulses to take away
+    float key[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        const float d = t[i] - yf[i];
+        key[i] = m < 0.0f ? -d : d;
+    }
+    int wins[D];
+    count_wins(key, wins);
+    const int need = (int)fabsf(m);
+    const float unit = m < 0.0f ? -1.0f : 1.0f;
+    int k = K;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        const bool adjust = wins[i] + need >= D;      // place = D-1-wins < need
+        int mag = (int)(yf[i] + (adjust ? unit : 0.0f));
+        if (degenerate) mag = 0;
+        if (i == D - 1) mag = k;                      // the last coordinate takes what is left
+        y[i] = (w[i] < 0.0f && !degenerate) ? -mag : mag;
+        k -= mag;
+    }
+    return ss;
+}
+
 }  // namespace pvq_quantize_dev

@@ -1,6 +1,7 @@
-// Device code shared by the kernels that quantise a group onto the pyramid (Sec. 2.5): the generic
-// encoder and the error correction of Sec. 3.3 Step 6.  float32, fixed evaluation order: the results
-// are part of the format.
+// Device code shared by the kernels that quantise a group onto the pyramid (Sec. 2.5): the encoders and
+// the error correction of Sec. 3.3 Step 6.  float32, fixed evaluation order: the results are part of the
+// format.  quantize_group<D> is the repair as a loop, for any D; quantize_group8 the same point without
+// branches for D = 8, built on count_wins, which the D = 8 encoder uses as well.
 #pragma once
 
 #include <hip/hip_runtime.h>

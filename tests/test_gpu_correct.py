@@ -133,6 +133,26 @@ def test_corrected_code_has_the_lower_proxy_loss():
     ctx.close()
 
 
+@pytest.mark.parametrize("D,K", [(8, 16), (16, 33)])
+def test_rounding_and_repair_ties_in_the_first_group(D, K):
+    # every row starts with an adversarial group (half-integers after projection, repeated magnitudes, zeros,
+    # one-hot, wide dynamic range): its point decides what the later columns receive
+    rows, cols = 4096, 128
+    W0 = np.asarray(si.gaussian_weights(rows, cols, 0.02, seed=97, rotate=False, bf16=False), dtype=np.float32)
+    W0[:, :D] = si.adversarial_groups(rows, D, seed=98).reshape(rows, D)
+    _, U = si.calibration_hessian(cols, 2 * cols, 99)
+    ctx = pvq.pvq_ctx_create(D, K)
+    Wd = gu.to_dev_f32(W0)
+    pvq.pvq_correct(ctx, Wd, gu.to_dev_f32(U))
+    ref, _ = oracle.correct(W0, U, D, K, nthreads=8)
+    got = Wd.cpu().numpy()
+    finite = np.isfinite(ref).all(axis=1)
+    assert finite.sum() > rows * 0.9
+    bad = np.argwhere(got[finite].view(np.uint32) != ref[finite].view(np.uint32))
+    assert bad.size == 0, f"{bad.shape[0]} differ, first {bad[0]}"
+    ctx.close()
+
+
 def test_rows_that_are_not_finite_do_not_disturb_the_others():
     # rows are independent: rows of zeros, with infinities or not-a-numbers give unspecified values in those
     # rows only (and no fault); every other row still equals the oracle's

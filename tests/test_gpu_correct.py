@@ -113,6 +113,30 @@ def test_the_call_can_be_captured_in_a_graph_and_replayed(rows):
     ctx.close()
 
 
+def test_random_configurations():
+    # seeded sweep: group size, pulse count, shape, amplitude kind, weight scale (bf16-valued weights in
+    # every third case: exact ties are likelier) and damping drawn at random
+    rng = np.random.default_rng(si.BASE_SEED + 570)
+    for case in range(16):
+        D = int(rng.choice([8, 16, 32]))
+        K = int(rng.integers(1, {8: 22, 16: 40, 32: 70}[D]))
+        rows = int(rng.integers(1, 400)); cols = 64 * int(rng.integers(1, 8))
+        amp = str(rng.choice(["l2", "ls"]))
+        sigma = float(rng.choice([1e-3, 0.02, 1.0, 50.0]))
+        W0 = np.asarray(si.gaussian_weights(rows, cols, sigma, seed=3000 + case, rotate=False, bf16=False), dtype=np.float32)
+        if case % 3 == 0:
+            W0 = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W0))
+        _, U = si.calibration_hessian(cols, 2 * cols, 4000 + case, damp=float(rng.choice([0.01, 0.1])))
+        ctx = pvq.pvq_ctx_create(D, K)
+        if amp == "ls":
+            ctx.set_amplitude("ls")
+        Wd = gu.to_dev_f32(W0)
+        pvq.pvq_correct(ctx, Wd, gu.to_dev_f32(U))
+        ref, _ = oracle.correct(W0, U, D, K, amplitude=amp, nthreads=8)
+        assert np.array_equal(Wd.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (case, D, K, rows, cols, amp, sigma)
+        ctx.close()
+
+
 def test_corrected_code_has_the_lower_proxy_loss():
     # the point of the step (Sec. 2.1, Sec. 3.3 Step 6), end to end through the library: rotate-free synthetic
     # weights, correct, encode, decode; Tr((W - W_hat) H (W - W_hat)^T) against the plain code of the same matrix

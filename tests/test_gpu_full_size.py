@@ -56,9 +56,11 @@ def test_llama3_8b_up_projection_wide_indices(D, budget):
 
 @pytest.mark.parametrize("name", ["k", "q", "down"])
 def test_llama3_70b_layer_shapes_2bit_amplitudes(name):
-    # 3.25 bits/weight: D=8, 24-bit index + 2-bit amplitude code; k/v, q/o and down shapes
+    # 3.25 bits/weight: D=8, 24-bit index + 2-bit amplitude code; k/v, q/o and down shapes; the fused product
+    # with 1, 3 and 16 vectors (the matrix-core pass with one and two row tiles per workgroup, and with rows
+    # of 56 slabs for the down projection)
     rows, cols = si.LLAMA3_70B_SHAPES[name]
-    encode_decode_case(rows, cols, 8, 24, 2, si.BASE_SEED + 1100 + rows % 97)
+    encode_decode_case(rows, cols, 8, 24, 2, si.BASE_SEED + 1100 + rows % 97, batches=(1, 3, 16))
 
 
 def test_llama3_70b_gate_projection_with_fused_product():

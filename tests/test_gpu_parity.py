@@ -147,6 +147,14 @@ def test_many_vectors_on_the_matrix_cores_long_rows(rows, cols, bits):
     run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 3), out_dtypes=())
 
 
+@pytest.mark.parametrize("rows,cols,bits,batch", [(4111, 8 * 320, 2, 5), (9001, 8 * 512, 0, 16), (20481, 8 * 256, 8, 3)])
+def test_many_vectors_with_several_row_tiles_per_workgroup(rows, cols, bits, batch):
+    # more than 256 tiles of 16 rows: workgroups own two to six tiles (the last one partial) and take them in
+    # rounds of four, two and one
+    wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 96 + rows, rotate=False, bf16=True)
+    run_case(wf, 8, 16, bits, src_bits=wb, batches=(batch,), out_dtypes=())
+
+
 @pytest.mark.parametrize("D,K", [(8, 16), (16, 33), (32, 60), (8, 1), (8, 127)])
 def test_adversarial_groups(D, K):
     # rounding ties, repair ties, zeros, one-hot, wide dynamic range; 64k groups

@@ -290,9 +290,29 @@ def to_f16(Wd) -> np.ndarray:
 
 
 def to_bf16_bits(Wd) -> np.ndarray:
-    """float64 -> bf16 bit patterns (uint16), round to nearest even (via float32; a double
-    rounding can differ from the direct one by one unit in the last place at most)."""
-    f = np.asarray(Wd, dtype=np.float64).astype(np.float32)
-    u = f.view(np.uint32).astype(np.uint64)
-    rounded = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
-    return rounded.astype(np.uint16)
+    """float64 -> bf16 bit patterns (uint16), rounded once to nearest, ties to even.
+
+    bf16 is the upper half of an IEEE binary32: 8 significant bits for normal numbers (exponents
+    -126..127), multiples of 2^-133 below 2^-126, overflow to infinity.  The value is divided by the
+    spacing of bf16 numbers at its magnitude (a power of two: exact), rounded to an integer with
+    ties to even, and multiplied back (exact); the result is a bf16 number, so its binary32 pattern
+    has zero low bits and the upper half is the answer.  No intermediate rounding to binary32."""
+    v = np.asarray(Wd, dtype=np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    finite = np.isfinite(v)
+    a = np.abs(np.where(finite, v, 0.0))
+    _, e = np.frexp(a)                      # a = m * 2^e with 0.5 <= m < 1, so floor(log2 a) = e - 1
+    e = np.maximum(e - 1, -126)             # below the normal range the spacing stays 2^-133
+    spacing = np.ldexp(1.0, e - 7)
+    r = np.rint(a / spacing) * spacing      # np.rint rounds half-way cases to even
+    with np.errstate(over="ignore"):
+        r32 = np.where(r >= 2.0 ** 128, np.inf, r).astype(np.float32)   # exact, or overflow
+    bits = (r32.view(np.uint32) >> 16).astype(np.uint16)
+    bits = bits | np.where(np.signbit(v), 0x8000, 0).astype(np.uint16)
+    out[...] = bits
+    # infinities and NaN keep their class (a NaN's payload is not specified)
+    nf = ~finite
+    if nf.any():
+        out[nf] = (np.asarray(v[nf], dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        out[nf & np.isnan(v)] |= 0x0040
+    return out

@@ -98,15 +98,6 @@ int pvq_max_k(int D, int bit_budget, int *K);
  */
 int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, double *centers);
 
-/*
- * Host-only diagnostic of the table-driven decoder that the kernels use for D = 8 when N(8,K) fits a
- * 32-bit word and the tables fit LDS: rebuilds those tables and replays the kernels' table walk on the
- * host for the indices [first, first + count) (clipped to N(8,K)), comparing every decoded point with
- * the coordinate-by-coordinate walk of App. B.3.  *mismatches (host) receives the number of indices
- * that differ (0 when the tables are right).  PVQ_E_UNSUPPORTED if (8,K) has no such tables.
- */
-int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mismatches);
-
 /* ---- context ------------------------------------------------------------------------------- */
 
 /*
@@ -273,10 +264,13 @@ int pvq_decode(const pvq_ctx *ctx, const uint32_t *index, const void *scale, con
  *
  *   x   device, bf16 [batch][ldx], 16-byte aligned, ldx >= cols, ldx a multiple of 8; 1 <= batch <= 16.
  *   y   device, float32 [batch][ldy], ldy >= rows.  Float32 accumulation in a fixed order
- *       (deterministic for a given shape and batch).  Weights are the float32 values gain * y, except in
- *       the pass that takes 3..16 vectors at once on the matrix cores (D = 8 with 24-bit indices and
- *       rows of 256 or more groups, a multiple of 64), where each weight enters as the sum of two bf16 terms
- *       (relative error below 2^-14; products with the bf16 activations exact in float32).
+ *       (deterministic for a given shape and batch).  Every pass multiplies the float32 weights gain * y
+ *       exactly (products with bf16 activations are exact in float32): the pass that takes 3..16 vectors at
+ *       once on the matrix cores (D = 8 with 24-bit indices and rows of 256 or more groups, a multiple of 64)
+ *       feeds each weight as three bf16 terms whose sum is the float32 weight.  What depends on the batch
+ *       size a vector is submitted in is the order of the float32 additions only: y[b] of the same x can
+ *       differ between batch sizes by accumulation rounding (about 1e-7 of the root sum of squares of the
+ *       terms), never by the weights used.
  */
 int pvq_decode_gemv(const pvq_ctx *ctx, const uint32_t *index, const void *scale,
                     const float *rownorm, int64_t rows, int64_t cols, const void *x, int batch,

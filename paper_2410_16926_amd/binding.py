@@ -14,10 +14,13 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables", "pvq_rotate_encode", "pvq_correct", "pvq_correct_work_bytes",
-    "pvq_fast_tables_selftest", "pvq_size_table_device", "pvq_hadamard",
+    "pvq_size_table_device", "pvq_hadamard",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
 ]
+
+# host-only diagnostics declared in csrc/pvq_diagnostics.h, exported for the tests
+DIAGNOSTICS = ["pvq_fast_tables_selftest"]
 
 
 class PvqError(RuntimeError):

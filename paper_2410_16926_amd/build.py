@@ -33,25 +33,39 @@ def is_stale() -> bool:
     t = os.path.getmtime(LIB_PATH)
     deps = sources() + [os.path.join(_CSRC, "pvq_internal.h"), os.path.join(_CSRC, "pvq_fast8.h"),
                         os.path.join(_CSRC, "pvq_hadamard_dev.h"), os.path.join(_CSRC, "pvq_quantize_dev.h"),
+                        os.path.join(_CSRC, "pvq_diagnostics.h"),
                         os.path.join(_INC, "pvq.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile the library.  Always compiles unless force=False and it is up to date."""
-    if not force and not is_stale():
-        return LIB_PATH
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", f"-I{_INC}", f"-I{_CSRC}", "-o", LIB_PATH, *sources()]
-    if verbose:
-        print(" ".join(cmd))
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
+    return err
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    """Compile the library: every source to an object of its own (side by side), then one link.
+    Always compiles unless force=False and the library is up to date."""
+    if not force and not is_stale():
+        return LIB_PATH
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    jobs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        jobs.append((obj, [hipcc, *compile_flags, "-x", "hip", f"-I{_INC}", f"-I{_CSRC}", "-c", src, "-o", obj]))
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+        errs = list(pool.map(lambda j: _run(j[1]), jobs))
+    errs.append(_run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB_PATH, *[j[0] for j in jobs]]))
+    if verbose:
+        print("\n".join(e for e in errs if e.strip()))
     return LIB_PATH
 
 

@@ -572,10 +572,12 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
 // k-blocks read 16 neighbouring groups (48 contiguous bytes of indices, one word of codes); the
 // activations of the same 8 columns, for vector l%16, are the other operand, loaded as they are (bf16)
 // from device memory, where the caches hold them.
-// Weights w = gain * y go in as two bf16 terms, hi = w cut to bf16 and lo = (w - hi) cut to bf16, one
-// instruction each: products with bf16 activations are exact in float32 and w is represented to
-// 2^-15, far inside the product's tolerance.  Float32 accumulation, in the instruction's own fixed
-// order.  The 16 x 16 results of the waves that share a row tile meet in LDS, four waves per phase,
+// Weights w = gain * y (float32) go in as three bf16 terms, one instruction each: hi = w cut to bf16,
+// mid = (w - hi) cut to bf16, lo = w - hi - mid.  Each cut keeps 8 of the 24 significant bits and each
+// difference is exact, so hi + mid + lo = w exactly (down to the float32 underflow range), and products
+// with bf16 activations are exact in float32: the pass multiplies the same float32 weights as the
+// vector-ALU kernels and differs from them only in the order of the float32 additions (the
+// instruction's own fixed order).  The 16 x 16 results of the waves that share a row tile meet in LDS, four waves per phase,
 // and are added in wave order (deterministic).
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -680,21 +682,28 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
                     float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]);
                     if constexpr (CODES) gain *= sqrtc_l[(codes >> (j * sb)) & ((1u << sb) - 1u)];
                     else gain *= __uint_as_float(cur.s[j]);
-                    uint32_t hi[4], lo[4];
+                    uint32_t hi[4], mid[4], lo[4];
 #pragma unroll
                     for (int p2 = 0; p2 < 4; p2++) {
                         const float w0 = gain * __uint_as_float(pr[j][p2] << 16);
                         const float w1 = gain * __uint_as_float(pr[j][p2] & 0xFFFF0000u);
                         const uint32_t u0 = __float_as_uint(w0), u1 = __float_as_uint(w1);
                         hi[p2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);      // upper halves: w cut to bf16
-                        const float l0 = w0 - __uint_as_float(u0 & 0xFFFF0000u);
-                        const float l1 = w1 - __uint_as_float(u1 & 0xFFFF0000u);
+                        const float m0 = w0 - __uint_as_float(u0 & 0xFFFF0000u);  // exact: 16 bits are left
+                        const float m1 = w1 - __uint_as_float(u1 & 0xFFFF0000u);
+                        const uint32_t v0 = __float_as_uint(m0), v1 = __float_as_uint(m1);
+                        mid[p2] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);
+                        const float l0 = m0 - __uint_as_float(v0 & 0xFFFF0000u);  // exact: 8 bits are left,
+                        const float l1 = m1 - __uint_as_float(v1 & 0xFFFF0000u);  // which a bf16 holds
                         lo[p2] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
                     }
-                    const uint4 hv = make_uint4(hi[0], hi[1], hi[2], hi[3]), lv = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    const uint4 hv = make_uint4(hi[0], hi[1], hi[2], hi[3]), mv = make_uint4(mid[0], mid[1], mid[2], mid[3]),
+                                lv = make_uint4(lo[0], lo[1], lo[2], lo[3]);
                     const bf16x8_t xb = __builtin_bit_cast(bf16x8_t, bx[j]);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hv), xb, acc, 0, 0, 0);
+                    // smallest terms first, so that they are not absorbed by the large ones one by one
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, lv), xb, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, mv), xb, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hv), xb, acc, 0, 0, 0);
                 }
                 cur = nxt;
             }

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "pvq.h"
+#include "pvq_diagnostics.h"
 #include "pvq_fast8.h"
 
 namespace {

@@ -74,20 +74,28 @@ def assert_decode_close(got_f32: np.ndarray, ref64: np.ndarray, rel=1e-6):
     assert ok.all(), f"{(~ok).sum()} weights off, worst rel {np.max(err / np.maximum(np.abs(ref64), 1e-300)):.3e}"
 
 
-def assert_gemv_close(y: np.ndarray, ref: np.ndarray, scale: np.ndarray = None, rel=1e-3):
-    """Per activation vector: ||y - ref||_2 <= rel * max(||ref||_2, ||scale||_2) and every element within
-    rel * (|ref_i| + max(rms(ref), scale_i)).  scale_i = sqrt(sum_c (w_ic x_c)^2), the root sum of squares
-    of the terms of output i: the size such a sum has when its terms do not cancel.  Without it (scale
-    None) the criterion is relative to ref alone, which a single output whose terms happen to cancel
-    cannot meet with any finite precision of the weights."""
+def assert_gemv_close(y: np.ndarray, ref: np.ndarray, scale: np.ndarray = None, rel=1e-3, rel_terms=1e-5):
+    """Per activation vector b, against ref = float64 matmul of the oracle's weights:
+      (1) ||y - ref||_2 <= rel * ||ref||_2
+      (2) |y_i - ref_i| <= rel * (|ref_i| + rms(ref))                      (1e-3 relative, config 4)
+      (3) |y_i - ref_i| <= rel_terms * s_i,  s_i = sqrt(sum_c (w_ic x_c)^2)  (with `scale` = s)
+    Every kernel behind pvq_decode_gemv multiplies the float32 weights gain*y exactly (products with bf16
+    activations are exact in float32; the matrix-core pass splits a weight into three bf16 terms that sum to
+    it) and accumulates in float32, so its error is accumulation rounding: a few 2^-24 of the partial sums,
+    about 1e-7 * s_i.  (3) pins that with a margin of 100; an error of 1e-4 in a gain or an amplitude, or a
+    weight cut to fewer than 17 significant bits, fails it.  (1) and (2) are the tolerance the workload
+    states; an output whose terms cancel to below 1e-3 of their size could fail (2) with correct arithmetic,
+    which none of the seeded cases does."""
     y = y.astype(np.float64)
     for b in range(ref.shape[0]):
         nrm = np.linalg.norm(ref[b])
         rms = nrm / np.sqrt(ref.shape[1])
-        s = np.zeros_like(ref[b]) if scale is None else scale[b]
-        bound = max(nrm, np.linalg.norm(s))
-        assert np.linalg.norm(y[b] - ref[b]) <= rel * bound, (b, np.linalg.norm(y[b] - ref[b]) / bound)
-        assert np.all(np.abs(y[b] - ref[b]) <= rel * (np.abs(ref[b]) + np.maximum(rms, s)))
+        d = np.abs(y[b] - ref[b])
+        assert np.linalg.norm(y[b] - ref[b]) <= rel * nrm, (b, np.linalg.norm(y[b] - ref[b]) / nrm)
+        assert np.all(d <= rel * (np.abs(ref[b]) + rms)), (b, float(np.max(d / (np.abs(ref[b]) + rms))))
+        if scale is not None:
+            worst = float(np.max(d / np.maximum(scale[b], 1e-300)))
+            assert np.all(d <= rel_terms * scale[b]), (b, worst)
 
 
 def product_scale(xf: np.ndarray, ref_weights: np.ndarray) -> np.ndarray:

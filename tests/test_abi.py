@@ -27,6 +27,15 @@ def test_header_and_library_agree_on_the_exports():
         assert getattr(L, n) is not None
 
 
+def test_diagnostics_are_declared_apart_from_the_public_header():
+    text = open(os.path.join(ROOT, "paper_2410_16926_amd", "csrc", "pvq_diagnostics.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    assert sorted(set(re.findall(r"\b(pvq_[a-z0-9_]+)\s*\(", text))) == sorted(pvq.DIAGNOSTICS)
+    assert not set(pvq.DIAGNOSTICS) & set(declared_functions())
+    for n in pvq.DIAGNOSTICS:
+        assert getattr(pvq.lib(), n) is not None
+
+
 def test_status_strings():
     L = pvq.lib()
     for code in (0, -1, -2, -3, -4, -5):

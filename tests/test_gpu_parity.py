@@ -409,7 +409,8 @@ def test_leading_dimensions_and_views():
     xv = gu.to_dev_bf16(xb)[:, :cols]
     y_big = torch.full((2, rows + 5), -3.0, dtype=torch.float32, device="cuda")
     pvq.pvq_decode_gemv(ctx, packed, xv, out=y_big[:, :rows])
-    gu.assert_gemv_close(y_big[:, :rows].cpu().numpy(), xf[:, :cols].astype(np.float64) @ ref.T)
+    gu.assert_gemv_close(y_big[:, :rows].cpu().numpy(), xf[:, :cols].astype(np.float64) @ ref.T,
+                         gu.product_scale(xf[:, :cols], ref))
     assert torch.all(y_big[:, rows:] == -3.0)
     ctx.close()
 

@@ -223,6 +223,23 @@ int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_
                 int64_t ldu, void *work, size_t work_bytes, void *stream);
 
 /*
+ * pvq_correct for callers that cannot allocate device memory or let a library allocate it: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, arithmetic
+ * and results as pvq_correct (bit for bit), without `work`: the t values of a panel go to a buffer that is
+ * part of the library's image on every GPU (static device memory, 4 MiB, held until the process ends),
+ * which bounds the rows of one call: rows <= *pvq_correct_static_max_rows (8192), else PVQ_E_UNSUPPORTED
+ * (rows are independent: a taller matrix is corrected in slices of rows, one call after the other).
+ * The call makes no hipMalloc / hipFree, no stream and no event: all kernels run on `stream`, one chunk of
+ * rows (pvq_correct runs up to four chunks side by side on streams it creates at its first call).
+ * Nothing in the buffer has to start at zero: every value read has been written by the same call.
+ * All calls on one GPU share that GPU's buffer: two calls that overlap in time on one GPU (different
+ * streams or threads) race and give wrong results; calls on one stream, or ordered by events, are safe.
+ */
+int pvq_correct_static_max_rows(int64_t *rows);
+int pvq_correct_static(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                       int64_t ldu, void *stream);
+
+/*
  * Rotation and encoding of activations in one pass (Sec. 3.3 Step 1 in front of Sec. 2.5 / App. B.2): every
  * row of X is rotated as by pvq_hadamard(X, ..., block, signs, inverse = 0, float32 result) and the rotated
  * float32 values are encoded as by pvq_encode, without being written: index_out and scale_out receive

@@ -14,6 +14,7 @@ PVQ_F32, PVQ_F16, PVQ_BF16 = 0, 1, 2
 
 EXPORTS = [
     "pvq_strerror", "pvq_last_hip_error", "pvq_count", "pvq_max_k", "pvq_beta_tables", "pvq_rotate_encode", "pvq_correct", "pvq_correct_work_bytes",
+    "pvq_correct_static", "pvq_correct_static_max_rows",
     "pvq_size_table_device", "pvq_hadamard",
     "pvq_ctx_create", "pvq_ctx_destroy", "pvq_ctx_info", "pvq_ctx_set_amplitude", "pvq_packed_sizes",
     "pvq_encode", "pvq_decode", "pvq_decode_gemv",
@@ -66,6 +67,8 @@ def lib():
         L.pvq_rotate_encode.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
         L.pvq_correct_work_bytes.argtypes = [i64, vp]
         L.pvq_correct.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, C.c_size_t, vp]
+        L.pvq_correct_static_max_rows.argtypes = [vp]
+        L.pvq_correct_static.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
         L.pvq_decode_gemv.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp]
         _lib = L
@@ -281,6 +284,25 @@ def pvq_correct(ctx: PvqContext, W, U, work=None):
     ldu = U.stride(0) if cols > 1 else 1
     _check(lib().pvq_correct(ctx.handle, _ptr(W), rows, cols, ldw, _ptr(U), ldu, _ptr(work), work.numel(),
                              _stream_ptr()), "pvq_correct")
+    return W
+
+
+def pvq_correct_static_max_rows() -> int:
+    n = C.c_int64(0)
+    _check(lib().pvq_correct_static_max_rows(C.byref(n)), "pvq_correct_static_max_rows")
+    return n.value
+
+
+def pvq_correct_static(ctx: PvqContext, W, U):
+    """pvq_correct with the library's static work buffer: no allocation, the caller's stream only, at most
+    pvq_correct_static_max_rows() rows.  Returns W."""
+    import torch
+    rows, cols = W.shape
+    assert W.dtype == torch.float32 and U.dtype == torch.float32 and tuple(U.shape) == (cols, cols)
+    ldw = W.stride(0) if rows > 1 else max(cols, 1)
+    ldu = U.stride(0) if cols > 1 else 1
+    _check(lib().pvq_correct_static(ctx.handle, _ptr(W), rows, cols, ldw, _ptr(U), ldu, _stream_ptr()),
+           "pvq_correct_static")
     return W
 
 

@@ -239,11 +239,13 @@ hipError_t make_side_streams(pvq_ctx *c)
 // side, the first on the caller's stream and the others on streams of the context that fork from and
 // join the caller's stream through events, so that one chunk's panel kernel runs beside another
 // chunk's trailing update.
-hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
-                              int64_t ldu, float *work, hipStream_t s)
+namespace {
+
+hipError_t launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                          int64_t ldu, float *work, hipStream_t s, int64_t max_chunks)
 {
     pvq_ctx *c = const_cast<pvq_ctx *>(cc);
-    const int64_t nch = std::max<int64_t>(1, std::min<int64_t>(1 + pvq_ctx::kSideStreams, rows / 512));
+    const int64_t nch = std::max<int64_t>(1, std::min<int64_t>(max_chunks, rows / 512));
     const int64_t chunk_rows = ((rows + nch - 1) / nch + kTile - 1) / kTile * kTile;
     std::lock_guard<std::mutex> hold(c->side_lock);   // the events below belong to one call at a time
     hipError_t e = hipSuccess;
@@ -284,4 +286,55 @@ hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t
         if (e == hipSuccess) e = j;
     }
     return e;
+}
+
+// Work buffer of the entry point that allocates nothing: the t values of a panel for up to kStaticRows rows
+// (128 floats per row), 4 MiB on every GPU that loads the library, until the process ends.
+constexpr int64_t kStaticRows = 8192;
+static __device__ __align__(256) float scratch[kStaticRows * kPanelCols];
+
+// The array's address on each device (in host code the array's name is only a stand-in for it), asked
+// for once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+float *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t scratch_on_current_device(float **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                              int64_t ldu, float *work, hipStream_t s)
+{
+    return launch_correct(cc, W, rows, cols, ldw, U, ldu, work, s, 1 + pvq_ctx::kSideStreams);
+}
+
+int64_t pvq_correct_static_max_rows(void) { return kStaticRows; }
+
+// The same chain of kernels with the library's own work buffer and on the caller's stream alone: one chunk
+// of rows, so no stream or event is made or used.
+hipError_t pvq_launch_correct_static(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw,
+                                     const float *U, int64_t ldu, hipStream_t s)
+{
+    if (rows > kStaticRows) return hipErrorInvalidValue;   // (the entry point has refused it already)
+    float *work = nullptr;
+    const hipError_t e = scratch_on_current_device(&work);
+    if (e != hipSuccess) return e;
+    return launch_correct(cc, W, rows, cols, ldw, U, ldu, work, s, 1);
 }

@@ -522,19 +522,50 @@ extern "C" int pvq_correct_work_bytes(int64_t rows, size_t *bytes)
     return PVQ_OK;
 }
 
-extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
-                           int64_t ldu, void *work, size_t work_bytes, void *stream)
+// what pvq_correct and pvq_correct_static check alike; *nothing_to_do for an empty matrix
+static int check_correct_args(const pvq_ctx *c, const float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                              int64_t ldu, bool *nothing_to_do)
 {
+    *nothing_to_do = false;
     int rc = check_shape(c, rows, cols);
     if (rc) return rc;
     // (column tiles of 128 are the second grid dimension of the update kernel: at most 65535 of them)
     if (c->wide || (c->D != 8 && c->D != 16 && c->D != 32) || cols % 64 || cols > (int64_t)1 << 22) return PVQ_E_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return PVQ_OK;
-    if (!W || !U || !work || ldw < cols || ldu < cols) return PVQ_E_INVALID_ARG;
-    if (work_bytes < (size_t)rows * 128 * sizeof(float)) return PVQ_E_INVALID_ARG;
-    if (!aligned(W, 16) || ldw % 4 || !aligned(U, 16) || ldu % 4 || !aligned(work, 16)) return PVQ_E_ALIGNMENT;
+    if (rows == 0 || cols == 0) { *nothing_to_do = true; return PVQ_OK; }
+    if (!W || !U || ldw < cols || ldu < cols) return PVQ_E_INVALID_ARG;
+    if (!aligned(W, 16) || ldw % 4 || !aligned(U, 16) || ldu % 4) return PVQ_E_ALIGNMENT;
+    return PVQ_OK;
+}
+
+extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                           int64_t ldu, void *work, size_t work_bytes, void *stream)
+{
+    bool empty;
+    int rc = check_correct_args(c, W, rows, cols, ldw, U, ldu, &empty);
+    if (rc || empty) return rc;
+    if (!work || work_bytes < (size_t)rows * 128 * sizeof(float)) return PVQ_E_INVALID_ARG;
+    if (!aligned(work, 16)) return PVQ_E_ALIGNMENT;
     if ((rc = check_device(c))) return rc;
     const hipError_t e = pvq_launch_correct(c, W, rows, cols, ldw, U, ldu, (float *)work, (hipStream_t)stream);
+    return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
+extern "C" int pvq_correct_static_max_rows(int64_t *rows)
+{
+    if (!rows) return PVQ_E_INVALID_ARG;
+    *rows = pvq_correct_static_max_rows();
+    return PVQ_OK;
+}
+
+extern "C" int pvq_correct_static(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                                  int64_t ldu, void *stream)
+{
+    bool empty;
+    int rc = check_correct_args(c, W, rows, cols, ldw, U, ldu, &empty);
+    if (rc || empty) return rc;
+    if (rows > pvq_correct_static_max_rows()) return PVQ_E_UNSUPPORTED;   // more rows than the static buffer holds
+    if ((rc = check_device(c))) return rc;
+    const hipError_t e = pvq_launch_correct_static(c, W, rows, cols, ldw, U, ldu, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 

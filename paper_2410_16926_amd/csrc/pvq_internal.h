@@ -97,12 +97,16 @@ hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int d
 hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
 
-hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s);
+hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s);   // p[0..n) = 0 by a kernel
 
 // error correction of Sec. 3.3 Step 6 (pvq_correct.hip): W rows x cols float32 in place, cols a multiple
 // of 64, U cols x cols upper triangular, work rows x 128 floats
 hipError_t pvq_launch_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
-                              int64_t ldu, float *work, hipStream_t s);   // p[0..n) = 0 by a kernel
+                              int64_t ldu, float *work, hipStream_t s);
+// the same with the library's static work buffer (at most pvq_correct_static_max_rows() rows), on `s` alone
+int64_t pvq_correct_static_max_rows(void);
+hipError_t pvq_launch_correct_static(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw,
+                                     const float *U, int64_t ldu, hipStream_t s);
 
 // size table on the GPU (pvq_size_table.hip): (D+1) x (K+1) entries of `words` words, one workgroup
 hipError_t pvq_launch_size_table(int D, int K, int words, uint32_t *table, uint32_t *overflow, hipStream_t s);

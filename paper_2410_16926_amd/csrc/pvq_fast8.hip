@@ -405,6 +405,143 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_kernel(fast8_launch f, pvq
     }
 }
 
+// One vector, no barriers: every wave works alone.  A wave owns the rows  wave, wave + 16, ...  of its
+// workgroup's range and takes them slice by slice (a slice = 256 groups, lane l: groups 4l .. 4l+3): all
+// its rows of slice 0, then all of slice 1, ...  So the activations in registers are those of one slice
+// (16 registers, reloaded when the slice changes), a row's partial sums are added up by the one wave that
+// owns the row (its lane 63 adds each slice's sum, formed inside the wave, to a float of its own in LDS, in
+// slice order: deterministic), and after the table copy nothing makes the sixteen waves of a unit meet:
+// they drift apart, and their table lookups come spread out instead of in bursts after every barrier.
+// S0 runs one item ahead with its block entries through the vector cache, as in gemv8_kernel<1, ., ., true>
+// (tables in the flavour that keeps S0's block table outside LDS).  Rows of whole slices; AMP as in
+// gemv8_kernel.
+constexpr int kRowMaxRowsPerWave = 32;   // partial sums in LDS: 16 waves x 32 rows
+
+template <int AMP, bool B24>
+__global__ __launch_bounds__(kGemvThreads) void gemv8_row_kernel(fast8_launch f, pvq_decode_args a, int b0,
+                                                                 int rows_per_block, int nsl)
+{
+    constexpr bool CODES = AMP != 0;
+    constexpr int kWaves = kGemvThreads / kWave;
+    __shared__ __align__(16) unsigned char lds[kLdsBytes];
+    float *sqrtc_l = reinterpret_cast<float *>(lds + (AMP == 2 ? f.p.lds_bytes : f.p.tab_bytes));
+    float *part = sqrtc_l + (AMP == 2 ? ((f.p.k2max + 1) << f.scale_bits) : 256);
+
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = std::min<int64_t>(a.rows, r_begin + rows_per_block);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // this wave's rows: r_begin + wave + 16 i, i < nrows; its items: (slice, row) pairs, rows innermost
+    const int nrows = r_begin + wave < r_end ? (int)((r_end - r_begin - wave + kWaves - 1) / kWaves) : 0;
+    const int nitems = nrows * nsl;
+    const int gl = lane * kGroupsPerLane;             // the lane's first group inside a slice
+    float *mine = part + wave * kRowMaxRowsPerWave;
+
+    // byte offsets of the lane's quad inside slice 0 of a row of the planes; a slice further on adds a constant
+    const quad_offsets q0 = make_quad_offsets<CODES, B24>(f, gl, true);
+    const uint32_t index_step = B24 ? (uint32_t)(kTileGroups / 4) * 12u : 0u;
+    const uint32_t scale_step = CODES ? (uint32_t)(kTileGroups / 32) * 4u * (uint32_t)f.scale_bits : (uint32_t)kTileGroups * 4u;
+
+    // the stream of fetches: item after item, (slice, row) kept as scalars; past the last item the last one is
+    // read again (nothing of it is kept)
+    int f_sl = 0, f_i = 0;
+    auto fetch_next = [&](quad_item_t<CODES> &it) {
+        quad_offsets o;
+        o.index = q0.index + (uint32_t)f_sl * index_step;
+        o.scale = q0.scale + (uint32_t)f_sl * scale_step;
+        fetch_quad<CODES, B24>(f, a, r_begin + wave + (int64_t)kWaves * f_i, f_sl * kTileGroups + gl, true, o, it);
+        if (f_i + 1 < nrows) f_i++;
+        else if (f_sl + 1 < nsl) { f_i = 0; f_sl++; }
+    };
+
+    quad_item_t<CODES> raw[2];
+    if (nitems > 0) { fetch_next(raw[0]); fetch_next(raw[1]); }
+    if (lane < kRowMaxRowsPerWave) mine[lane] = 0.0f;
+    load_tables<AMP == 2>(lds, f, sqrtc_l);          // ends with the kernel's only barrier before the last one
+
+    if (nitems > 0) {
+        struct ahead_t {
+            quad_split_t<CODES> q;
+            uint32_t r[kGroupsPerLane];
+            pvq_u32x4 b[kGroupsPerLane];
+        };
+        // takes the raw item out of set `slot` (an item of slice `sl`), refills the set from the stream, and
+        // starts S0 for the item taken
+        auto start_item = [&](int slot, int sl, ahead_t &n) {
+            split_quad<CODES, B24>(f, sl * kTileGroups + gl, raw[slot], n.q);
+            fetch_next(raw[slot]);
+            uint32_t addr[kGroupsPerLane];
+            pvq_fast8_s0_find<kGroupsPerLane, true>(lds, f.p, n.q.c, n.r, addr);
+#pragma unroll
+            for (int j = 0; j < kGroupsPerLane; j++) n.b[j] = *reinterpret_cast<const pvq_u32x4 *>(f.blob + addr[j]);
+        };
+        // (slice, row) of the item being decoded and of the one after it
+        int c_sl = 0, c_i = 0, n_sl = 0, n_i = 0;
+        auto advance = [&](int &sl, int &i) {
+            if (i + 1 < nrows) i++;
+            else { i = 0; sl++; }
+        };
+        ahead_t nx;
+        start_item(0, 0, nx);
+        advance(n_sl, n_i);
+
+        uint32_t xr[16];
+        int x_sl = -1;
+        for (int it = 0; it < nitems; it += 2) {
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                if (it + h < nitems) {
+                    ahead_t cu = nx;
+                    // item it + h + 1 sits in set (h + 1) % 2
+                    start_item((h + 1) % 2, std::min(n_sl, nsl - 1), nx);
+                    advance(n_sl, n_i);
+                    if (c_sl != x_sl) {
+                        const uint16_t *xp = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)b0 * a.ldx +
+                                             (int64_t)(c_sl * kTileGroups + gl) * 8;
+#pragma unroll
+                        for (int j = 0; j < 4; j++) {
+                            const uint4 v = *reinterpret_cast<const uint4 *>(xp + 8 * j);
+                            xr[4 * j] = v.x; xr[4 * j + 1] = v.y; xr[4 * j + 2] = v.z; xr[4 * j + 3] = v.w;
+                        }
+                        x_sl = c_sl;
+                    }
+                    uint32_t n2x4[kGroupsPerLane];
+                    float dot[kGroupsPerLane];
+                    auto emit = [&](int j, int pair, uint32_t w) {
+                        dot[j] = dot2_bf16(w, xr[4 * j + pair], pair == 0 ? 0.0f : dot[j]);
+                    };
+                    pvq_fast8_rest<kGroupsPerLane, true>(lds, f.blob, f.p, cu.r, cu.b, emit, n2x4);
+                    float acc = 0.0f;
+                    const uint32_t codes4 = cu.q.codes << 2;
+#pragma unroll
+                    for (int j = 0; j < kGroupsPerLane; j++) {
+                        float gain;
+                        if constexpr (AMP == 2) {
+                            const uint32_t code4 = (codes4 >> (j * f.scale_bits)) & (((1u << f.scale_bits) - 1u) << 2);
+                            gain = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(sqrtc_l) +
+                                                                    ((n2x4[j] << f.scale_bits) + code4));
+                        } else {
+                            gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]) *
+                                   amp_factor<CODES>(f, cu.q, j, sqrtc_l);
+                        }
+                        acc = fmaf(gain, dot[j], acc);
+                    }
+                    const float v = wave_sum_lane63(acc);
+                    // one lane, one address per row, slices in order: a plain sum in a fixed order
+                    if (lane == kWave - 1) atomicAdd(&mine[c_i], v);
+                    advance(c_sl, c_i);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (lane < nrows) {
+        const int64_t row = r_begin + wave + (int64_t)kWaves * lane;
+        const float v = mine[lane];
+        a.y[(int64_t)b0 * a.ldy + row] = CODES ? v * sqrtf(a.rownorm[row]) : v;
+    }
+}
+
 // Sums of 16 per-lane values over the 64 lanes, all 16 at once: at each of the first four steps a lane
 // hands half of its values to the partner lane (lane ^ 1, 2, 4, 8) and adds the partner's other half
 // to the ones it keeps, so the work halves every step (8 + 4 + 2 + 1 additions instead of 16 per
@@ -942,6 +1079,38 @@ hipError_t launch_gemv_pass(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
     return launch_gemv_nb<NB, AHEAD>(f, a, b0, nsl, rl, rows_per_block, grid, block, lds, s);
 }
 
+constexpr size_t kRowPartBytes = (kGemvThreads / kWave) * kRowMaxRowsPerWave * sizeof(float);
+
+// the fused gain table (amplitude codes of at most 2 bits) must fit behind the tables with the partial sums
+bool row_fused(const fast8_launch &f)
+{
+    const size_t fused_bytes = ((size_t)(f.p.k2max + 1) << f.scale_bits) * 4;
+    return f.scale_bits > 0 && f.scale_bits <= 2 && f.p.lds_bytes + fused_bytes + kRowPartBytes <= (size_t)kLdsBytes;
+}
+
+// one launch of the barrier-free single-vector kernel for vector b0
+hipError_t launch_gemv_row(const pvq_ctx *c, const pvq_decode_args &a, int b0, hipStream_t s)
+{
+    const fast8_launch f = make_launch(c, true);
+    constexpr int kWaves = kGemvThreads / kWave;
+    const int64_t units = g_num_cus > 0 ? g_num_cus : 256;
+    // whole rounds of sixteen rows per workgroup, at most 32 rounds (the partial sums' place in LDS)
+    const int64_t rounds = (a.rows + kWaves - 1) / kWaves;
+    const int64_t nblocks = std::max<int64_t>(std::min<int64_t>(units, rounds), (rounds + kRowMaxRowsPerWave - 1) / kRowMaxRowsPerWave);
+    const int rows_per_block = (int)(((rounds + nblocks - 1) / nblocks) * kWaves);
+    const dim3 grid((unsigned)((a.rows + rows_per_block - 1) / rows_per_block)), block((unsigned)kGemvThreads);
+    const int nsl = (int)(a.groups / kTileGroups);
+    const bool b24 = f.index_bits == 24;
+    const int amp = f.scale_bits == 0 ? 0 : (row_fused(f) ? 2 : 1);
+#define PVQ_ROW_CASE(AMP, B24) \
+    hipLaunchKernelGGL((gemv8_row_kernel<AMP, B24>), grid, block, 0, s, f, a, b0, rows_per_block, nsl)
+    if (amp == 2) { if (b24) PVQ_ROW_CASE(2, true); else PVQ_ROW_CASE(2, false); }
+    else if (amp == 1) { if (b24) PVQ_ROW_CASE(1, true); else PVQ_ROW_CASE(1, false); }
+    else { if (b24) PVQ_ROW_CASE(0, true); else PVQ_ROW_CASE(0, false); }
+#undef PVQ_ROW_CASE
+    return hipGetLastError();
+}
+
 }  // namespace
 
 namespace {
@@ -997,6 +1166,15 @@ bool wide_usable(const pvq_ctx *c, const pvq_decode_args &a)
            (size_t)c->fast8.tab_bytes + 256 * sizeof(float) + kWidePartBytes <= (size_t)kLdsBytes;
 }
 
+// the barrier-free kernel takes rows of whole slices of 256 groups, and pays off when every wave of every
+// unit gets a few rows
+bool row_usable(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    const int64_t units = g_num_cus > 0 ? g_num_cus : 256;
+    return a.groups % kTileGroups == 0 && a.groups / kTileGroups <= 4096 && a.rows >= units * 16 * 2 &&
+           (size_t)c->fast8g.tab_bytes + 256 * sizeof(float) + kRowPartBytes <= (size_t)kLdsBytes;
+}
+
 }  // namespace
 
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
@@ -1008,14 +1186,16 @@ hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hip
     while (b0 < a.batch) {
         const int left = a.batch - b0;
         hipError_t e;
-        // measured on the benchmark shape: 1 vector 84 us, 2 vectors 91 us and 4 vectors 111..125 us on the
-        // vector-ALU kernels; the matrix-core pass takes 105..117 us whatever the count, so it takes three
-        // vectors and more.  Where it cannot run, one 16-vector pass (about 215 us) beats two or more
-        // 4-vector passes from eight vectors on.
+        // measured on the benchmark shape: 1 vector 78 us on the barrier-free kernel (84 us with row batches and
+        // partial sums through LDS, which remains for short matrices and rows that are not whole slices),
+        // 2 vectors 91 us and 4 vectors 111..125 us on the vector-ALU kernels; the matrix-core pass takes
+        // 105..117 us whatever the count, so it takes three vectors and more.  Where it cannot run, one
+        // 16-vector pass (about 215 us) beats two or more 4-vector passes from eight vectors on.
         if (left >= 3 && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
         else if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
         else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
         else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
+        else if (ahead && row_usable(c, a)) { e = launch_gemv_row(c, a, b0, s); b0 += 1; }
         else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }
         if (e != hipSuccess) return e;
     }

@@ -78,6 +78,16 @@ def test_d8_other_pulse_counts(K, bits):
     run_case(wf, 8, K, bits, src_bits=wb, batches=(1, 2, 5))
 
 
+@pytest.mark.parametrize("rows,cols,K,bits", [(8192 + 21, 2048, 16, 2), (8192, 4096, 16, 0), (8200, 2048, 16, 8),
+                                              (8192 + 5, 2048, 13, 2), (8192 + 16, 6144, 16, 2)])
+def test_single_vector_on_tall_matrices(rows, cols, K, bits):
+    # from 8192 rows on (32 per wave of a 256-unit GPU) and rows of whole slices of 256 groups, one vector goes
+    # to the kernel in which every wave owns whole rows: a last workgroup with fewer rows, one to three
+    # slices, fused gain table / amplitude table / float32 amplitudes, indices that are not 24 bits wide
+    wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 80 + rows + cols + K, bf16=True)
+    run_case(wf, 8, K, bits, src_bits=wb, batches=(1, 2), out_dtypes=())
+
+
 @pytest.mark.parametrize("D,budget,bits,bf16", [(8, 24, 0, True), (8, 24, 2, True), (8, 24, 8, False),
                                                 (16, 52, 0, False), (16, 52, 4, True), (32, 104, 0, True)])
 def test_least_squares_amplitudes(D, budget, bits, bf16):

@@ -9,7 +9,10 @@ planes so that the fused product reads its codes from HBM rather than from the l
 
 Prints ONE JSON line.  `value` is the fused decode+GEMV's algorithmic bandwidth at batch 1
 (bytes the method must move per launch / the kernel's mean duration inside the timed steps, HIP
-events on the launch stream); the other kernels' rates are extra keys of the same line.
+events on the launch stream); the other kernels' rates are extra keys of the same line, and so are,
+timed after the steps, the benchmark's other workloads (`configs`: the 14336 x 4096 matrix with 8-bit
+amplitude codes, with groups of 16 and 32, decode-only over the seven Llama-3-70B shapes) and the
+device's plain copy rate.
 """
 from __future__ import annotations
 
@@ -64,10 +67,14 @@ def cpu_baseline(wf_rows, xf, K, threads):
     }
 
 
+TRAFFIC_FILE = "profiles/hbm_traffic_gate_70b.txt"
+
+
 def read_traffic(kernel="gemv_b1"):
-    """HBM bytes per launch of a kernel from the committed counter summary (rocprofv3 --pmc FETCH_SIZE
-    and WRITE_SIZE runs, scaled by a copy of known size; see the file), or None if it is not there."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_gate_70b.txt")
+    """HBM bytes per launch of a kernel from the COMMITTED counter summary (rocprofv3 --pmc FETCH_SIZE
+    and WRITE_SIZE runs, scaled by a copy of known size; see the file), or None if it is not there.
+    Not measured by this run: counters need the profiler."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     try:
         with open(path) as f:
             for line in f:
@@ -78,6 +85,105 @@ def read_traffic(kernel="gemv_b1"):
     return None
 
 
+def timed_ms(torch, fn, reps=10, warm=2):
+    """Mean duration of fn() in ms: HIP events on the current stream around each call."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    for i in range(reps):
+        ev[i].record(); fn()
+    ev[reps].record(); torch.cuda.synchronize()
+    return sum(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) / reps
+
+
+def other_configs(torch, pvq, si, dev):
+    """The other workloads of the benchmark definition, timed after the steps (not part of ms_per_step):
+    config 1 (Llama-3-8B up projection, 8-bit amplitude codes, encode and decode), config 2 (the same matrix
+    with groups of 16 and 32, 52- and 104-bit indices), config 3 (decode only, to bf16, over the seven weight
+    shapes of a Llama-3-70B decoder layer at 3.25 bits per weight), and the device's own copy rate as the
+    practical ceiling of the HBM-bound kernels.  Rates are algorithmic bytes / mean kernel time."""
+    out = {}
+    gbps = lambda nbytes, t_ms: round(nbytes / (t_ms * 1e-3) / 1e9, 1)
+    gw = lambda n, t_ms: round(n / (t_ms * 1e-3) / 1e9, 2)
+
+    # what a plain copy and a plain fill reach on this device (256 MiB; bytes read + bytes written)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    t_copy = timed_ms(torch, lambda: dst.copy_(src))
+    t_fill = timed_ms(torch, lambda: dst.zero_())
+    out["device_copy_GBps"] = gbps(2 * src.numel(), t_copy)
+    out["device_fill_GBps"] = gbps(src.numel(), t_fill)
+    del src, dst
+
+    # config 1 and config 2: 14336 x 4096, bf16 source
+    r8, c8 = si.LLAMA3_8B_UP
+    W8 = si.gaussian_weights_device(r8, c8, 0.015, si.BASE_SEED + 1, dev)
+    Wo8 = torch.empty((r8, c8), dtype=torch.bfloat16, device=dev)
+    n8 = r8 * c8
+
+    def enc_dec(Dg, budget, sbits, label):
+        Kg = pvq.pvq_max_k(Dg, budget)
+        if sbits:
+            e, c = pvq.pvq_beta_tables(Dg, c8 // Dg, sbits)
+            cx = pvq.pvq_ctx_create(Dg, Kg, sbits, e, c)
+        else:
+            cx = pvq.pvq_ctx_create(Dg, Kg)
+        pk = pvq.alloc_packed(cx, r8, c8, dev)
+        te = timed_ms(torch, lambda: pvq.pvq_encode(cx, W8, out=pk), reps=5)
+        td = timed_ms(torch, lambda: pvq.pvq_decode(cx, pk, out=Wo8), reps=5)
+        G_ = c8 // Dg
+        codes = r8 * ((G_ * cx.index_bits + 31) // 32 * 4 + ((G_ * sbits + 31) // 32 * 4 if sbits else G_ * 4))
+        rown = r8 * 4 if sbits else 0
+        out[label] = {
+            "shape": [r8, c8], "D": Dg, "K": Kg, "index_bits": cx.index_bits, "scale_bits": sbits,
+            "bits_per_weight": round(8.0 * codes / n8, 3),
+            "encode_ms": round(te, 4), "encode_gweights_per_s": gw(n8, te), "encode_GBps": gbps(2 * n8 + codes + rown, te),
+            "decode_ms": round(td, 4), "decode_gweights_per_s": gw(n8, td), "decode_GBps": gbps(2 * n8 + codes + rown, td),
+        }
+        cx.close()
+
+    enc_dec(8, 24, 8, "config1_llama3_8b_up_D8_8bit_codes")
+    enc_dec(16, 52, 0, "config2_D16_52bit_index_f32_amplitudes")
+    enc_dec(32, 104, 0, "config2_D32_104bit_index_f32_amplitudes")
+    del W8, Wo8
+
+    # config 3: decode only over the seven shapes (3.25 bits per weight: 24-bit index + 2-bit code per 8 weights)
+    K = pvq.pvq_max_k(8, 24)
+    ctxs, layers = {}, []
+    total_w = total_b = 0
+    for i, (name, (r, c)) in enumerate(si.LLAMA3_70B_SHAPES.items()):
+        if c not in ctxs:
+            e, cc = pvq.pvq_beta_tables(8, c // 8, 2)
+            ctxs[c] = pvq.pvq_ctx_create(8, K, 2, e, cc)
+        Wl = si.gaussian_weights_device(r, c, 0.015, si.BASE_SEED + 30 + i, dev)
+        pk = pvq.pvq_encode(ctxs[c], Wl)
+        del Wl
+        nbytes = pk.index.numel() * 4 + pk.scale.numel() * 4 + r * 4 + 2 * r * c
+        layers.append((name, r, c, pk, nbytes))
+        total_w += r * c
+        total_b += nbytes
+    biggest = max(r * c for _, r, c, _, _ in layers)
+    Wo = torch.empty(biggest, dtype=torch.bfloat16, device=dev)
+
+    def decode_layer():
+        for _, r, c, pk, _ in layers:
+            pvq.pvq_decode(ctxs[c], pk, out=Wo[: r * c].view(r, c))
+    t_all = timed_ms(torch, decode_layer, reps=5)
+    per = {}
+    for name, r, c, pk, nbytes in layers:
+        t = timed_ms(torch, lambda: pvq.pvq_decode(ctxs[c], pk, out=Wo[: r * c].view(r, c)), reps=5)
+        per[name] = {"shape": [r, c], "ms": round(t, 4), "GBps": gbps(nbytes, t)}
+    out["config3_llama3_70b_layer_decode_bf16"] = {
+        "weights": total_w, "algorithmic_bytes": total_b, "ms": round(t_all, 4),
+        "gweights_per_s": gw(total_w, t_all), "GBps": gbps(total_b, t_all),
+        "frac_of_hbm_peak": round(total_b / (t_all * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "per_shape": per,
+    }
+    for cx in ctxs.values():
+        cx.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,7 +191,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's sample (0 = auto)")
-    ap.add_argument("--sets", type=int, default=3, help="sets of packed planes the steps rotate over")
+    ap.add_argument("--sets", type=int, default=4, help="sets of packed planes the steps rotate over")
     ap.add_argument("--only", default="", help="comma-separated subset of encode,decode,gemv_b1,gemv_b4,"
                     "gemv_b16 to run in the timed steps (profiling aid; the JSON line is then partial)")
     ap.add_argument("--steps-only", action="store_true",
@@ -94,6 +200,8 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="after the timed steps also time, on the same matrix: pvq_encode with least-squares "
                     "amplitudes, and the D=16 / 52-bit index / 4-bit amplitude setting (generic kernels)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="leave out the other workloads (configs 1-3) and the device copy rate that follow the steps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (256 MiB read + 256 MiB written), so "
                     "that a counter run can scale FETCH_SIZE / WRITE_SIZE against a kernel of known traffic")
@@ -138,9 +246,9 @@ def main():
     only = set(filter(None, args.only.split(",")))
     if only - set(names):
         sys.exit(f"bench.py: --only takes names from {names}")
-    if only:   # every set must hold valid codes before a partial step can run
-        for p in sets:
-            pvq.pvq_encode(ctx, W, out=p)
+    # every set holds valid codes before the first step: a step's products read other sets than the one it encodes
+    for p in sets:
+        pvq.pvq_encode(ctx, W, out=p)
 
     def step(i, events=None):
         p = sets[i % len(sets)]
@@ -153,8 +261,10 @@ def main():
             pvq.pvq_decode(ctx, p, out=Wout)
         if ev: ev[2].record()
         for j, B in enumerate(BATCHES):
+            # each product reads the set that has gone longest without being touched (all sets hold the same
+            # codes), so that its codes come from HBM and not from the last-level cache
             if not only or f"gemv_b{B}" in only:
-                pvq.pvq_decode_gemv(ctx, p, xs[B], out=ys[B])
+                pvq.pvq_decode_gemv(ctx, sets[(i + 1 + j) % len(sets)], xs[B], out=ys[B])
             if ev: ev[3 + j].record()
 
     if args.copy_calibration:
@@ -258,10 +368,31 @@ def main():
             "unit": "GB/s",
             "frac": round(gemv1 / HBM_PEAK_GBPS, 4),
             "traffic": read_traffic(),
+            "traffic_source": TRAFFIC_FILE + " (committed rocprofv3 counter summary of this kernel; "
+                              "not measured by this run)",
             "algorithmic_bytes_per_launch": ab[1]["gemv"],
         },
         "input_generation_s": round(t_gen, 1),
     }
+    # which kernels each batch size ran on, and its fraction of both roofs: HBM (algorithmic bytes) and the
+    # arithmetic unit of its path (fp32 vector ALU 157.3 TFLOP/s; dense bf16 matrix cores 2500 TFLOP/s, where a
+    # weight goes in as three bf16 terms, so the unit does three times the product's flops)
+    paths = {}
+    for B in BATCHES:
+        plan = pvq.pvq_decode_gemv_plan(ctx, ROWS, COLS, B)
+        t = ms[f"gemv_b{B}"]
+        flops = 2.0 * weights * B / (t * 1e-3) / 1e12
+        mfma = any(k.startswith("mfma") for k, _ in plan)
+        paths[f"b{B}"] = {
+            "passes": [f"{k} x{n}" for k, n in plan],
+            "frac_of_hbm_peak": round(gbps(ab[B]["gemv"], t) / HBM_PEAK_GBPS, 4),
+            "arithmetic_roof": "mfma_bf16" if mfma else "valu_fp32",
+            "frac_of_arithmetic_peak": round(3 * flops / 2500.0 if mfma else flops / 157.3, 4),
+            "binds": "neither: decoding (LDS table lookups and integer work)",
+        }
+    result["gemv_paths"] = paths
+    if not only and not args.steps_only and not args.no_configs:
+        result["configs"] = other_configs(torch, pvq, si, dev)
 
     if args.extras:
         def timed(fn, reps=5):

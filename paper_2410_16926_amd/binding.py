@@ -21,7 +21,7 @@ EXPORTS = [
 ]
 
 # host-only diagnostics declared in csrc/pvq_diagnostics.h, exported for the tests
-DIAGNOSTICS = ["pvq_fast_tables_selftest"]
+DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_decode_gemv_plan"]
 
 
 class PvqError(RuntimeError):
@@ -56,6 +56,7 @@ def lib():
         L.pvq_max_k.argtypes = [i32, i32, vp]
         L.pvq_beta_tables.argtypes = [i32, i64, i32, vp, vp]
         L.pvq_fast_tables_selftest.argtypes = [i32, C.c_uint64, C.c_uint64, vp]
+        L.pvq_decode_gemv_plan.argtypes = [vp, i64, i64, i32, vp, vp, i32, vp]
         L.pvq_size_table_device.argtypes = [i32, i32, i32, vp, vp, vp]
         L.pvq_hadamard.argtypes = [vp, i32, i64, i64, i64, i32, vp, i32, vp, i32, i64, vp]
         L.pvq_ctx_create.argtypes = [vp, i32, i32, i32, vp, vp]
@@ -116,6 +117,17 @@ def pvq_fast_tables_selftest(K: int, first: int = 0, count: int = 1 << 40) -> in
     bad = C.c_uint64()
     _check(lib().pvq_fast_tables_selftest(K, first, count, C.byref(bad)), "pvq_fast_tables_selftest")
     return bad.value
+
+
+PASS_KINDS = {0: "valu_fp32_generic", 1: "valu_fp32", 2: "valu_fp32_rows", 3: "valu_fp32_16", 4: "mfma_bf16x3"}
+
+
+def pvq_decode_gemv_plan(ctx, rows: int, cols: int, batch: int):
+    """[(kind name, vectors)] per pass that pvq_decode_gemv would launch (nothing is launched)."""
+    kinds, nvecs, n = (C.c_int * 16)(), (C.c_int * 16)(), C.c_int()
+    _check(lib().pvq_decode_gemv_plan(ctx.handle, rows, cols, batch, kinds, nvecs, 16, C.byref(n)),
+           "pvq_decode_gemv_plan")
+    return [(PASS_KINDS[kinds[i]], nvecs[i]) for i in range(n.value)]
 
 
 def pvq_size_table_device(D: int, K: int, words: int, device=None):

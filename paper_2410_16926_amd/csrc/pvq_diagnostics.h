@@ -18,6 +18,18 @@ extern "C" {
  */
 int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mismatches);
 
+/*
+ * Which kernels pvq_decode_gemv would launch for a rows x cols matrix of this context and `batch` vectors,
+ * without launching anything: kinds[i] and nvecs[i] (host arrays of max_passes entries) receive the kind of
+ * pass i (0 generic coordinate-by-coordinate kernel, 1 table-driven vector-ALU kernel, 2 the same with whole
+ * rows per wave, 3 the 16-vector vector-ALU kernel, 4 the matrix-core kernel) and the number of vectors it
+ * takes; *passes the number of passes.  For reports (a benchmark line that says which path a batch size
+ * took).  PVQ_E_INVALID_ARG for NULL pointers, a batch outside 1..16 or max_passes < the passes needed.
+ */
+struct pvq_ctx;
+int pvq_decode_gemv_plan(const struct pvq_ctx *ctx, int64_t rows, int64_t cols, int batch, int *kinds, int *nvecs,
+                         int max_passes, int *passes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1177,27 +1177,53 @@ bool row_usable(const pvq_ctx *c, const pvq_decode_args &a)
 
 }  // namespace
 
-hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
+// The passes that a product of a.batch vectors is made of, in order: which kernel takes how many vectors.
+int pvq_fast8_plan_gemv(const pvq_ctx *c, const pvq_decode_args &a, pvq_gemv_pass *out)
 {
     // a single vector runs S0 a row ahead (if the tables exist in that flavour); with more vectors
     // the registers go to the activations instead
     const bool ahead = c->fast8g_blob != nullptr;
-    int b0 = 0;
+    int n = 0, b0 = 0;
     while (b0 < a.batch) {
         const int left = a.batch - b0;
-        hipError_t e;
         // measured on the benchmark shape: 1 vector 78 us on the barrier-free kernel (84 us with row batches and
         // partial sums through LDS, which remains for short matrices and rows that are not whole slices),
         // 2 vectors 91 us and 4 vectors 111..125 us on the vector-ALU kernels; the matrix-core pass takes
         // 105..117 us whatever the count, so it takes three vectors and more.  Where it cannot run, one
         // 16-vector pass (about 215 us) beats two or more 4-vector passes from eight vectors on.
-        if (left >= 3 && mfma_usable(c, a)) { const int n = std::min(left, 16); e = launch_gemv_mfma(c, a, b0, n, s); b0 += n; }
-        else if (left >= 8 && wide_usable(c, a)) { const int n = std::min(left, kWide); e = launch_gemv_wide(c, a, b0, n, s); b0 += n; }
-        else if (left >= 4) { e = launch_gemv_pass<4, false>(c, a, b0, s); b0 += 4; }
-        else if (left >= 2) { e = launch_gemv_pass<2, false>(c, a, b0, s); b0 += 2; }
-        else if (ahead && row_usable(c, a)) { e = launch_gemv_row(c, a, b0, s); b0 += 1; }
-        else { e = ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s); b0 += 1; }
+        pvq_gemv_pass p;
+        if (left >= 3 && mfma_usable(c, a)) p = {PVQ_PASS_MFMA, std::min(left, 16)};
+        else if (left >= 8 && wide_usable(c, a)) p = {PVQ_PASS_VALU16, std::min(left, kWide)};
+        else if (left >= 4) p = {PVQ_PASS_VALU, 4};
+        else if (left >= 2) p = {PVQ_PASS_VALU, 2};
+        else if (ahead && row_usable(c, a)) p = {PVQ_PASS_VALU_ROWS, 1};
+        else p = {PVQ_PASS_VALU, 1};
+        out[n++] = p;
+        b0 += p.nvec;
+    }
+    return n;
+}
+
+hipError_t pvq_fast8_launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
+{
+    const bool ahead = c->fast8g_blob != nullptr;
+    pvq_gemv_pass plan[16];
+    const int n = pvq_fast8_plan_gemv(c, a, plan);
+    int b0 = 0;
+    for (int i = 0; i < n; i++) {
+        const int nvec = plan[i].nvec;
+        hipError_t e;
+        switch (plan[i].kind) {
+        case PVQ_PASS_MFMA: e = launch_gemv_mfma(c, a, b0, nvec, s); break;
+        case PVQ_PASS_VALU16: e = launch_gemv_wide(c, a, b0, nvec, s); break;
+        case PVQ_PASS_VALU_ROWS: e = launch_gemv_row(c, a, b0, s); break;
+        default:
+            e = nvec == 4 ? launch_gemv_pass<4, false>(c, a, b0, s)
+                : nvec == 2 ? launch_gemv_pass<2, false>(c, a, b0, s)
+                : ahead ? launch_gemv_pass<1, true>(c, a, b0, s) : launch_gemv_pass<1, false>(c, a, b0, s);
+        }
         if (e != hipSuccess) return e;
+        b0 += nvec;
     }
     return hipSuccess;
 }

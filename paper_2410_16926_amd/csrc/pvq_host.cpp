@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "pvq_internal.h"
+#include "pvq_diagnostics.h"
 
 // ------------------------------------------------------------------------------------------
 // status
@@ -631,4 +632,24 @@ extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const vo
     hipError_t e = pvq_fast8_gemv_usable(c, a) ? pvq_fast8_launch_gemv(c, a, (hipStream_t)stream)
                                                : pvq_launch_decode_gemv(c, a, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
+}
+
+extern "C" int pvq_decode_gemv_plan(const pvq_ctx *c, int64_t rows, int64_t cols, int batch, int *kinds, int *nvecs,
+                                    int max_passes, int *passes)
+{
+    int rc = check_shape(c, rows, cols);
+    if (rc) return rc;
+    if (!kinds || !nvecs || !passes || batch < 1 || batch > 16 || max_passes < 1) return PVQ_E_INVALID_ARG;
+    if (c->wide) return PVQ_E_UNSUPPORTED;
+    pvq_decode_args a;
+    memset(&a, 0, sizeof a);
+    a.rows = rows; a.cols = cols; a.groups = cols / c->D; a.batch = batch;
+    pvq_gemv_pass plan[16];
+    int n = 1;
+    plan[0] = {PVQ_PASS_GENERIC, batch};
+    if (pvq_fast8_gemv_usable(c, a)) n = pvq_fast8_plan_gemv(c, a, plan);
+    if (n > max_passes) return PVQ_E_INVALID_ARG;
+    for (int i = 0; i < n; i++) { kinds[i] = plan[i].kind; nvecs[i] = plan[i].nvec; }
+    *passes = n;
+    return PVQ_OK;
 }

@@ -132,4 +132,15 @@ bool pvq_fast8_decode_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
 bool pvq_fast8_gemv_usable(const pvq_ctx *ctx, const pvq_decode_args &a);
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
+// The passes of a fused product: which kind of kernel takes how many vectors (a batch of up to 16 vectors
+// is at most 16 passes).  pvq_fast8_plan_gemv fills out[] and returns the number of passes.
+enum {
+    PVQ_PASS_GENERIC = 0,     // pvq_kernels.hip: coordinate-by-coordinate decoder, vector ALU, one pass per call
+    PVQ_PASS_VALU = 1,        // gemv8_kernel: 1, 2 or 4 vectors, float32 multiply-adds on the vector ALU
+    PVQ_PASS_VALU_ROWS = 2,   // gemv8_row_kernel: one vector, every wave owns whole rows
+    PVQ_PASS_VALU16 = 3,      // gemv8_wide_kernel: up to 16 vectors on the vector ALU
+    PVQ_PASS_MFMA = 4,        // gemv8_mfma_kernel: 3..16 vectors, weights as three bf16 terms on the matrix cores
+};
+struct pvq_gemv_pass { int kind, nvec; };
+int pvq_fast8_plan_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, pvq_gemv_pass *out);
 hipError_t pvq_fast8_prepare(void);  // one-time device queries

@@ -595,3 +595,21 @@ def test_hadamard_argument_errors():
     with pytest.raises(pvq.PvqError):
         pvq.pvq_hadamard(X.to(torch.float16), 32)
     assert pvq.pvq_hadamard(torch.zeros((0, 96), dtype=torch.float32, device="cuda"), 32).shape == (0, 96)
+
+
+def test_the_plan_of_passes_names_the_kernels_that_run():
+    # host logic of the dispatch, asked through the diagnostics entry point (nothing is launched)
+    e, c = pvq.pvq_beta_tables(8, 1024, 2)
+    ctx = pvq.pvq_ctx_create(8, 16, 2, e, c)
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 1) == [("valu_fp32_rows", 1)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 4) == [("mfma_bf16x3", 4)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 16) == [("mfma_bf16x3", 16)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 2) == [("valu_fp32", 2)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 1024, 8192, 1) == [("valu_fp32", 1)]          # too few rows per wave
+    assert pvq.pvq_decode_gemv_plan(ctx, 96, 8 * 36, 7) == [("valu_fp32", 4), ("valu_fp32", 2), ("valu_fp32", 1)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 96, 8 * 37, 7) == [("valu_fp32_generic", 7)]   # lanes take whole quads of groups
+    assert sum(n for _, n in pvq.pvq_decode_gemv_plan(ctx, 512, 2048, 16)) == 16
+    ctx.close()
+    ctx = pvq.pvq_ctx_create(16, 33)
+    assert pvq.pvq_decode_gemv_plan(ctx, 512, 2048, 5) == [("valu_fp32_generic", 5)]
+    ctx.close()

@@ -33,7 +33,7 @@ def is_stale() -> bool:
     t = os.path.getmtime(LIB_PATH)
     deps = sources() + [os.path.join(_CSRC, "pvq_internal.h"), os.path.join(_CSRC, "pvq_fast8.h"),
                         os.path.join(_CSRC, "pvq_hadamard_dev.h"), os.path.join(_CSRC, "pvq_quantize_dev.h"),
-                        os.path.join(_CSRC, "pvq_diagnostics.h"),
+                        os.path.join(_CSRC, "pvq_diagnostics.h"), os.path.join(_CSRC, "pvq_small_table.h"),
                         os.path.join(_INC, "pvq.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 

@@ -10,40 +10,11 @@
 #include "pvq.h"
 #include "pvq_diagnostics.h"
 #include "pvq_fast8.h"
+#include "pvq_small_table.h"
 
 namespace {
 
-// N(d,k) for d <= 8, small k, in 64 bits (checked against 32-bit use by the caller)
-struct SmallTable {
-    int K;
-    std::vector<uint64_t> n;  // (9) x (K+1)
-    explicit SmallTable(int K_) : K(K_), n((size_t)9 * (K_ + 1))
-    {
-        for (int k = 0; k <= K; k++) at(0, k) = (k == 0);
-        for (int d = 1; d <= 8; d++) {
-            at(d, 0) = 1;
-            for (int k = 1; k <= K; k++) at(d, k) = at(d - 1, k) + at(d, k - 1) + at(d - 1, k - 1);
-        }
-    }
-    uint64_t &at(int d, int k) { return n[(size_t)d * (K + 1) + k]; }
-    uint64_t at(int d, int k) const { return n[(size_t)d * (K + 1) + k]; }
-};
-
-// coordinate values in the order the enumeration visits them: 0, +1, -1, ..., +k, -k
-std::vector<int> visiting_order(int k)
-{
-    std::vector<int> v{0};
-    for (int j = 1; j <= k; j++) { v.push_back(j); v.push_back(-j); }
-    return v;
-}
-
-uint32_t bf16_of_int(int v)
-{
-    float f = (float)v;
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    return u >> 16;  // exact: |v| <= 256 has at most 8 significant bits
-}
+using namespace pvq_small;
 
 struct Block {
     uint64_t start, size;
@@ -295,21 +266,8 @@ extern "C" int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, u
         else pvq_fast8_decode<1, true>(blob.data(), blob.data(), p, cc, pr, nn);
         const uint32_t *pairs = pr[0];
         const uint32_t n2x4 = nn[0];
-        // plain walk
-        int y[8], k = K;
-        uint64_t r = c;
-        for (int i = 0; i < 7; i++) {
-            const int dp = 7 - i;
-            y[i] = 0;
-            if (k == 0) continue;
-            if (r < N.at(dp, k)) continue;
-            r -= N.at(dp, k);
-            int j = 1;
-            while (j < k && r >= 2 * N.at(dp, k - j)) { r -= 2 * N.at(dp, k - j); j++; }
-            if (r < N.at(dp, k - j)) y[i] = j; else { y[i] = -j; r -= N.at(dp, k - j); }
-            k -= j;
-        }
-        y[7] = r == 0 ? k : -k;
+        int y[8];
+        plain_walk(N, K, c, y);
         int n2 = 0;
         bool same = true;
         for (int i = 0; i < 8; i++) {

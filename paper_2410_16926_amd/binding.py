@@ -21,7 +21,7 @@ EXPORTS = [
 ]
 
 # host-only diagnostics declared in csrc/pvq_diagnostics.h, exported for the tests
-DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_decode_gemv_plan"]
+DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_walk_tables_selftest", "pvq_decode_gemv_plan"]
 
 
 class PvqError(RuntimeError):
@@ -56,6 +56,7 @@ def lib():
         L.pvq_max_k.argtypes = [i32, i32, vp]
         L.pvq_beta_tables.argtypes = [i32, i64, i32, vp, vp]
         L.pvq_fast_tables_selftest.argtypes = [i32, C.c_uint64, C.c_uint64, vp]
+        L.pvq_walk_tables_selftest.argtypes = [i32, i32, C.c_uint64, C.c_uint64, vp, vp, vp]
         L.pvq_decode_gemv_plan.argtypes = [vp, i64, i64, i32, vp, vp, i32, vp]
         L.pvq_size_table_device.argtypes = [i32, i32, i32, vp, vp, vp]
         L.pvq_hadamard.argtypes = [vp, i32, i64, i64, i64, i32, vp, i32, vp, i32, i64, vp]
@@ -117,6 +118,14 @@ def pvq_fast_tables_selftest(K: int, first: int = 0, count: int = 1 << 40) -> in
     bad = C.c_uint64()
     _check(lib().pvq_fast_tables_selftest(K, first, count, C.byref(bad)), "pvq_fast_tables_selftest")
     return bad.value
+
+
+def pvq_walk_tables_selftest(D: int, K: int, seed: int = 1, count: int = 100000):
+    """(mismatches, (dA, dB), table bytes) of the host replay of the coordinate-by-coordinate decoder's tables."""
+    bad, sched, nbytes = C.c_uint64(), (C.c_int * 2)(), C.c_uint32()
+    _check(lib().pvq_walk_tables_selftest(D, K, seed, count, C.byref(bad), sched, C.byref(nbytes)),
+           "pvq_walk_tables_selftest")
+    return bad.value, (sched[0], sched[1]), nbytes.value
 
 
 PASS_KINDS = {0: "valu_fp32_generic", 1: "valu_fp32", 2: "valu_fp32_rows", 3: "valu_fp32_16", 4: "mfma_bf16x3"}

@@ -10,7 +10,7 @@ _INC = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libpvq.so")
 
 SOURCES = ["pvq_host.cpp", "pvq_fast8_tables.cpp", "pvq_kernels.hip", "pvq_fast8.hip",
-           "pvq_encode8.hip", "pvq_size_table.hip", "pvq_hadamard.hip", "pvq_wide.hip", "pvq_correct.hip"]
+           "pvq_encode8.hip", "pvq_size_table.hip", "pvq_hadamard.hip", "pvq_wide.hip", "pvq_correct.hip", "pvq_walk.hip"]
 
 # -ffp-contract=off: the encoder's float32 results are part of the format (no fused multiply-adds
 # unless written as fmaf); correctly rounded float32 division and square root likewise.
@@ -33,7 +33,7 @@ def is_stale() -> bool:
     t = os.path.getmtime(LIB_PATH)
     deps = sources() + [os.path.join(_CSRC, "pvq_internal.h"), os.path.join(_CSRC, "pvq_fast8.h"),
                         os.path.join(_CSRC, "pvq_hadamard_dev.h"), os.path.join(_CSRC, "pvq_quantize_dev.h"),
-                        os.path.join(_CSRC, "pvq_diagnostics.h"), os.path.join(_CSRC, "pvq_small_table.h"),
+                        os.path.join(_CSRC, "pvq_diagnostics.h"), os.path.join(_CSRC, "pvq_small_table.h"), os.path.join(_CSRC, "pvq_walk.h"),
                         os.path.join(_INC, "pvq.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 

@@ -19,6 +19,18 @@ extern "C" {
 int pvq_fast_tables_selftest(int K, uint64_t first, uint64_t count, uint64_t *mismatches);
 
 /*
+ * The coordinate-by-coordinate decoder with one table probe per coordinate (groups of 16 and 32, multi-word
+ * indices): builds its tables for (D, K) and replays the kernels' walk on the host for `count` indices (the
+ * first and last index, two in the middle, then seeded random ones, a third of them near the start of the
+ * range), comparing every decoded point with the magnitude-by-magnitude walk of App. B.3.  *mismatches (host)
+ * receives the number that differ; schedule (host, 2 ints, may be NULL) the width schedule chosen (the
+ * dimensions from which on half- and quarter-width integers are used, 0 = none), *table_bytes (may be NULL)
+ * the size of the tables.  PVQ_E_UNSUPPORTED for D outside {8, 16, 32} or indices beyond 128 bits.
+ */
+int pvq_walk_tables_selftest(int D, int K, uint64_t seed, uint64_t count, uint64_t *mismatches, int *schedule,
+                             uint32_t *table_bytes);
+
+/*
  * Which kernels pvq_decode_gemv would launch for a rows x cols matrix of this context and `batch` vectors,
  * without launching anything: kinds[i] and nvecs[i] (host arrays of max_passes entries) receive the kind of
  * pass i (0 generic coordinate-by-coordinate kernel, 1 table-driven vector-ALU kernel, 2 the same with whole

@@ -8,6 +8,7 @@
 
 #include "pvq_internal.h"
 #include "pvq_diagnostics.h"
+#include "pvq_walk.h"
 
 // ------------------------------------------------------------------------------------------
 // status
@@ -196,6 +197,90 @@ extern "C" int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, 
 }
 
 // ------------------------------------------------------------------------------------------
+// tables of the coordinate-by-coordinate decoder (pvq_walk.hip)
+// ------------------------------------------------------------------------------------------
+
+namespace {
+
+U512 shifted_left(const U512 &v, int n)   // n < 512; bits shifted out are lost
+{
+    U512 r;
+    const int limbs = n / 64, bits = n % 64;
+    for (int i = 7; i >= limbs; i--) {
+        uint64_t x = v.limb[i - limbs] << bits;
+        if (bits && i - limbs - 1 >= 0) x |= v.limb[i - limbs - 1] >> (64 - bits);
+        r.limb[i] = x;
+    }
+    return r;
+}
+
+bool less_or_equal(const U512 &a, const U512 &b)
+{
+    for (int i = 7; i >= 0; i--)
+        if (a.limb[i] != b.limb[i]) return a.limb[i] < b.limb[i];
+    return true;
+}
+
+// Lays the blob out (pvq_walk.h has the layout's formulas) and fills it: rows d' = 1 .. D-1 of U(d',x),
+// x = -1 .. K+1; guess rows for d' >= 2: entry 0 for q/2 = 0, entry 1 + (e << mb) + f for q/2 in
+// [2^e (1 + f / 2^mb), 2^e (1 + (f+1) / 2^mb)) = the number of x in [0, K] with U(d',x) <= that bucket's lower edge.
+bool build_walk_tables(const SizeTable &t, int D, int K, int words, std::vector<unsigned char> &blob, pvq_walk_params &p)
+{
+    using namespace pvq_walk;
+    if (D > 32 || K > 253) return false;
+    memset(&p, 0, sizeof p);
+    int fit_half = 0, fit_quarter = 0;
+    for (int d = 1; d < D; d++) {
+        if (words >= 2 && t.at(d, K).bit_length() <= 16 * words) fit_half = d;
+        if (words >= 4 && t.at(d, K).bit_length() <= 8 * words) fit_quarter = d;
+    }
+    pvq_walk_schedule(D, words, fit_half, fit_quarter, &p.dA, &p.dB);
+    if (p.dA > fit_half || p.dB > fit_quarter || p.dB > p.dA) return false;
+    p.K = K;
+    for (int cls = 0; cls < 3; cls++) p.row_bytes[cls] = (uint32_t)(((size_t)(K + 3) * ((4 * words) >> cls) + 15) / 16 * 16);
+    blob.clear();
+    // cumulative rows
+    std::vector<std::vector<U512>> U(D);
+    for (int dp = 1; dp < D; dp++) {
+        const int es = pvq_walk_entry_bits(dp, words, p.dA, p.dB) / 8;
+        U512 run;
+        for (int x = 0; x <= K; x++) { run.add(t.at(dp, x)); U[dp].push_back(run); }
+        if (run.bit_length() > 8 * es) return false;
+        const size_t first = blob.size();
+        blob.resize(first + p.row_bytes[pvq_walk_class(dp, p.dA, p.dB)], 0);
+        for (int x = 0; x <= K; x++)
+            for (int w = 0; w < es / 4; w++) {
+                const uint32_t v = U[dp][x].word(w);
+                memcpy(&blob[first + (size_t)(x + 1) * es + 4 * w], &v, 4);
+            }
+        memset(&blob[first + (size_t)(K + 2) * es], 0xFF, es);        // never <= q/2
+    }
+    // guess rows
+    p.guess_base = (uint32_t)blob.size();
+    for (int dp = 2; dp < D; dp++) {
+        const int mb = pvq_walk_mb(dp);
+        const int n = (int)pvq_walk_guess_entries(dp, pvq_walk_entry_bits(dp, words, p.dA, p.dB));
+        if (blob.size() != p.guess_base + pvq_walk_guess_offset(dp, words, p.dA, p.dB)) return false;
+        for (int idx = 0; idx < n; idx++) {
+            int count = 0;
+            if (idx >= 1) {
+                const int e = (idx - 1) >> mb, f = (idx - 1) & ((1 << mb) - 1);
+                // U <= (2^mb + f) 2^(e - mb)   <=>   U 2^mb <= (2^mb + f) 2^e
+                const U512 edge = shifted_left(U512::of((uint64_t)((1 << mb) + f)), e);
+                for (int x = 0; x <= K; x++)
+                    if (less_or_equal(shifted_left(U[dp][x], mb), edge)) count = x + 1;
+            }
+            blob.push_back((unsigned char)count);
+        }
+    }
+    blob.resize((blob.size() + 15) / 16 * 16);
+    p.bytes = (uint32_t)blob.size();
+    return true;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------
 
@@ -330,6 +415,14 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
             }
         }
     }
+    if (e == hipSuccess && !wide) {
+        std::vector<unsigned char> blob;
+        // the decoders of pvq_walk.hip keep these in LDS: every supported (D, K) fits
+        if (!build_walk_tables(t, D, K, words, blob, c->walk)) { pvq_ctx_destroy(c); return PVQ_E_UNSUPPORTED; }
+        e = hipMalloc((void **)&c->walk_blob, blob.size());
+        if (e == hipSuccess) e = hipMemcpy(c->walk_blob, blob.data(), blob.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pvq_walk_usable(c)) { pvq_ctx_destroy(c); return PVQ_E_UNSUPPORTED; }
+    }
     if (e == hipSuccess && D == 8 && bits == 24) {
         // What coordinate i (7-i dimensions after it) adds to the index when k pulses are left and it
         // takes magnitude m with the given sign (App. B.2):
@@ -360,7 +453,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[8] = {c->tab_n, c->tab_u, c->tab_c, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->enc8_offs};
+    void *ptrs[9] = {c->tab_n, c->tab_u, c->tab_c, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->walk_blob, c->enc8_offs};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);
@@ -601,7 +694,7 @@ extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *s
     a.W_out = W_out; a.ldw = ldw;
     hipError_t e = c->wide ? pvq_wide_launch_decode(c, a, out_dtype, (hipStream_t)stream)
                    : pvq_fast8_decode_usable(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
-                                                   : pvq_launch_decode(c, a, out_dtype, (hipStream_t)stream);
+                                                   : pvq_walk_launch_decode(c, a, out_dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
@@ -630,7 +723,7 @@ extern "C" int pvq_decode_gemv(const pvq_ctx *c, const uint32_t *index, const vo
     if ((rc = check_device(c))) return rc;
     a.x = x; a.batch = batch; a.ldx = ldx; a.y = y; a.ldy = ldy;
     hipError_t e = pvq_fast8_gemv_usable(c, a) ? pvq_fast8_launch_gemv(c, a, (hipStream_t)stream)
-                                               : pvq_launch_decode_gemv(c, a, (hipStream_t)stream);
+                                               : pvq_walk_launch_gemv(c, a, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
@@ -652,4 +745,89 @@ extern "C" int pvq_decode_gemv_plan(const pvq_ctx *c, int64_t rows, int64_t cols
     for (int i = 0; i < n; i++) { kinds[i] = plan[i].kind; nvecs[i] = plan[i].nvec; }
     *passes = n;
     return PVQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// host replay of the coordinate-by-coordinate decoder's tables
+// ------------------------------------------------------------------------------------------
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+u128 low128(const U512 &v) { return ((u128)v.limb[1] << 64) | v.limb[0]; }
+
+// App. B.3 as printed (with the corrections of the boundary's decode contract), in 128-bit integers
+void plain_unrank(const SizeTable &t, int D, int K, u128 c, int *y)
+{
+    int k = K;
+    u128 r = c;
+    for (int i = 0; i < D - 1; i++) {
+        const int dp = D - 1 - i;
+        y[i] = 0;
+        if (k == 0) continue;
+        if (r < low128(t.at(dp, k))) continue;
+        r -= low128(t.at(dp, k));
+        int j = 1;
+        while (j < k && r >= 2 * low128(t.at(dp, k - j))) { r -= 2 * low128(t.at(dp, k - j)); j++; }
+        if (r < low128(t.at(dp, k - j))) y[i] = j; else { y[i] = -j; r -= low128(t.at(dp, k - j)); }
+        k -= j;
+    }
+    y[D - 1] = r == 0 ? k : -k;
+}
+
+template <int D, int W, int DA, int DB>
+uint64_t replay_walk(const SizeTable &t, int K, const std::vector<unsigned char> &blob, const pvq_walk_params &p,
+                     uint64_t seed, uint64_t count)
+{
+    using T = typename pvq_walk::wide<W>::type;
+    const u128 total = low128(t.at(D, K));
+    uint64_t bad = 0, state = seed;
+    auto next64 = [&]() {   // splitmix64
+        uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    };
+    for (uint64_t n = 0; n < count; n++) {
+        u128 c;
+        if (n < 4) c = n == 0 ? 0 : n == 1 ? total - 1 : n == 2 ? total / 2 : total / 3;   // ends and middles first
+        else {
+            c = (((u128)next64() << 64) | next64()) % total;
+            // a third of the samples near the start of the range, where long runs of equal coordinates lie
+            if (n % 3 == 0) c >>= (next64() % 100);
+        }
+        int want[D], got[D];
+        plain_unrank(t, D, K, c, want);
+        int n2w = 0;
+        for (int i = 0; i < D; i++) n2w += want[i] * want[i];
+        const int n2 = pvq_walk::unrank_walk<D, W, DA, DB>((T)c, blob.data(), p, [&](int i, int v) { got[i] = v; });
+        bool same = n2 == n2w;
+        for (int i = 0; i < D; i++) same = same && got[i] == want[i];
+        bad += !same;
+    }
+    return bad;
+}
+
+}  // namespace
+
+extern "C" int pvq_walk_tables_selftest(int D, int K, uint64_t seed, uint64_t count, uint64_t *mismatches,
+                                        int *schedule, uint32_t *table_bytes)
+{
+    if (!mismatches) return PVQ_E_INVALID_ARG;
+    if ((D != 8 && D != 16 && D != 32) || K < 1 || K > 127) return PVQ_E_UNSUPPORTED;
+    SizeTable t(D, K);
+    if (t.overflow) return PVQ_E_UNSUPPORTED;
+    const int bits = t.index_bits();
+    if (bits < 1 || bits > 128 || t.at(D, K).bit_length() > 128) return PVQ_E_UNSUPPORTED;
+    const int words = bits <= 32 ? 1 : (bits <= 64 ? 2 : 4);
+    if (t.at(D, K).bit_length() > 32 * words) return PVQ_E_UNSUPPORTED;
+    std::vector<unsigned char> blob;
+    pvq_walk_params p;
+    if (!build_walk_tables(t, D, K, words, blob, p)) return PVQ_E_UNSUPPORTED;
+    if (schedule) { schedule[0] = p.dA; schedule[1] = p.dB; }
+    if (table_bytes) *table_bytes = p.bytes;
+#define PVQ_WALK_REPLAY(D_, W_, DA_, DB_) (*mismatches = replay_walk<D_, W_, DA_, DB_>(t, K, blob, p, seed, count), PVQ_OK)
+    PVQ_WALK_DISPATCH(PVQ_WALK_REPLAY, D, words, p.dA, p.dB);
+#undef PVQ_WALK_REPLAY
 }

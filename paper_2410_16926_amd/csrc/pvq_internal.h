@@ -10,6 +10,20 @@
 #include "pvq.h"
 #include "pvq_fast8.h"
 
+// Tables of the coordinate-by-coordinate decoder (pvq_walk.hip), one blob copied to LDS by every workgroup:
+// rows of the cumulative size table U(d', x) = N(d',0) + ... + N(d',x) for d' = 1 .. D-1 in this order, entries
+// x = -1 .. K+1 (U(d',-1) = 0; the entry behind the row is all ones), each row in the width of its dimension's
+// arithmetic and padded to a multiple of 16 bytes; behind them a guess row of bytes per d' >= 2.  Where a row
+// lies follows from the schedule (known when the kernels are compiled) and three row sizes, so that the
+// kernels carry a handful of scalars rather than an offset per row (pvq_walk.h: pvq_walk_row, pvq_walk_guess).
+struct pvq_walk_params {
+    uint32_t bytes;         // of the blob (a multiple of 16)
+    int K;
+    int dA, dB;             // the width schedule: dimensions above dA in `words` words, above dB in half, the rest in a quarter
+    uint32_t row_bytes[3];  // bytes of a cumulative row in full, half and quarter width
+    uint32_t guess_base;    // byte offset of the first guess row (d' = 2)
+};
+
 struct pvq_ctx {
     int D, K;
     int index_bits;
@@ -34,6 +48,9 @@ struct pvq_ctx {
     // that flavour does not fit).
     unsigned char *fast8_blob, *fast8g_blob;
     pvq_fast8_params fast8, fast8g;
+    // Coordinate-by-coordinate decoder's tables (every context with D <= 32); nullptr if they were not made.
+    unsigned char *walk_blob = nullptr;
+    pvq_walk_params walk;
     int amplitude;   // PVQ_AMP_NORM or PVQ_AMP_LS
     // Per-coordinate index offsets for the D = 8 / 24-bit encoder: [7][K+1][K+1][2] words
     // (coordinate, pulses left, magnitude, sign); nullptr when the configuration has none.
@@ -94,8 +111,6 @@ __device__ inline float pvq_ls_amplitude(const float (&w)[D], const int (&y)[D])
 
 // Each returns a hipError_t from the launch (hipSuccess if enqueued).
 hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
-hipError_t pvq_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
-hipError_t pvq_launch_decode_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
 
 hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s);   // p[0..n) = 0 by a kernel
 
@@ -122,6 +137,12 @@ hipError_t pvq_wide_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, 
 // rotation of rows (blocks of `block` values, optional signs) and encoding in one kernel; D = 128, words <= 12
 hipError_t pvq_wide_launch_rotate_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, int block,
                                          const uint8_t *signs, hipStream_t s);
+
+// coordinate-by-coordinate decoder with one table probe per coordinate (pvq_walk.hip)
+void pvq_walk_schedule(int D, int words, int fit_half, int fit_quarter, int *dA, int *dB);
+bool pvq_walk_usable(const pvq_ctx *ctx);
+hipError_t pvq_walk_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
+hipError_t pvq_walk_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);
 
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);

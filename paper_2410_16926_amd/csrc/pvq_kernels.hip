@@ -1,4 +1,5 @@
-// gfx950 kernels of libpvq: encode, decode, decode fused into a matrix-vector product.
+// gfx950 kernels of libpvq: the generic encoder (every group size and index width that has no kernel of its
+// own); the matching decoders are in pvq_walk.hip.
 //
 // Work mapping (wave64): one lane owns one group of D weights from load to store, so the group's
 // float32 sums are plain register trees with a fixed order, and the index arithmetic is a carry
@@ -16,7 +17,6 @@ namespace {
 using namespace pvq_quantize_dev;
 
 constexpr int kThreads = 256;
-constexpr int kWave = 64;
 
 template <int W> struct wide;
 template <> struct wide<1> { using type = uint32_t; };
@@ -255,188 +255,6 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(tables_t tb, pvq_encod
 }
 
 // ---------------------------------------------------------------------------------------------
-// decode
-// ---------------------------------------------------------------------------------------------
-
-// App. B.3 over the cumulative table alone.  With U(d,x) = N(d,0) + ... + N(d,x) (U(d,-1) = 0), the points
-// of P(d,k) whose first coordinate has magnitude below m >= 1 number  N(d,k) - 2 U(d-1,k-m)  (all points
-// minus those of magnitude m or more, two signs each), and N(d,k) = U(d-1,k) + U(d-1,k-1).  The lane keeps
-// q = N(d,k) - 1 - r for the residual r in the sub-pyramid still open.  The coordinate's magnitude is the
-// smallest m with 2 U(d-1,k-1-m) <= q, that is  m = k - #{x in [0,k-1] : U(d-1,x) <= q/2}: a binary search
-// in a row of the table (the same number of steps in every lane, whatever the magnitudes), instead of
-// one step per unit of magnitude.  For m = 0 the next q is q - 2 U(d-1,k-1); for m >= 1, with x = k-m and
-// N' = N(d-1,x) = U(d-1,x) - U(d-1,x-1):  v = q - 2 U(d-1,x) + N'  is the place inside the block of +-m counted
-// from the end of its first half: v >= 0 means +m and the next q is v, v < 0 means -m and the next q is
-// v + N'.  (|v| < N' <= N(D,K)/3, so the top bit of the W-word integer is a sign bit.)
-// tab_u is the LDS copy of the rows U(d', .), d' = 0..D-1, each shifted by one entry so that U(-1) is stored.
-// Every table read stays inside its row whatever the stored field holds.  Returns the sum of squares.
-template <int D, int W>
-__device__ inline int unrank_point(typename wide<W>::type c, int K,
-                                   const typename wide<W>::type *tab_u, int (&y)[D])
-{
-    using T = typename wide<W>::type;
-    int top = 1;                                   // largest power of two <= K (K >= 1)
-    while (2 * top <= K) top *= 2;
-    const T *u0 = tab_u + (D - 1) * (K + 2) + 1;   // u0[x] = U(D-1, x)
-    T q = u0[K] + u0[K - 1] - 1 - c;               // N(D,K) - 1 - c
-    int k = K;
-    int n2 = 0;
-#pragma unroll
-    for (int i = 0; i < D - 1; i++) {
-        const T *u = tab_u + (D - 1 - i) * (K + 2) + 1;
-        int v = 0;
-        if (k > 0) {
-            const T h = q >> 1;
-            int count = 0;
-            for (int step = top; step > 0; step >>= 1) {
-                const int np = count + step;
-                const int at = np <= k ? np - 1 : k - 1;          // inside the row either way
-                if (np <= k && u[at] <= h) count = np;
-            }
-            const int m = k - count;
-            if (m == 0) {
-                q -= u[k - 1] + u[k - 1];
-            } else {
-                const T ux = u[count], np1 = ux - u[count - 1];   // U(d-1,x), N(d-1,x) with x = k - m
-                T vv = q - ux - ux + np1;
-                const bool negative = (vv >> (32 * W - 1)) != 0;
-                if (negative) vv += np1;
-                q = vv;
-                v = negative ? -m : m;
-                k = count;
-            }
-        }
-        y[i] = v;
-        n2 += v * v;
-    }
-    y[D - 1] = (q == 0) ? -k : k;                  // the two points +k, -k of P(1,k): q = 1, 0
-    n2 += k * k;
-    return n2;
-}
-
-// amplitude of group g of a row: the stored float32, or sqrt(center[q]) * sqrt(row normaliser)
-__device__ inline float load_amplitude(const tables_t &tb, const pvq_decode_args &a, int64_t row,
-                                       int g, float sqrt_rownorm, const float *sqrtc_lds)
-{
-    if (tb.scale_bits == 0) return reinterpret_cast<const float *>(a.scale)[row * a.groups + g];
-    const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
-    const uint32_t pos = (uint32_t)g * (uint32_t)tb.scale_bits;
-    const uint32_t q = (srow[pos >> 5] >> (pos & 31)) & ((1u << tb.scale_bits) - 1u);
-    return sqrtc_lds[q] * sqrt_rownorm;
-}
-
-template <int D, int W, int OUT>
-__global__ __launch_bounds__(kThreads) void decode_kernel(tables_t tb, pvq_decode_args a)
-{
-    using T = typename wide<W>::type;
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int K = tb.K;
-    T *tab_u = reinterpret_cast<T *>(smem);
-    float *sqrtc = reinterpret_cast<float *>(tab_u + D * (K + 2));
-    copy_to_lds(tab_u, reinterpret_cast<const T *>(tb.tab_u), D * (K + 2));
-    if (tb.scale_bits > 0) copy_to_lds(sqrtc, tb.sqrtc, 1 << tb.scale_bits);
-    __syncthreads();
-
-    const int G = (int)a.groups;
-    const int g = blockIdx.x * kThreads + threadIdx.x;
-    if (g >= G) return;
-    for (int64_t row = blockIdx.y; row < a.rows; row += gridDim.y) {
-        const uint32_t *irow = a.index + row * a.index_row_words;
-        const T c = load_field<W>(irow, (uint32_t)g * (uint32_t)tb.index_bits, tb.index_bits);
-        int y[D];
-        const int n2 = unrank_point<D, W>(c, K, tab_u, y);
-        const float srn = tb.scale_bits > 0 ? sqrtf(a.rownorm[row]) : 0.0f;
-        const float amp = load_amplitude(tb, a, row, g, srn, sqrtc);
-        // direction on the unit sphere times the amplitude (Sec. 2.4): w = amp * y / ||y||_2
-        const float gain = amp / sqrtf((float)n2);
-        if constexpr (OUT == PVQ_F32) {
-            float *o = reinterpret_cast<float *>(a.W_out) + row * a.ldw + (int64_t)g * D;
-#pragma unroll
-            for (int i = 0; i < D; i += 4)
-                *reinterpret_cast<float4 *>(o + i) = make_float4(gain * (float)y[i], gain * (float)y[i + 1],
-                                                                 gain * (float)y[i + 2], gain * (float)y[i + 3]);
-        } else {
-            uint16_t *o = reinterpret_cast<uint16_t *>(a.W_out) + row * a.ldw + (int64_t)g * D;
-#pragma unroll
-            for (int i = 0; i < D; i += 8) {
-                uint32_t p[4];
-#pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    const float f0 = gain * (float)y[i + 2 * j], f1 = gain * (float)y[i + 2 * j + 1];
-                    if constexpr (OUT == PVQ_F16) {
-                        p[j] = (uint32_t)f32_to_f16_rne(f0) | ((uint32_t)f32_to_f16_rne(f1) << 16);
-                    } else {
-                        p[j] = f32_to_bf16_rne(f0) | (f32_to_bf16_rne(f1) << 16);
-                    }
-                }
-                *reinterpret_cast<uint4 *>(o + i) = make_uint4(p[0], p[1], p[2], p[3]);
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// decode fused into y = W_hat x
-// ---------------------------------------------------------------------------------------------
-
-// One wave per row: lanes walk the row's groups with stride 64, each keeps NB float32 partial sums
-// (one per activation vector), and a fixed xor butterfly adds the 64 partial sums at the end.
-template <int D, int W, int NB>
-__global__ __launch_bounds__(kThreads) void gemv_kernel(tables_t tb, pvq_decode_args a, int b0)
-{
-    using T = typename wide<W>::type;
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int K = tb.K;
-    T *tab_u = reinterpret_cast<T *>(smem);
-    float *sqrtc = reinterpret_cast<float *>(tab_u + D * (K + 2));
-    copy_to_lds(tab_u, reinterpret_cast<const T *>(tb.tab_u), D * (K + 2));
-    if (tb.scale_bits > 0) copy_to_lds(sqrtc, tb.sqrtc, 1 << tb.scale_bits);
-    __syncthreads();
-
-    const int G = (int)a.groups;
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const uint16_t *xb = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)b0 * a.ldx;
-    for (int64_t row = (int64_t)blockIdx.x * (kThreads / kWave) + wave; row < a.rows;
-         row += (int64_t)gridDim.x * (kThreads / kWave)) {
-        const uint32_t *irow = a.index + row * a.index_row_words;
-        const float srn = tb.scale_bits > 0 ? sqrtf(a.rownorm[row]) : 0.0f;
-        float acc[NB];
-#pragma unroll
-        for (int b = 0; b < NB; b++) acc[b] = 0.0f;
-        for (int g = lane; g < G; g += kWave) {
-            const T c = load_field<W>(irow, (uint32_t)g * (uint32_t)tb.index_bits, tb.index_bits);
-            int y[D];
-            const int n2 = unrank_point<D, W>(c, K, tab_u, y);
-            const float amp = load_amplitude(tb, a, row, g, srn, sqrtc);
-            const float gain = amp / sqrtf((float)n2);
-#pragma unroll
-            for (int b = 0; b < NB; b++) {
-                const uint16_t *xp = xb + (int64_t)b * a.ldx + (int64_t)g * D;
-                float s = 0.0f;
-#pragma unroll
-                for (int i = 0; i < D; i += 8) {
-                    const uint4 q = *reinterpret_cast<const uint4 *>(xp + i);
-                    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        s = fmaf((float)y[i + 2 * j], bf16_to_f32(u[j] & 0xFFFFu), s);
-                        s = fmaf((float)y[i + 2 * j + 1], __uint_as_float(u[j] & 0xFFFF0000u), s);
-                    }
-                }
-                acc[b] = fmaf(gain, s, acc[b]);
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < NB; b++) {
-            float v = acc[b];
-#pragma unroll
-            for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-            if (lane == 0) a.y[(int64_t)(b0 + b) * a.ldy + row] = v;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 
@@ -465,42 +283,6 @@ hipError_t launch_encode_dw(const pvq_ctx *c, const pvq_encode_args &a, int dtyp
     return hipGetLastError();
 }
 
-template <int D, int W>
-hipError_t launch_decode_dw(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
-{
-    const size_t lds = (size_t)D * (c->K + 2) * W * 4 + 256 * 4;
-    if (lds > kMaxLds) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)((a.groups + kThreads - 1) / kThreads), (unsigned)std::min<int64_t>(a.rows, 65535));
-    const tables_t t = make_tables(c);
-    switch (out_dtype) {
-    case PVQ_F32: hipLaunchKernelGGL((decode_kernel<D, W, PVQ_F32>), grid, dim3(kThreads), lds, s, t, a); break;
-    case PVQ_F16: hipLaunchKernelGGL((decode_kernel<D, W, PVQ_F16>), grid, dim3(kThreads), lds, s, t, a); break;
-    default: hipLaunchKernelGGL((decode_kernel<D, W, PVQ_BF16>), grid, dim3(kThreads), lds, s, t, a); break;
-    }
-    return hipGetLastError();
-}
-
-template <int D, int W>
-hipError_t launch_gemv_dw(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
-{
-    const size_t lds = (size_t)D * (c->K + 2) * W * 4 + 256 * 4;
-    if (lds > kMaxLds) return hipErrorInvalidValue;
-    const int rows_per_block = kThreads / kWave;
-    const dim3 grid((unsigned)std::min<int64_t>((a.rows + rows_per_block - 1) / rows_per_block, 1 << 20));
-    const tables_t t = make_tables(c);
-    // the batch is cut into chunks of 4, 2 and 1 activation vectors per pass over the codes
-    int b0 = 0;
-    while (b0 < a.batch) {
-        const int left = a.batch - b0;
-        if (left >= 4) { hipLaunchKernelGGL((gemv_kernel<D, W, 4>), grid, dim3(kThreads), lds, s, t, a, b0); b0 += 4; }
-        else if (left >= 2) { hipLaunchKernelGGL((gemv_kernel<D, W, 2>), grid, dim3(kThreads), lds, s, t, a, b0); b0 += 2; }
-        else { hipLaunchKernelGGL((gemv_kernel<D, W, 1>), grid, dim3(kThreads), lds, s, t, a, b0); b0 += 1; }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
-}
-
 }  // namespace
 
 hipError_t pvq_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, int dtype, hipStream_t s)
@@ -517,38 +299,6 @@ hipError_t pvq_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, int dty
     if (c->words == 1) return launch_encode_dw<32, 1>(c, a, dtype, s);
     if (c->words == 2) return launch_encode_dw<32, 2>(c, a, dtype, s);
     return launch_encode_dw<32, 4>(c, a, dtype, s);
-}
-
-hipError_t pvq_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, int out_dtype, hipStream_t s)
-{
-    if (c->D == 8) {
-        if (c->words == 1) return launch_decode_dw<8, 1>(c, a, out_dtype, s);
-        return launch_decode_dw<8, 2>(c, a, out_dtype, s);
-    }
-    if (c->D == 16) {
-        if (c->words == 1) return launch_decode_dw<16, 1>(c, a, out_dtype, s);
-        if (c->words == 2) return launch_decode_dw<16, 2>(c, a, out_dtype, s);
-        return launch_decode_dw<16, 4>(c, a, out_dtype, s);
-    }
-    if (c->words == 1) return launch_decode_dw<32, 1>(c, a, out_dtype, s);
-    if (c->words == 2) return launch_decode_dw<32, 2>(c, a, out_dtype, s);
-    return launch_decode_dw<32, 4>(c, a, out_dtype, s);
-}
-
-hipError_t pvq_launch_decode_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s)
-{
-    if (c->D == 8) {
-        if (c->words == 1) return launch_gemv_dw<8, 1>(c, a, s);
-        return launch_gemv_dw<8, 2>(c, a, s);
-    }
-    if (c->D == 16) {
-        if (c->words == 1) return launch_gemv_dw<16, 1>(c, a, s);
-        if (c->words == 2) return launch_gemv_dw<16, 2>(c, a, s);
-        return launch_gemv_dw<16, 4>(c, a, s);
-    }
-    if (c->words == 1) return launch_gemv_dw<32, 1>(c, a, s);
-    if (c->words == 2) return launch_gemv_dw<32, 2>(c, a, s);
-    return launch_gemv_dw<32, 4>(c, a, s);
 }
 
 // ---------------------------------------------------------------------------------------------

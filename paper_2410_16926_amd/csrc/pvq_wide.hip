@@ -503,7 +503,6 @@ __global__ __launch_bounds__(512) void encode_wide16_kernel(encode_wide_params p
     const int ng = (int)min((int64_t)p.tile_groups, p.groups - g0);
     const int tile_words = (int)(((int64_t)ng * p.bits + 31) / 32);
     const int64_t first_word = g0 * p.bits / 32;   // exact: tile_groups * bits is a multiple of 32
-    const int K = p.K;
 
     for (int i = threadIdx.x; i < tile_words; i += blockDim.x) stream[i] = 0;
     __syncthreads();

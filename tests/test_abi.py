@@ -128,3 +128,25 @@ def test_pvq_correct_work_bytes():
     assert pvq.lib().pvq_correct_work_bytes(0, C.byref(n)) == 0 and n.value == 0
     assert pvq.lib().pvq_correct_work_bytes(-1, C.byref(n)) == -1
     assert pvq.lib().pvq_correct_work_bytes(5, None) == -1
+
+
+@pytest.mark.parametrize("D,K,schedule", [(16, 33, (8, 0)), (32, 60, (15, 6)), (16, 16, (8, 0)), (8, 40, (0, 0)),
+                                          (32, 9, (12, 0)), (32, 25, (15, 6)), (16, 60, (0, 0)), (8, 127, (0, 0)),
+                                          (16, 1, (0, 0)), (32, 2, (0, 0)), (8, 3, (0, 0))])
+def test_one_probe_per_coordinate_decoder_replays_sampled_indices(D, K, schedule):
+    # host logic: the cumulative rows and guess tables the D = 16 / 32 kernels walk, replayed on the CPU over the
+    # ends of the index range and seeded random indices against the magnitude-by-magnitude decoding; the width
+    # schedule (64-bit integers down to 9 dimensions and 32-bit ones from 8 on, for the 52-bit setting)
+    bad, sched, nbytes = pvq.pvq_walk_tables_selftest(D, K, seed=D * 1000 + K, count=60000)
+    assert bad == 0
+    assert sched == schedule
+    assert 0 < nbytes and nbytes % 16 == 0
+
+
+def test_one_probe_per_coordinate_decoder_limits():
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_walk_tables_selftest(64, 10)
+    assert e.value.status == -2
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_walk_tables_selftest(32, 127)       # index beyond 128 bits
+    assert e.value.status == -2

@@ -139,7 +139,6 @@ hipError_t pvq_wide_launch_rotate_encode(const pvq_ctx *ctx, const pvq_encode_ar
                                          const uint8_t *signs, hipStream_t s);
 
 // coordinate-by-coordinate decoder with one table probe per coordinate (pvq_walk.hip)
-void pvq_walk_schedule(int D, int words, int fit_half, int fit_quarter, int *dA, int *dB);
 bool pvq_walk_usable(const pvq_ctx *ctx);
 hipError_t pvq_walk_launch_decode(const pvq_ctx *ctx, const pvq_decode_args &a, int out_dtype, hipStream_t s);
 hipError_t pvq_walk_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hipStream_t s);

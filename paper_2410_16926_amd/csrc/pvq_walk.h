@@ -196,8 +196,18 @@ PVQ_HD int unrank_walk(typename wide<W>::type c, const unsigned char *lds, const
 
 }  // namespace pvq_walk
 
+// Which width schedule a context gets: fit_half / fit_quarter = the largest number of dimensions d whose
+// N(d,K) fits half / a quarter of the index's words.  Names only schedules listed in PVQ_WALK_DISPATCH.
+inline void pvq_walk_schedule(int D, int words, int fit_half, int fit_quarter, int *dA, int *dB)
+{
+    *dA = 0; *dB = 0;
+    if (D == 16 && words == 2 && fit_half >= 8) *dA = 8;
+    if (D == 32 && words == 2 && fit_half >= 12) *dA = 12;
+    if (D == 32 && words == 4 && fit_half >= 15 && fit_quarter >= 6) { *dA = 15; *dB = 6; }
+}
+
 // The instantiated width schedules <D, W, DA, DB>: CALL(D, W, DA, DB) for the schedule (dA, dB) chosen for a
-// context of group size D with `words`-word indices (pvq_walk_schedule names only schedules listed here).
+// context of group size D with `words`-word indices.
 #define PVQ_WALK_DISPATCH(CALL, D_, W_, dA_, dB_)                                                       \
     do {                                                                                                \
         if ((D_) == 8) {                                                                                \

@@ -347,16 +347,6 @@ hipError_t launch_gemv(const pvq_ctx *c, const pvq_decode_args &a, hipStream_t s
 
 }  // namespace
 
-// Which schedule a context gets: fit_half / fit_quarter = the largest number of dimensions d whose N(d,K) fits
-// half / a quarter of the index's words.  Must name one of the schedules instantiated above.
-void pvq_walk_schedule(int D, int words, int fit_half, int fit_quarter, int *dA, int *dB)
-{
-    *dA = 0; *dB = 0;
-    if (D == 16 && words == 2 && fit_half >= 8) *dA = 8;
-    if (D == 32 && words == 2 && fit_half >= 12) *dA = 12;
-    if (D == 32 && words == 4 && fit_half >= 15 && fit_quarter >= 6) { *dA = 15; *dB = 6; }
-}
-
 bool pvq_walk_usable(const pvq_ctx *c)
 {
     // the tables and the amplitude table must fit LDS

@@ -240,23 +240,29 @@ int pvq_correct_static(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols,
                        int64_t ldu, void *stream);
 
 /*
- * Rotation and encoding of activations in one pass (Sec. 3.3 Step 1 in front of Sec. 2.5 / App. B.2): every
- * row of X is rotated as by pvq_hadamard(X, ..., block, signs, inverse = 0, float32 result) and the rotated
- * float32 values are encoded as by pvq_encode, without being written: index_out and scale_out receive
- * exactly what those two calls in a row would give.  For contexts with D = 128 and N(D,K) < 2^384
- * (float32 amplitudes; the context's amplitude kind applies).
+ * Rotation and encoding in one pass (Sec. 3.3 Step 1 in front of Sec. 2.5 / App. B.2): every row of X is rotated as
+ * by pvq_hadamard(X, ..., block, signs, inverse = 0, float32 result) and the rotated float32 values are encoded as
+ * by pvq_encode, without being written: index_out, scale_out and rownorm_out receive exactly what those two calls
+ * in a row would give (the context's amplitude kind applies).  Two kinds of context:
+ *   D = 128 with N(D,K) < 2^384 (activations, float32 amplitudes): block 128 .. 8192;
+ *   D = 8 with 24-bit indices (weights; float32 amplitudes or amplitude codes): block 8 .. 8192, rows of at most
+ *     4096 groups that are whole chunks of max(256, min(1024, block / 8)) groups (e.g. 8192 columns with any
+ *     block, 4096 columns with blocks up to 4096).
  *
  *   X          device, [rows][ldx] of `dtype` (PVQ_F32 or PVQ_BF16), 16-byte aligned, ldx >= cols,
  *              ldx*sizeof(element) a multiple of 16.
- *   block      a power of two, 128 .. 8192, dividing cols.
+ *   block      a power of two dividing cols.
  *   signs      device, uint8 [cols] (non-zero = -1), 8-byte aligned, or NULL.
- *   index_out, scale_out   device, the planes of pvq_encode for this context and shape (4-byte aligned).
+ *   index_out, scale_out, rownorm_out   device, the planes of pvq_encode for this context and shape (4-byte
+ *              aligned); rownorm_out is required with amplitude codes and ignored (may be NULL) otherwise.
  *
- * PVQ_E_UNSUPPORTED: another context, block outside the above, or an index width for which the groups of
- * one workgroup (16, 32 or 64 of them, for blocks up to 2048, of 4096, of 8192) do not fill whole words.
+ * PVQ_E_UNSUPPORTED: another context, block or shape outside the above, or (D = 128) an index width for which
+ * the groups of one workgroup (16, 32 or 64 of them, for blocks up to 2048, of 4096, of 8192) do not fill
+ * whole words.
  */
 int pvq_rotate_encode(const pvq_ctx *ctx, const void *X, int dtype, int64_t rows, int64_t cols, int64_t ldx,
-                      int block, const uint8_t *signs, uint32_t *index_out, float *scale_out, void *stream);
+                      int block, const uint8_t *signs, uint32_t *index_out, void *scale_out, float *rownorm_out,
+                      void *stream);
 
 /*
  * Decode a matrix: App. B.3 (index -> point p), Sec. 2.4 (direction p/||p||_2 on the unit sphere),

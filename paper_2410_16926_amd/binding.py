@@ -66,7 +66,7 @@ def lib():
         L.pvq_ctx_set_amplitude.argtypes = [vp, i32]
         L.pvq_packed_sizes.argtypes = [vp, i64, i64, vp, vp, vp]
         L.pvq_encode.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
-        L.pvq_rotate_encode.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
+        L.pvq_rotate_encode.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp]
         L.pvq_correct_work_bytes.argtypes = [i64, vp]
         L.pvq_correct.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, C.c_size_t, vp]
         L.pvq_correct_static_max_rows.argtypes = [vp]
@@ -286,7 +286,7 @@ def pvq_rotate_encode(ctx: PvqContext, X, block: int, signs=None, out: Packed = 
         out = alloc_packed(ctx, rows, cols, X.device)
     ld = X.stride(0) if rows > 1 else max(cols, 1)
     _check(lib().pvq_rotate_encode(ctx.handle, _ptr(X), _dtype_code(X), rows, cols, ld, block, _ptr(signs),
-                                   _ptr(out.index), _ptr(out.scale), _stream_ptr()), "pvq_rotate_encode")
+                                   _ptr(out.index), _ptr(out.scale), _ptr(out.rownorm), _stream_ptr()), "pvq_rotate_encode")
     return out
 
 

@@ -20,7 +20,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 
+#include "pvq_hadamard_dev.h"
 #include "pvq_internal.h"
 #include "pvq_quantize_dev.h"
 
@@ -247,7 +249,175 @@ __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_enco
     }
 }
 
+// Rotation of the rows (Sec. 3.3 Step 1) and encoding of the rotated values in one kernel: the transform's
+// stages (pvq_hadamard_dev.h) end with 8 consecutive rotated values per lane, which is one group, so the
+// lane goes straight on into the encoder above and the rotated matrix is never written.  A workgroup of L
+// lanes takes whole rows, a chunk of 8 L values (whole blocks of the rotation) at a time; everything
+// after the rotation is encode8_kernel's (its lanes are groups in row order here too, so the row sum's
+// pair levels, the quads that assemble index words and the code words come out the same).  The rotated
+// values are float32 (scaled by float32(1 / sqrt(block))), exactly those of the rotation kernel with a
+// float32 result.  LOG2N as in pvq_hadamard.hip: 9 for blocks of up to 512 values, 10 .. 13 for that block.
+template <typename TIn, bool CODES, bool LS, int LOG2N>
+__device__ inline void rotate_encode8_body(const enc8_launch &f, const pvq_encode_args &a, int log2n,
+                                           const uint8_t *signs, float scale)
+{
+    using namespace pvq_hadamard_dev;
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int K = f.K, sb = f.scale_bits;
+    const int L = blockDim.x;
+    const int ntab = 7 * (K + 1) * (K + 1) * 2;
+    const int G = (int)a.groups;
+    uint32_t *offs = smem;
+    float *edges = reinterpret_cast<float *>(smem + ntab);       // 256 floats
+    float *wsum = edges + 256;                                    // 64 wave sums of the row (zero padded)
+    float *ss_row = wsum + 64;                                    // the row's sums of squares (CODES)
+    float *hbuf = ss_row + (CODES ? ((G + 3) & ~3) : 0);          // the rotation's exchange buffers
+    for (int i = threadIdx.x; i < ntab; i += L) offs[i] = f.offs[i];
+    if constexpr (CODES)
+        for (int i = threadIdx.x; i < (1 << sb); i += L) edges[i] = f.edges[i];
+    if (threadIdx.x < 64) wsum[threadIdx.x] = 0.0f;
+    __syncthreads();
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int quad_pos = lane & 3;
+    const int chunks = G / L;                                    // whole chunks: every lane has a group
+    const int waves = L / kWave;
+
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        const TIn *xrow = reinterpret_cast<const TIn *>(a.W) + row * a.ldw;
+        uint32_t *irow = a.index_out + row * a.index_row_words;
+        for (int ch = 0; ch < chunks; ch++) {
+            const int g = ch * L + tid;
+            float v[D];
+            load8<TIn>(xrow + (int64_t)g * D, v);
+            if (signs) {
+                const uint2 s8 = *reinterpret_cast<const uint2 *>(signs + (int64_t)g * D);
+#pragma unroll
+                for (int j = 0; j < D; j++) {
+                    const uint32_t byte = ((j < 4 ? s8.x : s8.y) >> (8 * (j & 3))) & 0xFFu;
+                    if (byte) v[j] = -v[j];
+                }
+            }
+            // one exchange buffer (a barrier in front of every exchange, which also keeps a chunk's writes
+            // behind the reads of the chunk before): two workgroups of 1024 lanes then fit a unit's LDS
+            hadamard_stages<LOG2N, false, true>(v, tid, log2n, hbuf, L);
+            float w[D];
+#pragma unroll
+            for (int j = 0; j < D; j++) w[j] = v[j] * scale;
+            int y[D];
+            float ss;
+            const uint32_t c = encode_group8(w, K, offs, ss, y);
+            float amp;
+            if constexpr (LS) { amp = pvq_ls_amplitude<D>(w, y); ss = amp * amp; }
+            else amp = sqrtf(ss);
+            if constexpr (CODES) ss_row[g] = ss;
+            else reinterpret_cast<float *>(a.scale_out)[row * G + g] = amp;
+            const uint32_t cn = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xF9, 0xF, 0xF, false);
+            const uint32_t lo = c | (cn << 24), hi = cn >> 8;
+            const uint32_t word = __builtin_amdgcn_alignbit(hi, lo, 8 * quad_pos);
+            if (quad_pos < 3) irow[3 * (g >> 2) + quad_pos] = word;
+            if constexpr (CODES) {
+                const float s64 = wave_pair_sum(ss);
+                if (lane == kWave - 1) wsum[ch * waves + wave] = s64;
+            }
+        }
+        if constexpr (CODES) {
+            __syncthreads();
+            float rowss = wsum[lane];
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) rowss += __shfl_xor(rowss, off, kWave);
+            if (threadIdx.x == 0) a.rownorm_out[row] = rowss;
+            uint32_t *srow = reinterpret_cast<uint32_t *>(a.scale_out) + row * a.scale_row_words;
+            const int nedges = (1 << sb) - 1;
+            const int lanes_per_word = 32 / sb;
+            for (int ch = 0; ch < chunks; ch++) {
+                const int g = ch * L + tid;
+                const float u = ss_row[g] / rowss;
+                int lo = 0, hi = nedges;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (edges[mid] <= u) lo = mid + 1; else hi = mid;
+                }
+                uint32_t code = (uint32_t)lo << ((lane * sb) & 31);
+                for (int off = 1; off < lanes_per_word; off <<= 1) code |= __shfl_xor(code, off, kWave);
+                if ((lane & (lanes_per_word - 1)) == 0) srow[((uint32_t)g * (uint32_t)sb) >> 5] = code;
+            }
+            __syncthreads();   // ss_row and wsum are rewritten by the next row
+        }
+    }
+}
+
+// Blocks of 8192 values need workgroups of 1024 lanes; two of them share a unit only within 64 registers a
+// lane (the body needs 68: a few values go to scratch), which measured 0.60 against 0.73 ms on 28672 x 8192.
+// The smaller workgroups of the other block sizes keep all their registers.
+template <typename TIn, bool CODES, bool LS, int LOG2N>
+__global__ __launch_bounds__(512) void rotate_encode8_kernel(enc8_launch f, pvq_encode_args a, int log2n,
+                                                            const uint8_t *signs, float scale)
+{
+    rotate_encode8_body<TIn, CODES, LS, LOG2N>(f, a, log2n, signs, scale);
+}
+
+template <typename TIn, bool CODES, bool LS>
+__global__ __launch_bounds__(1024, 8) void rotate_encode8_kernel_8192(enc8_launch f, pvq_encode_args a, int log2n,
+                                                                      const uint8_t *signs, float scale)
+{
+    rotate_encode8_body<TIn, CODES, LS, 13>(f, a, log2n, signs, scale);
+}
+
 }  // namespace
+
+// lanes of the fused kernel's workgroup for a rotation block: whole blocks, at least 256 lanes
+static int rotate8_lanes(int block) { return std::min(1024, std::max(256, block / 8)); }
+
+bool pvq_rotate_encode8_usable(const pvq_ctx *c, const pvq_encode_args &a, int block)
+{
+    // the encoder's own conditions, and rows of whole chunks (so that every lane of a workgroup has a group
+    // in every chunk and the transform's barriers are reached by all)
+    return pvq_encode8_usable(c, a) && a.pulses_out == nullptr && a.groups % rotate8_lanes(block) == 0;
+}
+
+hipError_t pvq_rotate_encode8_launch(const pvq_ctx *c, const pvq_encode_args &a, int dtype, int block,
+                                     const uint8_t *signs, hipStream_t s)
+{
+    enc8_launch f;
+    f.offs = c->enc8_offs; f.edges = c->edges; f.K = c->K; f.scale_bits = c->scale_bits;
+    int log2n = 0;
+    while ((1 << log2n) < block) log2n++;
+    const int L = rotate8_lanes(block);
+    const bool codes = c->scale_bits > 0, ls = a.ls_amplitude != 0;
+    const float scale = (float)(1.0 / std::sqrt((double)block));
+    const size_t hbuf = log2n > 9 ? (size_t)(8 * L + 8 * L / 32 + 1) : 0;
+    const size_t lds = ((size_t)7 * (c->K + 1) * (c->K + 1) * 2 + 256 + 64 + (codes ? (size_t)((a.groups + 3) & ~3) : 0) + hbuf) * 4;
+    const unsigned grid = (unsigned)std::min<int64_t>(a.rows, 8192);
+#define PVQ_RE8_LAUNCH(KERNEL)                                                                                   \
+    do {                                                                                                        \
+        if (lds > 64 * 1024) {                                                                                  \
+            const hipError_t e_ = hipFuncSetAttribute(reinterpret_cast<const void *>(KERNEL),                   \
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);    \
+            if (e_ != hipSuccess) return e_;                                                                    \
+        }                                                                                                       \
+        hipLaunchKernelGGL(KERNEL, dim3(grid), dim3(L), lds, s, f, a, log2n, signs, scale);                     \
+    } while (0)
+#define PVQ_RE8_N(T, C, LS_)                                                        \
+    switch (log2n) {                                                                \
+    case 13: PVQ_RE8_LAUNCH((rotate_encode8_kernel_8192<T, C, LS_>)); break;        \
+    case 12: PVQ_RE8_LAUNCH((rotate_encode8_kernel<T, C, LS_, 12>)); break;         \
+    case 11: PVQ_RE8_LAUNCH((rotate_encode8_kernel<T, C, LS_, 11>)); break;         \
+    case 10: PVQ_RE8_LAUNCH((rotate_encode8_kernel<T, C, LS_, 10>)); break;         \
+    default: PVQ_RE8_LAUNCH((rotate_encode8_kernel<T, C, LS_, 9>)); break;          \
+    }
+    if (dtype == PVQ_F32) {
+        if (codes) { if (ls) PVQ_RE8_N(float, true, true) else PVQ_RE8_N(float, true, false) }
+        else { if (ls) PVQ_RE8_N(float, false, true) else PVQ_RE8_N(float, false, false) }
+    } else {
+        if (codes) { if (ls) PVQ_RE8_N(uint16_t, true, true) else PVQ_RE8_N(uint16_t, true, false) }
+        else { if (ls) PVQ_RE8_N(uint16_t, false, true) else PVQ_RE8_N(uint16_t, false, false) }
+    }
+#undef PVQ_RE8_N
+#undef PVQ_RE8_LAUNCH
+    return hipGetLastError();
+}
 
 bool pvq_encode8_usable(const pvq_ctx *c, const pvq_encode_args &a)
 {

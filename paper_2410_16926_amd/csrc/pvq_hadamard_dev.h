@@ -72,9 +72,10 @@ __device__ constexpr uint32_t own_offset(int q)
 // Through LDS from ownership (P0, R0) to (P1, R1); the caller alternates two buffers, so that one barrier
 // per exchange is enough (a buffer is written again only after a barrier that every wave reaches after
 // its reads of it).
-template <int P0, int R0, int P1, int R1>
+template <int P0, int R0, int P1, int R1, bool SYNC_BEFORE = false>
 __device__ inline void exchange(float (&v)[8], float *buf, uint32_t lane)
 {
+    if constexpr (SYNC_BEFORE) __syncthreads();   // a single buffer: its readers of the exchange before are done
     float *w = buf + pad(own_base<P0, R0>(lane));
 #pragma unroll
     for (int q = 0; q < 8; q++) w[pad(own_offset<P0, R0>(q))] = v[q];
@@ -90,7 +91,9 @@ __device__ inline void exchange(float (&v)[8], float *buf, uint32_t lane)
 // has runs of four consecutive values per lane; with STAY the values are left there (register q holds
 // column own_base<P,1>(lane) + (q >> 1) + (q & 1) * 8^P of the chunk) instead of going through LDS once
 // more.  Otherwise the lane ends with its 8 consecutive values.
-template <int LOG2N, bool STAY>
+// ONEBUF: one buffer of pad(8 L) + 1 floats instead of two, with a barrier in front of every exchange as
+// well (for a kernel that would rather have the LDS than save the barriers).
+template <int LOG2N, bool STAY, bool ONEBUF = false>
 __device__ inline void hadamard_stages(float (&v)[8], int lane, int log2n, float *smem, int L)
 {
     if constexpr (LOG2N > 9) log2n = LOG2N;
@@ -106,15 +109,15 @@ __device__ inline void hadamard_stages(float (&v)[8], int lane, int log2n, float
     if constexpr (LOG2N > 9) {
         constexpr int R3 = LOG2N - 9 < 3 ? LOG2N - 9 : 3;
         constexpr bool kSingleLast = LOG2N == 10 || LOG2N == 13;
-        float *buf0 = smem, *buf1 = smem + pad(8u * (uint32_t)L) + 1u;
-        exchange<0, 3, 3, R3>(v, buf0, lane);
+        float *buf0 = smem, *buf1 = ONEBUF ? smem : smem + pad(8u * (uint32_t)L) + 1u;
+        exchange<0, 3, 3, R3, ONEBUF>(v, buf0, lane);
         stages_in_registers(v, R3);
         if constexpr (LOG2N > 12) {
-            exchange<3, R3, 4, LOG2N - 12>(v, buf1, lane);
+            exchange<3, R3, 4, LOG2N - 12, ONEBUF>(v, buf1, lane);
             stages_in_registers(v, LOG2N - 12);
-            if constexpr (!(STAY && kSingleLast)) exchange<4, LOG2N - 12, 0, 3>(v, buf0, lane);
+            if constexpr (!(STAY && kSingleLast)) exchange<4, LOG2N - 12, 0, 3, ONEBUF>(v, buf0, lane);
         } else if constexpr (!(STAY && kSingleLast)) {
-            exchange<3, R3, 0, 3>(v, buf1, lane);
+            exchange<3, R3, 0, 3, ONEBUF>(v, buf1, lane);
         }
     }
 }

@@ -583,29 +583,38 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
 
 extern "C" int pvq_rotate_encode(const pvq_ctx *c, const void *X, int dtype, int64_t rows, int64_t cols,
                                  int64_t ldx, int block, const uint8_t *signs, uint32_t *index_out,
-                                 float *scale_out, void *stream)
+                                 void *scale_out, float *rownorm_out, void *stream)
 {
     int rc = check_shape(c, rows, cols);
     if (rc) return rc;
     if (dtype != PVQ_F32 && dtype != PVQ_BF16) return PVQ_E_INVALID_ARG;
-    if (!c->wide || c->D != 128 || c->words > 12) return PVQ_E_UNSUPPORTED;
-    if (block < 128 || block > 8192 || (block & (block - 1)) || cols % block) return PVQ_E_UNSUPPORTED;
-    // a workgroup's groups must fill whole words of the index plane
-    const int per_chunk = std::min(1024, std::max(256, block / 8)) / 16;
-    if (((int64_t)per_chunk * c->index_bits) % 32) return PVQ_E_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return PVQ_OK;
-    if (!X || !index_out || !scale_out || ldx < cols) return PVQ_E_INVALID_ARG;
-    const size_t esz = dtype == PVQ_F32 ? 4 : 2;
-    if (!aligned(X, 16) || (ldx * esz) % 16 || !aligned(index_out, 4) || !aligned(scale_out, 4) || !aligned(signs, 8))
-        return PVQ_E_ALIGNMENT;
-    if ((rc = check_device(c))) return rc;
+    const bool long_groups = c->wide && c->D == 128 && c->words <= 12;
+    const bool groups_of_8 = !c->wide && c->D == 8 && c->index_bits == 24;
+    if (!long_groups && !groups_of_8) return PVQ_E_UNSUPPORTED;
+    if (block < (long_groups ? 128 : 8) || block > 8192 || (block & (block - 1)) || cols % block) return PVQ_E_UNSUPPORTED;
+    const int lanes = std::min(1024, std::max(256, block / 8));   // of a workgroup: whole blocks of the rotation
+    if (long_groups) {
+        // a workgroup's groups must fill whole words of the index plane
+        if (((int64_t)(lanes / 16) * c->index_bits) % 32) return PVQ_E_UNSUPPORTED;
+    }
     pvq_encode_args a;
     a.ls_amplitude = c->amplitude == PVQ_AMP_LS ? 1 : 0;
     a.W = X; a.rows = rows; a.cols = cols; a.ldw = ldx; a.groups = cols / c->D;
-    a.index_out = index_out; a.scale_out = scale_out; a.rownorm_out = nullptr; a.pulses_out = nullptr;
+    a.index_out = index_out; a.scale_out = scale_out; a.rownorm_out = rownorm_out; a.pulses_out = nullptr;
     a.index_row_words = stream_words(a.groups, c->index_bits);
-    a.scale_row_words = 0;
-    const hipError_t e = pvq_wide_launch_rotate_encode(c, a, dtype, block, signs, (hipStream_t)stream);
+    a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
+    // groups of 8: rows of whole chunks of `lanes` groups, at most 4096 groups
+    if (groups_of_8 && cols > 0 && !pvq_rotate_encode8_usable(c, a, block)) return PVQ_E_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return PVQ_OK;
+    if (!X || !index_out || !scale_out || ldx < cols) return PVQ_E_INVALID_ARG;
+    if (c->scale_bits > 0 && !rownorm_out) return PVQ_E_INVALID_ARG;
+    const size_t esz = dtype == PVQ_F32 ? 4 : 2;
+    if (!aligned(X, 16) || (ldx * esz) % 16 || !aligned(index_out, 4) || !aligned(scale_out, 4) || !aligned(signs, 8) ||
+        (rownorm_out && !aligned(rownorm_out, 4)))
+        return PVQ_E_ALIGNMENT;
+    if ((rc = check_device(c))) return rc;
+    const hipError_t e = long_groups ? pvq_wide_launch_rotate_encode(c, a, dtype, block, signs, (hipStream_t)stream)
+                                     : pvq_rotate_encode8_launch(c, a, dtype, block, signs, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 

@@ -146,6 +146,10 @@ hipError_t pvq_walk_launch_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, hi
 // D = 8 / 24-bit encoder (pvq_encode8.hip)
 bool pvq_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a);
 hipError_t pvq_encode8_launch(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
+// ... with the rotation of the rows (blocks of `block` values, optional signs) fused in front
+bool pvq_rotate_encode8_usable(const pvq_ctx *ctx, const pvq_encode_args &a, int block);
+hipError_t pvq_rotate_encode8_launch(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, int block,
+                                     const uint8_t *signs, hipStream_t s);
 
 // D = 8 table-driven kernels (pvq_fast8.hip).  `*_usable` says whether the shape qualifies.
 bool pvq_fast8_decode_usable(const pvq_ctx *ctx, const pvq_decode_args &a);

@@ -282,11 +282,77 @@ def test_rotation_and_encoding_in_one_kernel(tokens, hidden, block, bits_per_val
     ctx.close()
 
 
+@pytest.mark.parametrize("rows,cols,block,bits,bf16", [(5, 8192, 8192, 2, True), (3, 8192, 4096, 0, False),
+                                                       (9, 4096, 4096, 8, True), (4, 2048, 512, 2, True),
+                                                       (7, 2048, 64, 0, True), (3, 16384, 8192, 2, False),
+                                                       (130, 8192, 1024, 2, True), (2, 6144, 2048, 4, True),
+                                                       (1, 32768, 8, 1, False), (70, 8192, 8192, 0, True),
+                                                       (40, 8192, 1024, 0, False)])
+def test_rotation_and_encoding_in_one_kernel_for_groups_of_8(rows, cols, block, bits, bf16):
+    # the weight path (Sec. 3.3 Steps 1, 3-5): rotate the rows, encode groups of 8 to 24-bit indices with float32
+    # amplitudes or amplitude codes; indices, amplitudes / codes and row normalisers must be those of the oracle's
+    # rotation (float32) followed by the oracle's encoder, and those of the two separate calls
+    D, K = 8, 16
+    rng = np.random.default_rng(rows + cols + block)
+    sg = rng.integers(0, 2, size=cols).astype(np.uint8)
+    if bf16:
+        wf, wb = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 300 + block, rotate=False, bf16=True)
+        Xd = gu.to_dev_bf16(wb)
+    else:
+        wf = si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + 300 + block, rotate=False)
+        Xd = gu.to_dev_f32(wf)
+    rotated = oracle.hadamard_rows(wf, block, sg)
+    sgd = torch.from_numpy(sg).cuda()
+    for amplitude in ("l2", "ls"):
+        ctx, oe, oc = gu.make_ctx(D, K, bits, cols // D)
+        ctx.set_amplitude({"l2": "norm", "ls": "ls"}[amplitude])
+        packed = pvq.pvq_rotate_encode(ctx, Xd, block, sgd)
+        torch.cuda.synchronize()
+        enc = oracle.encode(rotated, D, K, bits, oe, nthreads=8, amplitude=amplitude)
+        gu.assert_encode_equal(packed, enc, check_pulses=False)
+        two = pvq.pvq_encode(ctx, pvq.pvq_hadamard(Xd, block, sgd, out_dtype=torch.float32))
+        assert torch.equal(two.index, packed.index) and torch.equal(two.scale, packed.scale)
+        if bits:
+            assert torch.equal(two.rownorm, packed.rownorm)
+        ctx.close()
+    ctx, oe, oc = gu.make_ctx(D, K, bits, cols // D)           # without signs
+    packed = pvq.pvq_rotate_encode(ctx, Xd, block)
+    gu.assert_encode_equal(packed, oracle.encode(oracle.hadamard_rows(wf, block), D, K, bits, oe, nthreads=8), check_pulses=False)
+    ctx.close()
+
+
+def test_rotation_and_encoding_for_groups_of_8_limits():
+    X = torch.zeros((2, 1024), dtype=torch.float32, device="cuda")
+    ctx = pvq.pvq_ctx_create(8, 16)
+    for block in (4, 96, 2048):                               # too small, no power of two, not dividing
+        with pytest.raises(pvq.PvqError) as e:
+            pvq.pvq_rotate_encode(ctx, X, block)
+        assert e.value.status == -2
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_rotate_encode(ctx, X, 1024)                   # 128 groups: not a whole chunk of 256
+    assert e.value.status == -2
+    ctx.close()
+    ctx = pvq.pvq_ctx_create(8, 13)                           # 22-bit indices: no fused kernel
+    with pytest.raises(pvq.PvqError) as e:
+        pvq.pvq_rotate_encode(ctx, torch.zeros((2, 2048), dtype=torch.float32, device="cuda"), 512)
+    assert e.value.status == -2
+    ctx.close()
+    e2, c2 = pvq.pvq_beta_tables(8, 256, 2)
+    ctx = pvq.pvq_ctx_create(8, 16, 2, e2, c2)                # amplitude codes need the row normaliser's plane
+    Xz = torch.zeros((2, 2048), dtype=torch.float32, device="cuda")
+    p = pvq.alloc_packed(ctx, 2, 2048, Xz.device)
+    import ctypes as C
+    rc = pvq.lib().pvq_rotate_encode(ctx.handle, C.c_void_p(Xz.data_ptr()), 0, 2, 2048, 2048, 512, None,
+                                     C.c_void_p(p.index.data_ptr()), C.c_void_p(p.scale.data_ptr()), None, None)
+    assert rc == -1
+    ctx.close()
+
+
 def test_rotation_and_encoding_argument_errors():
     X = torch.zeros((2, 1024), dtype=torch.float32, device="cuda")
     ctx8 = pvq.pvq_ctx_create(8, 16)
     with pytest.raises(pvq.PvqError) as e:
-        pvq.pvq_rotate_encode(ctx8, X, 1024)                 # groups of 128 only
+        pvq.pvq_rotate_encode(ctx8, X, 1024)                 # groups of 8: 128 groups are not a whole chunk
     assert e.value.status == -2
     ctx8.close()
     ctx = pvq.pvq_ctx_create(128, 187)

@@ -27,8 +27,10 @@ bool pvq_fast8_decode_usable(const pvq_ctx *, const pvq_decode_args &) { return 
 bool pvq_fast8_gemv_usable(const pvq_ctx *, const pvq_decode_args &) { return false; }
 hipError_t pvq_fast8_launch_decode(const pvq_ctx *, const pvq_decode_args &, int, hipStream_t) { return reached("pvq_fast8_launch_decode"); }
 hipError_t pvq_fast8_launch_gemv(const pvq_ctx *, const pvq_decode_args &, hipStream_t) { return reached("pvq_fast8_launch_gemv"); }
-int pvq_fast8_plan_gemv(const pvq_ctx *, const pvq_decode_args &, pvq_gemv_pass *) { reached("pvq_fast8_plan_gemv"); return 0; }
+int pvq_fast8_plan_gemv(const pvq_ctx *, const pvq_decode_args &, pvq_gemv_pass *) { (void)reached("pvq_fast8_plan_gemv"); return 0; }
 hipError_t pvq_fast8_prepare(void) { return reached("pvq_fast8_prepare"); }
 bool pvq_walk_usable(const pvq_ctx *) { return false; }
 hipError_t pvq_walk_launch_decode(const pvq_ctx *, const pvq_decode_args &, int, hipStream_t) { return reached("pvq_walk_launch_decode"); }
 hipError_t pvq_walk_launch_gemv(const pvq_ctx *, const pvq_decode_args &, hipStream_t) { return reached("pvq_walk_launch_gemv"); }
+bool pvq_rotate_encode8_usable(const pvq_ctx *, const pvq_encode_args &, int) { return false; }
+hipError_t pvq_rotate_encode8_launch(const pvq_ctx *, const pvq_encode_args &, int, int, const uint8_t *, hipStream_t) { return reached("pvq_rotate_encode8_launch"); }

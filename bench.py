@@ -454,15 +454,15 @@ def main():
                 act["oracle_one_core_Gvalues_per_s"] = round(tokens * 8192 / t_cpu / 1e9, 5)
         ctxa.close()
         ex["activation_pvq"] = act
-        # Sec. 3.3 Step 6: error correction group after group, a square projection (8192 x 8192) and the benchmark's
-        # matrix, float32 in place.  For timing the factor is any well-conditioned upper triangular matrix; the oracle beside it
+        # Sec. 3.3 Step 6: error correction group after group: a key / value projection (1024 x 8192), a square
+        # projection (8192 x 8192) and the benchmark's matrix, float32 in place.  For timing the factor is any well-conditioned upper triangular matrix; the oracle beside it
         # on 8 rows (rows are independent), one core.
         gcor = torch.Generator(device=dev); gcor.manual_seed(11)
         Uc = torch.triu(torch.randn((COLS, COLS), generator=gcor, device=dev) * (0.3 / COLS ** 0.5)) + torch.eye(COLS, device=dev)
         ctxc = pvq.pvq_ctx_create(8, K)
-        for cr, cc in ((8192, COLS), (ROWS, COLS)):
+        for cr, cc in ((1024, COLS), (8192, COLS), (ROWS, COLS)):
             Wc0 = torch.randn((cr, cc), generator=gcor, device=dev) * 0.02
-            work = torch.empty((cr * 512,), dtype=torch.uint8, device=dev)
+            work = torch.empty((cr * 1024,), dtype=torch.uint8, device=dev)
             Wc = Wc0.clone()
             pvq.pvq_correct(ctxc, Wc, Uc, work=work); torch.cuda.synchronize()
             ms = []

@@ -206,17 +206,15 @@ int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64
  *   W      device, float32 [rows][ldw], 16-byte aligned, ldw >= cols, ldw a multiple of 4; overwritten.
  *   U      device, float32 [cols][ldu], 16-byte aligned, ldu >= cols, ldu a multiple of 4; only the upper
  *          triangle is used (what lies below the diagonal may be anything).  Not modified.
- *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (128 floats per
- *          row), owned by the caller, contents undefined afterwards.
+ *   work   device, 16-byte aligned scratch of at least pvq_correct_work_bytes(rows) bytes (two buffers of 128
+ *          floats per row), owned by the caller, contents undefined afterwards.
  *
  * float32 throughout; q = (s / sqrt(sum y^2)) * y; the substitution and the updates are fused multiply-adds
  * applied one at a time in the order of the rows of U, so the result does not depend on the launch shape.
  * Contexts with D = 8, 16 or 32 and cols a multiple of 64, else PVQ_E_UNSUPPORTED.  A zero on the
  * diagonal of U gives non-finite weights (then encoded as pvq_encode encodes them), never a fault.
- * Launches cols/64 kernels; asynchronous.  From 1024 rows on, chunks of rows run side by side on
- * streams that the context owns (default priority); they fork from `stream` and join it again through events,
- * so work queued on `stream` after the call sees the finished matrix.  The call enqueues kernels, event records
- * and waits only, so it can be captured in a graph once the context has made its streams (at its first call).
+ * Launches 2 ceil(cols/128) - 1 kernels on `stream`, nothing else (no other stream, no event, no allocation), so
+ * the call can be captured in a graph; asynchronous.
  */
 int pvq_correct_work_bytes(int64_t rows, size_t *bytes);
 int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
@@ -224,13 +222,12 @@ int pvq_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_
 
 /*
  * pvq_correct for callers that cannot allocate device memory or let a library allocate it: code under HIP
- * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, arithmetic
- * and results as pvq_correct (bit for bit), without `work`: the t values of a panel go to a buffer that is
- * part of the library's image on every GPU (static device memory, 4 MiB, held until the process ends),
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels
+ * and results as pvq_correct (bit for bit), without `work`: the t values of the panels go to a buffer that is
+ * part of the library's image on every GPU (static device memory, 8 MiB, held until the process ends),
  * which bounds the rows of one call: rows <= *pvq_correct_static_max_rows (8192), else PVQ_E_UNSUPPORTED
  * (rows are independent: a taller matrix is corrected in slices of rows, one call after the other).
- * The call makes no hipMalloc / hipFree, no stream and no event: all kernels run on `stream`, one chunk of
- * rows (pvq_correct runs up to four chunks side by side on streams it creates at its first call).
+ * The call makes no hipMalloc / hipFree, no stream and no event: all kernels run on `stream`.
  * Nothing in the buffer has to start at zero: every value read has been written by the same call.
  * All calls on one GPU share that GPU's buffer: two calls that overlap in time on one GPU (different
  * streams or threads) race and give wrong results; calls on one stream, or ordered by events, are safe.

@@ -9,13 +9,23 @@
 // holds, for every group, the values that were quantised: encoding it gives the corrected code.
 //
 // Rows are independent, groups of a row strictly sequential, and U is the same for every row.  Columns are
-// taken in panels of 128:
-//   correct_panel_kernel   one lane per row goes through the panel's groups (pending updates from the
-//                          panel's earlier groups, quantise, substitution) and leaves the panel's t values
-//                          (rows x 128) in a work buffer.  Bound by its own latency: one wave per 64 rows.
-//   correct_trailing_kernel  applies the panel's 128 multiply-adds per element, in the same order, to all
-//                          columns behind it: 128 x 128 tiles, 8 x 8 per lane, t and U tiles in LDS (32 rows
-//                          of U at a time), W read and written once per panel.  Bound: float32 vector ALU.
+// taken in panels of 128.  Panel p takes two launches on the caller's stream:
+//   correct_narrow_kernel  panel p - 1's 128 multiply-adds per element onto the columns of panel p, which is all that
+//           panel p waits for: tiles of 16 rows x 128 columns, so that even a few rows spread over many compute units.
+//   correct_step_kernel    workgroups with one of two roles:
+//     panel   (the first ceil(rows / 64) workgroups) 64 rows of panel p, one lane per row, four waves that own the
+//             panel's groups in turn: the owner of a group quantises it and publishes its t values, the other
+//             waves meanwhile bring their own later groups up to date.  Leaves the panel's t values (rows x 128) in a
+//             work buffer.  Bound by the latency of one wave's quantiser and substitution, 128 / D times in a row.
+//     update  (all others) panel p - 1's 128 multiply-adds per element, in the same order, for the columns
+//             behind panel p: tiles of 128 rows x 128 columns, 8 x 8 per lane, t and U tiles in LDS (32 rows
+//             of U at a time), W read and written once per panel.  Bound: float32 vector ALU.
+// The two roles touch different columns, and the update reads panel p - 1's t values while the panel role writes
+// panel p's, which is why there are two work buffers used in turn.  The panel workgroups come first in the grid
+// and raise their waves' priority, so they are placed before the flood of update tiles and run beside it: the
+// chain of panels (each needs the one before) stays off the critical path as long as a launch has enough update
+// tiles to outlast it; with few rows the chain is what remains.  Both roles need the same LDS (33 KB), four
+// workgroups per compute unit.
 // Not on the matrix cores: their accumulation order inside an instruction is not the one defined above.
 #include <hip/hip_runtime.h>
 
@@ -28,171 +38,211 @@ namespace {
 
 using namespace pvq_quantize_dev;
 
-constexpr int kPanelCols = 128;   // columns per panel: two blocks, whose updates of the columns behind the panel go together
-constexpr int kTile = 128;        // rows and columns of a tile of the trailing update
-constexpr int kTrailThreads = 256;
-constexpr int kStage = 32;        // rows of U (and t values per row) that the trailing update holds in LDS at a time
+constexpr int kPanelCols = 128;   // columns per panel
+constexpr int kPanelWaves = 4;    // waves of a workgroup: group g of the panel belongs to wave g % 4
+constexpr int kThreads = 64 * kPanelWaves;
+constexpr int kTile = 128;        // rows and columns of an update tile
+constexpr int kStage = 32;        // rows of U (and t values per row) that an update tile holds in LDS at a time
+constexpr int kLdsFloats = kStage * (kTile + 4) + kStage * kTile;   // update: t tile and U tile; panel: 128 x 64 t values
+static_assert(kLdsFloats >= kPanelCols * 64, "the panel role's t values fit");
 
-struct correct_args {
-    float *W; int64_t ldw, rows, cols;
-    const float *U; int64_t ldu;
-    float *T;            // [rows][128]: the t values of the two blocks of a panel
+struct correct_shape {
+    int64_t ldw, rows, cols, ldu;
     int K, ls;
 };
 
-// A panel of `width` columns (128, or 64 at the end of a matrix with an odd number of blocks) from column p0
-// on, one lane per row.  Group after group: the group's D values come from W (requested while the group
-// before is worked on); they take the updates of the panel's earlier groups, which are still pending (rows
-// 0 .. G D - 1 of the panel's part of U, in that order: per element the same multiply-adds in the same order
-// as if every group had updated all later columns at once); then quantiser, amplitude, error and
-// substitution; the values go back to W, the group's t values to the work buffer and to LDS (a column per
-// lane: the pending updates of the later groups read them there, so that nothing is indexed by the group
-// number in registers and the groups are a real loop: the code stays small).  U is the same in every lane:
-// the rows that a group needs (its D columns of the panel's rows above it, and its own D x D part) are
-// fetched a group ahead, one or two rows per lane, parked in registers while the current group is worked
-// on, and then laid out in LDS, where every lane reads the same address (a broadcast).
+// Panel role.  Lane = row in each of the four waves; wave w holds the values of groups w, w + 4, ... of its rows
+// in registers.
+//   Step G (one barrier per step): the owner of group G applies to it the updates of group G - 1 (the only ones
+// still missing: it caught up with the rest one step earlier), stores what is then quantised to W, runs
+// quantiser, amplitude, error and substitution, and puts the t values into LDS and the work buffer; the other
+// waves apply the t values published so far to all groups they still own.  Per element these are the same
+// multiply-adds in the same order (rows of U ascending) as if every group had updated all later columns at
+// once.  The owner's step is the chain's length: one group's quantiser plus D rows of updates.
+//   U is the same for every lane.  No wave is ever more than two groups behind, so step G reads the rows of U of
+// groups G - 2, G - 1 and G only (and the t values of G - 2 and G - 1).  D = 8: rings of four groups in LDS, rows
+// of U ([slot][row][128 columns], the rows of group G + 1 are fetched during step G) and t values
+// ([slot][column][lane]).  D = 16, 32: such rings would not leave LDS for four workgroups per compute unit; all
+// t values of the panel are kept, and the rows of U come through scalar loads (the pointer is read-only for the
+// kernel and the address is the same in all lanes), which costs the owner a few exposed load latencies per step.
 template <int D>
-__global__ __launch_bounds__(64) void correct_panel_kernel(correct_args a, int64_t p0, int width)
+__device__ inline void panel_role(float *__restrict__ W, const float *__restrict__ U, float *__restrict__ Tcur,
+                                  const correct_shape &a, int64_t p0, int width, float *lds)
 {
-    __shared__ float ts[kPanelCols][64];                        // t values of the panel so far, [column][lane]
-    __shared__ __align__(16) float us[2][kPanelCols][D];        // the U rows of the current and the next group
-    const int lane = threadIdx.x;
+    constexpr int NG = kPanelCols / D, OWN = NG / kPanelWaves;
+    constexpr bool kRing = D == 8;
+    constexpr int R = 4;                                        // slots of the rings
+    static_assert(!kRing || (D * kPanelCols / 4 == kThreads && R * D * (kPanelCols + 64) <= kLdsFloats), "a float4 per lane fills a slot");
+    float *uring = lds;                                         // [slot][row of the group][column of the panel]
+    float *ts = kRing ? lds + R * D * kPanelCols : lds;         // ring: [slot][column of the group][lane]; else [column][lane]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = (int64_t)blockIdx.x * 64 + lane;
     const bool in = r < a.rows;
     // lanes beyond the rows work on the last row again (no lane waits for another); they store nothing
-    float *wrow = a.W + (in ? r : a.rows - 1) * a.ldw + p0;
-    float *trow = a.T + (in ? r : a.rows - 1) * kPanelCols;
-    const float *U = a.U + p0 * a.ldu + p0;                     // row p0 + i, column p0 + c of the factor
+    const int64_t row = in ? r : a.rows - 1;
+    float *wrow = W + row * a.ldw + p0;
     const int ngroups = width / D;
+    const float *Up = U + p0 * a.ldu + p0;                      // row p0 + k, column p0 + c of the factor
 
-    auto load_group_values = [&](int G, float (&v)[D]) {
+    float w[OWN][D];
+#pragma unroll
+    for (int o = 0; o < OWN; o++) {
+        const int g = wave + kPanelWaves * o;
 #pragma unroll
         for (int i = 0; i < D; i += 4) {
-            const float4 q = *reinterpret_cast<const float4 *>(wrow + G * D + i);
-            v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+            const float4 q = *reinterpret_cast<const float4 *>(wrow + (g < ngroups ? g : 0) * D + i);
+            w[o][i] = q.x; w[o][i + 1] = q.y; w[o][i + 2] = q.z; w[o][i + 3] = q.w;
         }
+    }
+
+    // the rows of U of group g, from device memory to the ring: a float4 per lane
+    const int ring_k = threadIdx.x / (kPanelCols / 4), ring_c = (threadIdx.x % (kPanelCols / 4)) * 4;
+    auto ring_fetch = [&](int g) {
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (g < ngroups && ring_c < width) v = *reinterpret_cast<const float4 *>(Up + (int64_t)(g * D + ring_k) * a.ldu + ring_c);
+        return v;
     };
-    // rows lane and lane + 64 of the panel, the D columns of group G (rows up to the group's last one are
-    // needed: (G + 1) D of them; the others are fetched from a row that exists and not used)
-    auto fetch_u = [&](int G, float (&v)[2][D]) {
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            const int k = lane + 64 * h;
-            const float *src = U + (int64_t)(k < (G + 1) * D ? k : 0) * a.ldu + G * D;
-#pragma unroll
-            for (int i = 0; i < D; i += 4) {
-                const float4 q = *reinterpret_cast<const float4 *>(src + i);
-                v[h][i] = q.x; v[h][i + 1] = q.y; v[h][i + 2] = q.z; v[h][i + 3] = q.w;
-            }
-        }
+    auto ring_store = [&](int g, const float4 &v) {
+        *reinterpret_cast<float4 *>(uring + ((g % R) * D + ring_k) * kPanelCols + ring_c) = v;
     };
-    auto park_u = [&](int buf, const float (&v)[2][D]) {
-#pragma unroll
-        for (int h = 0; h < 2; h++)
-#pragma unroll
-            for (int i = 0; i < D; i += 4)
-                *reinterpret_cast<float4 *>(&us[buf][lane + 64 * h][i]) = make_float4(v[h][i], v[h][i + 1], v[h][i + 2], v[h][i + 3]);
+    if constexpr (kRing) {
+        ring_store(0, ring_fetch(0));
+        __syncthreads();
+    }
+    // row k of the panel's part of U from column c on, and the t values of column k
+    auto u_at = [&](int k, int c) -> const float * {
+        if constexpr (kRing) return uring + (((k / D) % R) * D + k % D) * kPanelCols + c;
+        else return Up + (int64_t)k * a.ldu + c;
     };
-    float wg[D], wn[D], un[2][D];
-    load_group_values(0, wg);
-    fetch_u(0, un);
-    park_u(0, un);
-    __syncthreads();
-    for (int G = 0; G < ngroups; G++) {
-        const int Gn = G + 1 < ngroups ? G + 1 : G;
-        load_group_values(Gn, wn);
-        fetch_u(Gn, un);
-        const float (*ug)[D] = us[G & 1];
-        // pending updates: rows k = 0 .. G D - 1 of the panel, this group's columns
-        const int pending = G * D;
-#pragma unroll 8
-        for (int k = 0; k < pending; k++) {
-            const float tk = ts[k][lane];
-            float u[D];
+    auto t_at = [&](int k) -> float * {
+        if constexpr (kRing) return ts + (((k / D) % R) * D + k % D) * 64 + lane;
+        else return ts + k * 64 + lane;
+    };
+    float *trow = Tcur + row * kPanelCols;
+    // rows k0 .. k1 - 1 of the panel's part of U, times the t values of those columns, onto group g's values
+    auto apply = [&](float (&v)[D], int g, int k0, int k1) {
+        constexpr int kRowsAhead = 64 / D;    // rows of U on their way at a time
+#pragma unroll kRowsAhead
+        for (int k = k0; k < k1; k++) {
+            const float tk = *t_at(k);
+            const float *u = u_at(k, g * D);
+            float uv[D];
 #pragma unroll
             for (int j = 0; j < D; j += 4) {
-                const float4 q = *reinterpret_cast<const float4 *>(&ug[k][j]);
-                u[j] = q.x; u[j + 1] = q.y; u[j + 2] = q.z; u[j + 3] = q.w;
+                const float4 q = *reinterpret_cast<const float4 *>(u + j);
+                uv[j] = q.x; uv[j + 1] = q.y; uv[j + 2] = q.z; uv[j + 3] = q.w;
             }
 #pragma unroll
-            for (int j = 0; j < D; j++) wg[j] = __builtin_fmaf(-tk, u[j], wg[j]);
+            for (int j = 0; j < D; j++) v[j] = __builtin_fmaf(-tk, uv[j], v[j]);
         }
-        // what is quantised, and stays in W
-        if (in) {
+    };
+
+    int applied = 0;   // the wave's groups that are still to come hold the updates of groups 0 .. applied - 1
 #pragma unroll
-            for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(wrow + G * D + i) = make_float4(wg[i], wg[i + 1], wg[i + 2], wg[i + 3]);
+    for (int o = 0; o < OWN; o++) {
+#pragma unroll 1
+        for (int turn = 0; turn < kPanelWaves; turn++) {
+            const int G = kPanelWaves * o + turn;
+            if (G >= ngroups) break;                  // the same for every wave
+            float4 ahead;
+            if constexpr (kRing) ahead = ring_fetch(G + 1);
+            if (wave == turn) {
+                float (&wg)[D] = w[o];
+                apply(wg, G, applied * D, G * D);
+                // what is quantised, and stays in W
+                if (in) {
+#pragma unroll
+                    for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(wrow + G * D + i) = make_float4(wg[i], wg[i + 1], wg[i + 2], wg[i + 3]);
+                }
+                int y[D];
+                float ss;
+                if constexpr (D == 8) ss = quantize_group8(wg, a.K, y);
+                else ss = quantize_group<D>(wg, a.K, y);
+                const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
+                int n2 = 0;
+#pragma unroll
+                for (int i = 0; i < D; i++) n2 += y[i] * y[i];
+                const float gain = s / sqrtf((float)n2);
+                // t U_GG = e, row after row of the group's own D x D part: t_i is final once rows 0 .. i - 1 have been
+                // taken off e_i (for every e_j the multiply-adds come in the order of the rows)
+                float t[D];
+#pragma unroll
+                for (int j = 0; j < D; j++) t[j] = wg[j] - gain * (float)y[j];
+#pragma unroll
+                for (int i = 0; i < D; i++) {
+                    const float *u = u_at(G * D + i, G * D);
+                    float ui[D];
+#pragma unroll
+                    for (int j = 0; j < D; j += 4) {
+                        const float4 q = *reinterpret_cast<const float4 *>(u + j);
+                        ui[j] = q.x; ui[j + 1] = q.y; ui[j + 2] = q.z; ui[j + 3] = q.w;
+                    }
+                    t[i] = t[i] / ui[i];
+#pragma unroll
+                    for (int j = i + 1; j < D; j++) t[j] = __builtin_fmaf(-t[i], ui[j], t[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < D; j++) *t_at(G * D + j) = t[j];
+                if (in) {
+#pragma unroll
+                    for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(trow + G * D + i) = make_float4(t[i], t[i + 1], t[i + 2], t[i + 3]);
+                }
+            } else {
+#pragma unroll
+                for (int oo = 0; oo < OWN; oo++) {
+                    const int g = wave + kPanelWaves * oo;
+                    if (g > G && g < ngroups) apply(w[oo], g, applied * D, G * D);
+                }
+                applied = G;
+            }
+            if constexpr (kRing) ring_store(G + 1, ahead);      // a slot that no wave reads during this step
+            __syncthreads();      // the step's t values, and the next group's rows of U, are in LDS
         }
-        int y[D];
-        float ss;
-        if constexpr (D == 8) ss = quantize_group8(wg, a.K, y);
-        else ss = quantize_group<D>(wg, a.K, y);
-        const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
-        int n2 = 0;
-#pragma unroll
-        for (int i = 0; i < D; i++) n2 += y[i] * y[i];
-        const float gain = s / sqrtf((float)n2);
-        float t[D];
-#pragma unroll
-        for (int j = 0; j < D; j++) {
-            float acc = wg[j] - gain * (float)y[j];
-#pragma unroll
-            for (int i = 0; i < j; i++) acc = __builtin_fmaf(-t[i], ug[pending + i][j], acc);
-            t[j] = acc / ug[pending + j][j];
-        }
-#pragma unroll
-        for (int j = 0; j < D; j++) ts[pending + j][lane] = t[j];
-        if (in) {
-#pragma unroll
-            for (int i = 0; i < D; i += 4) *reinterpret_cast<float4 *>(trow + G * D + i) = make_float4(t[i], t[i + 1], t[i + 2], t[i + 3]);
-        }
-        park_u((G + 1) & 1, un);
-        __syncthreads();      // one wave: orders the LDS writes above before the next group's reads
-#pragma unroll
-        for (int i = 0; i < D; i++) wg[i] = wn[i];
     }
 }
 
-// Columns [c1, cend): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][n - 1] U[c0 + n - 1][c], n = 32 stages,
-// one multiply-add after the other; t[r][k] = T[r][t0 + k].  n = 128: a panel's update of everything behind it,
-// with the tile of W read and written once for 128 multiply-adds per element (with 64 per pass the kernel was
-// bound by HBM as much as by the vector ALU).  A stage = 32 rows of U and 32 t values per row in LDS (33 KB, four
-// workgroups per compute unit; with 64 per stage, two workgroups, the update ran at 57 instead of 66 TFLOP/s).
-// blockIdx.x = row tile (neighbouring workgroups share the tile of U), blockIdx.y = column tile.
-__global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct_args a, int64_t c0, int t0, int stages,
-                                                                          int64_t c1, int64_t cend)
+// Update role.  Tile (row tile, column tile) of the columns [c1, cols): W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ...
+// - t[r][127] U[c0 + 127][c], one multiply-add after the other, t = the t values of the panel at column c0; the
+// tile of W is read and written once for its 128 multiply-adds per element (with 64 per pass the update was
+// bound by HBM as much as by the vector ALU).  A stage = 32 rows of U and 32 t values per row in LDS (with 64
+// per stage, and two workgroups per compute unit, it ran at 57 instead of 66 TFLOP/s).
+// Neighbouring workgroups share the tile of U.
+__device__ inline void update_role(float *__restrict__ W, const float *__restrict__ U, const float *__restrict__ T,
+                                   const correct_shape &a, int64_t c0, int64_t c1, int row_tile, int col_tile, float *lds)
 {
-    __shared__ __align__(16) float Ts[kStage][kTile + 4];   // [k][row of the tile]
-    __shared__ __align__(16) float Us[kStage][kTile];       // [k][column of the tile]
-    const int64_t row0 = (int64_t)blockIdx.x * kTile, col0 = c1 + (int64_t)blockIdx.y * kTile;
+    float (*Ts)[kTile + 4] = reinterpret_cast<float (*)[kTile + 4]>(lds);               // [k][row of the tile]
+    float (*Us)[kTile] = reinterpret_cast<float (*)[kTile]>(lds + kStage * (kTile + 4)); // [k][column of the tile]
+    const int64_t row0 = (int64_t)row_tile * kTile, col0 = c1 + (int64_t)col_tile * kTile;
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;       // rows 8 ty .. 8 ty + 7, columns 8 tx .. 8 tx + 7 of the tile
-    const bool cols_in = col0 + 8 * tx < cend;    // eight columns are in or out together
+    const bool cols_in = col0 + 8 * tx < a.cols;  // eight columns are in or out together
     float acc[8][8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         const int64_t r = row0 + 8 * ty + i;
         float4 v0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), v1 = v0;
         if (r < a.rows && cols_in) {
-            const float *p = a.W + r * a.ldw + col0 + 8 * tx;
+            const float *p = W + r * a.ldw + col0 + 8 * tx;
             v0 = *reinterpret_cast<const float4 *>(p); v1 = *reinterpret_cast<const float4 *>(p + 4);
         }
         acc[i][0] = v0.x; acc[i][1] = v0.y; acc[i][2] = v0.z; acc[i][3] = v0.w;
         acc[i][4] = v1.x; acc[i][5] = v1.y; acc[i][6] = v1.z; acc[i][7] = v1.w;
     }
-    for (int st = 0; st < stages; st++) {
+    for (int st = 0; st < kPanelCols / kStage; st++) {
         if (st) __syncthreads();                  // the tiles of the stage before are no longer read
         // t tile: 128 rows x 32 values, a float4 per lane and pass, stored transposed
-        for (int e = tid; e < kTile * (kStage / 4); e += kTrailThreads) {
+        for (int e = tid; e < kTile * (kStage / 4); e += kThreads) {
             const int rr = e / (kStage / 4), k4 = (e % (kStage / 4)) * 4;
             float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(a.T + (row0 + rr) * kPanelCols + t0 + st * kStage + k4);
+            if (row0 + rr < a.rows) v = *reinterpret_cast<const float4 *>(T + (row0 + rr) * kPanelCols + st * kStage + k4);
             Ts[k4][rr] = v.x; Ts[k4 + 1][rr] = v.y; Ts[k4 + 2][rr] = v.z; Ts[k4 + 3][rr] = v.w;
         }
-        // U tile: 32 rows x 128 columns (columns in whole fours: cend is a multiple of 64)
-        for (int e = tid; e < kStage * (kTile / 4); e += kTrailThreads) {
+        // U tile: 32 rows x 128 columns (columns in whole fours: cols is a multiple of 64)
+        for (int e = tid; e < kStage * (kTile / 4); e += kThreads) {
             const int k = e / (kTile / 4), cc = (e % (kTile / 4)) * 4;
             float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (col0 + cc < cend) v = *reinterpret_cast<const float4 *>(a.U + (c0 + st * kStage + k) * a.ldu + col0 + cc);
+            if (col0 + cc < a.cols) v = *reinterpret_cast<const float4 *>(U + (c0 + st * kStage + k) * a.ldu + col0 + cc);
             *reinterpret_cast<float4 *>(&Us[k][cc]) = v;
         }
         __syncthreads();
@@ -212,86 +262,131 @@ __global__ __launch_bounds__(kTrailThreads) void correct_trailing_kernel(correct
     for (int i = 0; i < 8; i++) {
         const int64_t r = row0 + 8 * ty + i;
         if (r < a.rows && cols_in) {
-            float *p = a.W + r * a.ldw + col0 + 8 * tx;
+            float *p = W + r * a.ldw + col0 + 8 * tx;
             *reinterpret_cast<float4 *>(p) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
             *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
         }
     }
 }
 
-hipError_t make_side_streams(pvq_ctx *c)
+// Columns [c1, c1 + width) of all rows: W[r][c] <- W[r][c] - t[r][0] U[c0][c] - ... - t[r][127] U[c0 + 127][c], one
+// multiply-add after the other, t = the t values of the panel at column c0 = c1 - 128.  16 rows x 128 columns per
+// workgroup, 1 x 8 per lane; a stage = 32 rows of U and 32 t values per row in LDS.
+__global__ __launch_bounds__(kThreads) void correct_narrow_kernel(float *__restrict__ W, const float *__restrict__ U,
+                                                                   const float *__restrict__ T, correct_shape a, int64_t c1, int width)
 {
-    if (c->side_ready) return hipSuccess;
-    hipError_t e = hipEventCreateWithFlags(&c->side_fork, hipEventDisableTiming);
-    for (int i = 0; i < pvq_ctx::kSideStreams && e == hipSuccess; i++) {
-        e = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->side_join[i], hipEventDisableTiming);
-    }
-    c->side_ready = true;   // whatever was made is released with the context
-    return e;
-}
-
-}  // namespace
-
-// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: rows x 128 floats.
-// Rows are independent, and within a chunk of rows the launches form a chain in which every second one (the
-// panel kernel) is a single wave per 64 rows bound by its own latency: up to four chunks of rows run side by
-// side, the first on the caller's stream and the others on streams of the context that fork from and
-// join the caller's stream through events, so that one chunk's panel kernel runs beside another
-// chunk's trailing update.
-namespace {
-
-hipError_t launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
-                          int64_t ldu, float *work, hipStream_t s, int64_t max_chunks)
-{
-    pvq_ctx *c = const_cast<pvq_ctx *>(cc);
-    const int64_t nch = std::max<int64_t>(1, std::min<int64_t>(max_chunks, rows / 512));
-    const int64_t chunk_rows = ((rows + nch - 1) / nch + kTile - 1) / kTile * kTile;
-    std::lock_guard<std::mutex> hold(c->side_lock);   // the events below belong to one call at a time
-    hipError_t e = hipSuccess;
-    if (nch > 1) {
-        if ((e = make_side_streams(c)) != hipSuccess) return e;
-        if ((e = hipEventRecord(c->side_fork, s)) != hipSuccess) return e;
-        for (int i = 0; i + 1 < nch; i++)
-            if ((e = hipStreamWaitEvent(c->side[i], c->side_fork, 0)) != hipSuccess) return e;
-    }
-    for (int64_t p0 = 0; p0 < cols && e == hipSuccess; p0 += kPanelCols) {
-        const int width = (int)std::min<int64_t>(kPanelCols, cols - p0);   // 128, or 64 at the end
-        for (int64_t ch = 0; ch < nch; ch++) {
-            const int64_t r0 = ch * chunk_rows, nr = std::min(chunk_rows, rows - r0);
-            if (nr <= 0) continue;
-            hipStream_t st = ch == 0 ? s : c->side[ch - 1];
-            correct_args a;
-            a.W = W + r0 * ldw; a.ldw = ldw; a.rows = nr; a.cols = cols; a.U = U; a.ldu = ldu; a.T = work + r0 * kPanelCols;
-            a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
-            const dim3 pgrid((unsigned)((nr + 63) / 64)), pblock(64);
-            switch (c->D) {
-            case 8: hipLaunchKernelGGL((correct_panel_kernel<8>), pgrid, pblock, 0, st, a, p0, width); break;
-            case 16: hipLaunchKernelGGL((correct_panel_kernel<16>), pgrid, pblock, 0, st, a, p0, width); break;
-            default: hipLaunchKernelGGL((correct_panel_kernel<32>), pgrid, pblock, 0, st, a, p0, width); break;
-            }
-            // everything behind the panel takes the panel's 128 multiply-adds per element in one launch
-            const int64_t c1 = p0 + kPanelCols;
-            if (c1 < cols) {
-                const dim3 tgrid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((cols - c1 + kTile - 1) / kTile));
-                hipLaunchKernelGGL(correct_trailing_kernel, tgrid, dim3(kTrailThreads), 0, st, a, p0, 0, kPanelCols / kStage, c1, cols);
-            }
+    constexpr int RT = 16;
+    __shared__ __align__(16) float Ts[kStage][RT + 4];      // [k][row of the tile]
+    __shared__ __align__(16) float Us[kStage][kPanelCols];  // [k][column]
+    const int64_t row0 = (int64_t)blockIdx.x * RT, c0 = c1 - kPanelCols;
+    const int tid = threadIdx.x;
+    const int ty = tid >> 4, tx = tid & 15;       // row ty, columns 8 tx .. 8 tx + 7 of the tile
+    const int64_t r = row0 + ty;
+    const bool mine = r < a.rows && 8 * tx < width;          // (width is 128 or 64: eight columns are in or out together)
+    float acc[8];
+    {
+        float4 v0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), v1 = v0;
+        if (mine) {
+            const float *p = W + r * a.ldw + c1 + 8 * tx;
+            v0 = *reinterpret_cast<const float4 *>(p); v1 = *reinterpret_cast<const float4 *>(p + 4);
         }
-        e = hipGetLastError();
+        acc[0] = v0.x; acc[1] = v0.y; acc[2] = v0.z; acc[3] = v0.w; acc[4] = v1.x; acc[5] = v1.y; acc[6] = v1.z; acc[7] = v1.w;
     }
-    // join also after a failed launch, so that the caller's stream never runs ahead of the side streams
-    for (int i = 0; i + 1 < nch; i++) {
-        hipError_t j = hipEventRecord(c->side_join[i], c->side[i]);
-        if (j == hipSuccess) j = hipStreamWaitEvent(s, c->side_join[i], 0);
-        if (e == hipSuccess) e = j;
+    // t tile of a stage: 16 rows x 32 values = 128 float4 (lanes 0 .. 127), stored transposed; U tile: 32 rows x 128
+    // columns = 4 float4 per lane.  All four stages are requested at once (80 registers): the workgroup's time is
+    // one trip to memory plus its arithmetic, whatever the other workgroups of the compute unit do.
+    constexpr int kStages = kPanelCols / kStage;
+    const int t_rr = tid / (kStage / 4), t_k4 = (tid % (kStage / 4)) * 4;
+    const bool t_lane = tid < RT * (kStage / 4);
+    float4 tq[kStages], uq[kStages][4];
+#pragma unroll
+    for (int st = 0; st < kStages; st++) {
+        tq[st] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (t_lane && row0 + t_rr < a.rows) tq[st] = *reinterpret_cast<const float4 *>(T + (row0 + t_rr) * kPanelCols + st * kStage + t_k4);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int e = tid + i * kThreads, k = e / (kPanelCols / 4), cc = (e % (kPanelCols / 4)) * 4;
+            uq[st][i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (cc < width) uq[st][i] = *reinterpret_cast<const float4 *>(U + (c0 + st * kStage + k) * a.ldu + c1 + cc);
+        }
     }
-    return e;
+#pragma unroll
+    for (int st = 0; st < kStages; st++) {
+        if (st) __syncthreads();                  // the tiles of the stage before are no longer read
+        if (t_lane) { Ts[t_k4][t_rr] = tq[st].x; Ts[t_k4 + 1][t_rr] = tq[st].y; Ts[t_k4 + 2][t_rr] = tq[st].z; Ts[t_k4 + 3][t_rr] = tq[st].w; }
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int e = tid + i * kThreads, k = e / (kPanelCols / 4), cc = (e % (kPanelCols / 4)) * 4;
+            *reinterpret_cast<float4 *>(&Us[k][cc]) = uq[st][i];
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < kStage; k++) {
+            const float tv = Ts[k][ty];
+            const float4 b0 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx]), b1 = *reinterpret_cast<const float4 *>(&Us[k][8 * tx + 4]);
+            const float uv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[j] = __builtin_fmaf(-tv, uv[j], acc[j]);
+        }
+    }
+    if (mine) {
+        float *p = W + r * a.ldw + c1 + 8 * tx;
+        *reinterpret_cast<float4 *>(p) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4 *>(p + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
 }
 
-// Work buffer of the entry point that allocates nothing: the t values of a panel for up to kStaticRows rows
-// (128 floats per row), 4 MiB on every GPU that loads the library, until the process ends.
+// The panel at column p0 (its own 128 or 64 columns, which have taken the panel before's update), and the
+// panel before's update of the columns from p0 + 128 on.  Tprev: the t values of the panel before (unused for
+// p0 = 0), Tcur: where this panel's go.  panel_wgs = ceil(rows / 64), row_tiles = ceil(rows / 128); the grid is
+// panel_wgs + row_tiles * (column tiles behind the panel) workgroups, the latter none for p0 = 0.
+// (at most 128 registers per lane, four workgroups per compute unit; 170 and three for groups of 32)
+template <int D>
+__global__ __launch_bounds__(kThreads, D == 32 ? 3 : 4) void correct_step_kernel(float *__restrict__ W, const float *__restrict__ U,
+                                                                 const float *__restrict__ Tprev, float *__restrict__ Tcur,
+                                                                 correct_shape a, int64_t p0, int width, int panel_wgs, int row_tiles)
+{
+    __shared__ __align__(16) float lds[kLdsFloats];
+    if ((int)blockIdx.x < panel_wgs) {
+        // the chain's waves go first where they share a SIMD with update waves, which have plenty of others to fill in
+        __builtin_amdgcn_s_setprio(2);
+        panel_role<D>(W, U, Tcur, a, p0, width, lds);
+    } else {
+        const int tile = (int)blockIdx.x - panel_wgs;
+        update_role(W, U, Tprev, a, p0 - kPanelCols, p0 + kPanelCols, tile % row_tiles, tile / row_tiles, lds);
+    }
+}
+
+// W: rows x cols float32 (cols a multiple of 64), U: cols x cols, work: two buffers of rows x 128 floats.
+hipError_t launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+                          int64_t ldu, float *work, hipStream_t s)
+{
+    correct_shape a;
+    a.ldw = ldw; a.rows = rows; a.cols = cols; a.ldu = ldu; a.K = c->K; a.ls = c->amplitude == PVQ_AMP_LS ? 1 : 0;
+    const int panel_wgs = (int)((rows + 63) / 64), row_tiles = (int)((rows + kTile - 1) / kTile);
+    int p = 0;
+    for (int64_t p0 = 0; p0 < cols; p0 += kPanelCols, p++) {
+        const int width = (int)std::min<int64_t>(kPanelCols, cols - p0);   // 128, or 64 at the end
+        const int64_t behind = cols - (p0 + kPanelCols);
+        const int col_tiles = p0 > 0 && behind > 0 ? (int)((behind + kTile - 1) / kTile) : 0;
+        float *Tcur = work + (int64_t)(p & 1) * rows * kPanelCols, *Tprev = work + (int64_t)((p & 1) ^ 1) * rows * kPanelCols;
+        if (p0 > 0) hipLaunchKernelGGL(correct_narrow_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(kThreads), 0, s, W, U, Tprev, a, p0, width);
+        const dim3 grid((unsigned)(panel_wgs + row_tiles * col_tiles));
+        switch (c->D) {
+        case 8: hipLaunchKernelGGL((correct_step_kernel<8>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
+        case 16: hipLaunchKernelGGL((correct_step_kernel<16>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
+        default: hipLaunchKernelGGL((correct_step_kernel<32>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Work buffers of the entry point that allocates nothing: the t values of two panels for up to kStaticRows rows
+// (twice 128 floats per row), 8 MiB on every GPU that loads the library, until the process ends.
 constexpr int64_t kStaticRows = 8192;
-static __device__ __align__(256) float scratch[kStaticRows * kPanelCols];
+static __device__ __align__(256) float scratch[2 * kStaticRows * kPanelCols];
 
 // The array's address on each device (in host code the array's name is only a stand-in for it), asked
 // for once per device with that device current.
@@ -319,22 +414,21 @@ hipError_t scratch_on_current_device(float **ptr)
 
 }  // namespace
 
-hipError_t pvq_launch_correct(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
+hipError_t pvq_launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw, const float *U,
                               int64_t ldu, float *work, hipStream_t s)
 {
-    return launch_correct(cc, W, rows, cols, ldw, U, ldu, work, s, 1 + pvq_ctx::kSideStreams);
+    return launch_correct(c, W, rows, cols, ldw, U, ldu, work, s);
 }
 
 int64_t pvq_correct_static_max_rows(void) { return kStaticRows; }
 
-// The same chain of kernels with the library's own work buffer and on the caller's stream alone: one chunk
-// of rows, so no stream or event is made or used.
-hipError_t pvq_launch_correct_static(const pvq_ctx *cc, float *W, int64_t rows, int64_t cols, int64_t ldw,
+// The same launches with the library's own work buffers.
+hipError_t pvq_launch_correct_static(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw,
                                      const float *U, int64_t ldu, hipStream_t s)
 {
     if (rows > kStaticRows) return hipErrorInvalidValue;   // (the entry point has refused it already)
     float *work = nullptr;
     const hipError_t e = scratch_on_current_device(&work);
     if (e != hipSuccess) return e;
-    return launch_correct(cc, W, rows, cols, ldw, U, ldu, work, s, 1);
+    return launch_correct(c, W, rows, cols, ldw, U, ldu, work, s);
 }

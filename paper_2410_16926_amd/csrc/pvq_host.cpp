@@ -459,13 +459,6 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
         hipError_t e = hipFree(p);
         if (first == hipSuccess) first = e;
     }
-    if (c->side_ready) {
-        for (int i = 0; i < pvq_ctx::kSideStreams; i++) {
-            if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
-            if (c->side_join[i]) (void)hipEventDestroy(c->side_join[i]);
-        }
-        if (c->side_fork) (void)hipEventDestroy(c->side_fork);
-    }
     delete c;
     return first == hipSuccess ? PVQ_OK : hip_fail(first);
 }
@@ -621,7 +614,7 @@ extern "C" int pvq_rotate_encode(const pvq_ctx *c, const void *X, int dtype, int
 extern "C" int pvq_correct_work_bytes(int64_t rows, size_t *bytes)
 {
     if (rows < 0 || rows > (int64_t)1 << 30 || !bytes) return PVQ_E_INVALID_ARG;
-    *bytes = (size_t)rows * 128 * sizeof(float);
+    *bytes = (size_t)rows * 256 * sizeof(float);   // two buffers of 128 t values per row, used in turn
     return PVQ_OK;
 }
 
@@ -646,7 +639,7 @@ extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t col
     bool empty;
     int rc = check_correct_args(c, W, rows, cols, ldw, U, ldu, &empty);
     if (rc || empty) return rc;
-    if (!work || work_bytes < (size_t)rows * 128 * sizeof(float)) return PVQ_E_INVALID_ARG;
+    if (!work || work_bytes < (size_t)rows * 256 * sizeof(float)) return PVQ_E_INVALID_ARG;
     if (!aligned(work, 16)) return PVQ_E_ALIGNMENT;
     if ((rc = check_device(c))) return rc;
     const hipError_t e = pvq_launch_correct(c, W, rows, cols, ldw, U, ldu, (float *)work, (hipStream_t)stream);

@@ -55,13 +55,6 @@ struct pvq_ctx {
     // Per-coordinate index offsets for the D = 8 / 24-bit encoder: [7][K+1][K+1][2] words
     // (coordinate, pulses left, magnitude, sign); nullptr when the configuration has none.
     uint32_t *enc8_offs;
-    // Side streams of pvq_correct (row chunks run side by side), made at its first call under `side_lock`
-    // and kept until the context is destroyed; default priority.
-    static constexpr int kSideStreams = 3;
-    std::mutex side_lock;
-    bool side_ready = false;
-    hipStream_t side[kSideStreams] = {};
-    hipEvent_t side_fork = nullptr, side_join[kSideStreams] = {};
 };
 
 struct pvq_encode_args {

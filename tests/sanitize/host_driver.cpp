@@ -51,7 +51,7 @@ int main()
     CHECK(pvq_ctx_create(nullptr, 8, 16, 0, nullptr, nullptr) == PVQ_E_INVALID_ARG);
     CHECK(pvq_ctx_destroy(nullptr) == PVQ_OK);
     size_t n = 0;
-    CHECK(pvq_correct_work_bytes(1000, &n) == PVQ_OK && n == 1000u * 128 * 4);
+    CHECK(pvq_correct_work_bytes(1000, &n) == PVQ_OK && n == 1000u * 256 * 4);
     CHECK(pvq_strerror(PVQ_E_UNSUPPORTED) != nullptr);
     puts("host: ok");
     return 0;

@@ -121,10 +121,10 @@ def test_table_driven_decoder_limits():
 
 
 def test_pvq_correct_work_bytes():
-    # host-only helper: 128 float32 per row (the t values of a panel), errors for what cannot be
+    # host-only helper: two buffers of 128 float32 per row (the t values of a panel), errors for what cannot be
     import ctypes as C
     n = C.c_size_t(0)
-    assert pvq.lib().pvq_correct_work_bytes(1000, C.byref(n)) == 0 and n.value == 1000 * 128 * 4
+    assert pvq.lib().pvq_correct_work_bytes(1000, C.byref(n)) == 0 and n.value == 1000 * 256 * 4
     assert pvq.lib().pvq_correct_work_bytes(0, C.byref(n)) == 0 and n.value == 0
     assert pvq.lib().pvq_correct_work_bytes(-1, C.byref(n)) == -1
     assert pvq.lib().pvq_correct_work_bytes(5, None) == -1

@@ -57,13 +57,14 @@ def test_a_wider_matrix():
     run_correct(8, 16, 700, 1536, seed=si.BASE_SEED + 542)
 
 
-@pytest.mark.parametrize("rows", [1100, 2100])
-def test_row_chunks_side_by_side(rows):
-    # from 1024 rows on the rows go in two to four chunks on streams of the context that fork from and
-    # join the caller's stream; the last chunk is shorter; the call is repeated on the same context
-    W0, ref = run_correct(8, 16, rows, 192, seed=si.BASE_SEED + 543 + rows)
-    ctx = pvq.pvq_ctx_create(8, 16)
-    _, U = si.calibration_hessian(192, 2 * 192, si.BASE_SEED + 543 + rows + 1)
+@pytest.mark.parametrize("D,K,rows,cols", [(8, 16, 1100, 448), (16, 33, 300, 640), (32, 60, 150, 384), (8, 16, 2100, 320)])
+def test_wide_updates_beside_the_next_panel(D, K, rows, cols):
+    # from the third panel on a launch holds panel workgroups and update tiles of the panel before (several row
+    # tiles and column tiles, ragged ends), and the panels' t values alternate between two buffers; an odd number
+    # of 64-column blocks ends in a half panel; the call is repeated on the same context
+    W0, ref = run_correct(D, K, rows, cols, seed=si.BASE_SEED + 543 + rows)
+    ctx = pvq.pvq_ctx_create(D, K)
+    _, U = si.calibration_hessian(cols, 2 * cols, si.BASE_SEED + 543 + rows + 1)
     Ud = gu.to_dev_f32(U)
     for _ in range(2):
         Wd = gu.to_dev_f32(W0)
@@ -74,17 +75,16 @@ def test_row_chunks_side_by_side(rows):
     ctx.close()
 
 
-@pytest.mark.parametrize("rows", [200, 1100])
-def test_the_call_can_be_captured_in_a_graph_and_replayed(rows):
-    # kernels, event records and waits only (the context's streams exist after the first, eager call): one
-    # chunk on the capturing stream, or two chunks that fork from it and join it again; every replay must
-    # reproduce the eager result for the weights then in the buffer
-    D, K, cols = 8, 16, 256
+@pytest.mark.parametrize("rows,cols", [(200, 256), (1100, 640)])
+def test_the_call_can_be_captured_in_a_graph_and_replayed(rows, cols):
+    # kernels only, all on the capturing stream; every replay must reproduce the eager result for the weights
+    # then in the buffer
+    D, K = 8, 16
     ctx = pvq.pvq_ctx_create(D, K)
     _, U = si.calibration_hessian(cols, 2 * cols, si.BASE_SEED + 561)
     Ud = gu.to_dev_f32(U)
     W = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
-    work = torch.empty((rows * 512,), dtype=torch.uint8, device="cuda")
+    work = torch.empty((rows * 1024,), dtype=torch.uint8, device="cuda")
 
     def fill(seed):
         W.copy_(gu.to_dev_f32(si.gaussian_weights(rows, cols, 0.02, seed=si.BASE_SEED + seed, rotate=False, bf16=False)))

@@ -89,9 +89,9 @@ def test_prefill_batch_of_activations_long_groups():
 
 def test_error_correction_of_a_square_projection():
     # Sec. 3.3 Step 6 on 8192 x 8192 (the attention projections' shape), in the configuration that the
-    # benchmark's extras time: four chunks of rows side by side, 64 panels.  Rows are independent, so the
-    # oracle corrects a sample of rows (first and last rows of tiles and of chunks) and those must match bit
-    # for bit.  The factor is a seeded well-conditioned upper triangular matrix (any such matrix is the
+    # benchmark's extras time: 64 panels, each launch with 128 panel workgroups in front of up to 3968 update
+    # tiles.  Rows are independent, so the oracle corrects a sample of rows (first and last rows of panel
+    # workgroups and of update tiles, and rows in between) and those must match bit for bit.  The factor is a seeded well-conditioned upper triangular matrix (any such matrix is the
     # factor of some inverse Hessian); the arithmetic, not the statistics, is what is compared here.
     rows = cols = 8192
     D, K = 8, 16

@@ -1,10 +1,11 @@
 """The entry point that allocates nothing: pvq_correct_static against pvq_correct, through the C library.
 
 Two calls in a row on one GPU, the second with a smaller input, so that the second runs over what the
-first left in the library's static work buffer; results must equal pvq_correct's bit for bit (both run
+first left in the library's static work buffers; results must equal pvq_correct's bit for bit (both run
 the same kernels in the same order), and pvq_correct's results are the oracle's (tests/test_gpu_correct.py;
 one of the cases is checked against the oracle here too)."""
 import ctypes as C
+import gc
 
 import numpy as np
 import pytest
@@ -42,6 +43,7 @@ def test_two_calls_in_a_row_the_second_smaller(D, K):
         Ud = gu.to_dev_f32(U)
         want = pvq.pvq_correct(ctx, gu.to_dev_f32(W0), Ud).cpu().numpy()
         Wd = gu.to_dev_f32(W0)
+        gc.collect()                                            # tensors of earlier tests that are garbage go now, not in between
         before = torch.cuda.memory_allocated()
         assert correct_static_raw(ctx, Wd, Ud) == 0
         assert torch.cuda.memory_allocated() == before          # torch's allocator was not asked either

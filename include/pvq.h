@@ -102,8 +102,8 @@ int pvq_beta_tables(int D, int64_t G, int scale_bits, double *edges, double *cen
 
 /*
  * Builds the size tables for (D,K) on the host, uploads them (and the amplitude tables) to the
- * current HIP device, and returns an immutable context usable from any thread and stream of that
- * device.  D in {8,16,32}: 1 <= K <= 127, index_bits <= 128.
+ * current HIP device, and returns a context usable from any thread and stream of that device; its tables
+ * never change, its one setting (pvq_ctx_set_amplitude) is meant to be chosen before the context is shared.  D in {8,16,32}: 1 <= K <= 127, index_bits <= 128.
  * D in {64,128} (long groups, the setting of on-the-fly quantisation of activations, Sec. 3.2 and
  *   Sec. 4.3; e.g. D = 128, K = 187 for 3 bits per value): 1 <= K <= 1023, N(D,K) <= 2^512, float32
  *   amplitudes only (scale_bits == 0; Sec. 3.3 Step 5 quantises amplitudes for small groups);
@@ -187,6 +187,8 @@ int pvq_hadamard(const void *X, int dtype, int64_t rows, int64_t cols, int64_t l
  * to the lowest coordinate), so results do not depend on the launch shape.  A group of zeros (or so
  * small that K/||w||_1 overflows) gets the point (0,...,0,+K), index 0.  Non-finite weights give
  * unspecified codes (never an out-of-bounds access).
+ * PVQ_E_UNSUPPORTED besides: with amplitude codes a workgroup keeps its row's amplitudes in LDS (7 bytes per
+ * group beside the size table, 64 KB in all), so rows of more than about 8000 groups are refused.
  */
 int pvq_encode(const pvq_ctx *ctx, const void *W, int dtype, int64_t rows, int64_t cols,
                int64_t ldw, uint32_t *index_out, void *scale_out, float *rownorm_out,

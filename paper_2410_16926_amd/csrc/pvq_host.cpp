@@ -568,6 +568,7 @@ extern "C" int pvq_encode(const pvq_ctx *c, const void *W, int dtype, int64_t ro
     a.index_row_words = stream_words(a.groups, c->index_bits);
     a.scale_row_words = c->scale_bits ? stream_words(a.groups, c->scale_bits) : 0;
     if (c->wide && pulses_out && c->K > 127) return PVQ_E_UNSUPPORTED;   // int8 cannot hold such pulses
+    if (!c->wide && !pvq_encode8_usable(c, a) && !pvq_encode_fits(c, a)) return PVQ_E_UNSUPPORTED;   // rows too long for LDS
     hipError_t e = c->wide ? pvq_wide_launch_encode(c, a, dtype, (hipStream_t)stream)
                    : pvq_encode8_usable(c, a) ? pvq_encode8_launch(c, a, dtype, (hipStream_t)stream)
                                               : pvq_launch_encode(c, a, dtype, (hipStream_t)stream);

@@ -103,6 +103,8 @@ __device__ inline float pvq_ls_amplitude(const float (&w)[D], const int (&y)[D])
 }
 
 // Each returns a hipError_t from the launch (hipSuccess if enqueued).
+// false: a row's share of LDS (size table, and with amplitude codes the row's amplitudes) exceeds 64 KB
+bool pvq_encode_fits(const pvq_ctx *ctx, const pvq_encode_args &a);
 hipError_t pvq_launch_encode(const pvq_ctx *ctx, const pvq_encode_args &a, int dtype, hipStream_t s);
 
 hipError_t pvq_launch_fill_zero(float *p, int64_t n, hipStream_t s);   // p[0..n) = 0 by a kernel

@@ -268,13 +268,20 @@ tables_t make_tables(const pvq_ctx *c)
 
 constexpr size_t kMaxLds = 64 * 1024;
 
+// LDS of encode_kernel for a row of G groups: the size table's rows, the row's index words being assembled,
+// and with amplitude codes the row's amplitudes
+size_t encode_lds_bytes(const pvq_ctx *c, size_t G)
+{
+    size_t lds = (size_t)c->D * (c->K + 2) * c->words * 4 + (size_t)8 * c->index_bits * 4 + 64 * 4 + 256 * 4;
+    if (c->scale_bits > 0) lds += (G + (G + 1) / 2 + (G + 3) / 4 + 4) * 4;
+    return lds;
+}
+
 template <int D, int W>
 hipError_t launch_encode_dw(const pvq_ctx *c, const pvq_encode_args &a, int dtype, hipStream_t s)
 {
-    const size_t G = (size_t)a.groups;
-    size_t lds = (size_t)D * (c->K + 2) * W * 4 + (size_t)8 * c->index_bits * 4 + 64 * 4 + 256 * 4;
-    if (c->scale_bits > 0) lds += (G + (G + 1) / 2 + (G + 3) / 4 + 4) * 4;
-    if (lds > kMaxLds) return hipErrorInvalidValue;
+    const size_t lds = encode_lds_bytes(c, (size_t)a.groups);
+    if (lds > kMaxLds) return hipErrorInvalidValue;      // (the caller has asked pvq_encode_fits)
     const unsigned grid = (unsigned)std::min<int64_t>(a.rows, 1 << 20);
     if (dtype == PVQ_F32)
         hipLaunchKernelGGL((encode_kernel<D, W, float>), dim3(grid), dim3(kThreads), lds, s, make_tables(c), a);
@@ -284,6 +291,8 @@ hipError_t launch_encode_dw(const pvq_ctx *c, const pvq_encode_args &a, int dtyp
 }
 
 }  // namespace
+
+bool pvq_encode_fits(const pvq_ctx *c, const pvq_encode_args &a) { return encode_lds_bytes(c, (size_t)a.groups) <= kMaxLds; }
 
 hipError_t pvq_launch_encode(const pvq_ctx *c, const pvq_encode_args &a, int dtype, hipStream_t s)
 {

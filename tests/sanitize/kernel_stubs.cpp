@@ -11,6 +11,7 @@ static hipError_t reached(const char *what)
     abort();
 }
 
+bool pvq_encode_fits(const pvq_ctx *, const pvq_encode_args &) { return true; }
 hipError_t pvq_launch_encode(const pvq_ctx *, const pvq_encode_args &, int, hipStream_t) { return reached("pvq_launch_encode"); }
 hipError_t pvq_launch_fill_zero(float *, int64_t, hipStream_t) { return reached("pvq_launch_fill_zero"); }
 hipError_t pvq_launch_correct(const pvq_ctx *, float *, int64_t, int64_t, int64_t, const float *, int64_t, float *, hipStream_t) { return reached("pvq_launch_correct"); }

@@ -545,6 +545,18 @@ def test_empty_inputs_and_argument_errors():
     with pytest.raises(pvq.PvqError):
         pvq.pvq_ctx_create(8, 16, 3, np.zeros(7), np.zeros(8))
     ctx.close()
+    # amplitude codes and a row whose amplitudes do not fit a workgroup's LDS: refused as unsupported, not as a
+    # failed launch
+    for K, groups, want in ((5, 16384, -2), (16, 16384, -2), (5, 8192, 0)):
+        cols = 8 * groups
+        ctx, oe, oc = gu.make_ctx(8, K, 2, groups)
+        Wl = torch.ones((1, cols), dtype=torch.float32, device="cuda")
+        pl = pvq.alloc_packed(ctx, 1, cols, Wl.device)
+        rc = L.pvq_encode(ctx.handle, Wl.data_ptr(), 0, 1, cols, cols, pl.index.data_ptr(), pl.scale.data_ptr(),
+                          pl.rownorm.data_ptr(), None, None)
+        torch.cuda.synchronize()
+        assert rc == want, (K, groups, rc)
+        ctx.close()
 
 
 def test_zero_matrix_and_nonfinite_inputs_are_safe():

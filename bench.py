@@ -417,6 +417,16 @@ def main():
             "gemv_b1_ms": round(timed(lambda: pvq.pvq_decode_gemv(ctx16, p16, xs[1], out=ys[1])), 4),
         }
         ctx16.close()
+        K32 = pvq.pvq_max_k(32, 104)
+        ctx32 = pvq.pvq_ctx_create(32, K32)
+        p32 = pvq.alloc_packed(ctx32, ROWS, COLS, dev)
+        ex["d32_k60_f32_amplitudes"] = {
+            "encode_ms": round(timed(lambda: pvq.pvq_encode(ctx32, W, out=p32)), 4),
+            "decode_ms": round(timed(lambda: pvq.pvq_decode(ctx32, p32, out=Wout)), 4),
+            "gemv_b1_ms": round(timed(lambda: pvq.pvq_decode_gemv(ctx32, p32, xs[1], out=ys[1])), 4),
+        }
+        ctx32.close()
+        del p16, p32
         # App. C.2: the size table on the GPU (one workgroup, a latency-bound scan), and the oracle's beside it
         from oracle import pvq_oracle as oracle
         for (d_, k_, w_) in ((32, 60, 4), (128, 187, 12)):
@@ -431,6 +441,16 @@ def main():
             ms = timed(lambda: pvq.pvq_hadamard(W, blk, sg, out=Wout), reps=10)
             had[f"block_{blk}"] = {"ms": round(ms, 4), "GBps": round(2 * W.numel() * W.element_size() / ms / 1e6, 1)}
         ex["hadamard_bf16"] = had
+        # the same rotation fused in front of the D = 8 encoder (the rotated values are never written), against
+        # the two calls with a float32 matrix in between
+        Wf = torch.empty((ROWS, COLS), dtype=torch.float32, device=dev)
+        rot8 = {}
+        for blk in (64, 512, 4096, 8192):
+            tf = timed(lambda: pvq.pvq_rotate_encode(ctx, W, blk, sg, out=sets[0]), reps=10)
+            t2 = timed(lambda: (pvq.pvq_hadamard(W, blk, sg, out=Wf), pvq.pvq_encode(ctx, Wf, out=sets[0])), reps=10)
+            rot8[f"block_{blk}"] = {"fused_ms": round(tf, 4), "two_calls_ms": round(t2, 4)}
+        ex["rotate_encode_d8"] = rot8
+        del Wf
         # on-the-fly activation quantisation (Sec. 3.2, Sec. 4.3): groups of 128 values, 3 bits per value
         # (K = 187, 384-bit indices), a prefill batch and a decode batch of hidden size 8192
         K128 = pvq.pvq_max_k(128, 384)

@@ -21,7 +21,7 @@ EXPORTS = [
 ]
 
 # host-only diagnostics declared in csrc/pvq_diagnostics.h, exported for the tests
-DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_walk_tables_selftest", "pvq_decode_gemv_plan"]
+DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_walk_tables_selftest", "pvq_decode_gemv_plan", "pvq_correct_set_front_tiles"]
 
 
 class PvqError(RuntimeError):
@@ -70,6 +70,7 @@ def lib():
         L.pvq_correct_work_bytes.argtypes = [i64, vp]
         L.pvq_correct.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, C.c_size_t, vp]
         L.pvq_correct_static_max_rows.argtypes = [vp]
+        L.pvq_correct_set_front_tiles.argtypes = [i64, vp]
         L.pvq_correct_static.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
         L.pvq_decode_gemv.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp]
@@ -306,6 +307,14 @@ def pvq_correct(ctx: PvqContext, W, U, work=None):
     _check(lib().pvq_correct(ctx.handle, _ptr(W), rows, cols, ldw, _ptr(U), ldu, _ptr(work), work.numel(),
                              _stream_ptr()), "pvq_correct")
     return W
+
+
+def pvq_correct_set_front_tiles(tiles: int) -> int:
+    """Diagnostics: from how many update tiles on a launch of pvq_correct does the narrow update inside its panel
+    workgroups (process-wide; results do not depend on it).  Returns the number in force before."""
+    old = C.c_int64(0)
+    _check(lib().pvq_correct_set_front_tiles(int(tiles), C.byref(old)), "pvq_correct_set_front_tiles")
+    return old.value
 
 
 def pvq_correct_static_max_rows() -> int:

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "pvq_internal.h"
 #include "pvq_quantize_dev.h"
@@ -43,6 +44,9 @@ constexpr int kPanelWaves = 4;    // waves of a workgroup: group g of the panel 
 constexpr int kThreads = 64 * kPanelWaves;
 constexpr int kTile = 128;        // rows and columns of an update tile
 constexpr int kStage = 32;        // rows of U (and t values per row) that an update tile holds in LDS at a time
+// update tiles from which on a launch's panel workgroups do the narrow update themselves (one and a half rounds of
+// four workgroups on each of 256 units); a test lowers it to reach that path with small matrices
+std::atomic<int64_t> g_front_tiles{1536};
 constexpr int kLdsFloats = kStage * (kTile + 4) + kStage * kTile;   // update: t tile and U tile; panel: 128 x 64 t values
 static_assert(kLdsFloats >= kPanelCols * 64, "the panel role's t values fit");
 
@@ -53,6 +57,8 @@ struct correct_shape {
 
 // Panel role.  Lane = row in each of the four waves; wave w holds the values of groups w, w + 4, ... of its rows
 // in registers.
+//   With `front` (a launch with enough update tiles to outlast it), first the panel before's 128 multiply-adds per
+// element onto this panel's columns, which otherwise a launch of correct_narrow_kernel has done.
 //   Step G (one barrier per step): the owner of group G applies to it the updates of group G - 1 (the only ones
 // still missing: it caught up with the rest one step earlier), stores what is then quantised to W, runs
 // quantiser, amplitude, error and substitution, and puts the t values into LDS and the work buffer; the other
@@ -66,8 +72,9 @@ struct correct_shape {
 // t values of the panel are kept, and the rows of U come through scalar loads (the pointer is read-only for the
 // kernel and the address is the same in all lanes), which costs the owner a few exposed load latencies per step.
 template <int D>
-__device__ inline void panel_role(float *__restrict__ W, const float *__restrict__ U, float *__restrict__ Tcur,
-                                  const correct_shape &a, int64_t p0, int width, float *lds)
+__device__ inline void panel_role(float *__restrict__ W, const float *__restrict__ U, const float *__restrict__ Tprev,
+                                  float *__restrict__ Tcur, const correct_shape &a, int64_t p0, int width, bool front,
+                                  float *lds)
 {
     constexpr int NG = kPanelCols / D, OWN = NG / kPanelWaves;
     constexpr bool kRing = D == 8;
@@ -94,6 +101,82 @@ __device__ inline void panel_role(float *__restrict__ W, const float *__restrict
             const float4 q = *reinterpret_cast<const float4 *>(wrow + (g < ngroups ? g : 0) * D + i);
             w[o][i] = q.x; w[o][i + 1] = q.y; w[o][i + 2] = q.z; w[o][i + 3] = q.w;
         }
+    }
+
+    if (front) {
+        // w <- w - t'[0] U[p0 - 128][c] - ... - t'[127] U[p0 - 1][c] for the wave's 32 columns c, t' = the panel before's
+        // t values of the row: 32 rows of U and 32 t values per row go through LDS at a time, fetched into
+        // registers while the 32 before are worked on
+        constexpr int kChunk = 32, kTPitch = 65;                // t values transposed: [k][row], rows 65 words apart
+        float *uc = lds, *tc = lds + kChunk * kPanelCols;
+        static_assert((kChunk + 1) * kPanelCols + (kChunk + 1) * kTPitch <= kLdsFloats, "a chunk fits, and a row more may be read");
+        const float *Ub = U + (p0 - kPanelCols) * a.ldu + p0;   // row p0 - 128 + k, column p0 + c
+        const int64_t row0 = (int64_t)blockIdx.x * 64;
+        float4 uq[4], tq[2];
+        auto fetch = [&](int chunk) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int e = threadIdx.x + i * kThreads, k = e / (kPanelCols / 4), c = (e % (kPanelCols / 4)) * 4;
+                uq[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (c < width) uq[i] = *reinterpret_cast<const float4 *>(Ub + (int64_t)(chunk * kChunk + k) * a.ldu + c);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int e = threadIdx.x + i * kThreads, rr = e / (kChunk / 4), k4 = (e % (kChunk / 4)) * 4;
+                const int64_t rsrc = std::min<int64_t>(row0 + rr, a.rows - 1);
+                tq[i] = *reinterpret_cast<const float4 *>(Tprev + rsrc * kPanelCols + chunk * kChunk + k4);
+            }
+        };
+        fetch(0);
+        for (int chunk = 0; chunk < kPanelCols / kChunk; chunk++) {
+            if (chunk) __syncthreads();                         // the chunk before is no longer read
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int e = threadIdx.x + i * kThreads, k = e / (kPanelCols / 4), c = (e % (kPanelCols / 4)) * 4;
+                *reinterpret_cast<float4 *>(uc + k * kPanelCols + c) = uq[i];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int e = threadIdx.x + i * kThreads, rr = e / (kChunk / 4), k4 = (e % (kChunk / 4)) * 4;
+                tc[k4 * kTPitch + rr] = tq[i].x; tc[(k4 + 1) * kTPitch + rr] = tq[i].y;
+                tc[(k4 + 2) * kTPitch + rr] = tq[i].z; tc[(k4 + 3) * kTPitch + rr] = tq[i].w;
+            }
+            __syncthreads();
+            if (chunk + 1 < kPanelCols / kChunk) fetch(chunk + 1);
+            // the wave's 32 values of a row of U: one half on its way while the other is worked on (past the last
+            // row of a chunk the words behind it are read and not used)
+            auto half_row = [&](int k, int h, float4 (&q)[OWN * D / 8]) {
+                const float *urow = uc + k * kPanelCols;
+#pragma unroll
+                for (int i = 0; i < OWN * D / 8; i++) {
+                    const int col = h * (OWN * D / 2) + 4 * i;          // of the wave's values: group col / D, value col % D
+                    q[i] = *reinterpret_cast<const float4 *>(urow + (wave + kPanelWaves * (col / D)) * D + col % D);
+                }
+            };
+            auto half_fma = [&](float tk, int h, const float4 (&q)[OWN * D / 8]) {
+#pragma unroll
+                for (int i = 0; i < OWN * D / 8; i++) {
+                    const int col = h * (OWN * D / 2) + 4 * i, o = col / D, j = col % D;
+                    w[o][j] = __builtin_fmaf(-tk, q[i].x, w[o][j]);
+                    w[o][j + 1] = __builtin_fmaf(-tk, q[i].y, w[o][j + 1]);
+                    w[o][j + 2] = __builtin_fmaf(-tk, q[i].z, w[o][j + 2]);
+                    w[o][j + 3] = __builtin_fmaf(-tk, q[i].w, w[o][j + 3]);
+                }
+            };
+            float4 qa[OWN * D / 8], qb[OWN * D / 8];
+            half_row(0, 0, qa);
+            float tk = tc[lane];
+#pragma unroll 2
+            for (int k = 0; k < kChunk; k++) {
+                half_row(k, 1, qb);
+                half_fma(tk, 0, qa);
+                half_row(k + 1, 0, qa);
+                const float tn = tc[(k + 1) * kTPitch + lane];
+                half_fma(tk, 1, qb);
+                tk = tn;
+            }
+        }
+        __syncthreads();                                        // LDS now takes this panel's rows of U and t values
     }
 
     // the rows of U of group g, from device memory to the ring: a float4 per lane
@@ -344,13 +427,14 @@ __global__ __launch_bounds__(kThreads) void correct_narrow_kernel(float *__restr
 template <int D>
 __global__ __launch_bounds__(kThreads, D == 32 ? 3 : 4) void correct_step_kernel(float *__restrict__ W, const float *__restrict__ U,
                                                                  const float *__restrict__ Tprev, float *__restrict__ Tcur,
-                                                                 correct_shape a, int64_t p0, int width, int panel_wgs, int row_tiles)
+                                                                 correct_shape a, int64_t p0, int width, int panel_wgs, int row_tiles,
+                                                                 int front)
 {
     __shared__ __align__(16) float lds[kLdsFloats];
     if ((int)blockIdx.x < panel_wgs) {
         // the chain's waves go first where they share a SIMD with update waves, which have plenty of others to fill in
         __builtin_amdgcn_s_setprio(2);
-        panel_role<D>(W, U, Tcur, a, p0, width, lds);
+        panel_role<D>(W, U, Tprev, Tcur, a, p0, width, front != 0, lds);
     } else {
         const int tile = (int)blockIdx.x - panel_wgs;
         update_role(W, U, Tprev, a, p0 - kPanelCols, p0 + kPanelCols, tile % row_tiles, tile / row_tiles, lds);
@@ -370,12 +454,16 @@ hipError_t launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t cols
         const int64_t behind = cols - (p0 + kPanelCols);
         const int col_tiles = p0 > 0 && behind > 0 ? (int)((behind + kTile - 1) / kTile) : 0;
         float *Tcur = work + (int64_t)(p & 1) * rows * kPanelCols, *Tprev = work + (int64_t)((p & 1) ^ 1) * rows * kPanelCols;
-        if (p0 > 0) hipLaunchKernelGGL(correct_narrow_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(kThreads), 0, s, W, U, Tprev, a, p0, width);
+        // the panel before's update of this panel's columns: by the panel workgroups themselves (64 rows x 128 columns
+        // x 128 terms on four waves: 25 us) where the launch's update tiles outlast that, else by a launch of its own
+        // that spreads over the machine
+        const int front = p0 > 0 && (int64_t)row_tiles * col_tiles >= g_front_tiles.load(std::memory_order_relaxed) ? 1 : 0;
+        if (p0 > 0 && !front) hipLaunchKernelGGL(correct_narrow_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(kThreads), 0, s, W, U, Tprev, a, p0, width);
         const dim3 grid((unsigned)(panel_wgs + row_tiles * col_tiles));
         switch (c->D) {
-        case 8: hipLaunchKernelGGL((correct_step_kernel<8>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
-        case 16: hipLaunchKernelGGL((correct_step_kernel<16>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
-        default: hipLaunchKernelGGL((correct_step_kernel<32>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles); break;
+        case 8: hipLaunchKernelGGL((correct_step_kernel<8>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles, front); break;
+        case 16: hipLaunchKernelGGL((correct_step_kernel<16>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles, front); break;
+        default: hipLaunchKernelGGL((correct_step_kernel<32>), grid, dim3(kThreads), 0, s, W, U, Tprev, Tcur, a, p0, width, panel_wgs, row_tiles, front); break;
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -421,6 +509,8 @@ hipError_t pvq_launch_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t 
 }
 
 int64_t pvq_correct_static_max_rows(void) { return kStaticRows; }
+
+int64_t pvq_correct_front_tiles(int64_t tiles) { return g_front_tiles.exchange(tiles); }
 
 // The same launches with the library's own work buffers.
 hipError_t pvq_launch_correct_static(const pvq_ctx *c, float *W, int64_t rows, int64_t cols, int64_t ldw,

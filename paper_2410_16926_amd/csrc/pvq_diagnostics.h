@@ -42,6 +42,14 @@ struct pvq_ctx;
 int pvq_decode_gemv_plan(const struct pvq_ctx *ctx, int64_t rows, int64_t cols, int batch, int *kinds, int *nvecs,
                          int max_passes, int *passes);
 
+/*
+ * pvq_correct chooses per launch who applies the panel before's update to the panel's own columns: a launch of
+ * its own, or, from *tiles* update tiles in the launch on, the panel's workgroups themselves (default 1536, which
+ * small test matrices never reach).  Sets that number for the process and returns the one in force before in
+ * *previous (may be NULL); results do not depend on it.  PVQ_E_INVALID_ARG for tiles < 0.
+ */
+int pvq_correct_set_front_tiles(int64_t tiles, int64_t *previous);
+
 #ifdef __cplusplus
 }
 #endif

@@ -647,6 +647,14 @@ extern "C" int pvq_correct(const pvq_ctx *c, float *W, int64_t rows, int64_t col
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 
+extern "C" int pvq_correct_set_front_tiles(int64_t tiles, int64_t *previous)
+{
+    if (tiles < 0) return PVQ_E_INVALID_ARG;
+    const int64_t old = pvq_correct_front_tiles(tiles);
+    if (previous) *previous = old;
+    return PVQ_OK;
+}
+
 extern "C" int pvq_correct_static_max_rows(int64_t *rows)
 {
     if (!rows) return PVQ_E_INVALID_ARG;

@@ -115,6 +115,8 @@ hipError_t pvq_launch_correct(const pvq_ctx *ctx, float *W, int64_t rows, int64_
                               int64_t ldu, float *work, hipStream_t s);
 // the same with the library's static work buffer (at most pvq_correct_static_max_rows() rows), on `s` alone
 int64_t pvq_correct_static_max_rows(void);
+// sets the number of update tiles from which a launch does the narrow update inside its panel workgroups; returns the old one
+int64_t pvq_correct_front_tiles(int64_t tiles);
 hipError_t pvq_launch_correct_static(const pvq_ctx *ctx, float *W, int64_t rows, int64_t cols, int64_t ldw,
                                      const float *U, int64_t ldu, hipStream_t s);
 

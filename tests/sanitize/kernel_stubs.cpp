@@ -16,6 +16,7 @@ hipError_t pvq_launch_encode(const pvq_ctx *, const pvq_encode_args &, int, hipS
 hipError_t pvq_launch_fill_zero(float *, int64_t, hipStream_t) { return reached("pvq_launch_fill_zero"); }
 hipError_t pvq_launch_correct(const pvq_ctx *, float *, int64_t, int64_t, int64_t, const float *, int64_t, float *, hipStream_t) { return reached("pvq_launch_correct"); }
 int64_t pvq_correct_static_max_rows(void) { return 8192; }
+int64_t pvq_correct_front_tiles(int64_t) { return 1536; }
 hipError_t pvq_launch_correct_static(const pvq_ctx *, float *, int64_t, int64_t, int64_t, const float *, int64_t, hipStream_t) { return reached("pvq_launch_correct_static"); }
 hipError_t pvq_launch_size_table(int, int, int, uint32_t *, uint32_t *, hipStream_t) { return reached("pvq_launch_size_table"); }
 hipError_t pvq_launch_hadamard(const void *, int, int64_t, int64_t, int64_t, int, const uint8_t *, int, void *, int, int64_t, hipStream_t) { return reached("pvq_launch_hadamard"); }

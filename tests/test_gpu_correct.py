@@ -75,6 +75,19 @@ def test_wide_updates_beside_the_next_panel(D, K, rows, cols):
     ctx.close()
 
 
+@pytest.mark.parametrize("D,K,rows,cols,amplitude", [(8, 16, 700, 1536, "l2"), (8, 16, 130, 448, "ls"), (16, 33, 300, 640, "l2"),
+                                                     (32, 60, 150, 384, "ls"), (8, 5, 65, 320, "l2")])
+def test_narrow_update_inside_the_panel_workgroups(D, K, rows, cols, amplitude):
+    # a launch with many update tiles lets its panel workgroups apply the panel before's update to their own
+    # columns instead of a launch of its own; the threshold is lowered so that these small matrices take that path
+    # in every launch that has update tiles at all (the last two panels of a matrix keep the separate launch)
+    old = pvq.pvq_correct_set_front_tiles(1)
+    try:
+        run_correct(D, K, rows, cols, seed=si.BASE_SEED + 580 + rows + cols, amplitude=amplitude)
+    finally:
+        assert pvq.pvq_correct_set_front_tiles(old) == 1
+
+
 @pytest.mark.parametrize("rows,cols", [(200, 256), (1100, 640)])
 def test_the_call_can_be_captured_in_a_graph_and_replayed(rows, cols):
     # kernels only, all on the capturing stream; every replay must reproduce the eager result for the weights

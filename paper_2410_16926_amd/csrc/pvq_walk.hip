@@ -42,23 +42,56 @@ struct walk_launch {
 
 using namespace pvq_walk;
 
+// What a group needs from memory, as it comes: the W + 1 words its index may touch, its amplitude (the float, or the
+// word that holds its code) and, with codes, the row's normaliser.  Fetching does no arithmetic on loaded data and has
+// no load under a condition, so the loads stay in flight until the item is taken apart, one item later: a wait placed
+// right behind a load also waits for every store issued before it (memory operations complete in order).
 template <int W>
-__device__ inline typename wide<W>::type load_field(const uint32_t *__restrict__ row, uint32_t pos, int bits)
+struct raw_group {
+    uint32_t w[W + 1];
+    uint32_t amp;
+    float rownorm;
+};
+
+// row: the row's index words, last_word: index of the row's last word (words past the field's own are read
+// inside the row and dropped); srow: the row of the scale plane
+template <int W>
+__device__ inline void fetch_group(const uint32_t *__restrict__ row, uint32_t last_word, const void *__restrict__ srow,
+                                   const float *__restrict__ rownorm, int g, int index_bits, int scale_bits, raw_group<W> &r)
+{
+    const uint32_t w0 = ((uint32_t)g * (uint32_t)index_bits) >> 5;
+#pragma unroll
+    for (int i = 0; i <= W; i++) r.w[i] = row[std::min(w0 + (uint32_t)i, last_word)];
+    const uint32_t aw = scale_bits == 0 ? (uint32_t)g : ((uint32_t)g * (uint32_t)scale_bits) >> 5;
+    r.amp = reinterpret_cast<const uint32_t *>(srow)[aw];
+    r.rownorm = scale_bits == 0 ? 0.0f : *rownorm;
+}
+
+template <int W>
+__device__ inline typename wide<W>::type group_index(const raw_group<W> &r, int g, int bits)
 {
     using T = typename wide<W>::type;
-    const uint32_t w0 = pos >> 5, sh = pos & 31;
+    const uint32_t sh = ((uint32_t)g * (uint32_t)bits) & 31;
     const int span = (int)sh + bits;
-    T v = (T)(row[w0] >> sh);
+    T v = (T)(r.w[0] >> sh);
 #pragma unroll
     for (int i = 1; i <= W; i++) {
-        if (32 * i < span) {
-            const int off = 32 * i - (int)sh;
-            if (off < 32 * W) v |= (T)row[w0 + i] << off;
-        }
+        const int off = 32 * i - (int)sh;
+        if (32 * i < span && off < 32 * W) v |= (T)r.w[i] << off;
     }
     if (bits < 32 * W) v &= (((T)1) << bits) - 1;
     return v;
 }
+
+template <int W>
+__device__ inline float group_amp(const raw_group<W> &r, int g, int scale_bits, const float *sqrtc)
+{
+    if (scale_bits == 0) return __uint_as_float(r.amp);
+    const uint32_t pos = (uint32_t)g * (uint32_t)scale_bits;
+    const uint32_t code = (r.amp >> (pos & 31)) & ((1u << scale_bits) - 1u);
+    return sqrtc[code] * sqrtf(r.rownorm);
+}
+
 
 __device__ inline uint32_t f32_to_bf16_rne(float f)
 {
@@ -77,16 +110,6 @@ __device__ inline void tables_to_lds(unsigned char *lds, const walk_launch &wl, 
     if (wl.scale_bits > 0)
         for (int i = threadIdx.x; i < (1 << wl.scale_bits); i += blockDim.x) sqrtc[i] = wl.sqrtc[i];
     __syncthreads();
-}
-
-__device__ inline float group_amplitude(const walk_launch &wl, const pvq_decode_args &a, int64_t row, int g,
-                                        float sqrt_rownorm, const float *sqrtc)
-{
-    if (wl.scale_bits == 0) return reinterpret_cast<const float *>(a.scale)[row * a.groups + g];
-    const uint32_t *srow = reinterpret_cast<const uint32_t *>(a.scale) + row * a.scale_row_words;
-    const uint32_t pos = (uint32_t)g * (uint32_t)wl.scale_bits;
-    const uint32_t code = (srow[pos >> 5] >> (pos & 31)) & ((1u << wl.scale_bits) - 1u);
-    return sqrtc[code] * sqrt_rownorm;
 }
 
 // Decode to a matrix.  Workgroups stay for the whole launch (the tables are copied once each); after the copy
@@ -112,24 +135,31 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
     // wait for a load also waits for every memory operation issued before it, so loads that follow stores
     // would make each item wait for the stores of the one before.  A wave past its last item, and lanes
     // past a row's last group, fetch a valid place again and drop it.
-    T c_n = 0;
-    float amp_n = 0.0f;
+    raw_group<W> nx;
+    int g_nx = 0;
+    const uint32_t last_word = (uint32_t)a.index_row_words - 1u;
+    const int64_t srow_bytes = wl.scale_bits == 0 ? a.groups * 4 : a.scale_row_words * 4;
     auto fetch = [&](int64_t item) {
         const int64_t it = item < items ? item : items - 1;
         const int64_t row = it / tiles;
         const int g = (int)(it - row * tiles) * kWave + lane;
-        const int gg = g < G ? g : 0;
-        c_n = load_field<W>(a.index + row * a.index_row_words, (uint32_t)gg * (uint32_t)wl.index_bits, wl.index_bits);
-        const float srn = wl.scale_bits > 0 ? sqrtf(a.rownorm[row]) : 0.0f;
-        amp_n = group_amplitude(wl, a, row, gg, srn, sqrtc);
+        g_nx = g < G ? g : 0;
+        fetch_group<W>(a.index + row * a.index_row_words, last_word,
+                       reinterpret_cast<const unsigned char *>(a.scale) + row * srow_bytes,
+                       wl.scale_bits == 0 ? nullptr : a.rownorm + row, g_nx,
+                       wl.index_bits, wl.scale_bits, nx);
     };
     const int64_t first = (int64_t)blockIdx.x * kWaves + wave;
     if (first < items) fetch(first);
+    // The first item has arrived before the loop is entered (vmcnt(0), the other counters left alone): the loop then
+    // starts, on its first pass as on every other, with nothing but stores in flight behind the item it takes
+    // apart, and its waits are counted from there; sized for the entry path they would wait for the stores too.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     for (int64_t item = first; item < items; item += stride) {
         const int64_t row = item / tiles;
         const int g0 = (int)(item - row * tiles) * kWave;      // the wave's first group
-        const T c = c_n;
-        const float amp = amp_n;
+        const T c = group_index<W>(nx, g_nx, wl.index_bits);
+        const float amp = group_amp<W>(nx, g_nx, wl.scale_bits, sqrtc);
         fetch(item + stride);
         int y[D];
         const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, int v) { y[i] = v; });
@@ -157,12 +187,16 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
             else if (lane < valid) *reinterpret_cast<uint4 *>(o + ((size_t)lane * NC + j) * 16) = chunk;
         }
         if constexpr (STAGE) {
-            // the item's groups are NC * valid consecutive chunks of the output
+            // the item's groups are NC * valid consecutive chunks of the output.  Every lane stores in every pass:
+            // lanes past the item's end store its last chunk once more (the same bytes to the same place), so that
+            // the number of stores in flight is known where the next item's words are waited for, and that wait
+            // does not have to cover them
+            const int last = valid * NC - 1;
 #pragma unroll
             for (int j = 0; j < NC; j++) {
-                const int ch = j * kWave + lane;
+                const int ch = std::min(j * kWave + lane, last);
                 const uint4 v = stage[ch];                     // written by this wave only: no barrier
-                if (ch < valid * NC) *reinterpret_cast<uint4 *>(o + (size_t)ch * 16) = v;
+                *reinterpret_cast<uint4 *>(o + (size_t)ch * 16) = v;
             }
         }
     }
@@ -185,18 +219,20 @@ __global__ __launch_bounds__(kMaxThreads) void gemv_walk_kernel(walk_launch wl, 
     const int kWaves = (int)blockDim.x / kWave;
     for (int64_t row = (int64_t)blockIdx.x * kWaves + wave; row < a.rows; row += (int64_t)gridDim.x * kWaves) {
         const uint32_t *irow = a.index + row * a.index_row_words;
-        const float srn = wl.scale_bits > 0 ? sqrtf(a.rownorm[row]) : 0.0f;
+        const uint32_t last_word = (uint32_t)a.index_row_words - 1u;
+        const unsigned char *srow = reinterpret_cast<const unsigned char *>(a.scale) +
+                                    row * (wl.scale_bits == 0 ? a.groups * 4 : a.scale_row_words * 4);
         float acc[NB];
 #pragma unroll
         for (int b = 0; b < NB; b++) acc[b] = 0.0f;
         // what a group needs from memory; lanes past the row's end fetch group 0 again and drop it
-        T c_n = 0;
-        float amp_n = 0.0f;
+        raw_group<W> nx;
+        int g_nx = 0;
         uint4 x_n[NB][XW];
         auto fetch = [&](int g) {
             const int gg = g < G ? g : 0;
-            c_n = load_field<W>(irow, (uint32_t)gg * (uint32_t)wl.index_bits, wl.index_bits);
-            amp_n = group_amplitude(wl, a, row, gg, srn, sqrtc);
+            g_nx = gg;
+            fetch_group<W>(irow, last_word, srow, wl.scale_bits == 0 ? nullptr : a.rownorm + row, gg, wl.index_bits, wl.scale_bits, nx);
 #pragma unroll
             for (int b = 0; b < NB; b++)
 #pragma unroll
@@ -205,8 +241,8 @@ __global__ __launch_bounds__(kMaxThreads) void gemv_walk_kernel(walk_launch wl, 
         };
         fetch(lane);
         for (int g = lane; g < G; g += kWave) {
-            const T c = c_n;
-            const float amp = amp_n;
+            const T c = group_index<W>(nx, g_nx, wl.index_bits);
+            const float amp = group_amp<W>(nx, g_nx, wl.scale_bits, sqrtc);
             uint4 x[NB][XW];
 #pragma unroll
             for (int b = 0; b < NB; b++)

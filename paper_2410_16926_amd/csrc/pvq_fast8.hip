@@ -492,9 +492,9 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_row_kernel(fast8_launch f,
             for (int h = 0; h < 2; h++) {
                 if (it + h < nitems) {
                     ahead_t cu = nx;
-                    // item it + h + 1 sits in set (h + 1) % 2
-                    start_item((h + 1) % 2, std::min(n_sl, nsl - 1), nx);
-                    advance(n_sl, n_i);
+                    // (in front of the next item's requests: memory operations complete in order, so the wait for the
+                    // activations, which the compiler places before their use whether or not this branch ran, would
+                    // otherwise cover those requests too, in every item)
                     if (c_sl != x_sl) {
                         const uint16_t *xp = reinterpret_cast<const uint16_t *>(a.x) + (int64_t)b0 * a.ldx +
                                              (int64_t)(c_sl * kTileGroups + gl) * 8;
@@ -505,6 +505,9 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_row_kernel(fast8_launch f,
                         }
                         x_sl = c_sl;
                     }
+                    // item it + h + 1 sits in set (h + 1) % 2
+                    start_item((h + 1) % 2, std::min(n_sl, nsl - 1), nx);
+                    advance(n_sl, n_i);
                     uint32_t n2x4[kGroupsPerLane];
                     float dot[kGroupsPerLane];
                     auto emit = [&](int j, int pair, uint32_t w) {

@@ -80,18 +80,6 @@ __device__ inline void copy_to_lds(T *dst, const T *__restrict__ src, int n)
 
 __device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
-// v_cvt_pk_bf16_f32 (round to nearest even) on the value paired with zero
-__device__ inline uint32_t f32_to_bf16_rne(float f)
-{
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-    const f32x2_t pair = {f, 0.0f};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2_t)) & 0xFFFFu;
-}
-
-// v_cvt_f16_f32 rounds to nearest even
-__device__ inline uint16_t f32_to_f16_rne(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
-
 // ---------------------------------------------------------------------------------------------
 // encode
 // ---------------------------------------------------------------------------------------------

@@ -241,7 +241,7 @@ __device__ inline void panel_role(float *__restrict__ W, const float *__restrict
                 int y[D];
                 float ss;
                 if constexpr (D == 8) ss = quantize_group8(wg, a.K, y);
-                else ss = quantize_group<D>(wg, a.K, y);
+                else ss = quantize_group_select<D>(wg, a.K, y);
                 const float s = a.ls ? pvq_ls_amplitude<D>(wg, y) : sqrtf(ss);
                 int n2 = 0;
 #pragma unroll

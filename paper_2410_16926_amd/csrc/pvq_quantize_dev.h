@@ -1,7 +1,9 @@
 // Device code shared by the kernels that quantise a group onto the pyramid (Sec. 2.5): the encoders and
 // the error correction of Sec. 3.3 Step 6.  float32, fixed evaluation order: the results are part of the
-// format.  quantize_group<D> is the repair as a loop, for any D; quantize_group8 the same point without
-// branches for D = 8, built on count_wins, which the D = 8 encoder uses as well.
+// format.  The point: project onto the l1 ball of radius K, round to nearest even, then move single pulses on
+// the coordinates of largest deviation (lowest coordinate on ties) until the count is K.  quantize_group8 finds
+// it without branches for D = 8, built on count_wins, which the D = 8 encoder uses as well;
+// quantize_group_select<D> for any D, one round per pulse to move.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -17,77 +19,6 @@ __device__ inline float tree_sum(float (&v)[D])
 #pragma unroll
         for (int i = 0; i < D; i += 2 * s) v[i] = v[i] + v[i + s];
     return v[0];
-}
-
-// Sec. 2.5: project onto the l1 ball of radius K, round to nearest even, then move single pulses
-// on the coordinates of largest deviation (lowest coordinate on ties) until the count is K.
-// Returns the sum of squares; y gets the signed point.
-template <int D>
-__device__ inline float quantize_group(const float (&w)[D], int K, int (&y)[D])
-{
-    float a[D], t[D], tmp[D];
-#pragma unroll
-    for (int i = 0; i < D; i++) { a[i] = fabsf(w[i]); tmp[i] = a[i]; }
-    const float l1 = tree_sum<D>(tmp);
-#pragma unroll
-    for (int i = 0; i < D; i++) tmp[i] = w[i] * w[i];
-    const float ss = tree_sum<D>(tmp);
-
-    const float g = (float)K / l1;
-    if (!(l1 > 0.0f) || !(fabsf(g) < INFINITY)) {
-#pragma unroll
-        for (int i = 0; i < D; i++) y[i] = 0;
-        y[D - 1] = K;
-        return ss;
-    }
-    int S = 0;
-#pragma unroll
-    for (int i = 0; i < D; i++) {
-        t[i] = a[i] * g;
-        // a non-finite weight must not turn into an out-of-range pulse count
-        float r = fminf(rintf(t[i]), (float)K);
-        y[i] = r >= 0.0f ? (int)r : 0;
-        S += y[i];
-    }
-    // At most D adjustments ever make sense (each coordinate moves at most once for finite
-    // input); the bound also ends the loops for non-finite input.
-    for (int it = 0; it < D && S > K; it++) {
-        int best = -1;
-        float dev = 0.0f;
-#pragma unroll
-        for (int i = 0; i < D; i++) {
-            const float e = (float)y[i] - t[i];
-            const bool take = y[i] > 0 && (best < 0 || e > dev);
-            best = take ? i : best;
-            dev = take ? e : dev;
-        }
-#pragma unroll
-        for (int i = 0; i < D; i++) y[i] -= (i == best);
-        S -= best >= 0;
-    }
-    for (int it = 0; it < D && S < K; it++) {
-        int best = -1;
-        float dev = 0.0f;
-#pragma unroll
-        for (int i = 0; i < D; i++) {
-            const float e = t[i] - (float)y[i];
-            const bool take = best < 0 || e > dev;
-            best = take ? i : best;
-            dev = take ? e : dev;
-        }
-#pragma unroll
-        for (int i = 0; i < D; i++) y[i] += (i == best);
-        S += 1;
-    }
-    if (S != K) {  // only reachable with non-finite input: fall back to a valid point
-#pragma unroll
-        for (int i = 0; i < D; i++) y[i] = 0;
-        y[D - 1] = K;
-        return ss;
-    }
-#pragma unroll
-    for (int i = 0; i < D; i++) y[i] = w[i] < 0.0f ? -y[i] : y[i];
-    return ss;
 }
 
 // Position of every coordinate in the order of keys (largest first, lower coordinate first on
@@ -111,11 +42,11 @@ __device__ inline void count_wins(const float (&key)[8], int (&wins)[8])
     for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
 }
 
-// The quantiser above for groups of 8 without branches: the coordinates' places in the order of deviations
-// are counted with 28 comparisons and the |sum - K| first places are adjusted, which equals the one-at-a-time
-// repair because no coordinate is ever adjusted twice (for finite input the |sum - K| largest deviations are
-// all positive, and an adjusted coordinate drops below -1/2).  Same results as quantize_group<8> for finite
-// input; weights that are not finite give unspecified points.
+// Groups of 8 without branches: the coordinates' places in the order of deviations are counted with 28
+// comparisons and the |sum - K| first places are adjusted, which equals the one-at-a-time repair because no
+// coordinate is ever adjusted twice (for finite input the |sum - K| largest deviations are all positive, and an
+// adjusted coordinate drops below -1/2).  Returns the sum of squares; y gets the signed point.  Weights that are
+// not finite give (0, ..., 0, K).
 __device__ inline float quantize_group8(const float (&w)[8], int K, int (&y)[8])
 {
     constexpr int D = 8;
@@ -153,6 +84,71 @@ __device__ inline float quantize_group8(const float (&w)[8], int K, int (&y)[8])
         const bool adjust = wins[i] + need >= D;      // place = D-1-wins < need
         int mag = (int)(yf[i] + (adjust ? unit : 0.0f));
         if (degenerate) mag = 0;
+        if (i == D - 1) mag = k;                      // the last coordinate takes what is left
+        y[i] = (w[i] < 0.0f && !degenerate) ? -mag : mag;
+        k -= mag;
+    }
+    return ss;
+}
+
+// The same point for any D, without the two repair loops' re-evaluation of every deviation: the deviations are
+// formed once (as keys, negated when pulses have to be taken away), and each of the |sum - K| rounds picks the
+// largest key, lowest coordinate on ties, adjusts that coordinate and takes its key out.  This is the one-at-a-time
+// repair itself, since an adjusted coordinate never comes up again (see quantize_group8); a wave runs as many rounds
+// as its lane with the largest |sum - K| needs, two to five for D = 16 and 32 (re-evaluating all deviations in every
+// round, in one loop for pulses to take away and one for pulses to add, took 2.5 times the instructions).
+// Weights that are not finite give (0, ..., 0, K).
+template <int D>
+__device__ inline float quantize_group_select(const float (&w)[D], int K, int (&y)[D])
+{
+    float a[D], tmp[D];
+#pragma unroll
+    for (int i = 0; i < D; i++) { a[i] = fabsf(w[i]); tmp[i] = a[i]; }
+    const float l1 = tree_sum<D>(tmp);
+#pragma unroll
+    for (int i = 0; i < D; i++) tmp[i] = w[i] * w[i];
+    const float ss = tree_sum<D>(tmp);
+    const float g = (float)K / l1;
+    const bool degenerate = !(l1 > 0.0f) || !(l1 < INFINITY) || !(g < INFINITY);
+    float key[D], yf[D];
+    float S = 0.0f;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        const float t = a[i] * g;
+        yf[i] = rintf(t);
+        S += yf[i];                       // small integers: exact in any order
+        key[i] = t - yf[i];
+    }
+    const float m = (float)K - S;         // > 0: pulses to add, < 0: pulses to take away
+    const float unit = m < 0.0f ? -1.0f : 1.0f;
+    if (m < 0.0f) {
+#pragma unroll
+        for (int i = 0; i < D; i++) key[i] = -key[i];
+    }
+    const int need = degenerate ? 0 : (int)fminf(fabsf(m), (float)D);
+    for (int round = 0; round < D; round++) {
+        if (!__any(round < need)) break;
+        float best = key[0];
+        int at = 0;
+#pragma unroll
+        for (int i = 1; i < D; i++) {
+            const bool take = key[i] > best;
+            best = take ? key[i] : best;
+            at = take ? i : at;
+        }
+        if (round < need) {
+#pragma unroll
+            for (int i = 0; i < D; i++) {
+                const bool hit = i == at;
+                yf[i] += hit ? unit : 0.0f;
+                key[i] = hit ? -INFINITY : key[i];
+            }
+        }
+    }
+    int k = K;
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+        int mag = degenerate ? 0 : (int)yf[i];
         if (i == D - 1) mag = k;                      // the last coordinate takes what is left
         y[i] = (w[i] < 0.0f && !degenerate) ? -mag : mag;
         k -= mag;

@@ -158,15 +158,17 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
     for (int64_t item = first; item < items; item += stride) {
         const int64_t row = item / tiles;
         const int g0 = (int)(item - row * tiles) * kWave;      // the wave's first group
-        const T c = group_index<W>(nx, g_nx, wl.index_bits);
-        const float amp = group_amp<W>(nx, g_nx, wl.scale_bits, sqrtc);
+        const int g_mine = g_nx;                                // the lane's group: g0 + lane, or 0 past the row's end
+        const T c = group_index<W>(nx, g_mine, wl.index_bits);
+        const float amp = group_amp<W>(nx, g_mine, wl.scale_bits, sqrtc);
         fetch(item + stride);
         int y[D];
         const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, int v) { y[i] = v; });
         // direction on the unit sphere times the amplitude (Sec. 2.4): w = amp * y / ||y||_2
         const float gain = amp / sqrtf((float)n2);
         const int valid = std::min(kWave, G - g0);             // groups of this item inside the row
-        unsigned char *o = reinterpret_cast<unsigned char *>(a.W_out) + (row * a.ldw + (int64_t)g0 * D) * OSZ;
+        unsigned char *orow = reinterpret_cast<unsigned char *>(a.W_out) + row * a.ldw * OSZ;
+        unsigned char *o = orow + (int64_t)g0 * D * OSZ;
 #pragma unroll
         for (int j = 0; j < NC; j++) {
             uint4 chunk;
@@ -183,8 +185,11 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
                 }
                 chunk = make_uint4(pk[0], pk[1], pk[2], pk[3]);
             }
+            // without staging every lane stores its own group; lanes past the row's end have decoded the row's first
+            // group once more and store it where it belongs (the same bytes as its owner writes): no store is
+            // under a condition, see below
             if constexpr (STAGE) stage[lane * NC + j] = chunk;
-            else if (lane < valid) *reinterpret_cast<uint4 *>(o + ((size_t)lane * NC + j) * 16) = chunk;
+            else *reinterpret_cast<uint4 *>(orow + ((size_t)g_mine * NC + j) * 16) = chunk;
         }
         if constexpr (STAGE) {
             // the item's groups are NC * valid consecutive chunks of the output.  Every lane stores in every pass:

@@ -286,13 +286,14 @@ int pvq_decode(const pvq_ctx *ctx, const uint32_t *index, const void *scale, con
  *
  *   x   device, bf16 [batch][ldx], 16-byte aligned, ldx >= cols, ldx a multiple of 8; 1 <= batch <= 16.
  *   y   device, float32 [batch][ldy], ldy >= rows.  Float32 accumulation in a fixed order
- *       (deterministic for a given shape and batch).  Every pass multiplies the float32 weights gain * y
- *       exactly (products with bf16 activations are exact in float32): the pass that takes 3..16 vectors at
- *       once on the matrix cores (D = 8 with 24-bit indices and rows of 256 or more groups, a multiple of 64)
- *       feeds each weight as three bf16 terms whose sum is the float32 weight.  What depends on the batch
- *       size a vector is submitted in is the order of the float32 additions only: y[b] of the same x can
- *       differ between batch sizes by accumulation rounding (about 1e-7 of the root sum of squares of the
- *       terms), never by the weights used.
+ *       (deterministic for a given shape and batch).  A group contributes gain * (y . x): the
+ *       products of the integer pulses with bf16 activations are exact in float32, their sum over the group
+ *       and the multiplication by the float32 gain are rounded to float32.  The pass that takes 3..16 vectors
+ *       at once (D = 8 with 24-bit indices and rows of 256 or more groups, a multiple of 64) forms y . x on
+ *       the matrix cores, the pulses being exact in bf16, and applies the float32 gain on the vector ALUs as
+ *       the other passes do.  What depends on the batch size a vector is submitted in is the order of the
+ *       float32 additions only: y[b] of the same x can differ between batch sizes by rounding (about 1e-7 of
+ *       the root sum of squares of the terms), never by the weights used.
  */
 int pvq_decode_gemv(const pvq_ctx *ctx, const uint32_t *index, const void *scale,
                     const float *rownorm, int64_t rows, int64_t cols, const void *x, int batch,

@@ -129,7 +129,7 @@ def pvq_walk_tables_selftest(D: int, K: int, seed: int = 1, count: int = 100000)
     return bad.value, (sched[0], sched[1]), nbytes.value
 
 
-PASS_KINDS = {0: "valu_fp32_generic", 1: "valu_fp32", 2: "valu_fp32_rows", 3: "valu_fp32_16", 4: "mfma_bf16x3"}
+PASS_KINDS = {0: "valu_fp32_generic", 1: "valu_fp32", 2: "valu_fp32_rows", 3: "valu_fp32_16", 4: "mfma_bf16"}
 
 
 def pvq_decode_gemv_plan(ctx, rows: int, cols: int, batch: int):

@@ -716,36 +716,48 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_wide_kernel(fast8_launch f
 // Many activation vectors: the dot products on the matrix cores
 // ---------------------------------------------------------------------------------------------
 
-// With 5..16 vectors the dot products (8 x 16 multiply-adds per group) outweigh the decoding, and they
-// are a dense contraction: a tile of 16 rows x 32 columns of decoded weights times 32 x 16 activations
-// is one v_mfma_f32_16x16x32_bf16.  Lane l of a wave holds row l%16 of the tile and the k-block l/16 of
-// the instruction's 32 columns, which is exactly one decoded group (8 values) per lane and instruction.
-// A wave takes 16 rows x 64 consecutive groups: lane (m, kb) decodes the groups  slab + 16*q + 4*kb + j
-// of its row, quad q = 0..3 after quad (j = 0..3 through the table decoder at once), so that the four
-// k-blocks read 16 neighbouring groups (48 contiguous bytes of indices, one word of codes); the
-// activations of the same 8 columns, for vector l%16, are the other operand, loaded as they are (bf16)
-// from device memory, where the caches hold them.
-// Weights w = gain * y (float32) go in as three bf16 terms, one instruction each: hi = w cut to bf16,
-// mid = (w - hi) cut to bf16, lo = w - hi - mid.  Each cut keeps 8 of the 24 significant bits and each
-// difference is exact, so hi + mid + lo = w exactly (down to the float32 underflow range), and products
-// with bf16 activations are exact in float32: the pass multiplies the same float32 weights as the
-// vector-ALU kernels and differs from them only in the order of the float32 additions (the
-// instruction's own fixed order).  The 16 x 16 results of the waves that share a row tile meet in LDS, four waves per phase,
-// and are added in wave order (deterministic).
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+// With 3..16 vectors the dot products (8 x 16 multiply-adds per group) outweigh the decoding, and they go
+// to the matrix cores as small independent products: v_mfma_f32_4x4x4_16b_bf16 multiplies, in each of the
+// 16 blocks of four lanes, a 4 x 4 matrix A (row = lane of the block, 4 values along k per lane) by a 4 x 4
+// matrix B (column = lane of the block), and leaves column (lane of the block) of the 4 x 4 result in the
+// lane's four result registers.  B is what the decoder hands out: the lane's own pulse vector, small integers
+// and therefore exact in bf16, two instructions for its 8 coordinates.  A holds the activations of the same 8
+// columns for four vectors; with the instruction's broadcast control (cbsz 2: the blocks of a row of 16 lanes
+// all take the A of block `abid` of that row) one load per group, lane (m, kb) fetching vector m, serves all
+// sixteen lanes of the row for the vectors 4 abid .. 4 abid + 3.  A lane therefore gets y . x of ITS group for
+// four vectors per instruction pair, multiplies by the group's gain (float32, as in the single-vector kernels:
+// gain * (y . x), every product y_i x_i exact) and keeps a running sum per vector: four multiply-adds per group
+// and four vectors beside the decoding, nothing of the weights is converted or split.
+// A wave takes 16 rows x 64 consecutive groups: lane (m, kb) = (lane % 16, lane / 16) decodes the groups
+// slab + 16*q + 4*kb + j of row m, quad q = 0..3 after quad (j = 0..3 through the table decoder at once), so
+// that the four k-blocks read 16 neighbouring groups (48 contiguous bytes of indices, one word of codes).
+// The sums of the lanes and waves that share a row meet at the end of a round: the four k-blocks inside the
+// wave, then four waves per phase in LDS, added in wave order (deterministic).
+typedef __attribute__((ext_vector_type(4))) short bf16x4_bits_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// y . x for the lane's group and the vectors 4 S .. 4 S + 3 (xlo, xhi: this row of lanes' activations, columns
+// 0..3 and 4..7 of the group; ylo, yhi: the lane's pulses)
+template <int S>
+__device__ inline f32x4_t group_dots(bf16x4_bits_t xlo, bf16x4_bits_t xhi, bf16x4_bits_t ylo, bf16x4_bits_t yhi)
+{
+    const f32x4_t zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4_t d = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(xlo, ylo, zero, 2, S, 0);
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(xhi, yhi, d, 2, S, 0);
+}
 
 constexpr int kMfmaRows = 16;                 // rows of a tile
 constexpr int kMfmaSlab = 64;                 // groups of a row that one wave takes
 constexpr int kMfmaSlots = 4;                 // waves whose results meet in LDS at a time
 constexpr size_t kMfmaPartBytes = kMfmaSlots * 256 * sizeof(float);
 
-// AMP: 0 = float32 amplitudes, 1 = amplitude codes.  24-bit indices.  nslabs = slabs per row.  A workgroup
+// AMP: 0 = float32 amplitudes, 1 = amplitude codes.  NS = vectors / 4, rounded up.  24-bit indices.
+// nslabs = slabs per row.  A workgroup
 // owns tiles_per_block consecutive row tiles and takes them in rounds: four tiles at a time while four are
 // left (four waves per tile, every wave the slabs slice, slice + 4, ...), then two (eight waves each), then
 // one (sixteen waves, or as many as the row has slabs, rounded up to four).  Few, long rounds keep the
 // barriers of the reduction and the unhidden first loads of a tile rare.
-template <int AMP>
+template <int AMP, int NS>
 __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f, pvq_decode_args a, int b0,
                                                                   int nvec, int tiles_per_block, int nslabs)
 {
@@ -812,7 +824,10 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
         const int nsl = R.nsl, nwaves = R.nwaves, nq = R.nq;
         const bool live = R.live;
         auto quad_group = [&](int qq) { return R.gl0 + (uint32_t)((qq >> 2) * nsl * kMfmaSlab + 16 * (qq & 3)); };
-        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        // tot[s][r]: this lane's part of (row m) . (vector 4 s + r)
+        f32x4_t tot[4];
+#pragma unroll
+        for (int v = 0; v < 4; v++) tot[v] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
         if (!live && N.live) fetch(N.row, N.gl0, cur);
         if (live) {
 #pragma unroll 1
@@ -835,42 +850,53 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
                     float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]);
                     if constexpr (CODES) gain *= sqrtc_l[(codes >> (j * sb)) & ((1u << sb) - 1u)];
                     else gain *= __uint_as_float(cur.s[j]);
-                    uint32_t hi[4], mid[4], lo[4];
+                    const bf16x4_bits_t xlo = __builtin_bit_cast(bf16x4_bits_t, make_uint2(bx[j].x, bx[j].y)),
+                                        xhi = __builtin_bit_cast(bf16x4_bits_t, make_uint2(bx[j].z, bx[j].w)),
+                                        ylo = __builtin_bit_cast(bf16x4_bits_t, make_uint2(pr[j][0], pr[j][1])),
+                                        yhi = __builtin_bit_cast(bf16x4_bits_t, make_uint2(pr[j][2], pr[j][3]));
+                    f32x4_t d[4];
+                    d[0] = group_dots<0>(xlo, xhi, ylo, yhi);
+                    if constexpr (NS > 1) d[1] = group_dots<1>(xlo, xhi, ylo, yhi);
+                    if constexpr (NS > 2) d[2] = group_dots<2>(xlo, xhi, ylo, yhi);
+                    if constexpr (NS > 3) d[3] = group_dots<3>(xlo, xhi, ylo, yhi);
 #pragma unroll
-                    for (int p2 = 0; p2 < 4; p2++) {
-                        const float w0 = gain * __uint_as_float(pr[j][p2] << 16);
-                        const float w1 = gain * __uint_as_float(pr[j][p2] & 0xFFFF0000u);
-                        const uint32_t u0 = __float_as_uint(w0), u1 = __float_as_uint(w1);
-                        hi[p2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);      // upper halves: w cut to bf16
-                        const float m0 = w0 - __uint_as_float(u0 & 0xFFFF0000u);  // exact: 16 bits are left
-                        const float m1 = w1 - __uint_as_float(u1 & 0xFFFF0000u);
-                        const uint32_t v0 = __float_as_uint(m0), v1 = __float_as_uint(m1);
-                        mid[p2] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);
-                        const float l0 = m0 - __uint_as_float(v0 & 0xFFFF0000u);  // exact: 8 bits are left,
-                        const float l1 = m1 - __uint_as_float(v1 & 0xFFFF0000u);  // which a bf16 holds
-                        lo[p2] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
+                    for (int v = 0; v < NS; v++) {
+#pragma unroll
+                        for (int r = 0; r < 4; r++) tot[v][r] = fmaf(gain, d[v][r], tot[v][r]);
                     }
-                    const uint4 hv = make_uint4(hi[0], hi[1], hi[2], hi[3]), mv = make_uint4(mid[0], mid[1], mid[2], mid[3]),
-                                lv = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                    const bf16x8_t xb = __builtin_bit_cast(bf16x8_t, bx[j]);
-                    // smallest terms first, so that they are not absorbed by the large ones one by one
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, lv), xb, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, mv), xb, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hv), xb, acc, 0, 0, 0);
                 }
                 cur = nxt;
             }
         }
-        // acc[r] = partial sum for row 4*kb + r of the tile and vector m.  Phases of four waves (nsl is a
-        // multiple of four, so a phase lies within one row tile); thread (tile row, vector) of the first
-        // 256 adds them in wave order.
+        // The four k-blocks of a row sit in lanes m, m + 16, m + 32, m + 48: two exchanges, in each of which a
+        // lane gives away half of the vectors it still holds and adds the partner's part of the half it keeps.
+        // Lane (m, kb) ends with the wave's sums of row m for the vectors 4 s .. 4 s + 3, s = 2 (kb & 1) + (kb >> 1).
+        f32x4_t fin;
+        {
+            const bool odd = kb & 1, upper = kb & 2;
+            f32x4_t k0, k1;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float keep0 = odd ? tot[2][r] : tot[0][r], keep1 = odd ? tot[3][r] : tot[1][r];
+                const float send0 = odd ? tot[0][r] : tot[2][r], send1 = odd ? tot[1][r] : tot[3][r];
+                k0[r] = keep0 + __shfl_xor(send0, 16, kWave);
+                k1[r] = keep1 + __shfl_xor(send1, 16, kWave);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float keep = upper ? k1[r] : k0[r], send = upper ? k0[r] : k1[r];
+                fin[r] = keep + __shfl_xor(send, 32, kWave);
+            }
+        }
+        const int fin_vec = 4 * (2 * (kb & 1) + (kb >> 1));
+        // Phases of four waves (nsl is a multiple of four, so a phase lies within one row tile); thread
+        // (tile row, vector) of the first 256 adds them in wave order.
         float sum = 0.0f;
         const int phases = nwaves / kMfmaSlots;
         for (int ph = 0; ph < phases; ph++) {
             if (wave / kMfmaSlots == ph) {
                 float *slot = part + (wave % kMfmaSlots) * 256;
-#pragma unroll
-                for (int r = 0; r < 4; r++) slot[(4 * kb + r) * 16 + m] = live ? acc[r] : 0.0f;
+                *reinterpret_cast<f32x4_t *>(slot + m * 16 + fin_vec) = fin;
             }
             __syncthreads();
             if (threadIdx.x < 256) {
@@ -1160,8 +1186,15 @@ hipError_t launch_gemv_mfma(const pvq_ctx *c, const pvq_decode_args &a, int b0, 
     const int64_t nblocks = std::max<int64_t>(1, std::min<int64_t>(g_num_cus > 0 ? g_num_cus : 256, tiles));
     const int tiles_per_block = (int)((tiles + nblocks - 1) / nblocks);
     const dim3 grid((unsigned)((tiles + tiles_per_block - 1) / tiles_per_block)), block((unsigned)kGemvThreads);
-    if (f.scale_bits > 0) hipLaunchKernelGGL((gemv8_mfma_kernel<1>), grid, block, 0, s, f, a, b0, nvec, tiles_per_block, nslabs);
-    else hipLaunchKernelGGL((gemv8_mfma_kernel<0>), grid, block, 0, s, f, a, b0, nvec, tiles_per_block, nslabs);
+#define PVQ_MFMA_CASE(AMP, NS) \
+    hipLaunchKernelGGL((gemv8_mfma_kernel<AMP, NS>), grid, block, 0, s, f, a, b0, nvec, tiles_per_block, nslabs)
+    const int ns = (nvec + 3) / 4;
+    if (f.scale_bits > 0) {
+        if (ns == 1) PVQ_MFMA_CASE(1, 1); else if (ns == 2) PVQ_MFMA_CASE(1, 2); else if (ns == 3) PVQ_MFMA_CASE(1, 3); else PVQ_MFMA_CASE(1, 4);
+    } else {
+        if (ns == 1) PVQ_MFMA_CASE(0, 1); else if (ns == 2) PVQ_MFMA_CASE(0, 2); else if (ns == 3) PVQ_MFMA_CASE(0, 3); else PVQ_MFMA_CASE(0, 4);
+    }
+#undef PVQ_MFMA_CASE
     return hipGetLastError();
 }
 

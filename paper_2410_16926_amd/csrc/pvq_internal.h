@@ -160,7 +160,7 @@ enum {
     PVQ_PASS_VALU = 1,        // gemv8_kernel: 1, 2 or 4 vectors, float32 multiply-adds on the vector ALU
     PVQ_PASS_VALU_ROWS = 2,   // gemv8_row_kernel: one vector, every wave owns whole rows
     PVQ_PASS_VALU16 = 3,      // gemv8_wide_kernel: up to 16 vectors on the vector ALU
-    PVQ_PASS_MFMA = 4,        // gemv8_mfma_kernel: 3..16 vectors, weights as three bf16 terms on the matrix cores
+    PVQ_PASS_MFMA = 4,        // gemv8_mfma_kernel: 3..16 vectors, the groups' dot products on the matrix cores
 };
 struct pvq_gemv_pass { int kind, nvec; };
 int pvq_fast8_plan_gemv(const pvq_ctx *ctx, const pvq_decode_args &a, pvq_gemv_pass *out);

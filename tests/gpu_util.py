@@ -79,10 +79,10 @@ def assert_gemv_close(y: np.ndarray, ref: np.ndarray, scale: np.ndarray = None, 
       (1) ||y - ref||_2 <= rel * ||ref||_2
       (2) |y_i - ref_i| <= rel * (|ref_i| + rms(ref))                      (1e-3 relative, config 4)
       (3) |y_i - ref_i| <= rel_terms * s_i,  s_i = sqrt(sum_c (w_ic x_c)^2)  (with `scale` = s)
-    Every kernel behind pvq_decode_gemv multiplies the float32 weights gain*y exactly (products with bf16
-    activations are exact in float32; the matrix-core pass splits a weight into three bf16 terms that sum to
-    it) and accumulates in float32, so its error is accumulation rounding: a few 2^-24 of the partial sums,
-    about 1e-7 * s_i.  (3) pins that with a margin of 100; an error of 1e-4 in a gain or an amplitude, or a
+    Every kernel behind pvq_decode_gemv works with the float32 gain and the exact pulses (products of pulses
+    with bf16 activations are exact in float32, on the vector ALUs and on the matrix cores alike) and
+    accumulates in float32, so its error is rounding of sums and of the gain's multiplication: a few 2^-24 of
+    the partial sums, about 1e-7 * s_i.  (3) pins that with a margin of 100; an error of 1e-4 in a gain or an amplitude, or a
     weight cut to fewer than 17 significant bits, fails it.  (1) and (2) are the tolerance the workload
     states; an output whose terms cancel to below 1e-3 of their size could fail (2) with correct arithmetic,
     which none of the seeded cases does."""

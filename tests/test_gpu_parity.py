@@ -680,8 +680,8 @@ def test_the_plan_of_passes_names_the_kernels_that_run():
     e, c = pvq.pvq_beta_tables(8, 1024, 2)
     ctx = pvq.pvq_ctx_create(8, 16, 2, e, c)
     assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 1) == [("valu_fp32_rows", 1)]
-    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 4) == [("mfma_bf16x3", 4)]
-    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 16) == [("mfma_bf16x3", 16)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 4) == [("mfma_bf16", 4)]
+    assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 16) == [("mfma_bf16", 16)]
     assert pvq.pvq_decode_gemv_plan(ctx, 28672, 8192, 2) == [("valu_fp32", 2)]
     assert pvq.pvq_decode_gemv_plan(ctx, 1024, 8192, 1) == [("valu_fp32", 1)]          # too few rows per wave
     assert pvq.pvq_decode_gemv_plan(ctx, 96, 8 * 36, 7) == [("valu_fp32", 4), ("valu_fp32", 2), ("valu_fp32", 1)]

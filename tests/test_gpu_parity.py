@@ -142,7 +142,7 @@ def test_many_vectors_on_ragged_shapes(rows, cols, bits):
                                             (120, 8 * 320, 2), (49, 8 * 448, 0), (97, 8 * 832, 2)])
 def test_many_vectors_on_the_matrix_cores(rows, cols, bits):
     # 3..16 vectors with rows of 4, 5, 7, 8, 12, 13, 16 slabs of 64 groups: the pass whose dot products
-    # run as 16x16x32 matrix instructions; row counts that leave partial tiles of 16 rows and rounds of
+    # run as 4x4x4 matrix instructions, one to four per half group; row counts that leave partial tiles of 16 rows and rounds of
     # four, two and one tile, every amplitude format
     wf, wb = si.gaussian_weights(rows, cols, 0.015, seed=si.BASE_SEED + 90 + rows, rotate=False, bf16=True)
     run_case(wf, 8, 16, bits, src_bits=wb, batches=(16, 5, 9, 13, 3), out_dtypes=())

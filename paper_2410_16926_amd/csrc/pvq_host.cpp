@@ -812,7 +812,7 @@ uint64_t replay_walk(const SizeTable &t, int K, const std::vector<unsigned char>
         plain_unrank(t, D, K, c, want);
         int n2w = 0;
         for (int i = 0; i < D; i++) n2w += want[i] * want[i];
-        const int n2 = pvq_walk::unrank_walk<D, W, DA, DB>((T)c, blob.data(), p, [&](int i, int v) { got[i] = v; });
+        const int n2 = pvq_walk::unrank_walk<D, W, DA, DB>((T)c, blob.data(), p, [&](int i, uint32_t m, bool negative) { got[i] = negative ? -(int)m : (int)m; });
         bool same = n2 == n2w;
         for (int i = 0; i < D; i++) same = same && got[i] == want[i];
         bad += !same;

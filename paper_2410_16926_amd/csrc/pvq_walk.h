@@ -73,46 +73,56 @@ PVQ_HD uint32_t pvq_walk_row(const pvq_walk_params &p)
 // h in [2^e (1 + f / 2^MB), 2^e (1 + (f+1) / 2^MB)), or the bucket below when h lies within 2^-20 (relative)
 // of the bucket's lower edge: conversions and sums round to nearest, the last factor takes back more than
 // they can add, so the float is not above h.
-template <typename T, int MB>
-PVQ_HD uint32_t bucket_of(T h)
+template <int MB>
+PVQ_HD uint32_t bucket_of_float(float f, uint32_t cap)
 {
-    float f;
-    if constexpr (sizeof(T) == 4) {
-        f = (float)h;
-    } else if constexpr (sizeof(T) == 8) {
-        uint32_t hi = (uint32_t)(h >> 32);
-        const uint32_t lo = (uint32_t)h;
-        PVQ_WALK_OPAQUE(hi);
-        f = fmaf((float)hi, 4294967296.0f, (float)lo);
-    } else {
-        uint32_t w3 = (uint32_t)(h >> 96), w2 = (uint32_t)(h >> 64), w1 = (uint32_t)(h >> 32);
-        PVQ_WALK_OPAQUE(w3); PVQ_WALK_OPAQUE(w2); PVQ_WALK_OPAQUE(w1);
-        f = fmaf((float)w3, 4294967296.0f, (float)w2);
-        f = fmaf(f, 4294967296.0f, (float)w1);
-        f = fmaf(f, 4294967296.0f, (float)(uint32_t)h);
-    }
     f *= 1.0f - 0x1p-21f;
     constexpr uint32_t base = (127u << MB) - 1u;
-    uint32_t idx = std::max(pvq_float_bits(f) >> (23u - MB), base) - base;
-    if constexpr (sizeof(T) == 16) idx = std::min(idx, (130u << MB));       // 2^128 - 1 rounds to infinity
-    return idx;
+    const uint32_t idx = std::max(pvq_float_bits(f) >> (23u - MB), base) - base;
+    return std::min(idx, cap);
+}
+
+// Half of q as the integer h, and its bucket.  For two-word integers h is put together from the two words that
+// the conversion to float uses, so that the shift is made once.
+template <typename T, int MB>
+PVQ_HD uint32_t half_and_bucket(T q, T &h)
+{
+    if constexpr (sizeof(T) == 4) {
+        h = q >> 1;
+        return bucket_of_float<MB>((float)h, 0xFFFFFFFFu);
+    } else if constexpr (sizeof(T) == 8) {
+        uint32_t hi = (uint32_t)(q >> 33);
+        const uint32_t lo = (uint32_t)(q >> 1);
+        PVQ_WALK_OPAQUE(hi);
+        h = ((T)hi << 32) | lo;
+        return bucket_of_float<MB>(fmaf((float)hi, 4294967296.0f, (float)lo), 0xFFFFFFFFu);
+    } else {
+        h = q >> 1;
+        uint32_t w3 = (uint32_t)(h >> 96), w2 = (uint32_t)(h >> 64), w1 = (uint32_t)(h >> 32);
+        PVQ_WALK_OPAQUE(w3); PVQ_WALK_OPAQUE(w2); PVQ_WALK_OPAQUE(w1);
+        float f = fmaf((float)w3, 4294967296.0f, (float)w2);
+        f = fmaf(f, 4294967296.0f, (float)w1);
+        f = fmaf(f, 4294967296.0f, (float)(uint32_t)h);
+        return bucket_of_float<MB>(f, 130u << MB);                            // 2^128 - 1 rounds to infinity
+    }
 }
 
 // One coordinate with d = DP + 1 dimensions left (row DP of the cumulative table) under the schedule
-// <W, DA, DB>.  q, k in and out; returns the coordinate's value and adds its square to n2.
+// <W, DA, DB>.  q, k in and out; returns the coordinate's magnitude, sets `negative` and adds the square to n2.
 template <typename T, int DP, int W, int DA, int DB>
-PVQ_HD int walk_step(const unsigned char *lds, const pvq_walk_params &p, T &q, int &k, int &n2)
+PVQ_HD uint32_t walk_step(const unsigned char *lds, const pvq_walk_params &p, T &q, int &k, int &n2, bool &negative)
 {
-    const T h = q >> 1;
+    T h;
     uint32_t C;
     T um, ux;
     if constexpr (DP == 1) {
         // U(1,x) = 2x + 1
+        h = q >> 1;
         C = (uint32_t)std::min<T>((h + 1) >> 1, (T)(uint32_t)k);
         ux = (T)(2u * C + 1u);
         um = C ? (T)(2u * C - 1u) : (T)0;
     } else {
-        const uint32_t idx = bucket_of<T, pvq_walk_mb(DP)>(h);
+        const uint32_t idx = half_and_bucket<T, pvq_walk_mb(DP)>(q, h);
         C = lds[p.guess_base + pvq_walk_guess_offset(DP, W, DA, DB) + idx];
         const T *u = reinterpret_cast<const T *>(lds + pvq_walk_row<DP, W, DA, DB>(p));   // u[x] = U(DP, x), x = -1 .. K+1
         um = u[(int)C - 1];
@@ -124,7 +134,7 @@ PVQ_HD int walk_step(const unsigned char *lds, const pvq_walk_params &p, T &q, i
     }
     const uint32_t m = (uint32_t)k - C;
     const T t = q - um;
-    const bool negative = t < ux;
+    negative = t < ux;
     q = negative ? t - um : t - ux;
     k = (int)C;
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -132,7 +142,7 @@ PVQ_HD int walk_step(const unsigned char *lds, const pvq_walk_params &p, T &q, i
 #else
     n2 += (int)(m * m);
 #endif
-    return negative ? -(int)m : (int)m;
+    return m;
 }
 
 // The state of a walk: the residual in the three widths (one of them is live at a time), pulses left, sum of
@@ -151,18 +161,19 @@ struct walk_state {
     PVQ_HD void coordinate(const unsigned char *lds, const pvq_walk_params &p, Emit &emit)
     {
         constexpr int d = D - I;                 // dimensions left, this coordinate included
-        int v;
+        uint32_t v;
+        bool negative;
         if constexpr (d > DA) {
-            v = walk_step<T0, d - 1, W, DA, DB>(lds, p, q0, k, n2);
+            v = walk_step<T0, d - 1, W, DA, DB>(lds, p, q0, k, n2, negative);
             if constexpr (d - 1 == DA) q1 = (T1)q0;          // the next coordinate runs in the narrower type
             if constexpr (d - 1 == DA && DA == DB) q2 = (T2)q0;
         } else if constexpr (d > DB) {
-            v = walk_step<T1, d - 1, W, DA, DB>(lds, p, q1, k, n2);
+            v = walk_step<T1, d - 1, W, DA, DB>(lds, p, q1, k, n2, negative);
             if constexpr (d - 1 == DB) q2 = (T2)q1;
         } else {
-            v = walk_step<T2, d - 1, W, DA, DB>(lds, p, q2, k, n2);
+            v = walk_step<T2, d - 1, W, DA, DB>(lds, p, q2, k, n2, negative);
         }
-        emit(I, v);
+        emit(I, v, negative);
     }
     template <typename Emit, int... Is>
     PVQ_HD void all(const unsigned char *lds, const pvq_walk_params &p, Emit &emit, std::integer_sequence<int, Is...>)
@@ -171,7 +182,8 @@ struct walk_state {
     }
 };
 
-// The whole point from its index c.  emit(i, y_i) for i = 0 .. D-1 in order; returns sum y_i^2.
+// The whole point from its index c.  emit(i, |y_i|, y_i < 0) for i = 0 .. D-1 in order (a coordinate that is 0
+// may come with either sign); returns sum y_i^2.
 template <int D, int W, int DA, int DB, typename Emit>
 PVQ_HD int unrank_walk(typename wide<W>::type c, const unsigned char *lds, const pvq_walk_params &p,
                                   Emit &&emit)
@@ -189,7 +201,7 @@ PVQ_HD int unrank_walk(typename wide<W>::type c, const unsigned char *lds, const
     if constexpr (DB >= 1) zero = st.q2 == 0;
     else if constexpr (DA >= 1) zero = st.q1 == 0;
     else zero = st.q0 == 0;
-    emit(D - 1, zero ? -st.k : st.k);
+    emit(D - 1, (uint32_t)st.k, zero);
     return st.n2 + st.k * st.k;
 }
 

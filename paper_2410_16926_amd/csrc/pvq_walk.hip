@@ -59,10 +59,10 @@ template <int W>
 __device__ inline void fetch_group(const uint32_t *__restrict__ row, uint32_t last_word, const void *__restrict__ srow,
                                    const float *__restrict__ rownorm, int g, int index_bits, int scale_bits, raw_group<W> &r)
 {
-    const uint32_t w0 = ((uint32_t)g * (uint32_t)index_bits) >> 5;
+    const uint32_t w0 = __umul24((uint32_t)g, (uint32_t)index_bits) >> 5;     // (rows have at most 2^21 groups)
 #pragma unroll
     for (int i = 0; i <= W; i++) r.w[i] = row[std::min(w0 + (uint32_t)i, last_word)];
-    const uint32_t aw = scale_bits == 0 ? (uint32_t)g : ((uint32_t)g * (uint32_t)scale_bits) >> 5;
+    const uint32_t aw = scale_bits == 0 ? (uint32_t)g : __umul24((uint32_t)g, (uint32_t)scale_bits) >> 5;
     r.amp = reinterpret_cast<const uint32_t *>(srow)[aw];
     r.rownorm = scale_bits == 0 ? 0.0f : *rownorm;
 }
@@ -71,7 +71,7 @@ template <int W>
 __device__ inline typename wide<W>::type group_index(const raw_group<W> &r, int g, int bits)
 {
     using T = typename wide<W>::type;
-    const uint32_t sh = ((uint32_t)g * (uint32_t)bits) & 31;
+    const uint32_t sh = __umul24((uint32_t)g, (uint32_t)bits) & 31;
     const int span = (int)sh + bits;
     T v = (T)(r.w[0] >> sh);
 #pragma unroll
@@ -87,7 +87,7 @@ template <int W>
 __device__ inline float group_amp(const raw_group<W> &r, int g, int scale_bits, const float *sqrtc)
 {
     if (scale_bits == 0) return __uint_as_float(r.amp);
-    const uint32_t pos = (uint32_t)g * (uint32_t)scale_bits;
+    const uint32_t pos = __umul24((uint32_t)g, (uint32_t)scale_bits);
     const uint32_t code = (r.amp >> (pos & 31)) & ((1u << scale_bits) - 1u);
     return sqrtc[code] * sqrtf(r.rownorm);
 }
@@ -139,10 +139,11 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
     int g_nx = 0;
     const uint32_t last_word = (uint32_t)a.index_row_words - 1u;
     const int64_t srow_bytes = wl.scale_bits == 0 ? a.groups * 4 : a.scale_row_words * 4;
-    auto fetch = [&](int64_t item) {
-        const int64_t it = item < items ? item : items - 1;
-        const int64_t row = it / tiles;
-        const int g = (int)(it - row * tiles) * kWave + lane;
+    // (row, tile) of an item without a division per item: a wave moves on by `stride` items at a time
+    const int64_t step_rows = stride / tiles;
+    const int step_tiles = (int)(stride - step_rows * tiles);
+    auto fetch = [&](int64_t row, int tile) {
+        const int g = tile * kWave + lane;
         g_nx = g < G ? g : 0;
         fetch_group<W>(a.index + row * a.index_row_words, last_word,
                        reinterpret_cast<const unsigned char *>(a.scale) + row * srow_bytes,
@@ -150,22 +151,32 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
                        wl.index_bits, wl.scale_bits, nx);
     };
     const int64_t first = (int64_t)blockIdx.x * kWaves + wave;
-    if (first < items) fetch(first);
+    int64_t row_n = first / tiles;                              // the item that is being fetched
+    int tile_n = (int)(first - row_n * tiles);
+    if (first < items) fetch(row_n, tile_n);
     // The first item has arrived before the loop is entered (vmcnt(0), the other counters left alone): the loop then
     // starts, on its first pass as on every other, with nothing but stores in flight behind the item it takes
     // apart, and its waits are counted from there; sized for the entry path they would wait for the stores too.
     __builtin_amdgcn_s_waitcnt(0x0F70);
     for (int64_t item = first; item < items; item += stride) {
-        const int64_t row = item / tiles;
-        const int g0 = (int)(item - row * tiles) * kWave;      // the wave's first group
+        const int64_t row = row_n;
+        const int g0 = tile_n * kWave;                          // the wave's first group
         const int g_mine = g_nx;                                // the lane's group: g0 + lane, or 0 past the row's end
         const T c = group_index<W>(nx, g_mine, wl.index_bits);
         const float amp = group_amp<W>(nx, g_mine, wl.scale_bits, sqrtc);
-        fetch(item + stride);
-        int y[D];
-        const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, int v) { y[i] = v; });
+        row_n += step_rows;
+        tile_n += step_tiles;
+        if (tile_n >= tiles) { tile_n -= tiles; row_n++; }
+        if (row_n >= a.rows) { row_n = a.rows - 1; tile_n = tiles - 1; }   // past the last item: its place again, dropped
+        fetch(row_n, tile_n);
+        float y[D];
+        const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, uint32_t m, bool negative) {
+            y[i] = negative ? -(float)m : (float)m;            // (a zero coordinate comes as -0)
+        });
         // direction on the unit sphere times the amplitude (Sec. 2.4): w = amp * y / ||y||_2
         const float gain = amp / sqrtf((float)n2);
+        // gain * y + 0: the product as it is, and +0 for a zero coordinate
+        auto value = [&](int i) { return fmaf(gain, y[i], 0.0f); };
         const int valid = std::min(kWave, G - g0);             // groups of this item inside the row
         unsigned char *orow = reinterpret_cast<unsigned char *>(a.W_out) + row * a.ldw * OSZ;
         unsigned char *o = orow + (int64_t)g0 * D * OSZ;
@@ -173,13 +184,13 @@ __global__ __launch_bounds__(kMaxThreads) void decode_walk_kernel(walk_launch wl
         for (int j = 0; j < NC; j++) {
             uint4 chunk;
             if constexpr (OUT == PVQ_F32) {
-                chunk = make_uint4(__float_as_uint(gain * (float)y[4 * j]), __float_as_uint(gain * (float)y[4 * j + 1]),
-                                   __float_as_uint(gain * (float)y[4 * j + 2]), __float_as_uint(gain * (float)y[4 * j + 3]));
+                chunk = make_uint4(__float_as_uint(value(4 * j)), __float_as_uint(value(4 * j + 1)),
+                                   __float_as_uint(value(4 * j + 2)), __float_as_uint(value(4 * j + 3)));
             } else {
                 uint32_t pk[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    const float f0 = gain * (float)y[8 * j + 2 * e], f1 = gain * (float)y[8 * j + 2 * e + 1];
+                    const float f0 = value(8 * j + 2 * e), f1 = value(8 * j + 2 * e + 1);
                     if constexpr (OUT == PVQ_F16) pk[e] = (uint32_t)f32_to_f16_rne(f0) | ((uint32_t)f32_to_f16_rne(f1) << 16);
                     else pk[e] = f32_to_bf16_rne(f0) | (f32_to_bf16_rne(f1) << 16);
                 }
@@ -257,8 +268,8 @@ __global__ __launch_bounds__(kMaxThreads) void gemv_walk_kernel(walk_launch wl, 
             float s[NB];
 #pragma unroll
             for (int b = 0; b < NB; b++) s[b] = 0.0f;
-            const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, int v) {
-                const float yv = (float)v;
+            const int n2 = unrank_walk<D, W, DA, DB>(c, lds, wl.p, [&](int i, uint32_t m, bool negative) {
+                const float yv = negative ? -(float)m : (float)m;
 #pragma unroll
                 for (int b = 0; b < NB; b++) {
                     const uint4 q = x[b][i / 8];

@@ -61,6 +61,24 @@ __device__ inline float wave_pair_sum(float v)
     return v;
 }
 
+// OR of v over aligned runs of n lanes (n = 1, 2, 4, ... 32), in every lane of the run: the first four levels
+// by lane patterns inside a row of 16 lanes (within a quad; then, the quads being uniform, the mirror images
+// inside 8 and 16 lanes bring the other half), the fifth across rows.
+template <int CTRL>
+__device__ inline uint32_t dpp_or(uint32_t v)
+{
+    return v | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+__device__ inline uint32_t or_over_lanes(uint32_t v, int n)
+{
+    if (n > 1) v = dpp_or<0xB1>(v);            // quad_perm [1,0,3,2]
+    if (n > 2) v = dpp_or<0x4E>(v);            // quad_perm [2,3,0,1]
+    if (n > 4) v = dpp_or<0x141>(v);           // row_half_mirror
+    if (n > 8) v = dpp_or<0x140>(v);           // row_mirror
+    if (n > 16) v |= __shfl_xor(v, 16, kWave);
+    return v;
+}
+
 // Sum over adjacent pairs, level by level (fixed order, float32).
 __device__ inline float tree8(float (&v)[D])
 {
@@ -241,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void encode8_kernel(enc8_launch f, pvq_enco
                     }
                     v = (uint32_t)lo << ((lane * sb) & 31);
                 }
-                for (int off = 1; off < lanes_per_word; off <<= 1) v |= __shfl_xor(v, off, kWave);
+                v = or_over_lanes(v, lanes_per_word);
                 if ((lane & (lanes_per_word - 1)) == 0 && g < G) srow[((uint32_t)g * (uint32_t)sb) >> 5] = v;
             }
             __syncthreads();   // ss_row and wsum are rewritten by the next row
@@ -340,7 +358,7 @@ __device__ inline void rotate_encode8_body(const enc8_launch &f, const pvq_encod
                     if (edges[mid] <= u) lo = mid + 1; else hi = mid;
                 }
                 uint32_t code = (uint32_t)lo << ((lane * sb) & 31);
-                for (int off = 1; off < lanes_per_word; off <<= 1) code |= __shfl_xor(code, off, kWave);
+                code = or_over_lanes(code, lanes_per_word);
                 if ((lane & (lanes_per_word - 1)) == 0) srow[((uint32_t)g * (uint32_t)sb) >> 5] = code;
             }
             __syncthreads();   // ss_row and wsum are rewritten by the next row

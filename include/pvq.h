@@ -271,7 +271,11 @@ int pvq_rotate_encode(const pvq_ctx *ctx, const void *X, int dtype, int64_t rows
  *                           scale_bits == 0).
  *   W_out       device, [rows][ldw] of out_dtype (PVQ_F32, PVQ_F16 or PVQ_BF16), 16-byte aligned,
  *               ldw >= cols and ldw*sizeof(element) a multiple of 16.  Float32 arithmetic, one
- *               round-to-nearest-even conversion to the output type.
+ *               round-to-nearest-even conversion to the output type.  For D = 8 with 24-bit indices small
+ *               matrices (fewer than about 1.5 M groups) and large ones run on different decoders, whose
+ *               float32 gains amplitude / ||p||_2 can differ in the last place (a division by the square
+ *               root, or a multiplication by its tabulated reciprocal): values are deterministic for a
+ *               given shape and within the stated 1e-6 of the exact ones on either.
  * A stored index >= N(D,K) (corrupt data) decodes to unspecified values without any out-of-bounds
  * access.
  */

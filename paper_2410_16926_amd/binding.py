@@ -21,7 +21,8 @@ EXPORTS = [
 ]
 
 # host-only diagnostics declared in csrc/pvq_diagnostics.h, exported for the tests
-DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_walk_tables_selftest", "pvq_decode_gemv_plan", "pvq_correct_set_front_tiles"]
+DIAGNOSTICS = ["pvq_fast_tables_selftest", "pvq_walk_tables_selftest", "pvq_decode_gemv_plan", "pvq_correct_set_front_tiles",
+               "pvq_decode_set_table_decoder_min_groups"]
 
 
 class PvqError(RuntimeError):
@@ -71,6 +72,7 @@ def lib():
         L.pvq_correct.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, C.c_size_t, vp]
         L.pvq_correct_static_max_rows.argtypes = [vp]
         L.pvq_correct_set_front_tiles.argtypes = [i64, vp]
+        L.pvq_decode_set_table_decoder_min_groups.argtypes = [i64, vp]
         L.pvq_correct_static.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         L.pvq_decode.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp]
         L.pvq_decode_gemv.argtypes = [vp, vp, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp]
@@ -314,6 +316,15 @@ def pvq_correct_set_front_tiles(tiles: int) -> int:
     workgroups (process-wide; results do not depend on it).  Returns the number in force before."""
     old = C.c_int64(0)
     _check(lib().pvq_correct_set_front_tiles(int(tiles), C.byref(old)), "pvq_correct_set_front_tiles")
+    return old.value
+
+
+def pvq_decode_set_table_decoder_min_groups(groups: int) -> int:
+    """Diagnostics: matrices of fewer groups of 8 than this are decoded coordinate by coordinate instead of through
+    the tables (process-wide).  Returns the number in force before."""
+    old = C.c_int64(0)
+    _check(lib().pvq_decode_set_table_decoder_min_groups(int(groups), C.byref(old)),
+           "pvq_decode_set_table_decoder_min_groups")
     return old.value
 
 

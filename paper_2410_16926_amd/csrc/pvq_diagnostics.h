@@ -50,6 +50,16 @@ int pvq_decode_gemv_plan(const struct pvq_ctx *ctx, int64_t rows, int64_t cols, 
  */
 int pvq_correct_set_front_tiles(int64_t tiles, int64_t *previous);
 
+/*
+ * pvq_decode for groups of 8 with 24-bit indices has two decoders: the table decoder, whose tables take most of a
+ * unit's LDS and some microseconds to copy there, and the coordinate-by-coordinate one, which starts at once and
+ * takes longer per group.  Matrices of fewer than *groups* groups (rows x cols / 8; default 1 572 864) go to the
+ * second.  Sets that number for the process and returns the one in force before in *previous (may be NULL).  Both
+ * decoders give the same pulses; their float32 gains can differ in the last place (one divides the amplitude by
+ * sqrt(sum y^2), the other multiplies by a tabulated reciprocal).  PVQ_E_INVALID_ARG for groups < 0.
+ */
+int pvq_decode_set_table_decoder_min_groups(int64_t groups, int64_t *previous);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,5 +1,6 @@
 // Host side of libpvq: status codes, exact size tables, the choice of K, Beta quantile tables,
 // the context, and argument validation in front of the kernel launchers.
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -688,6 +689,24 @@ static int fill_decode_args(const pvq_ctx *c, pvq_decode_args &a, const uint32_t
     return PVQ_OK;
 }
 
+// The table decoder for groups of 8 copies 155 KB of tables into every unit's LDS before its first group (about
+// 13 us a launch); the coordinate-by-coordinate decoder starts with 3 KB.  Measured to bf16: 1024 x 8192 (1.0 M
+// groups) 22.2 against 17.8 us, 512 x 512 27 against 14 us, 2048 x 8192 (2.1 M groups) 24.1 against 25.4 us.
+static std::atomic<int64_t> g_table_decoder_min_groups{1572864};
+
+static bool table_decoder_pays(const pvq_ctx *c, const pvq_decode_args &a)
+{
+    return pvq_fast8_decode_usable(c, a) && a.rows * a.groups >= g_table_decoder_min_groups.load(std::memory_order_relaxed);
+}
+
+extern "C" int pvq_decode_set_table_decoder_min_groups(int64_t groups, int64_t *previous)
+{
+    if (groups < 0) return PVQ_E_INVALID_ARG;
+    const int64_t old = g_table_decoder_min_groups.exchange(groups);
+    if (previous) *previous = old;
+    return PVQ_OK;
+}
+
 extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *scale,
                           const float *rownorm, int64_t rows, int64_t cols, void *W_out,
                           int out_dtype, int64_t ldw, void *stream)
@@ -704,8 +723,8 @@ extern "C" int pvq_decode(const pvq_ctx *c, const uint32_t *index, const void *s
     if ((rc = check_device(c))) return rc;
     a.W_out = W_out; a.ldw = ldw;
     hipError_t e = c->wide ? pvq_wide_launch_decode(c, a, out_dtype, (hipStream_t)stream)
-                   : pvq_fast8_decode_usable(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
-                                                   : pvq_walk_launch_decode(c, a, out_dtype, (hipStream_t)stream);
+                   : table_decoder_pays(c, a) ? pvq_fast8_launch_decode(c, a, out_dtype, (hipStream_t)stream)
+                                              : pvq_walk_launch_decode(c, a, out_dtype, (hipStream_t)stream);
     return e == hipSuccess ? PVQ_OK : hip_fail(e);
 }
 

@@ -2,6 +2,8 @@
 through its binding, fetch results as numpy, compare with the oracle."""
 from __future__ import annotations
 
+import contextlib
+
 import numpy as np
 
 import paper_2410_16926_amd as pvq
@@ -64,6 +66,24 @@ def ulp_f16(ref_bits: np.ndarray, got_bits: np.ndarray) -> int:
         b = b.astype(np.int32)
         return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
     return int(np.abs(line(ref_bits) - line(got_bits)).max()) if ref_bits.size else 0
+
+
+def decoder_settings(D):
+    """Values for pvq_decode_set_table_decoder_min_groups that force either decoder for groups of 8 (for other
+    group sizes the setting has no effect: one pass with the default)."""
+    return (0, 1 << 62) if D == 8 else (None,)
+
+
+@contextlib.contextmanager
+def decoder_setting(min_groups):
+    if min_groups is None:
+        yield
+        return
+    old = pvq.pvq_decode_set_table_decoder_min_groups(min_groups)
+    try:
+        yield
+    finally:
+        pvq.pvq_decode_set_table_decoder_min_groups(old)
 
 
 def assert_decode_close(got_f32: np.ndarray, ref64: np.ndarray, rel=1e-6):

@@ -28,15 +28,17 @@ def run_case(W32, D, K, scale_bits, src_bits=None, batches=(1, 4), out_dtypes=("
     gu.assert_encode_equal(packed, enc)
 
     ref, _, _ = oracle.decode(enc, oc, nthreads=8)
-    if "f32" in out_dtypes:
-        got = pvq.pvq_decode(ctx, packed, torch.float32).cpu().numpy()
-        gu.assert_decode_close(got, ref)
-    if "f16" in out_dtypes:
-        got = pvq.pvq_decode(ctx, packed, torch.float16).cpu().numpy()
-        assert gu.ulp_f16(oracle.to_f16(ref).view(np.uint16), got.view(np.uint16)) <= 1
-    if "bf16" in out_dtypes:
-        got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
-        assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
+    for setting in gu.decoder_settings(D):          # groups of 8: both decoders, whatever the matrix's size
+        with gu.decoder_setting(setting):
+            if "f32" in out_dtypes:
+                got = pvq.pvq_decode(ctx, packed, torch.float32).cpu().numpy()
+                gu.assert_decode_close(got, ref)
+            if "f16" in out_dtypes:
+                got = pvq.pvq_decode(ctx, packed, torch.float16).cpu().numpy()
+                assert gu.ulp_f16(oracle.to_f16(ref).view(np.uint16), got.view(np.uint16)) <= 1
+            if "bf16" in out_dtypes:
+                got = gu.bf16_tensor_bits(pvq.pvq_decode(ctx, packed, torch.bfloat16))
+                assert gu.ulp_f16(oracle.to_bf16_bits(ref), got) <= 1
     for B in batches:
         xf, xb = si.activations(B, cols, seed=seed + B)
         y = pvq.pvq_decode_gemv(ctx, packed, gu.to_dev_bf16(xb)).cpu().numpy()
@@ -476,11 +478,13 @@ def test_leading_dimensions_and_views():
     packed = pvq.pvq_encode(ctx, view, want_pulses=True)
     enc = oracle.encode(np.ascontiguousarray(wf[:, :cols]), D, K)
     gu.assert_encode_equal(packed, enc)
-    out_big = torch.full((rows, ld), 7.0, dtype=torch.float32, device="cuda")
-    pvq.pvq_decode(ctx, packed, out=out_big[:, :cols])
     ref, _, _ = oracle.decode(enc)
-    gu.assert_decode_close(out_big[:, :cols].cpu().numpy(), ref)
-    assert torch.all(out_big[:, cols:] == 7.0)          # nothing written past cols
+    for setting in gu.decoder_settings(D):
+        with gu.decoder_setting(setting):
+            out_big = torch.full((rows, ld), 7.0, dtype=torch.float32, device="cuda")
+            pvq.pvq_decode(ctx, packed, out=out_big[:, :cols])
+            gu.assert_decode_close(out_big[:, :cols].cpu().numpy(), ref)
+            assert torch.all(out_big[:, cols:] == 7.0)          # nothing written past cols
     xf, xb = si.activations(2, ld, seed=5)
     xv = gu.to_dev_bf16(xb)[:, :cols]
     y_big = torch.full((2, rows + 5), -3.0, dtype=torch.float32, device="cuda")
@@ -565,7 +569,9 @@ def test_zero_matrix_and_nonfinite_inputs_are_safe():
     W = torch.zeros((8, 256), dtype=torch.float32, device="cuda")
     packed = pvq.pvq_encode(ctx, W, want_pulses=True)
     assert torch.all(packed.index == 0) and torch.all(packed.scale == 0)
-    assert torch.all(pvq.pvq_decode(ctx, packed, torch.float32) == 0)
+    for setting in gu.decoder_settings(D):
+        with gu.decoder_setting(setting):
+            assert torch.all(pvq.pvq_decode(ctx, packed, torch.float32) == 0)
     W[0, 3] = float("nan"); W[1, 9] = float("inf"); W[2, :] = float("-inf"); W[3, 0] = 3e38; W[3, 1] = 3e38
     packed = pvq.pvq_encode(ctx, W, want_pulses=True)
     torch.cuda.synchronize()
@@ -584,7 +590,11 @@ def test_corrupt_indices_do_not_fault():
     ctx = pvq.pvq_ctx_create(D, K)
     idx = torch.full((16, 768), -1, dtype=torch.int32, device="cuda")     # every field = 2^24-1 >= N
     p = pvq.Packed(16, 8192, idx, torch.ones((16, 1024), device="cuda"), torch.ones(16, device="cuda"))
-    out = pvq.pvq_decode(ctx, p, torch.float32)
+    for setting in gu.decoder_settings(D):
+        with gu.decoder_setting(setting):
+            out = pvq.pvq_decode(ctx, p, torch.float32)
+            torch.cuda.synchronize()
+            assert out.shape == (16, 8192) and bool(torch.isfinite(out).all())
     x = torch.ones((16, 8192), dtype=torch.bfloat16, device="cuda")
     for b in (1, 4, 16):                     # the single-vector, four-vector and matrix-core passes
         y = pvq.pvq_decode_gemv(ctx, p, x[:b])

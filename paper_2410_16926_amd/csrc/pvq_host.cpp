@@ -324,7 +324,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     // tab_n[dp][k] = N(dp,k); tab_u[dp][k+1] = N(dp,0) + ... + N(dp,k), tab_u[dp][0] = 0.
     // Every entry is below N(D,K) (the pyramid of one more dimension contains all of them), so it
     // fits `words` words.
-    std::vector<uint32_t> hn, hu, hc;
+    std::vector<uint32_t> hn, hu, hc, hkey;
     if (wide) {
         // tab_n[d][k] = N(d,k), d = 0..D;  tab_u[d][k] = 2 (N(d,0) + ... + N(d,k)) mod 2^(32 words), d = 0..D-1
         hn.resize((size_t)(D + 1) * (K + 1) * words);
@@ -342,6 +342,8 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
                 }
             }
         }
+        hkey.resize((size_t)D * (K + 1));
+        for (size_t i = 0; i < hkey.size(); i++) hkey[i] = pvq_wide_key(&hu[i * words], words);
         // The encoders' table: what a cell (d,k) of the walk adds to the index, in its four forms
         //   N,  -E,  N - E,  2N - E   (modulo 2^(32 words); E = 0 in row D, whose cell only ever adds N),
         // entry ((d (K+1) + k) 4 + form) of `words` words.
@@ -384,7 +386,7 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     pvq_ctx *c = new (std::nothrow) pvq_ctx();
     if (!c) return PVQ_E_NOMEM;
     c->D = D; c->K = K; c->index_bits = bits; c->words = words; c->scale_bits = scale_bits; c->wide = wide ? 1 : 0;
-    c->tab_n = c->tab_u = c->tab_c = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
+    c->tab_n = c->tab_u = c->tab_c = c->tab_key = nullptr; c->edges = c->sqrtc = nullptr; c->fast8_blob = c->fast8g_blob = nullptr; c->enc8_offs = nullptr; c->amplitude = PVQ_AMP_NORM;
     c->tab_n_bytes = hn.size() * 4; c->tab_u_bytes = hu.size() * 4;
 
     hipError_t e = hipGetDevice(&c->device);
@@ -395,6 +397,8 @@ extern "C" int pvq_ctx_create(pvq_ctx **out, int D, int K, int scale_bits, const
     if (e == hipSuccess && !hc.empty()) {
         e = hipMalloc((void **)&c->tab_c, hc.size() * 4);
         if (e == hipSuccess) e = hipMemcpy(c->tab_c, hc.data(), hc.size() * 4, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc((void **)&c->tab_key, hkey.size() * 4);
+        if (e == hipSuccess) e = hipMemcpy(c->tab_key, hkey.data(), hkey.size() * 4, hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && scale_bits) {
         // the edge table is padded to 2^b entries with +inf so that kernels may read a full table
@@ -454,7 +458,7 @@ extern "C" int pvq_ctx_destroy(pvq_ctx *c)
 {
     if (!c) return PVQ_OK;
     hipError_t first = hipSuccess;
-    void *ptrs[9] = {c->tab_n, c->tab_u, c->tab_c, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->walk_blob, c->enc8_offs};
+    void *ptrs[10] = {c->tab_key, c->tab_n, c->tab_u, c->tab_c, c->edges, c->sqrtc, c->fast8_blob, c->fast8g_blob, c->walk_blob, c->enc8_offs};
     for (void *p : ptrs) {
         if (!p) continue;
         hipError_t e = hipFree(p);

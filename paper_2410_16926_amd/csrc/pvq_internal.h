@@ -24,6 +24,24 @@ struct pvq_walk_params {
     uint32_t guess_base;    // byte offset of the first guess row (d' = 2)
 };
 
+// A multi-word integer (w[0] the lowest word) as 32 bits that order like the integer wherever they differ: its
+// bit length in the upper 10 bits, below them the 22 leading bits (0 for 0).  key(a) < key(b) implies a < b;
+// equal keys decide nothing.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline uint32_t pvq_wide_key(const uint32_t *w, int words)
+{
+    uint32_t hi = 0, lo = 0;
+    int t = -1;
+    for (int i = 0; i < words; i++)
+        if (w[i] != 0) { t = i; hi = w[i]; lo = i > 0 ? w[i - 1] : 0u; }
+    if (t < 0) return 0;
+    const int lead = __builtin_clz(hi);
+    const uint32_t top = lead ? (hi << lead) | (lo >> (32 - lead)) : hi;
+    return ((uint32_t)(32 * t + 32 - lead) << 22) | (top >> 10);
+}
+
 struct pvq_ctx {
     int D, K;
     int index_bits;
@@ -39,6 +57,7 @@ struct pvq_ctx {
     uint32_t *tab_n;
     uint32_t *tab_u;
     uint32_t *tab_c;   // wide only: [D+1][K+1][4][words], the four forms N, -E, N-E, 2N-E of a cell (encoders)
+    uint32_t *tab_key; // wide only: [D][K+1], pvq_wide_key of tab_u's entries (the decoder's search)
     float *edges;   // 2^scale_bits - 1 float32 edges (or nullptr)
     float *sqrtc;   // 2^scale_bits float32 sqrt(centers) (or nullptr)
     size_t tab_n_bytes, tab_u_bytes;

@@ -613,23 +613,41 @@ struct decode_wide_params {
     const float *scale;
     int64_t groups, total_groups, index_row_words, ldw;
     int K, bits;
-    const uint32_t *tab_n, *tab_e;
+    const uint32_t *tab_n, *tab_e, *tab_key;
     void *W_out;
 };
 
 constexpr int kDecodeLanes = 128;
 
-// OUT: pvq_dtype of the result.  LDS: kDecodeLanes x (D + 2) int16 points, kDecodeLanes float32 gains.
+// Bytes of LDS per lane for the decoded point of a group of D: magnitudes and signs.  With K <= 255 a magnitude is a
+// byte and the signs are a bit each (D + D/8 bytes); else int16 values.  Rounded up to an odd number of words, so
+// that the lanes' rows spread over the banks.
+__host__ __device__ inline int decode_point_bytes(int D, int K)
+{
+    const int words = K <= 255 ? D / 4 + D / 32 : D / 2;
+    return 4 * (words | 1);
+}
+
+// OUT: pvq_dtype of the result.  LDS: kDecodeLanes points (decode_point_bytes each), kDecodeLanes float32 gains;
+// little per lane, so that many waves share a unit: a wave's walk is a chain of dependent steps, and what a unit
+// gets done is the number of chains it holds.
+// A coordinate's magnitude is the smallest m with E(d-1,k-1-m) <= q.  Tried one m after the other with the
+// multi-word entries, that is a dependent trip to the tables and a multi-word subtraction per unit of magnitude,
+// and a wave takes as many as its largest magnitude.  Here the search runs on 32-bit keys of the entries
+// (pvq_wide_key), four at a time, against the key of q: keys that differ order the integers, and equal keys (about
+// one comparison in a million) send the lane through the multi-word search.  The entries themselves are then read
+// once per coordinate, together: E at the magnitude found, and N for the sign.
 template <int OUT, int CP, int W>
-__global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_params p)
+__global__ __launch_bounds__(kDecodeLanes, 4) void decode_wide_kernel(decode_wide_params p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    constexpr int D = 64 * CP, LD = D + 2;   // int16 per group, odd number of words: lanes spread over the banks
-    int16_t *pts = reinterpret_cast<int16_t *>(lds_raw);
-    float *gains = reinterpret_cast<float *>(lds_raw + (size_t)kDecodeLanes * LD * 2);
+    constexpr int D = 64 * CP;
     const int K = p.K;
+    const bool bytes = K <= 255;
+    const int LB = decode_point_bytes(D, K);
+    float *gains = reinterpret_cast<float *>(lds_raw + (size_t)kDecodeLanes * LB);
     const int64_t gid = (int64_t)blockIdx.x * kDecodeLanes + threadIdx.x;
-    int16_t *mine = pts + (size_t)threadIdx.x * LD;
+    unsigned char *mine = lds_raw + (size_t)threadIdx.x * LB;      // magnitudes [D], sign bytes [D/8]; or int16 [D]
 
     if (gid < p.total_groups) {
         const int64_t row = gid / p.groups, g = gid - row * p.groups;
@@ -664,6 +682,7 @@ __global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_p
         }
         int k = valid ? K : 0;
         int n2 = 0;
+        uint32_t sign_byte = 0;
         for (int i = 0; i < D; i++) {
             const int d = D - i;
             int y = 0;
@@ -676,19 +695,49 @@ __global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_p
                     y = zero ? -k : k;
                     k = 0;
                 } else {
-                    const uint32_t *erow = p.tab_e + (int64_t)(d - 1) * (K + 1) * W;
-                    int m = 0;
-                    wint<W> diff = q;       // q - E(d-1, k-m) of the last step that failed
-                    for (; m < k; m++) {
+                    const int rw = d - 1;                                   // the tables' row
+                    const uint32_t *erow = p.tab_e + (int64_t)rw * (K + 1) * W;
+                    const uint32_t *krow = p.tab_key + (int64_t)rw * (K + 1);
+                    // the search on keys: m = the magnitude, or `unsure` at a pair of equal keys
+                    const uint32_t kq = pvq_wide_key(q.w, W);
+                    int m = k;
+                    bool unsure = false;
+                    for (int m0 = 0; m0 < k; m0 += 4) {
+                        uint32_t ke[4];
+#pragma unroll
+                        for (int u = 0; u < 4; u++) ke[u] = krow[max(k - 1 - m0 - u, 0)];
+                        bool done = false;
+#pragma unroll
+                        for (int u = 0; u < 4; u++) {
+                            if (!done && m0 + u < k && ke[u] <= kq) {
+                                done = true;
+                                m = m0 + u;
+                                unsure = ke[u] == kq;
+                            }
+                        }
+                        if (done) break;
+                    }
+                    wint<W> diff = q;       // q - E(d-1, k-m), the entry of the last magnitude that failed
+                    if (unsure) {
+                        // the multi-word search from the start
+                        for (m = 0; m < k; m++) {
+                            uint32_t b;
+                            const wint<W> t = subtract(q, load_entry<W>(erow, k - 1 - m), &b);
+                            if (!b) { if (m == 0) q = t; break; }   // E <= q: magnitude m; for m = 0 the next q is q - E
+                            diff = t;
+                        }
+                    }
+                    // (requested together; for m = 0 the second is not used)
+                    const wint<W> e = load_entry<W>(erow, m == 0 ? k - 1 : k - m);
+                    const wint<W> n = load_entry<W>(p.tab_n, (int64_t)rw * (K + 1) + (k - m));
+                    if (!unsure) {
                         uint32_t b;
-                        const wint<W> t = subtract(q, load_entry<W>(erow, k - 1 - m), &b);
-                        if (!b) { if (m == 0) q = t; break; }   // E <= q: magnitude m; for m = 0 the next q is q - E
-                        diff = t;
+                        const wint<W> t = subtract(q, e, &b);
+                        if (m == 0) q = t; else diff = t;
                     }
                     if (m > 0) {
                         // inside the block of magnitude m: v = q - E(d-1,k-m) + N(d-1,k-m); negative means
                         // the second half of the block (the coordinate is -m), whose q is v + N(d-1,k-m)
-                        const wint<W> n = load_entry<W>(p.tab_n, (int64_t)(d - 1) * (K + 1) + (k - m));
                         add_to(diff, n);
                         const bool negative = diff.w[W - 1] >> 31;
                         if (negative) add_to(diff, n);
@@ -698,7 +747,13 @@ __global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_p
                     }
                 }
             }
-            mine[i] = (int16_t)y;
+            if (bytes) {
+                mine[i] = (unsigned char)(y < 0 ? -y : y);
+                sign_byte = ((i & 7) ? sign_byte : 0u) | ((y < 0 ? 1u : 0u) << (i & 7));
+                if ((i & 7) == 7) mine[D + (i >> 3)] = (unsigned char)sign_byte;
+            } else {
+                reinterpret_cast<int16_t *>(mine)[i] = (int16_t)y;
+            }
             n2 += y * y;
         }
         gains[threadIdx.x] = valid ? p.scale[gid] / sqrtf((float)n2) : 0.0f;
@@ -712,10 +767,20 @@ __global__ __launch_bounds__(kDecodeLanes) void decode_wide_kernel(decode_wide_p
         if (og >= p.total_groups) break;
         const int64_t row = og / p.groups, g = og - row * p.groups;
         const float gain = gains[s];
-        const int16_t *pt = pts + (size_t)s * LD + CP * lane;
+        const unsigned char *pt = lds_raw + (size_t)s * LB;
         float v[CP];
 #pragma unroll
-        for (int j = 0; j < CP; j++) v[j] = gain * (float)pt[j];
+        for (int j = 0; j < CP; j++) {
+            const int c = CP * lane + j;
+            int y;
+            if (bytes) {
+                const int mag = pt[c];
+                y = (pt[D + (c >> 3)] >> (c & 7)) & 1 ? -mag : mag;
+            } else {
+                y = reinterpret_cast<const int16_t *>(pt)[c];
+            }
+            v[j] = gain * (float)y;
+        }
         const int64_t at = row * p.ldw + g * D + CP * lane;
         if constexpr (OUT == PVQ_F32) {
             float *o = reinterpret_cast<float *>(p.W_out) + at;
@@ -828,9 +893,9 @@ hipError_t pvq_wide_launch_decode(const pvq_ctx *c, const pvq_decode_args &a, in
     decode_wide_params p;
     p.index = a.index; p.scale = reinterpret_cast<const float *>(a.scale);
     p.groups = a.groups; p.total_groups = a.rows * a.groups; p.index_row_words = a.index_row_words; p.ldw = a.ldw;
-    p.K = c->K; p.bits = c->index_bits; p.tab_n = c->tab_n; p.tab_e = c->tab_u; p.W_out = a.W_out;
+    p.K = c->K; p.bits = c->index_bits; p.tab_n = c->tab_n; p.tab_e = c->tab_u; p.tab_key = c->tab_key; p.W_out = a.W_out;
     if ((p.total_groups + kDecodeLanes - 1) / kDecodeLanes > 0x7FFFFFFF) return hipErrorInvalidValue;
-    const size_t lds = (size_t)kDecodeLanes * (c->D + 2) * 2 + (size_t)kDecodeLanes * 4;
+    const size_t lds = (size_t)kDecodeLanes * decode_point_bytes(c->D, c->K) + (size_t)kDecodeLanes * 4;
     const dim3 grid((unsigned)((p.total_groups + kDecodeLanes - 1) / kDecodeLanes)), blk(kDecodeLanes);
 #define PVQ_WIDE_DEC(O, CP, W) hipLaunchKernelGGL((decode_wide_kernel<O, CP, W>), grid, blk, lds, s, p)
 #define PVQ_WIDE_DEC_W(O, CP)                                  \

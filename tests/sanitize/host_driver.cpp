@@ -9,6 +9,7 @@
 
 #include "pvq.h"
 #include "pvq_diagnostics.h"
+#include "pvq_internal.h"   // pvq_wide_key
 
 #define CHECK(cond) do { if (!(cond)) { fprintf(stderr, "check failed at line %d: %s\n", __LINE__, #cond); exit(1); } } while (0)
 
@@ -43,6 +44,31 @@ int main()
         CHECK(pvq_walk_tables_selftest(dk.first, dk.second, 7, 20000, &bad, sched, &nbytes) == PVQ_OK && bad == 0 && nbytes > 0);
     }
     CHECK(pvq_walk_tables_selftest(64, 10, 7, 10, &bad, sched, &nbytes) == PVQ_E_UNSUPPORTED);
+    // the long-group decoder's search keys: keys that differ order the integers as the integers themselves do
+    {
+        uint64_t state = 12345;
+        auto next = [&]() { state = state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(state >> 32); };
+        auto less = [](const uint32_t *a, const uint32_t *b, int n) {
+            for (int i = n - 1; i >= 0; i--) if (a[i] != b[i]) return a[i] < b[i];
+            return false;
+        };
+        for (int trial = 0; trial < 200000; trial++) {
+            const int n = 4 * (1 + (int)(next() % 4));
+            uint32_t a[16] = {0}, b[16] = {0};
+            const int top = (int)(next() % (uint32_t)n);                 // highest word that may be set
+            for (int i = 0; i <= top; i++) { a[i] = next(); b[i] = next(); }
+            const uint32_t kind = next() % 4;
+            if (kind == 0) for (int i = top; i >= 0 && i > top - 2; i--) b[i] = a[i];    // agree in the leading words
+            if (kind == 1) { a[top] >>= next() % 32; b[top] >>= next() % 32; }                // any bit length
+            if (kind == 2) { for (int i = 0; i <= top; i++) b[i] = a[i]; b[0] ^= 1u; }      // neighbours
+            const uint32_t ka = pvq_wide_key(a, n), kb = pvq_wide_key(b, n);
+            if (ka < kb) CHECK(less(a, b, n));
+            if (ka > kb) CHECK(less(b, a, n));
+        }
+        const uint32_t zero[4] = {0, 0, 0, 0}, one[4] = {1, 0, 0, 0}, big[4] = {0, 0, 0, 0x80000000u};
+        CHECK(pvq_wide_key(zero, 4) == 0 && pvq_wide_key(one, 4) == ((1u << 22) | (1u << 21)));
+        CHECK(pvq_wide_key(big, 4) == ((128u << 22) | (1u << 21)));
+    }
     // argument checks that return before any device call
     pvq_ctx *ctx = nullptr;
     CHECK(pvq_ctx_create(&ctx, 7, 16, 0, nullptr, nullptr) == PVQ_E_UNSUPPORTED && ctx == nullptr);

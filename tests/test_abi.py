@@ -36,6 +36,16 @@ def test_diagnostics_are_declared_apart_from_the_public_header():
         assert getattr(pvq.lib(), n) is not None
 
 
+def test_process_wide_settings_of_the_diagnostics():
+    # the two setters keep their number in host memory: they run without a GPU
+    for setter, default in ((pvq.pvq_correct_set_front_tiles, 1536), (pvq.pvq_decode_set_table_decoder_min_groups, 1572864)):
+        assert setter(7) == default
+        assert setter(default) == 7
+        with pytest.raises(pvq.PvqError):
+            setter(-1)
+        assert setter(default) == default              # a refused value changes nothing
+
+
 def test_status_strings():
     L = pvq.lib()
     for code in (0, -1, -2, -3, -4, -5):

@@ -319,7 +319,11 @@ __device__ inline void rotate_encode8_body(const enc8_launch &f, const pvq_encod
             }
             // one exchange buffer (a barrier in front of every exchange, which also keeps a chunk's writes
             // behind the reads of the chunk before): two workgroups of 1024 lanes then fit a unit's LDS
-            hadamard_stages<LOG2N, false, true>(v, tid, log2n, hbuf, L);
+            // (which cross-lane stages go through the LDS permute unit: all of them for blocks of up to 512 values,
+            // where the encoder's arithmetic is what the kernel waits for and that unit is idle; only the one over
+            // 4 lanes for 1024 and 2048; none from 4096 on, where the exchanges through LDS need it: measured)
+            constexpr int kPermuted = LOG2N <= 9 ? 4 + 8 + 16 + 32 : LOG2N <= 11 ? 4 : 0;
+            hadamard_stages<LOG2N, false, true, kPermuted>(v, tid, log2n, hbuf, L);
             float w[D];
 #pragma unroll
             for (int j = 0; j < D; j++) w[j] = v[j] * scale;

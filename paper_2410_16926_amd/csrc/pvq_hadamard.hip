@@ -80,7 +80,7 @@ __global__ __launch_bounds__(1024) void hadamard_kernel(const void *X, int64_t l
     // runs 8^P apart, instead of going through LDS once more.
     constexpr bool kSplitStore = LOG2N == 10 || LOG2N == 13;
     constexpr int kSplitP = LOG2N == 13 ? 4 : 3;
-    hadamard_stages<LOG2N, true>(v, lane, log2n, smem, L);
+    hadamard_stages<LOG2N, true, false, LOG2N <= 9 ? 4 : 0>(v, lane, log2n, smem, L);
 
     if constexpr (kSplitStore) {
         // register q holds column  own_base(lane) + (q >> 1) + (q & 1) * 8^P  of the chunk

@@ -33,22 +33,67 @@ __device__ inline void stages_in_registers(float (&v)[8], int bits)
     }
 }
 
-// One butterfly stage between lanes `mask` apart: the lane whose bit is clear holds a and gets a + b, the
-// other holds b and gets a - b.
-template <int MASK>
+// One butterfly stage between lanes MASK apart: the lane whose bit is clear holds a and gets a + b, the
+// other holds b and gets a - b.  No stage goes through LDS.
+// MASK 1, 2, 4, 8: the partner's value comes by a lane pattern inside the row of 16 lanes (a quad
+// permutation; for 4 a rotation by 12 into the lanes whose bit is clear and by 4 into the others; for 8 a
+// rotation by 8).
+// MASK 16, 32: two registers at a time trade places instead.  v_permlane16_swap exchanges the odd rows of one
+// register with the even rows of another (v_permlane32_swap: the upper half of one with the lower half of the
+// other), after which every lane holds both partners of a butterfly, one in each register: rows 0 and 2 (the
+// lower half) those of the first register, the others those of the second.  One addition and one subtraction
+// later the same exchange puts sums and differences where they belong.
+template <int MASK, bool PERMUTE = false>
 __device__ inline void stage_across_lanes(float (&v)[8], int lane)
 {
-    const bool upper = lane & MASK;
+    if constexpr (PERMUTE && MASK > 2) {
+        const bool upper = lane & MASK;
 #pragma unroll
-    for (int j = 0; j < 8; j++) {
-        float partner;
-        if constexpr (MASK == 1)
-            partner = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[j]), 0xB1, 0xF, 0xF, false));
-        else if constexpr (MASK == 2)
-            partner = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[j]), 0x4E, 0xF, 0xF, false));
-        else
-            partner = __shfl_xor(v[j], MASK, 64);
-        v[j] = upper ? partner - v[j] : v[j] + partner;
+        for (int j = 0; j < 8; j++) {
+            const float partner = __shfl_xor(v[j], MASK, 64);
+            v[j] = upper ? partner - v[j] : v[j] + partner;
+        }
+    } else if constexpr (MASK == 16 || MASK == 32) {
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) {
+            uint32_t lo, hi;
+            if constexpr (MASK == 16) {
+                const auto t = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[j]), __float_as_uint(v[j + 1]), false, false);
+                lo = t[0]; hi = t[1];
+            } else {
+                const auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[j]), __float_as_uint(v[j + 1]), false, false);
+                lo = t[0]; hi = t[1];
+            }
+            const float a = __uint_as_float(lo), b = __uint_as_float(hi);
+            const float sum = a + b, diff = a - b;
+            if constexpr (MASK == 16) {
+                const auto t = __builtin_amdgcn_permlane16_swap(__float_as_uint(sum), __float_as_uint(diff), false, false);
+                v[j] = __uint_as_float(t[0]); v[j + 1] = __uint_as_float(t[1]);
+            } else {
+                const auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(sum), __float_as_uint(diff), false, false);
+                v[j] = __uint_as_float(t[0]); v[j + 1] = __uint_as_float(t[1]);
+            }
+        }
+    } else {
+        const bool upper = lane & MASK;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int x = __builtin_bit_cast(int, v[j]);
+            int moved;
+            if constexpr (MASK == 1) {
+                moved = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);          // quad_perm [1,0,3,2]
+            } else if constexpr (MASK == 2) {
+                moved = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);          // quad_perm [2,3,0,1]
+            } else if constexpr (MASK == 4) {
+                moved = __builtin_amdgcn_update_dpp(0, x, 0x12C, 0xF, 0x5, false);         // row_ror:12 into lanes 0-3, 8-11
+                moved = __builtin_amdgcn_update_dpp(moved, x, 0x124, 0xF, 0xA, false);     // row_ror:4 into lanes 4-7, 12-15
+            } else {
+                static_assert(MASK == 8, "lane distances 1 .. 32");
+                moved = __builtin_amdgcn_update_dpp(0, x, 0x128, 0xF, 0xF, false);         // row_ror:8
+            }
+            const float partner = __builtin_bit_cast(float, moved);
+            v[j] = upper ? partner - v[j] : v[j] + partner;
+        }
     }
 }
 
@@ -93,7 +138,7 @@ __device__ inline void exchange(float (&v)[8], float *buf, uint32_t lane)
 // more.  Otherwise the lane ends with its 8 consecutive values.
 // ONEBUF: one buffer of pad(8 L) + 1 floats instead of two, with a barrier in front of every exchange as
 // well (for a kernel that would rather have the LDS than save the barriers).
-template <int LOG2N, bool STAY, bool ONEBUF = false>
+template <int LOG2N, bool STAY, bool ONEBUF = false, int PERMUTED = 0>
 __device__ inline void hadamard_stages(float (&v)[8], int lane, int log2n, float *smem, int L)
 {
     if constexpr (LOG2N > 9) log2n = LOG2N;
@@ -101,10 +146,10 @@ __device__ inline void hadamard_stages(float (&v)[8], int lane, int log2n, float
     stages_in_registers(v, log2n < 3 ? log2n : 3);
     if (log2n > 3) stage_across_lanes<1>(v, lane);
     if (log2n > 4) stage_across_lanes<2>(v, lane);
-    if (log2n > 5) stage_across_lanes<4>(v, lane);
-    if (log2n > 6) stage_across_lanes<8>(v, lane);
-    if (log2n > 7) stage_across_lanes<16>(v, lane);
-    if (log2n > 8) stage_across_lanes<32>(v, lane);
+    if (log2n > 5) stage_across_lanes<4, (PERMUTED & 4) != 0>(v, lane);
+    if (log2n > 6) stage_across_lanes<8, (PERMUTED & 8) != 0>(v, lane);
+    if (log2n > 7) stage_across_lanes<16, (PERMUTED & 16) != 0>(v, lane);
+    if (log2n > 8) stage_across_lanes<32, (PERMUTED & 32) != 0>(v, lane);
     // from bit 9 on the partners sit in other waves
     if constexpr (LOG2N > 9) {
         constexpr int R3 = LOG2N - 9 < 3 ? LOG2N - 9 : 3;

@@ -5,11 +5,10 @@
 //   * one lane per group, workgroups of 256 lanes that take whole rows, 256 groups at a time (several
 //     workgroups share a compute unit, so one's loads and barriers hide behind the others' arithmetic;
 //     1024-lane workgroups measured twice as slow);
-//   * the pulse-count repair (Sec. 2.5) is branch-free: every coordinate's place in the order of
-//     deviations is counted with 28 comparisons, and the |sum - K| first places are adjusted.  This
-//     equals the one-at-a-time repair because no coordinate is ever adjusted twice (for finite
-//     input the |sum - K| largest deviations are all positive, an adjusted coordinate drops below
-//     -1/2);
+//   * the pulse-count repair (Sec. 2.5) adjusts the coordinates that hold the |sum - K| first places in the
+//     order of deviations, found in one short round per place (first_places8).  This equals the
+//     one-at-a-time repair because no coordinate is ever adjusted twice (for finite input the
+//     |sum - K| largest deviations are all positive, an adjusted coordinate drops below -1/2);
 //   * the index (App. B.2) is a sum of seven table entries, one per coordinate, from a table of
 //     per-coordinate offsets indexed by (coordinate, pulses left, magnitude, sign);
 //   * four neighbouring lanes assemble their 24-bit indices into three dwords with DPP moves and write
@@ -28,7 +27,6 @@
 
 namespace {
 
-using pvq_quantize_dev::count_wins;
 
 constexpr int kWave = 64;
 constexpr int D = 8;
@@ -137,16 +135,15 @@ __device__ inline uint32_t encode_group8(const float (&w)[D], int K, const uint3
         const float d = t[i] - yf[i];     // how far below its projected value
         key[i] = m < 0.0f ? -d : d;
     }
-    int wins[D];
-    count_wins(key, wins);
-    const int need = (int)fabsf(m);       // coordinates to adjust; they hold the places 0 .. need-1
+    const int need = degenerate ? 0 : (int)fminf(fabsf(m), (float)D);   // coordinates to adjust; they hold the places 0 .. need-1
+    bool adj[D];
+    pvq_quantize_dev::first_places8(key, need, adj);
     const float unit = m < 0.0f ? -1.0f : 1.0f;
     uint32_t c = 0;
     int k = K;
 #pragma unroll
     for (int i = 0; i < D; i++) {
-        const bool adjust = wins[i] + need >= D;      // place = D-1-wins < need
-        int mag = (int)(yf[i] + (adjust ? unit : 0.0f));
+        int mag = (int)(yf[i] + (adj[i] ? unit : 0.0f));
         // sign bit of the weight; a degenerate group takes +K.  (-0.0 never carries a pulse: a
         // coordinate whose projection is zero is not among the ones raised.)
         const uint32_t neg = __float_as_uint(w[i]) >> 31;

@@ -2,8 +2,8 @@
 // the error correction of Sec. 3.3 Step 6.  float32, fixed evaluation order: the results are part of the
 // format.  The point: project onto the l1 ball of radius K, round to nearest even, then move single pulses on
 // the coordinates of largest deviation (lowest coordinate on ties) until the count is K.  quantize_group8 finds
-// it without branches for D = 8, built on count_wins, which the D = 8 encoder uses as well;
-// quantize_group_select<D> for any D, one round per pulse to move.
+// it without branches for D = 8 (count_wins); the D = 8 encoder and quantize_group_select<D>, for any D, take one
+// round per pulse to move (first_places8 for D = 8).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -42,8 +42,33 @@ __device__ inline void count_wins(const float (&key)[8], int (&wins)[8])
     for (int j = 0; j < D; j++) wins[j] += j - lose[j];   // j beat every earlier coordinate it did not lose to
 }
 
-// Groups of 8 without branches: the coordinates' places in the order of deviations are counted with 28
-// comparisons and the |sum - K| first places are adjusted, which equals the one-at-a-time repair because no
+// adj[i] = coordinate i holds one of the `need` first places in the order of keys (largest first, lower coordinate
+// first on ties).  A round takes the largest key left (three-operand maxima), marks the first coordinate that has
+// it and takes its key out; a wave runs as many rounds as its lane with the largest `need`, two or three for
+// groups of 8, at 20 instructions each, against a hundred for count_wins: the form for kernels that are short of
+// vector instructions (the encoders).  Changes key.
+__device__ inline void first_places8(float (&key)[8], int need, bool (&adj)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; i++) adj[i] = false;
+    for (int round = 0; round < 8; round++) {
+        if (!__any(round < need)) break;
+        const float best = fmaxf(fmaxf(fmaxf(key[0], key[1]), fmaxf(key[2], key[3])),
+                                 fmaxf(fmaxf(key[4], key[5]), fmaxf(key[6], key[7])));
+        bool taken = !(round < need);             // a lane that needs no more takes nothing
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const bool hit = !taken && key[i] == best;
+            adj[i] = adj[i] || hit;
+            taken = taken || hit;
+            key[i] = hit ? -INFINITY : key[i];
+        }
+    }
+}
+
+// Groups of 8 without branches (for the error correction, whose waves wait for one group after the other: rounds
+// with a wave-wide vote measured 2 % slower there): the coordinates' places in the order of deviations are counted
+// with 28 comparisons and the |sum - K| first places are adjusted, which equals the one-at-a-time repair because no
 // coordinate is ever adjusted twice (for finite input the |sum - K| largest deviations are all positive, and an
 // adjusted coordinate drops below -1/2).  Returns the sum of squares; y gets the signed point.  Weights that are
 // not finite give (0, ..., 0, K).

@@ -79,6 +79,16 @@ __device__ inline wint<W> subtract(const wint<W> &a, const wint<W> &b, uint32_t 
     return r;
 }
 
+// a -= b (modulo 2^(32W)); *borrow = 1 when b > a
+template <int W>
+__device__ inline void subtract_from(wint<W> &a, const wint<W> &b, uint32_t *borrow)
+{
+    uint32_t br = 0;
+#pragma unroll
+    for (int i = 0; i < W; i++) a.w[i] = __builtin_subc(a.w[i], b.w[i], br, &br);
+    *borrow = br;
+}
+
 // A lane's value moved by one data-parallel-primitive pattern; lanes whose row is not in ROWS, or whose
 // source lies outside their row, get `idle`.
 template <int CTRL, int ROWS = 0xF>
@@ -717,31 +727,31 @@ __global__ __launch_bounds__(kDecodeLanes, 4) void decode_wide_kernel(decode_wid
                         }
                         if (done) break;
                     }
-                    wint<W> diff = q;       // q - E(d-1, k-m), the entry of the last magnitude that failed
+                    // q - E(d-1, k-1) for m = 0 (the next q); for m > 0, q - E(d-1, k-m), the entry of the last
+                    // magnitude that failed.  In place: the walk's integers are not copied.
+                    // (requested together with E; for m = 0 it is not used.  After the rare search below m is another,
+                    // and it is read again)
+                    wint<W> n = load_entry<W>(p.tab_n, (int64_t)rw * (K + 1) + (k - m));
                     if (unsure) {
                         // the multi-word search from the start
+                        const wint<W> q0 = q;
                         for (m = 0; m < k; m++) {
                             uint32_t b;
-                            const wint<W> t = subtract(q, load_entry<W>(erow, k - 1 - m), &b);
-                            if (!b) { if (m == 0) q = t; break; }   // E <= q: magnitude m; for m = 0 the next q is q - E
-                            diff = t;
+                            const wint<W> t = subtract(q0, load_entry<W>(erow, k - 1 - m), &b);
+                            if (!b) { if (m == 0) q = t; break; }   // E <= q: magnitude m
+                            q = t;
                         }
-                    }
-                    // (requested together; for m = 0 the second is not used)
-                    const wint<W> e = load_entry<W>(erow, m == 0 ? k - 1 : k - m);
-                    const wint<W> n = load_entry<W>(p.tab_n, (int64_t)rw * (K + 1) + (k - m));
-                    if (!unsure) {
+                        n = load_entry<W>(p.tab_n, (int64_t)rw * (K + 1) + (k - m));
+                    } else {
                         uint32_t b;
-                        const wint<W> t = subtract(q, e, &b);
-                        if (m == 0) q = t; else diff = t;
+                        subtract_from(q, load_entry<W>(erow, m == 0 ? k - 1 : k - m), &b);
                     }
                     if (m > 0) {
                         // inside the block of magnitude m: v = q - E(d-1,k-m) + N(d-1,k-m); negative means
                         // the second half of the block (the coordinate is -m), whose q is v + N(d-1,k-m)
-                        add_to(diff, n);
-                        const bool negative = diff.w[W - 1] >> 31;
-                        if (negative) add_to(diff, n);
-                        q = diff;
+                        add_to(q, n);
+                        const bool negative = q.w[W - 1] >> 31;
+                        if (negative) add_to(q, n);
                         y = negative ? -m : m;
                         k -= m;
                     }

@@ -835,9 +835,16 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
                 const uint32_t gq = quad_group(q);
                 const bool last = q + 1 == nq;
                 fetch(last && N.live ? N.row : R.row, last ? (N.live ? N.gl0 : gq) : quad_group(q + 1), nxt);
+                // With many vectors the activations' loads are what the vector memory path is busy with.  A lane's own
+                // four groups lie side by side, so a load for "group j of every k-block" takes 16 bytes out of every 64;
+                // with kSwap the four k-blocks of a row trade decoded groups instead (lane kb gets group kb of lane t for
+                // instruction t: a 4 x 4 transposition over the rows of 16 lanes by register pairs trading halves and
+                // rows), and instruction t's activations are 64 bytes in a row per vector.
+                constexpr bool kSwap = NS >= 3;
                 uint4 bx[4];
 #pragma unroll
-                for (int j = 0; j < 4; j++) bx[j] = *reinterpret_cast<const uint4 *>(xvec + (int64_t)(gq + j) * 8);
+                for (int j = 0; j < 4; j++)
+                    bx[j] = *reinterpret_cast<const uint4 *>(xvec + (int64_t)(kSwap ? gq - 4 * kb + 4 * j + kb : gq + j) * 8);
                 uint32_t c[4], pr[4][4], n2x4[4];
                 c[0] = cur.w[0] & 0xFFFFFFu;
                 c[1] = __builtin_amdgcn_alignbit(cur.w[1], cur.w[0], 24) & 0xFFFFFFu;
@@ -845,11 +852,34 @@ __global__ __launch_bounds__(kGemvThreads) void gemv8_mfma_kernel(fast8_launch f
                 c[3] = cur.w[2] >> 8;
                 pvq_fast8_decode<4, false>(lds, f.blob, f.p, c, pr, n2x4);
                 const uint32_t codes = CODES ? cur.s[0] >> ((gq * sb) & 31u) : 0u;
+                float gains[4];
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
                     float gain = *reinterpret_cast<const float *>(lds + f.p.invs + n2x4[j]);
                     if constexpr (CODES) gain *= sqrtc_l[(codes >> (j * sb)) & ((1u << sb) - 1u)];
                     else gain *= __uint_as_float(cur.s[j]);
+                    gains[j] = gain;
+                }
+                if constexpr (kSwap) {
+                    // value j of row kb <-> value kb of row j, for the pulses' four words and the gain
+                    auto transpose = [](uint32_t &r0, uint32_t &r1, uint32_t &r2, uint32_t &r3) {
+                        auto a = __builtin_amdgcn_permlane32_swap(r0, r2, false, false);
+                        auto b = __builtin_amdgcn_permlane32_swap(r1, r3, false, false);
+                        auto e = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+                        auto g = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+                        r0 = e[0]; r1 = e[1]; r2 = g[0]; r3 = g[1];
+                    };
+#pragma unroll
+                    for (int w = 0; w < 4; w++) transpose(pr[0][w], pr[1][w], pr[2][w], pr[3][w]);
+                    uint32_t g0 = __float_as_uint(gains[0]), g1 = __float_as_uint(gains[1]), g2 = __float_as_uint(gains[2]),
+                             g3 = __float_as_uint(gains[3]);
+                    transpose(g0, g1, g2, g3);
+                    gains[0] = __uint_as_float(g0); gains[1] = __uint_as_float(g1); gains[2] = __uint_as_float(g2);
+                    gains[3] = __uint_as_float(g3);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const float gain = gains[j];
                     const bf16x4_bits_t xlo = __builtin_bit_cast(bf16x4_bits_t, make_uint2(bx[j].x, bx[j].y)),
                                         xhi = __builtin_bit_cast(bf16x4_bits_t, make_uint2(bx[j].z, bx[j].w)),
                                         ylo = __builtin_bit_cast(bf16x4_bits_t, make_uint2(pr[j][0], pr[j][1])),
